@@ -1,0 +1,151 @@
+/*
+ * sdgp.h -- C ABI of the SDGP backward-data library for AMD MI355X (gfx950).
+ *
+ * SDGP (Structured Data Gradient Pruning, arXiv 2202.00774) keeps n of every m
+ * consecutive channels of the output data gradient dL/dO and zeroes the rest
+ * (Alg. 1, Sec. III-A), then computes the input data gradient dL/dD from the
+ * pruned tensor (Fig. 1, Fig. 2, Sec. II-A).  This library is that path and
+ * nothing else: the prune primitive, and the backward-data product for linear
+ * and convolution layers with the prune fused in.
+ *
+ * Conventions that hold for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or retains it.  Inputs are const and are never
+ *     written: dL/dO must survive because the weight gradient is computed from
+ *     the unpruned tensor (Sec. III-A, last paragraph).
+ *   - Tensors are contiguous, the pruned axis (channels) is the last one with
+ *     stride 1 (Sec. III-A), and groups are the aligned runs
+ *     [g*m, g*m+m) of that axis.  Groups never cross rows.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without synchronising.
+ *   - All arguments are validated before anything is launched; a call that
+ *     returns an error has had no effect on device memory.
+ *   - A tensor with zero elements is a successful no-op.
+ *   - Return value: SDGP_OK (0) or a negative sdgp_status.  No C++ exception
+ *     crosses this boundary.
+ */
+#ifndef SDGP_H_
+#define SDGP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SDGP_OK = 0,
+    SDGP_ERR_NULL = -1,      /* a required pointer is NULL                                   */
+    SDGP_ERR_NM = -2,        /* n < 1, n > m, m > 32 (Sec. III-A: group size at most 32)     */
+    SDGP_ERR_SHAPE = -3,     /* channels not a multiple of m, negative size, element count
+                                overflow, inconsistent convolution geometry, misaligned ptr  */
+    SDGP_ERR_DTYPE = -4,     /* dtype is not an sdgp_dtype                                   */
+    SDGP_ERR_RANKER = -5,    /* ranker is not an sdgp_ranker                                 */
+    SDGP_ERR_WORKSPACE = -6, /* workspace is NULL or smaller than the size query returns     */
+    SDGP_ERR_HIP = -7        /* the HIP runtime refused a launch (the HIP error is consumed) */
+} sdgp_status;
+
+typedef enum {
+    SDGP_F32 = 0, /* IEEE binary32                                                     */
+    SDGP_BF16 = 1 /* bfloat16 storage, fp32 arithmetic and accumulation, RNE on output */
+} sdgp_dtype;
+
+/* The three pruning functions of Sec. III-B.  "greedy" is the paper's Magnitude,
+ * "greedy-adjusted" its Rescaled Magnitude. */
+typedef enum {
+    SDGP_RANDOM = 0,
+    SDGP_GREEDY = 1,
+    SDGP_GREEDY_ADJUSTED = 2
+} sdgp_ranker;
+
+/*
+ * sdgp_prune -- Alg. 1 with the pruning function P of Sec. III-B.
+ *
+ *   dO      [rows, C] of `dt`, read only.
+ *   n, m    keep n of every m consecutive channels; 1 <= n <= m <= 32, C % m == 0.
+ *   rk      ranking rule.  The kept set of a group is the n positions with the
+ *           largest (key, -position): larger key first, equal keys -> lower position.
+ *             greedy, greedy-adjusted: key = |x| compared as the sign-cleared bit
+ *               pattern (so -0 == +0, subnormals are not flushed).
+ *             random: key = the 32-bit counter hash of (seed, flat element index
+ *               row*C + channel); the values are not looked at.
+ *           greedy-adjusted then multiplies the kept values of a group by
+ *           s = (sum |x| over the group) / (sum |x| over the kept), both sums taken
+ *           in fp32 in ascending channel order, one IEEE division, s = 1 when the
+ *           denominator is 0; the product is rounded to `dt` (RNE).  This keeps
+ *           the L1 norm of every group (Sec. III-B, Rescaled Magnitude).
+ *   seed    only read by the random ranker.
+ *   pruned  [rows, C] of `dt` or NULL: the dense-shaped pruned copy (the tensor
+ *           Alg. 1 returns); dropped positions hold +0.
+ *   vals    [rows, C*n/m] of `dt` or NULL: kept values in ascending channel order.
+ *   idx     [rows, C*n/m] uint8 or NULL: position 0..m-1 of each kept value inside
+ *           its group, strictly ascending inside a group.  vals and idx must be
+ *           both NULL or both non-NULL.  At least one output must be requested.
+ *
+ * Pointers must be aligned to 16 bytes when C*sizeof(dt) is a multiple of 16
+ * (any allocation from hipMalloc or torch is).
+ */
+int sdgp_prune(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, int rk, uint64_t seed,
+               void* pruned, void* vals, uint8_t* idx, void* hip_stream);
+
+/*
+ * sdgp_linear_bwd_data -- dL/dD of a fully connected layer from the pruned dL/dO
+ * (Fig. 2 right, Sec. II-A, with SDGP applied to dL/dO first).
+ *
+ *   dO  [rows, C_out] of `dt`       the layer's output data gradient (forward was O = D * W^T)
+ *   W   [C_out, C_in] of `dt`       the layer's weights
+ *   dD  [rows, C_in]  of `dt`       dD = prune(dO; n, m, rk, seed) * W, fp32 accumulation
+ *
+ * The prune is the one sdgp_prune defines (same keys, tie rule, rescale and flat
+ * element index row*C_out + channel) and happens inside the kernel; no pruned
+ * copy is written to memory.  n == m skips the ranker and is the dense product.
+ */
+int sdgp_linear_bwd_data(const void* dO, const void* W, void* dD, int64_t rows, int64_t C_out,
+                         int64_t C_in, int dt, int n, int m, int rk, uint64_t seed,
+                         void* hip_stream);
+
+/*
+ * sdgp_conv_bwd_data -- dL/dD of a 2-D convolution layer from the pruned dL/dO
+ * (Fig. 3, Sec. III-A; convolution as a matrix product per Sec. II-A).
+ *
+ *   dO  [B, P, Q, C_out] NHWC      P = (H + 2*pad - R)/stride + 1, Q likewise from Wd and S
+ *   W   [C_out, R, S, C_in]        (channels-last memory of a [C_out, C_in, R, S] weight)
+ *   dD  [B, H, Wd, C_in] NHWC
+ *
+ *   dD[b,h,w,c] = sum over taps (r,s) and channels k of
+ *                 prune(dO)[b,p,q,k] * W[k,r,s,c],   p = (h + pad - r)/stride, q = (w + pad - s)/stride,
+ *   taking only taps for which p and q are integers inside [0,P) x [0,Q).
+ *   The forward pass was a cross-correlation with dilation 1 and one group.
+ *   Input pixels that no tap reaches receive 0.  Each dO element is pruned once,
+ *   with flat element index ((b*P + p)*Q + q)*C_out + k.
+ *
+ *   workspace / workspace_bytes: scratch memory of at least
+ *   sdgp_conv_bwd_data_workspace(...) bytes (16-byte aligned); may be NULL when the
+ *   query returns 0.  Its contents are undefined afterwards.  Calls that share a
+ *   workspace must be ordered on one stream.
+ *
+ * Requires 1 <= R,S <= 11, 1 <= stride <= 4, 0 <= pad < R and pad < S,
+ * H + 2*pad >= R, Wd + 2*pad >= S.
+ */
+int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd,
+                       int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dt, int n,
+                       int m, int rk, uint64_t seed, void* workspace, size_t workspace_bytes,
+                       void* hip_stream);
+
+/* Bytes of workspace sdgp_conv_bwd_data needs for these arguments (0 when the
+ * call is fully fused); (size_t)-1 when the arguments are invalid. */
+size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                                    int R, int S, int stride, int pad, int dt, int n, int m);
+
+/* Static, NUL-terminated description of a status code. */
+const char* sdgp_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int sdgp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* SDGP_H_ */
