@@ -1,0 +1,127 @@
+// extern "C" boundary of the SDGP library: argument validation and dispatch.
+// Every check happens before the first launch, so a failing call has no effect.
+#include "common.h"
+
+namespace sdgp {
+int prune_launch(const void* dO, int64_t total, int dt, int n, int m, int rk, uint64_t seed, void* pruned, void* vals,
+                 uint8_t* idx, hipStream_t stream);
+int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                      int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed,
+                      hipStream_t stream);
+}  // namespace sdgp
+
+namespace {
+
+constexpr int64_t kMaxElements = (int64_t)1 << 40;
+
+bool valid_dtype(int dt) { return dt == SDGP_F32 || dt == SDGP_BF16; }
+bool valid_ranker(int rk) { return rk == SDGP_RANDOM || rk == SDGP_GREEDY || rk == SDGP_GREEDY_ADJUSTED; }
+bool valid_nm(int n, int m) { return n >= 1 && n <= m && m <= 32; }
+
+// a*b with overflow / range check against kMaxElements; false when out of range.
+bool mul_checked(int64_t a, int64_t b, int64_t* out) {
+    if (a < 0 || b < 0) return false;
+    if (a == 0 || b == 0) {
+        *out = 0;
+        return true;
+    }
+    if (a > kMaxElements / b) return false;
+    *out = a * b;
+    return true;
+}
+
+
+struct ConvGeom {
+    int64_t P, Q, n_dO, n_W, n_dD;
+};
+
+// Full validation of a convolution backward-data problem; SDGP_OK and the derived sizes, or the error.
+int check_conv(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad,
+               int dt, int n, int m, ConvGeom* g) {
+    if (!valid_dtype(dt)) return SDGP_ERR_DTYPE;
+    if (!valid_nm(n, m)) return SDGP_ERR_NM;
+    if (B < 0 || H < 0 || Wd < 0 || C_in < 0 || C_out < 0) return SDGP_ERR_SHAPE;
+    if (R < 1 || R > 11 || S < 1 || S > 11 || stride < 1 || stride > 4 || pad < 0 || pad >= R || pad >= S)
+        return SDGP_ERR_SHAPE;
+    if ((C_out % m) != 0) return SDGP_ERR_SHAPE;
+    if (H > kMaxElements || Wd > kMaxElements) return SDGP_ERR_SHAPE;
+    if (H + 2 * pad < R || Wd + 2 * pad < S) return SDGP_ERR_SHAPE;
+    g->P = (H + 2 * pad - R) / stride + 1;
+    g->Q = (Wd + 2 * pad - S) / stride + 1;
+    int64_t t = 0;
+    if (!mul_checked(B, g->P, &t) || !mul_checked(t, g->Q, &t) || !mul_checked(t, C_out, &g->n_dO)) return SDGP_ERR_SHAPE;
+    if (!mul_checked(C_out, (int64_t)R * S, &t) || !mul_checked(t, C_in, &g->n_W)) return SDGP_ERR_SHAPE;
+    if (!mul_checked(B, H, &t) || !mul_checked(t, Wd, &t) || !mul_checked(t, C_in, &g->n_dD)) return SDGP_ERR_SHAPE;
+    return SDGP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sdgp_prune(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, int rk, uint64_t seed, void* pruned,
+               void* vals, uint8_t* idx, void* hip_stream) {
+    if (!valid_dtype(dt)) return SDGP_ERR_DTYPE;
+    if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
+    if (!valid_nm(n, m)) return SDGP_ERR_NM;
+    int64_t total = 0;
+    if (!mul_checked(rows, C, &total) || (C % m) != 0) return SDGP_ERR_SHAPE;
+    if (total == 0) return SDGP_OK;  // nothing to read or write; pointers of empty tensors may be NULL
+    if ((vals == nullptr) != (idx == nullptr)) return SDGP_ERR_NULL;
+    if (pruned == nullptr && vals == nullptr) return SDGP_ERR_NULL;
+    if (dO == nullptr) return SDGP_ERR_NULL;
+    return sdgp::prune_launch(dO, total, dt, n, m, rk, seed, pruned, vals, idx, static_cast<hipStream_t>(hip_stream));
+}
+
+int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                       int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ConvGeom g;
+    const int rc = check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g);
+    if (rc != SDGP_OK) return rc;
+    if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
+    if (g.n_dD == 0) return SDGP_OK;
+    if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
+    const size_t need = sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SDGP_ERR_WORKSPACE;
+    return sdgp::bwd_simple_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed,
+                                   static_cast<hipStream_t>(hip_stream));
+}
+
+size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
+                                    int stride, int pad, int dt, int n, int m) {
+    ConvGeom g;
+    if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g) != SDGP_OK) return (size_t)-1;
+    return 0;
+}
+
+int sdgp_linear_bwd_data(const void* dO, const void* W, void* dD, int64_t rows, int64_t C_out, int64_t C_in, int dt,
+                         int n, int m, int rk, uint64_t seed, void* hip_stream) {
+    // A linear layer is a 1x1 convolution over rows "pixels".
+    ConvGeom g;
+    const int rc = check_conv(rows, 1, 1, C_in, C_out, 1, 1, 1, 0, dt, n, m, &g);
+    if (rc != SDGP_OK) return rc;
+    if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
+    if (g.n_dD == 0) return SDGP_OK;
+    if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
+    return sdgp::bwd_simple_launch(dO, W, dD, rows, 1, 1, C_in, C_out, 1, 1, 1, 0, dt, n, m, rk, seed,
+                                   static_cast<hipStream_t>(hip_stream));
+}
+
+const char* sdgp_status_string(int status) {
+    switch (status) {
+        case SDGP_OK: return "ok";
+        case SDGP_ERR_NULL: return "a required pointer is NULL";
+        case SDGP_ERR_NM: return "n and m must satisfy 1 <= n <= m <= 32";
+        case SDGP_ERR_SHAPE: return "invalid shape: channels not a multiple of m, negative or overflowing size, or inconsistent geometry";
+        case SDGP_ERR_DTYPE: return "unknown dtype";
+        case SDGP_ERR_RANKER: return "unknown ranker";
+        case SDGP_ERR_WORKSPACE: return "workspace missing or too small";
+        case SDGP_ERR_HIP: return "the HIP runtime reported an error";
+        default: return "unknown status";
+    }
+}
+
+int sdgp_version(void) { return 100; }
+
+}  // extern "C"

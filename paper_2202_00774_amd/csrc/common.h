@@ -1,0 +1,59 @@
+// Shared device/host helpers of the SDGP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sdgp.h"
+
+namespace sdgp {
+
+// ---------------------------------------------------------------- bit casts
+
+__device__ __forceinline__ float bits_to_float(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t float_to_bits(float f) { return __float_as_uint(f); }
+
+// bfloat16 is the upper half of a binary32.
+__device__ __forceinline__ float bf16_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+
+// binary32 -> bfloat16 bits, round to nearest, ties to even; NaN stays NaN.
+__device__ __forceinline__ uint32_t float_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? ((u >> 16) | 0x40u) : r;
+}
+
+// ------------------------------------------------------- counter-based hash
+//
+// Key of flat element e under `seed` for the random pruning function
+// (Sec. III-B, "Random"; the paper names no generator, this is the library's
+// definition).  With x = low and y = high word of e, s0/s1 the words of seed:
+//   v = 0xA54FF53A ^ x ^ s0*0x9E3779B9 ^ y*0xBB67AE85 ^ s1*0x510E527F
+//   v ^= v>>16; v *= 0x6A09E667; v ^= v>>15; v *= 0xBB67AE85; v ^= v>>16
+// The seed terms are folded on the host (seed_mix), the y term once per group
+// (hash_row), leaving two multiplies per element.
+
+__host__ __device__ inline uint32_t seed_mix(uint64_t seed) {
+    return 0xA54FF53Au ^ ((uint32_t)seed * 0x9E3779B9u) ^ ((uint32_t)(seed >> 32) * 0x510E527Fu);
+}
+
+__device__ __forceinline__ uint32_t hash_row(uint32_t mix, uint32_t e_hi) { return mix ^ (e_hi * 0xBB67AE85u); }
+
+__device__ __forceinline__ uint32_t hash_elem(uint32_t row, uint32_t e_lo) {
+    uint32_t v = row ^ e_lo;
+    v ^= v >> 16;
+    v *= 0x6A09E667u;
+    v ^= v >> 15;
+    v *= 0xBB67AE85u;
+    v ^= v >> 16;
+    return v;
+}
+
+// ------------------------------------------------------------ host helpers
+
+inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Consumes and maps the HIP error state after a launch.
+inline int launch_status() { return hipGetLastError() == hipSuccess ? SDGP_OK : SDGP_ERR_HIP; }
+
+}  // namespace sdgp

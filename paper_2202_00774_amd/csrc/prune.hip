@@ -1,0 +1,272 @@
+// sdgp_prune: Alg. 1 (Sec. III-A) as a streaming HIP kernel for gfx950.
+//
+// Because the channel count is a multiple of m, the aligned m-groups of every
+// row are also the aligned m-groups of the flattened tensor, so the kernel
+// walks the tensor as a 1-D array of "items": the larger of one group and one
+// 16-byte vector.  A lane owns whole groups, so ranking needs no cross-lane
+// traffic and no LDS; the kernel is bound by HBM (one read and one write of
+// the tensor for the dense-shaped output).
+//
+// Two kernels:
+//   prune_items    vector loads/stores, m in {4, 8, 16, 32}, any n; the
+//                  selection network is chosen at compile time (see ranker.h)
+//   prune_groups   one thread per group, scalar accesses, any 1 <= n <= m <= 32;
+//                  used for other m, for tails and for unaligned pointers.
+#include "ranker.h"
+
+namespace sdgp {
+
+namespace {
+
+constexpr int kBlock = 256;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT>
+struct Storage;
+template <>
+struct Storage<kF32> {
+    using type = uint32_t;
+    static constexpr int kPerVec = 4;  // elements in 16 bytes
+};
+template <>
+struct Storage<kBF16> {
+    using type = uint16_t;
+    static constexpr int kPerVec = 8;
+};
+
+// ------------------------------------------------------------ vector kernel
+
+template <int DT, int M, int RK, bool NLE2, bool MASKED, bool COMPACT>
+__global__ void __launch_bounds__(kBlock)
+prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, void* __restrict__ pruned_,
+            void* __restrict__ vals_, uint8_t* __restrict__ idx) {
+    using T = typename Storage<DT>::type;
+    constexpr int PV = Storage<DT>::kPerVec;
+    constexpr int ITEM = (M > PV) ? M : PV;  // elements per item
+    constexpr int VECS = ITEM / PV;          // 16-byte vectors per item
+    constexpr int GROUPS = ITEM / M;         // groups per item
+
+    const int64_t item = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (item >= nitems) return;
+
+    const u32x4* src = reinterpret_cast<const u32x4*>(dO_) + item * VECS;
+    u32x4 v[VECS];
+#pragma unroll
+    for (int i = 0; i < VECS; ++i) v[i] = __builtin_nontemporal_load(src + i);
+
+    uint32_t raw[ITEM];
+#pragma unroll
+    for (int i = 0; i < VECS; ++i) {
+        const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if constexpr (DT == kBF16) {
+                raw[i * 8 + 2 * k] = w[k] & 0xFFFFu;
+                raw[i * 8 + 2 * k + 1] = w[k] >> 16;
+            } else {
+                raw[i * 4 + k] = w[k];
+            }
+        }
+    }
+
+    const uint64_t e0 = (uint64_t)item * ITEM;  // flat index of the item's first element
+    const uint32_t hrow = hash_row(mix, (uint32_t)(e0 >> 32));
+
+    uint32_t out[ITEM];
+    bool keep[ITEM];
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+        uint32_t r[M], o[M];
+        bool k[M];
+#pragma unroll
+        for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
+        prune_group<DT, M, RK, NLE2>(r, n, hrow, (uint32_t)e0 + g * M, k, o);
+#pragma unroll
+        for (int j = 0; j < M; ++j) {
+            out[g * M + j] = o[j];
+            keep[g * M + j] = k[j];
+        }
+    }
+
+    if constexpr (MASKED) {
+        u32x4* dst = reinterpret_cast<u32x4*>(pruned_) + item * VECS;
+#pragma unroll
+        for (int i = 0; i < VECS; ++i) {
+            uint32_t w[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if constexpr (DT == kBF16) w[k] = out[i * 8 + 2 * k] | (out[i * 8 + 2 * k + 1] << 16);
+                else w[k] = out[i * 4 + k];
+            }
+            const u32x4 pk = {w[0], w[1], w[2], w[3]};
+            __builtin_nontemporal_store(pk, dst + i);
+        }
+    }
+
+    if constexpr (COMPACT) {
+        // Kept values and positions in ascending position; n per group.
+        T* vals = reinterpret_cast<T*>(vals_);
+        int64_t o = (int64_t)item * GROUPS * n;
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) {
+#pragma unroll
+            for (int j = 0; j < M; ++j) {
+                if (keep[g * M + j]) {
+                    vals[o] = (T)out[g * M + j];
+                    idx[o] = (uint8_t)j;
+                    ++o;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------- group kernel
+
+template <int DT>
+__global__ void __launch_bounds__(kBlock)
+prune_groups(const void* __restrict__ dO_, int64_t ngroups, int64_t e_base, int n, int m, int rk, uint32_t mix,
+             void* __restrict__ pruned_, void* __restrict__ vals_, uint8_t* __restrict__ idx) {
+    using T = typename Storage<DT>::type;
+    const int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (g >= ngroups) return;
+    const T* src = reinterpret_cast<const T*>(dO_) + g * m;
+    constexpr uint32_t kMagMask = (DT == kBF16) ? 0x7FFFu : 0x7FFFFFFFu;
+
+    uint32_t raw[32], key[32];
+    const uint64_t e0 = (uint64_t)e_base + (uint64_t)g * (uint64_t)m;
+    for (int j = 0; j < m; ++j) {
+        raw[j] = (uint32_t)src[j];
+        const uint64_t e = e0 + (uint64_t)j;
+        key[j] = (rk == kRandom) ? hash_elem(hash_row(mix, (uint32_t)(e >> 32)), (uint32_t)e) : (raw[j] & kMagMask);
+    }
+    uint32_t keepmask = 0;
+    for (int j = 0; j < m; ++j) {
+        int rank = 0;
+        for (int i = 0; i < m; ++i) rank += (key[i] > key[j] || (key[i] == key[j] && i < j)) ? 1 : 0;
+        if (rank < n) keepmask |= 1u << j;
+    }
+    float scale = 1.0f;
+    if (rk == kAdjusted) {
+        float total = 0.0f, kept = 0.0f;
+        for (int j = 0; j < m; ++j) {
+            const float x = (DT == kBF16) ? bf16_to_float(raw[j]) : bits_to_float(raw[j]);
+            const float a = bits_to_float(float_to_bits(x) & 0x7FFFFFFFu);
+            total = __fadd_rn(total, a);
+            if ((keepmask >> j) & 1u) kept = __fadd_rn(kept, a);
+        }
+        scale = (kept == 0.0f) ? 1.0f : __fdiv_rn(total, kept);
+    }
+    T* pruned = reinterpret_cast<T*>(pruned_);
+    T* vals = reinterpret_cast<T*>(vals_);
+    int64_t o = g * n;
+    for (int j = 0; j < m; ++j) {
+        uint32_t y = 0;
+        const bool k = (keepmask >> j) & 1u;
+        if (k) {
+            y = raw[j];
+            if (rk == kAdjusted) {
+                const float x = (DT == kBF16) ? bf16_to_float(raw[j]) : bits_to_float(raw[j]);
+                const float p = __fmul_rn(x, scale);
+                y = (DT == kBF16) ? float_to_bf16(p) : float_to_bits(p);
+            }
+        }
+        if (pruned) pruned[g * m + j] = (T)y;
+        if (k && vals) {
+            vals[o] = (T)y;
+            idx[o] = (uint8_t)j;
+            ++o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ dispatch
+
+struct PruneArgs {
+    const void* dO;
+    int64_t total;  // elements
+    int n, m, rk;
+    uint32_t mix;
+    void* pruned;
+    void* vals;
+    uint8_t* idx;
+    hipStream_t stream;
+};
+
+template <int DT, int M, int RK, bool NLE2>
+void launch_items_out(const PruneArgs& a, int64_t nitems) {
+    const dim3 grid((unsigned)((nitems + kBlock - 1) / kBlock)), block(kBlock);
+    if (a.pruned && a.vals)
+        hipLaunchKernelGGL((prune_items<DT, M, RK, NLE2, true, true>), grid, block, 0, a.stream, a.dO, nitems, a.n, a.mix,
+                           a.pruned, a.vals, a.idx);
+    else if (a.pruned)
+        hipLaunchKernelGGL((prune_items<DT, M, RK, NLE2, true, false>), grid, block, 0, a.stream, a.dO, nitems, a.n, a.mix,
+                           a.pruned, a.vals, a.idx);
+    else
+        hipLaunchKernelGGL((prune_items<DT, M, RK, NLE2, false, true>), grid, block, 0, a.stream, a.dO, nitems, a.n, a.mix,
+                           a.pruned, a.vals, a.idx);
+}
+
+template <int DT, int M>
+void launch_items(const PruneArgs& a, int64_t nitems) {
+    const bool nle2 = a.n <= 2;
+    switch (a.rk) {
+        case kRandom:
+            nle2 ? launch_items_out<DT, M, kRandom, true>(a, nitems) : launch_items_out<DT, M, kRandom, false>(a, nitems);
+            break;
+        case kGreedy:
+            nle2 ? launch_items_out<DT, M, kGreedy, true>(a, nitems) : launch_items_out<DT, M, kGreedy, false>(a, nitems);
+            break;
+        default:
+            nle2 ? launch_items_out<DT, M, kAdjusted, true>(a, nitems) : launch_items_out<DT, M, kAdjusted, false>(a, nitems);
+            break;
+    }
+}
+
+template <int DT>
+void launch_groups(const PruneArgs& a, int64_t first_elem, int64_t nelems) {
+    using T = typename Storage<DT>::type;
+    const int64_t ngroups = nelems / a.m;
+    if (ngroups == 0) return;
+    const int64_t kept0 = first_elem / a.m * a.n;
+    const dim3 grid((unsigned)((ngroups + kBlock - 1) / kBlock)), block(kBlock);
+    hipLaunchKernelGGL((prune_groups<DT>), grid, block, 0, a.stream,
+                       (const void*)(reinterpret_cast<const T*>(a.dO) + first_elem), ngroups, first_elem, a.n, a.m, a.rk,
+                       a.mix, a.pruned ? (void*)(reinterpret_cast<T*>(a.pruned) + first_elem) : nullptr,
+                       a.vals ? (void*)(reinterpret_cast<T*>(a.vals) + kept0) : nullptr, a.idx ? a.idx + kept0 : nullptr);
+}
+
+template <int DT>
+void prune_dtype(const PruneArgs& a) {
+    constexpr int PV = Storage<DT>::kPerVec;
+    const bool vec_m = (a.m == 4 || a.m == 8 || a.m == 16 || a.m == 32);
+    const bool aligned = is_aligned16(a.dO) && (!a.pruned || is_aligned16(a.pruned));
+    int64_t done = 0;
+    if (vec_m && aligned) {
+        const int item = a.m > PV ? a.m : PV;
+        const int64_t nitems = a.total / item;
+        if (nitems > 0) {
+            switch (a.m) {
+                case 4: launch_items<DT, 4>(a, nitems); break;
+                case 8: launch_items<DT, 8>(a, nitems); break;
+                case 16: launch_items<DT, 16>(a, nitems); break;
+                default: launch_items<DT, 32>(a, nitems); break;
+            }
+        }
+        done = nitems * item;
+    }
+    if (done < a.total) launch_groups<DT>(a, done, a.total - done);
+}
+
+}  // namespace
+
+// Validated arguments in; launches on `stream`.  total = rows * C.
+int prune_launch(const void* dO, int64_t total, int dt, int n, int m, int rk, uint64_t seed, void* pruned, void* vals,
+                 uint8_t* idx, hipStream_t stream) {
+    PruneArgs a{dO, total, n, m, rk, seed_mix(seed), pruned, vals, idx, stream};
+    if (dt == kBF16) prune_dtype<kBF16>(a);
+    else prune_dtype<kF32>(a);
+    return launch_status();
+}
+
+}  // namespace sdgp

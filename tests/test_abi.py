@@ -1,0 +1,121 @@
+"""The C ABI without a GPU: the library loads, exports what include/sdgp.h declares, and validates arguments
+before touching the device (so every error path can be driven from a CPU-only machine)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2202_00774_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, E_NULL, E_NM, E_SHAPE, E_DTYPE, E_RANKER, E_WS, E_HIP = 0, -1, -2, -3, -4, -5, -6, -7
+P = ctypes.c_void_p(16)       # never dereferenced: validation fails first
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sdgp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sdgp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = binding.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert binding.status_string(-99) == "unknown status"
+    assert binding.version() >= 100
+
+
+def prune(lib, rows=4, C=16, dt=1, n=2, m=4, rk=1, dO=P, pruned=P, vals=None, idx=None):
+    return lib.sdgp_prune(dO, rows, C, dt, n, m, rk, 0, pruned, vals, idx, None)
+
+
+def test_prune_argument_errors(lib):
+    assert prune(lib, dt=2) == E_DTYPE
+    assert prune(lib, rk=3) == E_RANKER
+    assert prune(lib, rk=-1) == E_RANKER
+    for n, m in ((0, 4), (5, 4), (2, 33), (-1, 4)):
+        assert prune(lib, n=n, m=m, C=m * 4 if m > 0 else 16) == E_NM
+    assert prune(lib, C=18) == E_SHAPE                 # 18 % 4 != 0
+    assert prune(lib, rows=-1) == E_SHAPE
+    assert prune(lib, rows=2 ** 40, C=2 ** 30) == E_SHAPE
+    assert prune(lib, dO=None) == E_NULL
+    assert prune(lib, pruned=None) == E_NULL           # no output requested
+    assert prune(lib, vals=P, idx=None) == E_NULL      # vals without idx
+    assert prune(lib, vals=None, idx=P) == E_NULL
+    assert prune(lib, rows=0) == OK                    # empty tensor: nothing to do
+    assert prune(lib, rows=0, dO=None) == OK
+    assert prune(lib, C=0) == OK
+
+
+def linear(lib, rows=4, C_out=16, C_in=8, dt=1, n=2, m=4, rk=1, dO=P, W=P, dD=P):
+    return lib.sdgp_linear_bwd_data(dO, W, dD, rows, C_out, C_in, dt, n, m, rk, 0, None)
+
+
+def test_linear_argument_errors(lib):
+    assert linear(lib, dt=7) == E_DTYPE
+    assert linear(lib, rk=9) == E_RANKER
+    assert linear(lib, n=3, m=2) == E_NM
+    assert linear(lib, C_out=18) == E_SHAPE
+    assert linear(lib, rows=-2) == E_SHAPE
+    assert linear(lib, C_in=-1) == E_SHAPE
+    assert linear(lib, dO=None) == E_NULL
+    assert linear(lib, W=None) == E_NULL
+    assert linear(lib, dD=None) == E_NULL
+    assert linear(lib, rows=0) == OK
+    assert linear(lib, C_in=0) == OK
+
+
+def conv(lib, B=2, H=8, Wd=8, C_in=8, C_out=16, R=3, S=3, stride=1, pad=1, dt=1, n=2, m=4, rk=1, dO=P, W=P, dD=P,
+         ws=None, ws_bytes=0):
+    return lib.sdgp_conv_bwd_data(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, 0, ws, ws_bytes, None)
+
+
+def test_conv_argument_errors(lib):
+    assert conv(lib, dt=-1) == E_DTYPE
+    assert conv(lib, rk=5) == E_RANKER
+    assert conv(lib, n=0) == E_NM
+    assert conv(lib, C_out=10) == E_SHAPE
+    assert conv(lib, R=0) == E_SHAPE
+    assert conv(lib, S=12) == E_SHAPE
+    assert conv(lib, stride=0) == E_SHAPE
+    assert conv(lib, stride=5) == E_SHAPE
+    assert conv(lib, pad=3) == E_SHAPE                  # pad >= R
+    assert conv(lib, pad=-1) == E_SHAPE
+    assert conv(lib, H=1, Wd=1, R=5, S=5, pad=1) == E_SHAPE   # filter larger than the padded input
+    assert conv(lib, B=-1) == E_SHAPE
+    assert conv(lib, dO=None) == E_NULL
+    assert conv(lib, W=None) == E_NULL
+    assert conv(lib, dD=None) == E_NULL
+    assert conv(lib, B=0) == OK
+    assert conv(lib, C_in=0) == OK
+    bad = ctypes.c_size_t(-1).value
+    assert lib.sdgp_conv_bwd_data_workspace(2, 8, 8, 8, 10, 3, 3, 1, 1, 1, 2, 4) == bad
+    assert lib.sdgp_conv_bwd_data_workspace(2, 8, 8, 8, 16, 3, 3, 1, 1, 1, 2, 4) != bad
+
+
+def test_workspace_too_small_is_rejected(lib):
+    # wherever the library asks for workspace, passing none or too little is an error before any launch
+    shapes = [(512, 32, 32, 64, 128, 3, 3, 1, 1), (128, 56, 56, 256, 64, 1, 1, 1, 0), (256, 56, 56, 128, 128, 3, 3, 2, 1)]
+    for B, H, Wd, C_in, C_out, R, S, st, pad in shapes:
+        for n, m in ((2, 4), (2, 8), (4, 4)):
+            need = lib.sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, st, pad, 1, n, m)
+            if need:
+                assert conv(lib, B, H, Wd, C_in, C_out, R, S, st, pad, n=n, m=m) == E_WS
+                assert conv(lib, B, H, Wd, C_in, C_out, R, S, st, pad, n=n, m=m, ws=P, ws_bytes=need - 1) == E_WS
