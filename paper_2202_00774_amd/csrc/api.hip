@@ -8,6 +8,9 @@ int prune_launch(const void* dO, int64_t total, int dt, int n, int m, int rk, ui
 int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                       int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed,
                       hipStream_t stream);
+int bwd_tiled_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                     int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
+                     hipStream_t stream);
 }  // namespace sdgp
 
 namespace {
@@ -55,6 +58,17 @@ int check_conv(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, in
     return SDGP_OK;
 }
 
+
+// Matrix-core kernel when the problem fits it, the shape-agnostic kernel otherwise.
+int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                 int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
+    if (dt == SDGP_BF16 && sdgp::is_aligned16(dD)) {
+        const int rc = sdgp::bwd_tiled_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
+        if (rc <= 0) return rc;
+    }
+    return sdgp::bwd_simple_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -84,8 +98,8 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
     const size_t need = sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SDGP_ERR_WORKSPACE;
-    return sdgp::bwd_simple_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed,
-                                   static_cast<hipStream_t>(hip_stream));
+    return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed,
+                        static_cast<hipStream_t>(hip_stream));
 }
 
 size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
@@ -104,8 +118,8 @@ int sdgp_linear_bwd_data(const void* dO, const void* W, void* dD, int64_t rows, 
     if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
     if (g.n_dD == 0) return SDGP_OK;
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
-    return sdgp::bwd_simple_launch(dO, W, dD, rows, 1, 1, C_in, C_out, 1, 1, 1, 0, dt, n, m, rk, seed,
-                                   static_cast<hipStream_t>(hip_stream));
+    return bwd_dispatch(dO, W, dD, rows, 1, 1, C_in, C_out, 1, 1, 1, 0, dt, n, m, rk, seed,
+                        static_cast<hipStream_t>(hip_stream));
 }
 
 const char* sdgp_status_string(int status) {

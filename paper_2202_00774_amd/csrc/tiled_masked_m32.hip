@@ -1,0 +1,7 @@
+// Instantiates the tiled kernel for 2 < n < m = 32 (pruned halo stored dense, dense matrix instruction).
+#include "bwd_tiled_launch.h"
+namespace sdgp {
+int launch_tiled_masked_m32(const TiledParams& p, int bn, int rk, hipStream_t stream) {
+    return launch_tiled_rk<64, 1, 32>(p, bn, rk, stream);
+}
+}  // namespace sdgp
