@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the SDGP backward-data path on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): the six 3x3
+convolutions of a CIFAR ResNet-9 at batch 512, NHWC bf16, dL/dO ~ Laplace(0, 1e-3)
+with 30 % exact zeros, He-normal weights, 2:4 pruning with each of the three
+rankers.  One "step" is one pass of the whole hot path over that batch: for
+every layer and every ranker one fused call (rank + prune + backward-data
+product), 18 calls.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is the effective rate: the FLOPs of the unpruned
+products divided by the time the pruned path took.  Extra fields give, per
+layer, the fused and the dense hand-written kernel's times (speedup at 2:4, 2:8,
+2:16), the prune pass's GB/s, a roofline object for the dominant kernel and the
+CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+PAPER_CONTEXT = ("the paper reports no measured rate for this path; it estimates a 15-25 % cut of total training time "
+                 "assuming 2:4 sparse tensor-core support on an A100 (abstract, Sec. IV-C)")
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=512, help="batch of the ResNet-9 workload (512 is the named config)")
+    ap.add_argument("--cpu-batch", type=int, default=128, help="batch of the CPU-oracle sample (0 skips it)")
+    ap.add_argument("--no-extras", action="store_true", help="only the timed steps: no per-layer table, no CPU leg")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build contains no multi-GPU path (every box here has one GPU); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2202_00774_amd as sdgp
+    from paper_2202_00774_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    sdgp.binding.load()  # fails loudly when the HIP library is missing
+    dev = torch.device("cuda:0")
+
+    def gpu(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    layers = wl.resnet9_layers(args.batch)
+    rankers = (("random", sdgp.RANDOM), ("greedy", sdgp.GREEDY), ("greedy-adjusted", sdgp.GREEDY_ADJUSTED))
+    data = []
+    for i, L in enumerate(layers):
+        dO, W = wl.layer_inputs(L, 1e-3, 0.3, seed=2000 + i, dtype=wl.BF16)
+        data.append((L, gpu(dO), gpu(W), torch.empty(L.dD_shape, dtype=torch.bfloat16, device=dev)))
+    total_flops = sum(L.dense_flops for L in layers) * len(rankers)
+
+    def call(L, dO, W, out, n, m, rk):
+        sdgp.sdgp_conv_bwd_data(dO, W, L.H, L.Wd, L.stride, L.pad, n, m, rk, 0, out=out)
+
+    def step():
+        for L, dO, W, out in data:
+            for _, rk in rankers:
+                call(L, dO, W, out, 2, 4, rk)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    result = {
+        "metric": "bwd-data effective TFLOP/s + speedup vs dense at 2:4/2:8; prune-pass GB/s",
+        "value": round(total_flops / (elapsed / args.steps) / 1e12, 2),
+        "unit": "TFLOP/s (effective: dense-equivalent FLOPs / pruned-path time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "ResNet-9 conv3x3 backward-data sweep, batch %d, NHWC bf16, 2:4, rankers random+greedy+"
+                               "greedy-adjusted (6 layers x 3 rankers per step)" % args.batch,
+                   "n": 2, "m": 4, "batch": args.batch},
+        "paper_context": PAPER_CONTEXT,
+    }
+
+    def time_call(fn, reps=10, warm=2):
+        """Average duration in ms, HIP events on the stream the kernels are launched on (torch's current stream)."""
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    # ---- roofline of the dominant kernel: the fused sparse kernel of the layer that takes the largest share
+    per_layer = []
+    for L, dO, W, out in data:
+        t_fused = {name: time_call(lambda rk=rk: call(L, dO, W, out, 2, 4, rk)) for name, rk in rankers}
+        per_layer.append((L, t_fused))
+    dom_i = max(range(len(layers)), key=lambda i: sum(per_layer[i][1].values()))
+    Ld, td = per_layer[dom_i]
+    dom_ms = td["greedy"]
+    issued = 0.5 * Ld.dense_flops  # the structured-sparse instruction issues half of the dense multiply-adds
+    result["roofline"] = {
+        "bound": "mfma", "kernel": "bwd_tiled (sparse 2:4, greedy) on %s" % Ld.name,
+        "achieved": round(issued / (dom_ms * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(issued / (dom_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+        "launch_us": round(dom_ms * 1e3, 2),
+        "note": "achieved = FLOPs actually issued per launch (half the dense count: one 2:4 sparse MFMA per two dense "
+                "ones) / mean launch time from HIP events; effective rate is twice that",
+    }
+
+    if not args.no_extras:
+        table = []
+        for (L, dO, W, out), (_, t_fused) in zip(data, per_layer):
+            t_dense = time_call(lambda: call(L, dO, W, out, 4, 4, sdgp.GREEDY))
+            t28 = time_call(lambda: call(L, dO, W, out, 2, 8, sdgp.GREEDY))
+            t216 = time_call(lambda: call(L, dO, W, out, 2, 16, sdgp.GREEDY))
+            row = {"layer": L.name, "gflop_dense": round(L.dense_flops / 1e9, 2), "dense_us": round(t_dense * 1e3, 1),
+                   "dense_tflops": round(L.dense_flops / t_dense / 1e9, 1)}
+            for name in t_fused:
+                row["fused_2:4_%s_us" % name] = round(t_fused[name] * 1e3, 1)
+            row["speedup_2:4"] = round(t_dense / t_fused["greedy"], 3)
+            row["speedup_2:8"] = round(t_dense / t28, 3)
+            row["speedup_2:16"] = round(t_dense / t216, 3)
+            row["effective_tflops_2:4"] = round(L.dense_flops / t_fused["greedy"] / 1e9, 1)
+            row["hbm_floor_us"] = round(L.bytes_moved() / (HBM_PEAK_GBS * 1e9) * 1e6, 1)
+            table.append(row)
+        result["layers"] = table
+
+        # ---- prune pass: dense-shaped output, tensors too large for the 256 MB last-level cache, rotated
+        nelem = 256 * 112 * 112 * 64
+        srcs = [gpu(wl.laplace_with_zeros((nelem // 64, 64), 1e-3, 0.3, seed=9000 + i, dtype=wl.BF16)) for i in range(2)]
+        dsts = [torch.empty_like(s) for s in srcs]
+        lib = sdgp.binding.load()
+        import ctypes
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        k = [0]
+        prune = {}
+        for name, rk in rankers:
+            def f(rk=rk):
+                s, d = srcs[k[0] % 2], dsts[k[0] % 2]
+                k[0] += 1
+                rc = lib.sdgp_prune(ctypes.c_void_p(s.data_ptr()), s.shape[0], s.shape[1], sdgp.BF16, 2, 4, rk, 0,
+                                    ctypes.c_void_p(d.data_ptr()), None, None, stream)
+                assert rc == 0
+            ms = time_call(f, reps=20, warm=3)
+            prune[name] = {"us": round(ms * 1e3, 1), "GB/s": round(4.0 * nelem / (ms * 1e-3) / 1e9, 1),
+                           "frac_of_hbm_peak": round(4.0 * nelem / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        result["prune_pass"] = {"tensor": "[%d, 64] bf16 (411 MB), 2:4, dense-shaped output, 4 B per element" % (nelem // 64),
+                                **prune}
+        result["roofline_prune"] = {"bound": "hbm", "kernel": "prune_items (2:4 greedy)",
+                                    "achieved": prune["greedy"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": prune["greedy"]["frac_of_hbm_peak"], "traffic": None}
+        del srcs, dsts
+
+        # ---- the CPU oracle on a bounded sample of the same workload
+        if args.cpu_batch > 0:
+            import oracle
+            t_cpu, f_cpu = 0.0, 0.0
+            for i, L in enumerate(wl.resnet9_layers(args.cpu_batch)):
+                dO, W = wl.layer_inputs(L, 1e-3, 0.3, seed=2000 + i, dtype=wl.BF16)
+                c0 = time.perf_counter()
+                pruned = oracle.prune(dO, 2, 4, oracle.GREEDY, seed=0)[0]
+                oracle.conv_bwd_data(pruned, W, L.H, L.Wd, L.stride, L.pad)
+                t_cpu += time.perf_counter() - c0
+                f_cpu += L.dense_flops
+            result["cpu_baseline"] = {
+                "value": round(f_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s (effective)", "cores": oracle.threads(),
+                "kind": "oracle",
+                "sample": "the same six layers at batch %d, 2:4 greedy, prune + fp64 product, %.1f s" % (args.cpu_batch, t_cpu),
+            }
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
