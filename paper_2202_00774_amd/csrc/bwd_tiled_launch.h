@@ -16,7 +16,7 @@ int launch_tiled_one(const TiledParams& p, hipStream_t stream) {
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsPerCu);
     if (attr != hipSuccess) return SDGP_ERR_HIP;
-    hipLaunchKernelGGL(kern, dim3(p.nblocks), dim3(256), lds, stream, p);
+    hipLaunchKernelGGL(kern, dim3(p.nblocks), dim3(512), lds, stream, p);
     return launch_status();
 }
 

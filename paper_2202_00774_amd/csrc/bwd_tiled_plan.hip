@@ -108,28 +108,32 @@ int bwd_tiled_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t
     const int bn = (C_in > 64) ? 128 : 64;
     p.ntiles_n = ((int)C_in + bn - 1) / bn;
 
-    // ---- tile shape: minimise (matrix work + halo traffic) summed over classes, under the LDS budget.
-    // One workgroup should leave room for a second on the same CU when it can.
+    // ---- tile shape: minimise (matrix work + halo traffic) summed over classes, under the LDS budget
+    // (one workgroup of eight wavefronts per CU).
+    const int items_per_pix = (mode == 1 && m == 32) ? 2 : 4;
     double best = 1e300;
     int bTB = 0, bTH = 0, bTW = 0;
     const int maxH = std::max(p.cls[0].HH, 1), maxW = std::max(p.cls[0].WW, 1);
     for (int TH = 1; TH <= std::min(maxH, kTileRows); ++TH) {
         for (int TW = 1; TW <= std::min(maxW, kTileRows / TH); ++TW) {
-            const int TB = std::max(1, std::min((int)B, kTileRows / (TH * TW)));
-            double cost = 0;
-            int halo_max = 0;
-            for (int c = 0; c < p.nclass; ++c) {
-                const TileClass& cl = p.cls[c];
-                if (cl.HH <= 0 || cl.WW <= 0) continue;
-                const double tiles = (double)((B + TB - 1) / TB) * ((cl.HH + TH - 1) / TH) * ((cl.WW + TW - 1) / TW);
-                const int halo = TB * (TH + ct[c].dpmax - ct[c].dpmin) * (TW + ct[c].dqmax - ct[c].dqmin);
-                halo_max = std::max(halo_max, halo);
-                cost += tiles * (kTileRows * (double)ct[c].count * p.ntiles_n + 3.0 * halo * p.ntiles_n + 64.0);
+            const int tb_max = std::max(1, std::min((int)B, kTileRows / (TH * TW)));
+            // whole images per tile only pay off for small images; try the largest count and its halvings
+            for (int TB = tb_max; TB >= 1; TB = (TB > 1 ? TB / 2 : 0)) {
+                double cost = 0;
+                int halo_max = 0;
+                for (int c = 0; c < p.nclass; ++c) {
+                    const TileClass& cl = p.cls[c];
+                    if (cl.HH <= 0 || cl.WW <= 0) continue;
+                    const double tiles = (double)((B + TB - 1) / TB) * ((cl.HH + TH - 1) / TH) * ((cl.WW + TW - 1) / TW);
+                    const int halo = TB * (TH + ct[c].dpmax - ct[c].dpmin) * (TW + ct[c].dqmax - ct[c].dqmin);
+                    halo_max = std::max(halo_max, halo);
+                    cost += tiles * (kTileRows * (double)ct[c].count * p.ntiles_n + 3.0 * halo * p.ntiles_n + 64.0);
+                }
+                const int lds = lds_bytes(mode, bn, halo_max);
+                if (lds > 160 * 1024) continue;
+                if (halo_max * items_per_pix > 256 * kMaxHaloItems) continue;  // a producer lane holds at most that many
+                if (cost < best || (cost == best && TW > bTW)) best = cost, bTB = TB, bTH = TH, bTW = TW;
             }
-            const int lds = lds_bytes(mode, bn, halo_max);
-            if (lds > 160 * 1024) continue;
-            if (lds > 80 * 1024) cost *= 1.3;  // a lone workgroup per CU hides less latency
-            if (cost < best || (cost == best && TW > bTW)) best = cost, bTB = TB, bTH = TH, bTW = TW;
         }
     }
     if (bTB == 0) return 1;
