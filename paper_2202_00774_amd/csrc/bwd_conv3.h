@@ -19,8 +19,8 @@
 //   * Sparse (MODE 2): the raw halo streams through a ring of 4 batches (64 pixels each); the
 //     producers read a batch back from LDS three stages after requesting it, rank / prune /
 //     compress it (Sec. III-B) and write the compressed halo buffer of the next chunk.
-//   * Pixels outside the image are not zero-filled in LDS: the copy reads a clamped address
-//     and the consumer zeroes the fragment of an out-of-range (pixel, tap) in registers.
+//   * Pixels outside the image are copied from a 128-byte row of zeros in device memory, so the
+//     padding needs no arithmetic anywhere.
 #pragma once
 
 #include <type_traits>
@@ -44,6 +44,8 @@ struct Conv3Params {
     int nhalo, nunits;              // halo pixels, 8-pixel copy units
     int ntaps;
     int ntiles_n, nblocks;
+    int exp;                        // development aid: switches parts off (0 in normal use)
+    unsigned long long* trace;      // development aid: per-stage cycle stamps of workgroup 0 (NULL in normal use)
     TapEntry taps[kMaxTaps];
 };
 
@@ -64,13 +66,17 @@ struct Conv3Layout {
     __host__ __device__ static int off_w() { return 0; }
     __host__ __device__ static int off_sink() { return kC3Slots * kWSlab; }
     __host__ __device__ static int off_rowpix() { return off_sink() + 1024; }
-    __host__ __device__ static int off_raw() { return off_rowpix() + kTileRows * 4; }
-    __host__ __device__ static int off_a() { return off_raw() + (kSparse ? kC3RawSlots * kRawSlot : 0); }
+    __host__ __device__ static int off_halopix(int) { return off_rowpix() + kTileRows * 4; }
+    __host__ __device__ static int off_raw_h(int halo) { return off_halopix(halo) + pad8(halo) * 4; }
+    __host__ __device__ static int off_a_h(int halo) { return off_raw_h(halo) + (kSparse ? kC3RawSlots * kRawSlot : 0); }
     __host__ __device__ static int a_bytes(int halo) { return pad8(halo) * kAPitch; }
-    __host__ __device__ static int off_meta(int halo) { return off_a() + 2 * a_bytes(halo); }
+    __host__ __device__ static int off_meta(int halo) { return off_a_h(halo) + 2 * a_bytes(halo); }
     __host__ __device__ static int meta_bytes(int halo) { return kSparse ? pad8(halo) * kMetaPitch : 0; }
     __host__ __device__ static int total(int halo) { return off_meta(halo) + 2 * meta_bytes(halo); }
 };
+
+// 128 bytes of zeros in device memory: the source of halo pixels that lie outside the image.
+__device__ const uint32_t kZeroRow[32] = {0};
 
 // 16 bytes per lane from global memory straight into LDS: lane i lands at lds_base + 16*i.
 // The compiler does not see this as a memory instruction; callers count copies and wait with wait_copies.
@@ -87,12 +93,14 @@ __device__ __forceinline__ void wait_copies() {
 }
 
 template <int BN, int MODE, int M, int RK>
-__global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
+__global__ void __launch_bounds__(768) bwd_conv3(const Conv3Params p) {
     using L = Conv3Layout<BN, MODE>;
     constexpr bool SPARSE = MODE == 2;
     constexpr int KC = kC3KC;
+    // 8 consumer wavefronts (two per SIMD, so one wave's LDS reads and address arithmetic issue while the
+    // other's matrix instructions execute) and 4 producer wavefronts
     constexpr int WAVES_N = BN / 64;
-    constexpr int WAVES_M = 4 / WAVES_N;
+    constexpr int WAVES_M = 8 / WAVES_N;
     constexpr int WM = kTileRows / WAVES_M;
     constexpr int TM = WM / 32;
     constexpr int TN = 2;
@@ -110,10 +118,14 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool producer = wave >= 4;
-    const int cw = wave & 3;
+    const bool producer = wave >= 8;
+    const int cw = producer ? wave - 8 : wave;  // index inside the role
     const int wm = cw / WAVES_N, wn = cw % WAVES_N;
-    const int ptid = tid & 255;
+    const int ptid = tid - 512;                 // producers: 0..255
+    auto stamp = [&](int i) {
+        if (p.trace && blockIdx.x == 0 && (tid == 0 || tid == 512) && i < 128) p.trace[(tid >> 9) * 128 + i] = clock64();
+    };
+    stamp(0);
 
     int lid = blockIdx.x;
     {
@@ -136,9 +148,9 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
 
     SDGP_LDS int* rowpix = (SDGP_LDS int*)(smem + L::off_rowpix());
     SDGP_LDS unsigned char* lds_w = smem + L::off_w();
-    SDGP_LDS unsigned char* lds_a = smem + L::off_a();
+    SDGP_LDS unsigned char* lds_a = smem + L::off_a_h(p.nhalo);
     SDGP_LDS unsigned char* lds_meta = smem + L::off_meta(p.nhalo);
-    SDGP_LDS unsigned char* lds_raw = smem + L::off_raw();
+    SDGP_LDS unsigned char* lds_raw = smem + L::off_raw_h(p.nhalo);
     const int a_buf_bytes = L::a_bytes(p.nhalo), meta_buf_bytes = L::meta_bytes(p.nhalo);
 
     if (tid < kTileRows) {
@@ -176,33 +188,52 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
     if (producer) {
         // =============================================================== producers
         const int pw = cw;
-        // W: copy unit uu of the slab of stage q into ring slot q % 4
-        auto copy_w = [&](int q) {
-            if (q >= nstages) q = nstages - 1;  // a free slot receives valid data nobody reads: the count stays exact
-            const int chunk = q / ntaps, ti = q - chunk * ntaps;
-            const int woff = p.taps[ti].woff;
-            const uint32_t slot = smem_base + L::off_w() + (uint32_t)(q & (kC3Slots - 1)) * L::kWSlab;
+        __builtin_amdgcn_s_setprio(3);  // few, short instructions: let them through ahead of the matrix waves
+        // Loop-invariant values live in registers: nothing below reads the kernel arguments again.
+        const uint16_t* const gW = p.W;
+        const uint16_t* const gdO = p.dO;
+        const int c_out = p.C_out, w_row = p.w_row, nunits = p.nunits, nhalo = p.nhalo;
+        int my_woff = 0;                       // lane ti holds the W offset of tap ti (fetched with readlane)
+        if (lane < ntaps) my_woff = p.taps[lane].woff;
+        // per-lane W column (swizzled chunk) and row of each copy unit this wavefront owns
+        int w_lane_off[WPW];
 #pragma unroll
-            for (int i = 0; i < WPW; ++i) {
-                const int uu = pw * WPW + i;
-                const int row = uu * RPU + lane / CPR;
-                const int lchunk = (lane % CPR) ^ (2 * (row & 3));
-                int col = n0 + lchunk * 8;
-                if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
-                copy16_to_lds(p.W + (size_t)(chunk * KC + row) * p.w_row + woff + col, slot + uu * 1024);
-            }
+        for (int i = 0; i < WPW; ++i) {
+            const int uu = pw * WPW + i;
+            const int row = uu * RPU + lane / CPR;
+            const int lchunk = (lane % CPR) ^ (2 * (row & 3));
+            int col = n0 + lchunk * 8;
+            if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
+            w_lane_off[i] = row * w_row + col;
+        }
+        // halo position -> flat gradient pixel (clamped into the tensor), kept in LDS for the whole kernel
+        SDGP_LDS int* halopix = (SDGP_LDS int*)(smem + L::off_halopix(p.nhalo));
+        for (int hp = ptid; hp < L::pad8(nhalo); hp += 256) {
+            bool ok;
+            const int gp = halo_pixel(hp, ok);
+            halopix[hp] = ok ? gp : -1;
+        }
+
+        // W: the slab of stage (chunk, ti) into ring slot `slot`
+        auto copy_w = [&](int chunk, int ti, int slot) {
+            const int woff = __builtin_amdgcn_readlane(my_woff, ti);
+            const uint16_t* src = gW + (size_t)chunk * KC * w_row + woff;
+            const uint32_t dst = smem_base + L::off_w() + (uint32_t)slot * L::kWSlab + pw * WPW * 1024;
+#pragma unroll
+            for (int i = 0; i < WPW; ++i) copy16_to_lds(src + w_lane_off[i], dst + i * 1024);
         };
         // halo: copy unit u (8 pixels x 128 B of `chunk`) to LDS address dst (+ lane*16)
         auto copy_halo_unit = [&](int u, int chunk, uint32_t dst, bool dense_swizzle) {
             const int hp = u * 8 + (lane >> 3);
-            bool ok;
-            const int gp = halo_pixel(hp, ok);
+            const int gp = halopix[hp];
             int c16 = lane & 7;
             if (dense_swizzle) c16 ^= (hp >> 1) & 7;
             else c16 ^= (lane >> 3);
-            copy16_to_lds(p.dO + (size_t)gp * p.C_out + chunk * KC + c16 * 8, dst);
+            const uint16_t* src = gdO + (size_t)(gp < 0 ? 0 : gp) * c_out + chunk * KC + c16 * 8;
+            if (gp < 0) src = reinterpret_cast<const uint16_t*>(kZeroRow) + c16 * 8;  // outside the image: zeros
+            copy16_to_lds(src, dst);
         };
-        auto copy_sink = [&]() { copy16_to_lds(p.W + lane * 8, smem_base + L::off_sink()); };
+        auto copy_sink = [&]() { copy16_to_lds(gW + lane * 8, smem_base + L::off_sink()); };
 
         // prune one raw batch (already in LDS slot `rslot`) into the compressed halo buffer of `chunk`
         auto prune_batch = [&](int batch, int chunk, int rslot, int units_per_batch) {
@@ -210,24 +241,23 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
                 const int unit = ptid >> 5, px = (ptid >> 2) & 7, part = ptid & 3;
                 const int u = batch * units_per_batch + unit;
                 const int hp = u * 8 + px;
-                bool ok;
-                const int gp = halo_pixel(hp, ok);
-                if (unit < units_per_batch && u < p.nunits && hp < p.nhalo) {
+                if (unit < units_per_batch && u < nunits && hp < nhalo) {
+                    const int gp = max(halopix[hp], 0);  // an outside pixel is all zeros: any index gives zeros
                     SDGP_LDS unsigned char* src = lds_raw + rslot * L::kRawSlot + unit * 1024 + px * 128;
                     u32x4_t v[2];
                     v[0] = *(SDGP_LDS u32x4_t*)(src + (((2 * part) ^ px) * 16));
                     v[1] = *(SDGP_LDS u32x4_t*)(src + (((2 * part + 1) ^ px) * 16));
-                    const uint64_t e0 = (uint64_t)gp * (uint64_t)p.C_out + (uint64_t)(chunk * KC + part * 16);
+                    const uint64_t e0 = (uint64_t)gp * (uint64_t)c_out + (uint64_t)(chunk * KC + part * 16);
                     halo_item_to_lds<KC, MODE, M, RK, 16>(v, hp, part, e0, p.n, p.mix, lds_a + (chunk & 1) * a_buf_bytes,
                                                           lds_meta + (chunk & 1) * meta_buf_bytes);
                 }
             }
         };
+        __syncthreads();  // halopix visible to all producers (the consumers join this barrier too)
 
-        // ---- prologue: W stages 0..2 requested; first chunk's halo brought in synchronously
+        // ---- prologue: first chunk's halo brought in synchronously
         if constexpr (MODE == 0) {
-            for (int u = pw; u < p.nunits; u += 4)
-                copy_halo_unit(u, 0, smem_base + L::off_a() + u * 1024, true);
+            for (int u = pw; u < nunits; u += 4) copy_halo_unit(u, 0, smem_base + L::off_a_h(p.nhalo) + u * 1024, true);
             wait_copies<0>();
             __syncthreads();
         } else {
@@ -235,7 +265,7 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
 #pragma unroll
                 for (int j = 0; j < HPW; ++j) {
                     const int u = r * kC3UnitsPerStep + pw * HPW + j;
-                    copy_halo_unit(u < p.nunits ? u : 0, 0, smem_base + L::off_raw() + (pw * HPW + j) * 1024, false);
+                    copy_halo_unit(u < nunits ? u : 0, 0, smem_base + L::off_raw_h(p.nhalo) + (pw * HPW + j) * 1024, false);
                 }
                 wait_copies<0>();
                 __syncthreads();
@@ -243,66 +273,67 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
                 __syncthreads();
             }
         }
-        // steady-state schedule: at stage g request W of stage g+3 and the raw batch / halo units of stage g+3
-        const int nb = SPARSE ? ntaps - 1 : ntaps - 3;                   // stages of a chunk that carry halo work
-        const int upb = (p.nunits + nb - 1) / nb;                        // units per batch (<= 8, host-checked)
-        auto issue = [&](int g) {  // everything that is requested "at stage g" (g may be negative in the prologue)
-            copy_w(g + 3);
-            const int gh = g + 3;  // the stage at which this halo batch is consumed (sparse) / slot index (dense)
+        // Steady-state schedule.  "Issuing for stage g" requests the W slab of stage g+3 and the halo work tied to
+        // stage g+3 (sparse: the raw batch that is pruned during stage g+3; dense: the units of window stage g).
+        // (wc, wt) = (chunk, tap) of stage g+3; (gc, gt) = (chunk, tap) of stage g.  Both advance by one per issue.
+        const int nb = SPARSE ? ntaps - 1 : ntaps - 3;  // stages of a chunk that carry halo work
+        const int upb = (nunits + nb - 1) / nb;          // units per batch (<= 8, host-checked)
+        int wc = 0, wt = 0, wslot = 0;                   // stage g+3, starting at stage 0 for g = -3
+        int gc = 0, gt = 0;                              // stage g, valid once g >= 0
+        auto issue = [&](bool g_valid) {
+            // stages past the end re-copy the last slab into a slot nobody reads: the copy count stays exact
+            const bool w_live = wc < nchunks;
+            copy_w(w_live ? wc : nchunks - 1, w_live ? wt : ntaps - 1, wslot);
 #pragma unroll
             for (int j = 0; j < HPW; ++j) {
                 const int unit = pw * HPW + j;
                 bool real = false;
                 if constexpr (SPARSE) {
-                    const int chunk = gh / ntaps, b = gh - chunk * ntaps;  // pruned at stage gh into buffer of chunk+1
-                    const int u = b * upb + unit;
-                    real = gh >= 0 && gh < nstages && b < nb && chunk + 1 < nchunks && unit < upb && u < p.nunits;
-                    if (real)
-                        copy_halo_unit(u, chunk + 1, smem_base + L::off_raw() + (gh & (kC3RawSlots - 1)) * L::kRawSlot + unit * 1024, false);
+                    const int u = wt * upb + unit;       // batch wt of chunk wc+1 is pruned during stage (wc, wt)
+                    real = w_live && wt < nb && wc + 1 < nchunks && unit < upb && u < nunits;
+                    if (real) copy_halo_unit(u, wc + 1, smem_base + L::off_raw_h(p.nhalo) + wslot * L::kRawSlot + unit * 1024, false);
                 } else {
-                    const int chunk = g / ntaps, ti = g - chunk * ntaps;   // dense: straight into the next chunk's buffer
-                    const int u = ti * kC3UnitsPerStep + unit;
-                    real = g >= 0 && g < nstages && ti < nb && chunk + 1 < nchunks && u < p.nunits;
-                    if (real)
-                        copy_halo_unit(u, chunk + 1, smem_base + L::off_a() + ((chunk + 1) & 1) * a_buf_bytes + u * 1024, true);
+                    const int u = gt * kC3UnitsPerStep + unit;  // dense: straight into the next chunk's buffer
+                    real = g_valid && gc < nchunks && gt < nb && gc + 1 < nchunks && u < nunits;
+                    if (real) copy_halo_unit(u, gc + 1, smem_base + L::off_a_h(p.nhalo) + ((gc + 1) & 1) * a_buf_bytes + u * 1024, true);
                 }
                 if (!real) copy_sink();
             }
+            if (++wt == ntaps) wt = 0, ++wc;
+            wslot = (wslot + 1) & (kC3Slots - 1);
+            if (g_valid && ++gt == ntaps) gt = 0, ++gc;
         };
-        issue(-3);
-        issue(-2);
-        issue(-1);
+        static_assert(kC3Slots == kC3RawSlots, "the W ring and the raw halo ring advance together");
+        issue(false);
+        issue(false);
+        issue(false);
         wait_copies<0>();
+        stamp(1);
         __syncthreads();
+        stamp(2);
 
         for (int g = 0; g < nstages; ++g) {
-            issue(g);
+            const int pc = gc, pt = gt;  // (chunk, tap) of stage g, before issue() advances them
+            issue(true);
             if constexpr (SPARSE) {
-                const int chunk = g / ntaps, b = g - chunk * ntaps;
-                if (b < nb && chunk + 1 < nchunks) prune_batch(b, chunk + 1, g & (kC3RawSlots - 1), upb);
+                if (pt < nb && pc + 1 < nchunks) prune_batch(pt, pc + 1, g & (kC3RawSlots - 1), upb);
             }
+            stamp(3 + 2 * g);
             wait_copies<2 * kPer>();
             __syncthreads();
+            stamp(4 + 2 * g);
         }
     } else {
         // =============================================================== consumers
         // per-lane row data: halo position and the set of taps that fall inside the image
-        int rowbase[TM];
-        uint64_t tapmask[TM];
+        int rowbase[TM];  // halo position of each of this lane's rows (tap offsets are added per stage)
 #pragma unroll
         for (int t = 0; t < TM; ++t) {
             const int m = wm * WM + t * 32 + (lane & 31);
             rowbase[t] = 0;
-            tapmask[t] = 0;
             if (m < tile_rows) {
                 const int tb = m / tile_hw, rem = m % tile_hw;
-                const int th = rem / p.TW, tw = rem % p.TW;
-                rowbase[t] = (tb * p.HTH + th) * p.HTW + tw;
-                const int b = b0 + tb, hh = hh0 + th, ww = ww0 + tw;
-                for (int ti = 0; ti < ntaps; ++ti) {
-                    const int pp = hh + p.taps[ti].dp, qq = ww + p.taps[ti].dq;
-                    if (b < p.B && pp >= 0 && pp < p.P && qq >= 0 && qq < p.Q) tapmask[t] |= 1ull << ti;
-                }
+                rowbase[t] = (tb * p.HTH + rem / p.TW) * p.HTW + rem % p.TW;
             }
         }
         int my_tap_off = 0;
@@ -317,6 +348,7 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
             b_lane[u] = (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (2 * (L16 >> 2))) * 16) + (L16 & 1) * 8;
         }
 
+        __syncthreads();  // producers' halo table
         if constexpr (MODE == 0) {
             __syncthreads();
         } else {
@@ -325,10 +357,12 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
                 __syncthreads();
             }
         }
+        stamp(1);
         __syncthreads();  // end of the producers' prologue
+        stamp(2);
 
         struct Frags {
-            bf16x8_t a[TM];
+            u32x4_t a[TM];
             int meta[TM];
             typename std::conditional<SPARSE, bf16x16_t, bf16x8_t>::type b[TN];
         };
@@ -348,9 +382,7 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
                     const int c16 = (ks * 2 + (lane >> 5)) ^ ((hp >> 1) & 7);
                     araw = *(SDGP_LDS u32x4_t*)(abuf + hp * 128 + c16 * 16);
                 }
-                const bool inside = (tapmask[t] >> ti) & 1ull;
-                if (!inside) araw = u32x4_t{0u, 0u, 0u, 0u};
-                f.a[t] = __builtin_bit_cast(bf16x8_t, araw);
+                f.a[t] = araw;
             }
             if constexpr (SPARSE) {
 #pragma unroll
@@ -380,14 +412,17 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
             }
         };
         auto mma = [&](const Frags& f) {
+            bf16x8_t a[TM];
+#pragma unroll
+            for (int t = 0; t < TM; ++t) a[t] = __builtin_bit_cast(bf16x8_t, f.a[t]);
 #pragma unroll
             for (int t = 0; t < TM; ++t)
 #pragma unroll
                 for (int u = 0; u < TN; ++u) {
                     if constexpr (SPARSE)
-                        acc[t][u] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(f.a[t], f.b[u], acc[t][u], f.meta[t], 0, 0);
+                        acc[t][u] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[t], f.b[u], acc[t][u], f.meta[t], 0, 0);
                     else
-                        acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[t], f.b[u], acc[t][u], 0, 0, 0);
+                        acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], f.b[u], acc[t][u], 0, 0, 0);
                 }
         };
 
@@ -404,15 +439,22 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
             const bool has_next = s + 1 < nstages;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
+                // keep the order "request the next fragments, then issue this k-step's matrix instructions":
+                // the reads then have a whole k-step of matrix work to land behind
                 if (ks + 1 < NKS) load_frags(fr[(ks + 1) & 1], slot, chunk, ti, ks + 1);
                 else if (has_next) load_frags(fr[0], nslot, nchunk, nti, 0);
+                __builtin_amdgcn_sched_barrier(0);
                 mma(fr[ks & 1]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            stamp(3 + 2 * s);
             __syncthreads();
+            stamp(4 + 2 * s);
             ti = nti, chunk = nchunk;
         }
     }
 
+    stamp(126);
     // ---- epilogue (consumers): fp32 -> bf16 (RNE), NHWC store
     if (!producer) {
 #pragma unroll
@@ -430,6 +472,7 @@ __global__ void __launch_bounds__(512) bwd_conv3(const Conv3Params p) {
             }
         }
     }
+    stamp(127);
 }
 
 }  // namespace sdgp
