@@ -8,6 +8,9 @@ int prune_launch(const void* dO, int64_t total, int dt, int n, int m, int rk, ui
 int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                       int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed,
                       hipStream_t stream);
+int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                      int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
+                      hipStream_t stream);
 int bwd_conv3_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                      int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                      hipStream_t stream);
@@ -65,6 +68,10 @@ int check_conv(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, in
 // Matrix-core kernel when the problem fits it, the shape-agnostic kernel otherwise.
 int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                  int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
+    if (dt == SDGP_BF16 && C_in <= 4) {
+        const int rc = sdgp::bwd_narrow_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
+        if (rc <= 0) return rc;
+    }
     if (dt == SDGP_BF16 && sdgp::is_aligned16(dD)) {
         int rc = sdgp::bwd_conv3_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
         if (rc <= 0) return rc;

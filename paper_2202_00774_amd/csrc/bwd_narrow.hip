@@ -1,0 +1,201 @@
+// Backward-data for layers with very few input channels (C_in <= 4: the first convolution of a network).
+//
+// With three columns the product is not matrix-core work: it is bound by reading dL/dO once.  A workgroup owns a
+// TH x TW tile of input pixels of one image.  It brings every gradient pixel its taps can reach into LDS once,
+// pruning each m-group with the register ranker on the way (Sec. III-B; stored dense with zeros), converts the
+// filter to fp32 in LDS, and then every thread accumulates its own pixel over taps and channels on the vector
+// ALU (Fig. 3 left, any filter size, stride and padding).  bf16 storage, fp32 accumulation.
+#include "ranker.h"
+
+namespace sdgp {
+
+namespace {
+
+constexpr int kNarrowKC = 64;  // output channels per pass through LDS
+typedef uint32_t u32x4n __attribute__((ext_vector_type(4)));
+typedef float f32x4n __attribute__((ext_vector_type(4)));
+#define SDGP_LDSN __attribute__((address_space(3)))
+
+struct NarrowParams {
+    const uint16_t* dO;
+    const uint16_t* W;
+    uint16_t* dD;
+    int B, H, Wd, P, Q, C_in, C_out, R, S, stride, pad;
+    int TH, TW, tiles_h, tiles_w;
+    int HP, HQ;  // gradient pixels per tile (rows, columns), upper bound
+    int n;
+    uint32_t mix;
+};
+
+constexpr int kAPitchN = kNarrowKC * 2 + 16;  // bytes per gradient pixel in LDS (padded against bank conflicts)
+
+template <int M, int RK, bool PRUNE, bool NLE2>
+__global__ void __launch_bounds__(256) bwd_narrow(const NarrowParams p) {
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    SDGP_LDSN unsigned char* smem = (SDGP_LDSN unsigned char*)smem_generic;
+    const int tid = threadIdx.x;
+    const int tile = blockIdx.x;
+    const int tw_i = tile % p.tiles_w, th_i = (tile / p.tiles_w) % p.tiles_h, b = tile / (p.tiles_w * p.tiles_h);
+    const int h0 = th_i * p.TH, w0 = tw_i * p.TW;
+    // gradient rows/columns the tile's taps can reach: p = (h + pad - r) / stride
+    const int lo_h = h0 + p.pad - (p.R - 1), lo_w = w0 + p.pad - (p.S - 1);
+    const int pmin = lo_h <= 0 ? 0 : (lo_h + p.stride - 1) / p.stride;
+    const int qmin = lo_w <= 0 ? 0 : (lo_w + p.stride - 1) / p.stride;
+    const int npix = p.HP * p.HQ;
+
+    SDGP_LDSN unsigned char* lds_a = smem;                                        // [npix][kAPitchN]
+    SDGP_LDSN f32x4n* lds_w = (SDGP_LDSN f32x4n*)(smem + ((npix * kAPitchN + 15) & ~15));  // [KC][R*S] x 4 floats
+
+    const int th = tid / p.TW, tw = tid % p.TW;
+    const int h = h0 + th, w = w0 + tw;
+    const bool live = tid < p.TH * p.TW && h < p.H && w < p.Wd;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const int taps = p.R * p.S;
+
+    for (int kc0 = 0; kc0 < p.C_out; kc0 += kNarrowKC) {
+        __syncthreads();
+        // ---- gradient halo, pruned, into LDS (16 channels per item)
+        for (int it = tid; it < npix * (kNarrowKC / 16); it += 256) {
+            const int hp = it >> 2, part = it & 3;
+            const int pp = pmin + hp / p.HQ, qq = qmin + hp % p.HQ;
+            const int k = kc0 + part * 16;
+            u32x4n v[2] = {u32x4n{0u, 0u, 0u, 0u}, u32x4n{0u, 0u, 0u, 0u}};
+            const bool ok = pp < p.P && qq < p.Q;
+            const size_t gp = ok ? ((size_t)(b * p.P + pp) * p.Q + qq) : 0;
+            if (ok) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    if (k + i * 8 < p.C_out)
+                        v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4n*>(p.dO + gp * p.C_out + k + i * 8));
+            }
+            if constexpr (PRUNE) {
+                uint32_t raw[16], out[16];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
+                        raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
+                    }
+                const uint64_t e0 = (uint64_t)gp * (uint64_t)p.C_out + (uint64_t)k;
+#pragma unroll
+                for (int g = 0; g < 16 / M; ++g) {
+                    uint32_t r[M], o[M];
+                    bool kk[M];
+#pragma unroll
+                    for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
+                    const uint64_t eg = e0 + (uint64_t)(g * M);
+                    prune_group<kBF16, M, RK, NLE2>(r, p.n, hash_row(p.mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+#pragma unroll
+                    for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) v[i][x] = out[i * 8 + 2 * x] | (out[i * 8 + 2 * x + 1] << 16);
+            }
+            *(SDGP_LDSN u32x4n*)(lds_a + hp * kAPitchN + part * 32) = v[0];
+            *(SDGP_LDSN u32x4n*)(lds_a + hp * kAPitchN + part * 32 + 16) = v[1];
+        }
+        // ---- filter slice [kc0, kc0+64) x taps x C_in -> fp32, four floats per (k, tap)
+        for (int it = tid; it < kNarrowKC * taps; it += 256) {
+            const int kk = it / taps, t = it % taps;
+            f32x4n wv = {0.f, 0.f, 0.f, 0.f};
+            if (kc0 + kk < p.C_out)
+                for (int c = 0; c < p.C_in; ++c)
+                    wv[c] = bf16_to_float(p.W[((size_t)(kc0 + kk) * taps + t) * p.C_in + c]);
+            lds_w[it] = wv;
+        }
+        __syncthreads();
+
+        if (live) {
+            for (int r = 0; r < p.R; ++r) {
+                const int hr = h + p.pad - r;
+                if (hr < 0 || hr % p.stride != 0) continue;
+                const int pp = hr / p.stride;
+                if (pp >= p.P) continue;
+                for (int s = 0; s < p.S; ++s) {
+                    const int ws = w + p.pad - s;
+                    if (ws < 0 || ws % p.stride != 0) continue;
+                    const int qq = ws / p.stride;
+                    if (qq >= p.Q) continue;
+                    const int hp = (pp - pmin) * p.HQ + (qq - qmin);
+                    const int t = r * p.S + s;
+#pragma unroll
+                    for (int c8 = 0; c8 < kNarrowKC / 8; ++c8) {
+                        const u32x4n a = *(SDGP_LDSN u32x4n*)(lds_a + hp * kAPitchN + c8 * 16);
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            const float lo = __uint_as_float(a[x] << 16), hi = __uint_as_float(a[x] & 0xFFFF0000u);
+                            const f32x4n w0v = lds_w[(c8 * 8 + 2 * x) * taps + t];
+                            const f32x4n w1v = lds_w[(c8 * 8 + 2 * x + 1) * taps + t];
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) acc[c] = fmaf(lo, w0v[c], fmaf(hi, w1v[c], acc[c]));
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (live) {
+        uint16_t* dst = p.dD + ((size_t)(b * p.H + h) * p.Wd + w) * p.C_in;
+        for (int c = 0; c < p.C_in; ++c) dst[c] = (uint16_t)float_to_bf16(acc[c]);
+    }
+}
+
+template <int M, bool NLE2>
+int launch_narrow_rk(const NarrowParams& p, int rk, int grid, int lds, hipStream_t stream) {
+#define SDGP_NARROW(RKV)                                                                                              \
+    {                                                                                                                 \
+        auto kern = bwd_narrow<M, RKV, true, NLE2>;                                                                   \
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);   \
+        if (attr != hipSuccess) return SDGP_ERR_HIP;                                                                  \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, p);                                              \
+    }
+    if (rk == kRandom) SDGP_NARROW(kRandom)
+    else if (rk == kGreedy) SDGP_NARROW(kGreedy)
+    else SDGP_NARROW(kAdjusted)
+#undef SDGP_NARROW
+    return launch_status();
+}
+
+}  // namespace
+
+// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
+int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                      int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
+                      hipStream_t stream) {
+    if (C_in < 1 || C_in > 4 || (C_out % 8) != 0 || !is_aligned16(dO)) return 1;
+    const bool dense = n == m;
+    if (!dense && !(m == 4 || m == 8 || m == 16)) return 1;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    if (B * P * Q >= INT32_MAX || B * H * Wd >= INT32_MAX) return 1;
+    NarrowParams p{};
+    p.dO = static_cast<const uint16_t*>(dO), p.W = static_cast<const uint16_t*>(W), p.dD = static_cast<uint16_t*>(dD);
+    p.B = (int)B, p.H = (int)H, p.Wd = (int)Wd, p.P = (int)P, p.Q = (int)Q, p.C_in = (int)C_in, p.C_out = (int)C_out;
+    p.R = R, p.S = S, p.stride = stride, p.pad = pad, p.n = n, p.mix = seed_mix(seed);
+    p.TW = (int)(Wd < 16 ? Wd : 16);
+    p.TH = (int)(H < 256 / p.TW ? H : 256 / p.TW);
+    p.tiles_h = ((int)H + p.TH - 1) / p.TH, p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
+    p.HP = (p.TH - 1 + R - 1) / stride + 2, p.HQ = (p.TW - 1 + S - 1) / stride + 2;
+    const int64_t grid = (int64_t)B * p.tiles_h * p.tiles_w;
+    if (grid >= INT32_MAX) return 1;
+    const int lds = ((p.HP * p.HQ * kAPitchN + 15) & ~15) + kNarrowKC * R * S * 16;
+    if (lds > 160 * 1024) return 1;
+    if (grid == 0) return SDGP_OK;
+    if (dense) {
+        auto kern = bwd_narrow<4, kGreedy, false, true>;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr != hipSuccess) return SDGP_ERR_HIP;
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, stream, p);
+        return launch_status();
+    }
+    const bool nle2 = n <= 2;
+    if (m == 4) return nle2 ? launch_narrow_rk<4, true>(p, rk, (int)grid, lds, stream) : launch_narrow_rk<4, false>(p, rk, (int)grid, lds, stream);
+    if (m == 8) return nle2 ? launch_narrow_rk<8, true>(p, rk, (int)grid, lds, stream) : launch_narrow_rk<8, false>(p, rk, (int)grid, lds, stream);
+    return nle2 ? launch_narrow_rk<16, true>(p, rk, (int)grid, lds, stream) : launch_narrow_rk<16, false>(p, rk, (int)grid, lds, stream);
+}
+
+}  // namespace sdgp
