@@ -53,6 +53,10 @@ constexpr int kC3KC = 64;           // reduction channels per chunk
 constexpr int kC3Slots = 4;         // W ring
 constexpr int kC3RawSlots = 4;      // raw halo ring (sparse)
 constexpr int kC3UnitsPerStep = 8;  // halo copy units (8 pixels x 128 B) per stage
+#ifndef SDGP_C3_CONSUMERS
+#define SDGP_C3_CONSUMERS 8
+#endif
+constexpr int kC3Consumers = SDGP_C3_CONSUMERS;  // matrix wavefronts per workgroup (4 producers follow them)
 
 template <int BN, int MODE>
 struct Conv3Layout {
@@ -93,14 +97,14 @@ __device__ __forceinline__ void wait_copies() {
 }
 
 template <int BN, int MODE, int M, int RK>
-__global__ void __launch_bounds__(768) bwd_conv3(const Conv3Params p) {
+__global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3Params p) {
     using L = Conv3Layout<BN, MODE>;
     constexpr bool SPARSE = MODE == 2;
     constexpr int KC = kC3KC;
     // 8 consumer wavefronts (two per SIMD, so one wave's LDS reads and address arithmetic issue while the
     // other's matrix instructions execute) and 4 producer wavefronts
     constexpr int WAVES_N = BN / 64;
-    constexpr int WAVES_M = 8 / WAVES_N;
+    constexpr int WAVES_M = kC3Consumers / WAVES_N;
     constexpr int WM = kTileRows / WAVES_M;
     constexpr int TM = WM / 32;
     constexpr int TN = 2;
@@ -118,12 +122,12 @@ __global__ void __launch_bounds__(768) bwd_conv3(const Conv3Params p) {
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool producer = wave >= 8;
-    const int cw = producer ? wave - 8 : wave;  // index inside the role
+    const bool producer = wave >= kC3Consumers;
+    const int cw = producer ? wave - kC3Consumers : wave;  // index inside the role
     const int wm = cw / WAVES_N, wn = cw % WAVES_N;
-    const int ptid = tid - 512;                 // producers: 0..255
+    const int ptid = tid - kC3Consumers * 64;   // producers: 0..255
     auto stamp = [&](int i) {
-        if (p.trace && blockIdx.x == 0 && (tid == 0 || tid == 512) && i < 128) p.trace[(tid >> 9) * 128 + i] = clock64();
+        if (p.trace && blockIdx.x == 0 && (tid == 0 || tid == kC3Consumers * 64) && i < 128) p.trace[(tid ? 1 : 0) * 128 + i] = clock64();
     };
     stamp(0);
 
@@ -370,6 +374,9 @@ __global__ void __launch_bounds__(768) bwd_conv3(const Conv3Params p) {
             const int tap_off = __builtin_amdgcn_readlane(my_tap_off, ti);
             SDGP_LDS unsigned char* wbuf = lds_w + slot * L::kWSlab;
             SDGP_LDS unsigned char* abuf = lds_a + (chunk & 1) * a_buf_bytes;
+#ifdef SDGP_TRACE
+            if (!(p.exp & 8))
+#endif
 #pragma unroll
             for (int t = 0; t < TM; ++t) {
                 const int hp = rowbase[t] + tap_off;
@@ -398,6 +405,15 @@ __global__ void __launch_bounds__(768) bwd_conv3(const Conv3Params p) {
                     f.b[u] = __builtin_bit_cast(bf16x16_t, all);
                 }
             } else {
+#ifdef SDGP_TRACE
+                if (p.exp & 16) return;
+                if (p.exp & 4) {
+#pragma unroll
+                    for (int u = 0; u < TN; ++u)
+                        f.b[u] = __builtin_bit_cast(bf16x8_t, *(SDGP_LDS u32x4_t*)(wbuf + (lane & 31) * 128 + (((lane >> 5) + ks * 2) ^ (lane & 7)) * 16 + u * 4096));
+                    return;
+                }
+#endif
 #pragma unroll
                 for (int u = 0; u < TN; ++u) {
                     s16x4_t q[2];
