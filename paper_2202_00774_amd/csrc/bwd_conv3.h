@@ -56,7 +56,11 @@ constexpr int kC3UnitsPerStep = 8;  // halo copy units (8 pixels x 128 B) per st
 #ifndef SDGP_C3_CONSUMERS
 #define SDGP_C3_CONSUMERS 8
 #endif
-constexpr int kC3Consumers = SDGP_C3_CONSUMERS;  // matrix wavefronts per workgroup (4 producers follow them)
+constexpr int kC3Consumers = SDGP_C3_CONSUMERS;  // matrix wavefronts per workgroup (the producers follow them)
+// Producer wavefronts: copies alone need few instructions, ranking a halo needs many, and one wavefront issues
+// at most one instruction every four cycles -- so the pruning kernels get two producers per SIMD.
+__host__ __device__ constexpr int conv3_producers(int mode) { return mode == 2 ? 8 : 4; }
+__host__ __device__ constexpr int conv3_threads(int mode) { return (kC3Consumers + conv3_producers(mode)) * 64; }
 
 template <int BN, int MODE>
 struct Conv3Layout {
@@ -97,7 +101,7 @@ __device__ __forceinline__ void wait_copies() {
 }
 
 template <int BN, int MODE, int M, int RK>
-__global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3Params p) {
+__global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Params p) {
     using L = Conv3Layout<BN, MODE>;
     constexpr bool SPARSE = MODE == 2;
     constexpr int KC = kC3KC;
@@ -111,8 +115,10 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
     constexpr int KSTEP = SPARSE ? 32 : 16;
     constexpr int NKS = KC / KSTEP;
     constexpr int W_UNITS = L::kWSlab / 1024;          // 1 KB copy units per slab
-    constexpr int WPW = W_UNITS / 4;                   // per producer wavefront
-    constexpr int HPW = kC3UnitsPerStep / 4;           // halo units per producer wavefront per stage
+    constexpr int NP = conv3_producers(MODE);          // producer wavefronts
+    constexpr int WPW = W_UNITS / NP;                  // per producer wavefront
+    constexpr int HPW = kC3UnitsPerStep / NP;          // halo units per producer wavefront per stage
+    static_assert(WPW >= 1 && HPW >= 1 && WPW * NP == W_UNITS && HPW * NP == kC3UnitsPerStep, "copy units divide evenly");
     constexpr int kPer = WPW + HPW;                    // copies a producer wavefront issues per stage
     constexpr int CPR = BN / 8;                        // 16-byte chunks per W row
     constexpr int RPU = 1024 / L::kWRow;               // W rows per copy unit
@@ -125,7 +131,7 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
     const bool producer = wave >= kC3Consumers;
     const int cw = producer ? wave - kC3Consumers : wave;  // index inside the role
     const int wm = cw / WAVES_N, wn = cw % WAVES_N;
-    const int ptid = tid - kC3Consumers * 64;   // producers: 0..255
+    const int ptid = tid - kC3Consumers * 64;   // producers: 0 .. NP*64-1
     auto stamp = [&](int i) {
         if (p.trace && blockIdx.x == 0 && (tid == 0 || tid == kC3Consumers * 64) && i < 128) p.trace[(tid ? 1 : 0) * 128 + i] = clock64();
     };
@@ -212,7 +218,7 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
         }
         // halo position -> flat gradient pixel (clamped into the tensor), kept in LDS for the whole kernel
         SDGP_LDS int* halopix = (SDGP_LDS int*)(smem + L::off_halopix(p.nhalo));
-        for (int hp = ptid; hp < L::pad8(nhalo); hp += 256) {
+        for (int hp = ptid; hp < L::pad8(nhalo); hp += NP * 64) {
             bool ok;
             const int gp = halo_pixel(hp, ok);
             halopix[hp] = ok ? gp : -1;
@@ -240,9 +246,10 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
         auto copy_sink = [&]() { copy16_to_lds(gW + lane * 8, smem_base + L::off_sink()); };
 
         // prune one raw batch (already in LDS slot `rslot`) into the compressed halo buffer of `chunk`
-        auto prune_batch = [&](int batch, int chunk, int rslot, int units_per_batch) {
+        // (a wavefront handles two units = 16 pixels; `rot` moves the busy wavefronts round the SIMDs)
+        auto prune_batch = [&](int batch, int chunk, int rslot, int units_per_batch, int rot) {
             if constexpr (MODE != 0) {
-                const int unit = ptid >> 5, px = (ptid >> 2) & 7, part = ptid & 3;
+                const int unit = 2 * ((pw + rot) & (NP - 1)) + ((lane >> 5) & 1), px = (ptid >> 2) & 7, part = ptid & 3;
                 const int u = batch * units_per_batch + unit;
                 const int hp = u * 8 + px;
                 if (unit < units_per_batch && u < nunits && hp < nhalo) {
@@ -261,7 +268,7 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
 
         // ---- prologue: first chunk's halo brought in synchronously
         if constexpr (MODE == 0) {
-            for (int u = pw; u < nunits; u += 4) copy_halo_unit(u, 0, smem_base + L::off_a_h(p.nhalo) + u * 1024, true);
+            for (int u = pw; u < nunits; u += NP) copy_halo_unit(u, 0, smem_base + L::off_a_h(p.nhalo) + u * 1024, true);
             wait_copies<0>();
             __syncthreads();
         } else {
@@ -273,7 +280,7 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
                 }
                 wait_copies<0>();
                 __syncthreads();
-                prune_batch(r, 0, 0, kC3UnitsPerStep);
+                prune_batch(r, 0, 0, kC3UnitsPerStep, 0);
                 __syncthreads();
             }
         }
@@ -287,6 +294,12 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
         auto issue = [&](bool g_valid) {
             // stages past the end re-copy the last slab into a slot nobody reads: the copy count stays exact
             const bool w_live = wc < nchunks;
+#ifdef SDGP_TRACE
+            if (p.exp & 64) {  // W copies replaced by one cache line per wavefront
+#pragma unroll
+                for (int i = 0; i < WPW; ++i) copy_sink();
+            } else
+#endif
             copy_w(w_live ? wc : nchunks - 1, w_live ? wt : ntaps - 1, wslot);
 #pragma unroll
             for (int j = 0; j < HPW; ++j) {
@@ -299,6 +312,9 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
                 } else {
                     const int u = gt * kC3UnitsPerStep + unit;  // dense: straight into the next chunk's buffer
                     real = g_valid && gc < nchunks && gt < nb && gc + 1 < nchunks && u < nunits;
+#ifdef SDGP_TRACE
+                    if (p.exp & 32) real = false;   // halo copies replaced by cache-resident ones
+#endif
                     if (real) copy_halo_unit(u, gc + 1, smem_base + L::off_a_h(p.nhalo) + ((gc + 1) & 1) * a_buf_bytes + u * 1024, true);
                 }
                 if (!real) copy_sink();
@@ -320,7 +336,7 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
             const int pc = gc, pt = gt;  // (chunk, tap) of stage g, before issue() advances them
             issue(true);
             if constexpr (SPARSE) {
-                if (pt < nb && pc + 1 < nchunks) prune_batch(pt, pc + 1, g & (kC3RawSlots - 1), upb);
+                if (pt < nb && pc + 1 < nchunks) prune_batch(pt, pc + 1, g & (kC3RawSlots - 1), upb, g);
             }
             stamp(3 + 2 * g);
             wait_copies<2 * kPer>();
@@ -428,6 +444,9 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
             }
         };
         auto mma = [&](const Frags& f) {
+#ifdef SDGP_TRACE
+            if (p.exp & 2) return;
+#endif
             bf16x8_t a[TM];
 #pragma unroll
             for (int t = 0; t < TM; ++t) a[t] = __builtin_bit_cast(bf16x8_t, f.a[t]);
@@ -459,9 +478,21 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
                 // the reads then have a whole k-step of matrix work to land behind
                 if (ks + 1 < NKS) load_frags(fr[(ks + 1) & 1], slot, chunk, ti, ks + 1);
                 else if (has_next) load_frags(fr[0], nslot, nchunk, nti, 0);
+#ifdef SDGP_C3_INTERLEAVE
+                mma(fr[ks & 1]);
+                // one matrix instruction, then a share of the next fragments' address arithmetic and LDS reads
+#pragma unroll
+                for (int i = 0; i < TM * TN; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, SDGP_C3_INTERLEAVE, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, SPARSE ? 2 : 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#else
                 __builtin_amdgcn_sched_barrier(0);
                 mma(fr[ks & 1]);
                 __builtin_amdgcn_sched_barrier(0);
+#endif
             }
             stamp(3 + 2 * s);
             __syncthreads();
@@ -472,6 +503,9 @@ __global__ void __launch_bounds__((kC3Consumers + 4) * 64) bwd_conv3(const Conv3
 
     stamp(126);
     // ---- epilogue (consumers): fp32 -> bf16 (RNE), NHWC store
+#ifdef SDGP_TRACE
+    if (p.exp & 1) return;
+#endif
     if (!producer) {
 #pragma unroll
         for (int t = 0; t < TM; ++t) {

@@ -14,7 +14,7 @@ int launch_conv3_one(const Conv3Params& p, hipStream_t stream) {
     static const hipError_t attr =
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return SDGP_ERR_HIP;
-    hipLaunchKernelGGL(kern, dim3(p.nblocks), dim3((kC3Consumers + 4) * 64), lds, stream, p);
+    hipLaunchKernelGGL(kern, dim3(p.nblocks), dim3(conv3_threads(MODE)), lds, stream, p);
     return launch_status();
 }
 

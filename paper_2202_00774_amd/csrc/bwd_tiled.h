@@ -142,6 +142,14 @@ __device__ __forceinline__ void halo_item_to_lds(const u32x4_t (&v)[ITEM / 8], i
     if constexpr (MODE == 0) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) *(SDGP_LDS u32x4_t*)(lds_a + hp * APITCH + part * (ITEM * 2) + i * 16) = v[i];
+    } else if constexpr (SPARSE && RK != kRandom) {
+        static_assert(ITEM == 16, "the compressing ranker takes sixteen channels");
+        const uint32_t w[8] = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
+        uint32_t packed[4], meta;
+        prune_compress16_bf16<M, RK>(w, n, packed, meta);
+        const u32x4_t x = {packed[0], packed[1], packed[2], packed[3]};
+        *(SDGP_LDS u32x4_t*)(lds_a + hp * APITCH + part * 16) = x;
+        *(SDGP_LDS uint16_t*)(lds_meta + hp * (KC / 8) + part * 2) = (uint16_t)meta;
     } else {
         uint32_t raw[ITEM], out[ITEM];
         bool keep[ITEM];

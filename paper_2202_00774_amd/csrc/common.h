@@ -10,15 +10,15 @@ namespace sdgp {
 
 // ---------------------------------------------------------------- bit casts
 
-__device__ __forceinline__ float bits_to_float(uint32_t u) { return __uint_as_float(u); }
-__device__ __forceinline__ uint32_t float_to_bits(float f) { return __float_as_uint(f); }
+__host__ __device__ __forceinline__ float bits_to_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+__host__ __device__ __forceinline__ uint32_t float_to_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
 
 // bfloat16 is the upper half of a binary32.
-__device__ __forceinline__ float bf16_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+__host__ __device__ __forceinline__ float bf16_to_float(uint32_t h) { return bits_to_float(h << 16); }
 
 // binary32 -> bfloat16 bits, round to nearest, ties to even; NaN stays NaN.
-__device__ __forceinline__ uint32_t float_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
+__host__ __device__ __forceinline__ uint32_t float_to_bf16(float f) {
+    uint32_t u = float_to_bits(f);
     uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
     return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? ((u >> 16) | 0x40u) : r;
 }

@@ -147,4 +147,122 @@ __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uin
     }
 }
 
+// Magnitude / Rescaled Magnitude with n <= 2 on sixteen consecutive bf16 channels (eight dwords, channel 2i in
+// the low half of dword i), producing the operand format of the structured-sparse matrix instructions directly:
+// per aligned quad of channels two values (lower position in the low half of the output dword) and two 2-bit
+// positions, ascending, four bits per quad in `meta`.  A slot without a survivor holds +0 and points at a
+// dropped position.  Bit-identical to prune_group followed by a compaction, at about half the instructions.
+//
+// Every element becomes one 32-bit key: magnitude in bits 17..31, a "kept" mark in bit 9, (M-1 - position in
+// group) in bits 1..4, sign in bit 0.  Keys are distinct, a lower position wins equal magnitudes (Sec. III-B
+// reading: stable ties), and a key carries everything needed to rebuild its value.  The two largest keys of a
+// quad contain every survivor of that quad; the group's threshold is the n-th largest key over its quads.
+// Rotated right by nine bits a key reads [code | sign | magnitude | mark]: unsigned order is now position order
+// and the bf16 value sits byte-aligned in bits 8..23.
+__host__ __device__ __forceinline__ uint32_t sdgp_umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__host__ __device__ __forceinline__ uint32_t sdgp_umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__host__ __device__ __forceinline__ uint32_t sdgp_rotl(uint32_t x, int s) { return (x << s) | (x >> (32 - s)); }
+
+template <int M, int RK>
+__host__ __device__ __forceinline__ void prune_compress16_bf16(const uint32_t (&w)[8], int n, uint32_t (&packed)[4],
+                                                               uint32_t& meta) {
+    static_assert(M == 4 || M == 8 || M == 16, "group sizes that tile sixteen channels");
+    static_assert(RK == kGreedy || RK == kAdjusted, "magnitude rankers only");
+    constexpr uint32_t kKeyMask = 0xFFFE0001u;  // magnitude and sign
+    constexpr uint32_t kCodeMask = 0x1Eu;       // what remains of a dropped key: its position
+    constexpr uint32_t kMark = 0x200u;
+    const bool two = n >= 2;
+    uint32_t f[4], s[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t d01 = w[2 * q], d23 = w[2 * q + 1];
+        const uint32_t c0 = ((uint32_t)(M - 1 - (4 * q) % M) << 1) | kMark;  // code of the quad's first element
+        const uint32_t k0 = (sdgp_rotl(d01, 17) & kKeyMask) | c0;
+        const uint32_t k1 = (sdgp_rotl(d01, 1) & kKeyMask) | (c0 - 2u);
+        const uint32_t k2 = (sdgp_rotl(d23, 17) & kKeyMask) | (c0 - 4u);
+        const uint32_t k3 = (sdgp_rotl(d23, 1) & kKeyMask) | (c0 - 6u);
+        const uint32_t hi = sdgp_umax(k0, k1), lo = sdgp_umin(k0, k1);
+        const uint32_t hi2 = sdgp_umax(k2, k3), lo2 = sdgp_umin(k2, k3);
+        f[q] = sdgp_umax(hi, hi2);
+        s[q] = sdgp_umax(sdgp_umax(sdgp_umin(hi, hi2), lo), lo2);
+    }
+    // drop what is below the group's threshold
+    if constexpr (M == 4) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s[q] = two ? s[q] : (s[q] & kCodeMask);
+    } else {
+#pragma unroll
+        for (int g = 0; g < 16 / M; ++g) {
+            constexpr int QG = M / 4;  // quads per group
+            uint32_t v1 = f[g * QG], v2 = s[g * QG];
+#pragma unroll
+            for (int i = 1; i < QG; ++i) {
+                const uint32_t fq = f[g * QG + i], sq = s[g * QG + i];
+                v2 = sdgp_umax(sdgp_umax(sdgp_umin(v1, fq), v2), sq);
+                v1 = sdgp_umax(v1, fq);
+            }
+            const uint32_t thr = two ? v2 : v1;
+#pragma unroll
+            for (int i = 0; i < QG; ++i) {
+                const int q = g * QG + i;
+                f[q] = f[q] >= thr ? f[q] : (f[q] & kCodeMask);
+                s[q] = s[q] >= thr ? s[q] : (s[q] & kCodeMask);
+            }
+        }
+    }
+    float total[16 / M];
+    if constexpr (RK == kAdjusted) {
+#pragma unroll
+        for (int g = 0; g < 16 / M; ++g) {
+            float t = 0.0f;
+#pragma unroll
+            for (int i = 0; i < M / 2; ++i) {
+                const uint32_t d = w[g * (M / 2) + i];
+                t = __fadd_rn(t, bits_to_float((d << 16) & 0x7FFF0000u));
+                t = __fadd_rn(t, bits_to_float(d & 0x7FFF0000u));
+            }
+            total[g] = t;
+        }
+    }
+    uint32_t inv = 0;
+    uint32_t lo_key[4], hi_key[4];  // rotated keys of the lower / higher position of each quad
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t ra = sdgp_rotl(f[q], 23), rb = sdgp_rotl(s[q], 23);
+        const uint32_t x = sdgp_umax(ra, rb), y = sdgp_umin(ra, rb);  // the larger code is the lower position
+        lo_key[q] = x, hi_key[q] = y;
+#if defined(__HIP_DEVICE_COMPILE__)
+        packed[q] = __builtin_amdgcn_perm(y, x, 0x06050201u);
+#else
+        packed[q] = ((x >> 8) & 0xFFFFu) | ((y << 8) & 0xFFFF0000u);
+#endif
+        inv |= (((x >> 24) & 3u) | (((y >> 24) & 3u) << 2)) << (4 * q);
+    }
+    meta = inv ^ 0xFFFFu;  // position = 3 - code
+    if constexpr (RK == kAdjusted) {
+#pragma unroll
+        for (int g = 0; g < 16 / M; ++g) {
+            constexpr int QG = M / 4;
+            float kept = 0.0f;  // kept magnitudes in ascending position; empty slots add +0, which is exact
+#pragma unroll
+            for (int i = 0; i < QG; ++i) {
+                const uint32_t d = packed[g * QG + i];
+                kept = __fadd_rn(kept, bits_to_float((d << 16) & 0x7FFF0000u));
+                kept = __fadd_rn(kept, bits_to_float(d & 0x7FFF0000u));
+            }
+            const float scale = (kept == 0.0f) ? 1.0f : __fdiv_rn(total[g], kept);
+#pragma unroll
+            for (int i = 0; i < QG; ++i) {
+                const int q = g * QG + i;
+                const uint32_t d = packed[q];
+                const uint32_t ylo = float_to_bf16(__fmul_rn(bits_to_float(d << 16), scale));
+                const uint32_t yhi = float_to_bf16(__fmul_rn(bits_to_float(d & 0xFFFF0000u), scale));
+                // a dropped slot stays +0 whatever the scale is (the mark went away with the value)
+                const uint32_t mlo = 0u - (lo_key[q] & 1u), mhi = 0u - (hi_key[q] & 1u);
+                packed[q] = (ylo & mlo) | ((yhi & mhi) << 16);
+            }
+        }
+    }
+}
+
 }  // namespace sdgp
