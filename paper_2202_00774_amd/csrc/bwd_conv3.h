@@ -75,7 +75,7 @@ struct Conv3Layout {
     __host__ __device__ static int off_sink() { return kC3Slots * kWSlab; }
     __host__ __device__ static int off_rowpix() { return off_sink() + 1024; }
     __host__ __device__ static int off_halopix(int) { return off_rowpix() + kTileRows * 4; }
-    __host__ __device__ static int off_raw_h(int halo) { return off_halopix(halo) + pad8(halo) * 4; }
+    __host__ __device__ static int off_raw_h(int halo) { return off_halopix(halo) + pad8(halo) * 8; }
     __host__ __device__ static int off_a_h(int halo) { return off_raw_h(halo) + (kSparse ? kC3RawSlots * kRawSlot : 0); }
     __host__ __device__ static int a_bytes(int halo) { return pad8(halo) * kAPitch; }
     __host__ __device__ static int off_meta(int halo) { return off_a_h(halo) + 2 * a_bytes(halo); }
@@ -83,14 +83,23 @@ struct Conv3Layout {
     __host__ __device__ static int total(int halo) { return off_meta(halo) + 2 * meta_bytes(halo); }
 };
 
-// 128 bytes of zeros in device memory: the source of halo pixels that lie outside the image.
-__device__ const uint32_t kZeroRow[32] = {0};
+// A row of zeros in device memory: the source of halo pixels that lie outside the image.  Long enough for every
+// chunk offset of the widest gradient the kernel takes, so those pixels need no special case when a chunk advances.
+constexpr int kC3MaxCout = 4096;
+__device__ const uint32_t kZeroRow[kC3MaxCout / 2 + 32] = {0};
 
 // 16 bytes per lane from global memory straight into LDS: lane i lands at lds_base + 16*i.
 // The compiler does not see this as a memory instruction; callers count copies and wait with wait_copies.
 __device__ __forceinline__ void copy16_to_lds(const void* gptr, uint32_t lds_base) {
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);  // wave-uniform by construction
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
+}
+
+// Same, with the address split into a wave-uniform base and a 32-bit byte offset per lane (no address arithmetic on
+// the vector unit when only the base moves).
+__device__ __forceinline__ void copy16_to_lds(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
+                 : "memory");
 }
 
 // Waits until at most N of this wavefront's vector-memory operations are outstanding.
@@ -127,13 +136,16 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
     SDGP_LDS unsigned char* smem = (SDGP_LDS unsigned char*)smem_generic;
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: role and per-wave constants stay off the vector unit
     const bool producer = wave >= kC3Consumers;
     const int cw = producer ? wave - kC3Consumers : wave;  // index inside the role
     const int wm = cw / WAVES_N, wn = cw % WAVES_N;
     const int ptid = tid - kC3Consumers * 64;   // producers: 0 .. NP*64-1
     auto stamp = [&](int i) {
+#ifdef SDGP_TRACE
         if (p.trace && blockIdx.x == 0 && (tid == 0 || tid == kC3Consumers * 64) && i < 128) p.trace[(tid ? 1 : 0) * 128 + i] = clock64();
+#endif
     };
     stamp(0);
 
@@ -206,7 +218,7 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
         int my_woff = 0;                       // lane ti holds the W offset of tap ti (fetched with readlane)
         if (lane < ntaps) my_woff = p.taps[lane].woff;
         // per-lane W column (swizzled chunk) and row of each copy unit this wavefront owns
-        int w_lane_off[WPW];
+        uint32_t w_lane_off[WPW];  // bytes
 #pragma unroll
         for (int i = 0; i < WPW; ++i) {
             const int uu = pw * WPW + i;
@@ -214,15 +226,20 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
             const int lchunk = (lane % CPR) ^ (2 * (row & 3));
             int col = n0 + lchunk * 8;
             if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
-            w_lane_off[i] = row * w_row + col;
+            w_lane_off[i] = (uint32_t)(row * w_row + col) * 2u;
         }
         // halo position -> flat gradient pixel (clamped into the tensor), kept in LDS for the whole kernel
-        SDGP_LDS int* halopix = (SDGP_LDS int*)(smem + L::off_halopix(p.nhalo));
+        // halo position -> address of channel 0 of its gradient pixel (the row of zeros when outside the image)
+        typedef unsigned long long u64_t;
+        SDGP_LDS u64_t* haloaddr = (SDGP_LDS u64_t*)(smem + L::off_halopix(p.nhalo));
         for (int hp = ptid; hp < L::pad8(nhalo); hp += NP * 64) {
             bool ok;
             const int gp = halo_pixel(hp, ok);
-            halopix[hp] = ok ? gp : -1;
+            haloaddr[hp] = ok ? (u64_t)(uintptr_t)(gdO + (size_t)gp * c_out) : (u64_t)(uintptr_t)kZeroRow;
         }
+        const uint32_t c16_dense[2] = {(uint32_t)(((lane & 7) ^ ((lane >> 4) & 7)) * 16),
+                                       (uint32_t)(((lane & 7) ^ ((4 + (lane >> 4)) & 7)) * 16)};
+        const uint32_t c16_raw = (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
 
         // W: the slab of stage (chunk, ti) into ring slot `slot`
         auto copy_w = [&](int chunk, int ti, int slot) {
@@ -230,18 +247,14 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
             const uint16_t* src = gW + (size_t)chunk * KC * w_row + woff;
             const uint32_t dst = smem_base + L::off_w() + (uint32_t)slot * L::kWSlab + pw * WPW * 1024;
 #pragma unroll
-            for (int i = 0; i < WPW; ++i) copy16_to_lds(src + w_lane_off[i], dst + i * 1024);
+            for (int i = 0; i < WPW; ++i) copy16_to_lds(src, w_lane_off[i], dst + i * 1024);
         };
         // halo: copy unit u (8 pixels x 128 B of `chunk`) to LDS address dst (+ lane*16)
         auto copy_halo_unit = [&](int u, int chunk, uint32_t dst, bool dense_swizzle) {
-            const int hp = u * 8 + (lane >> 3);
-            const int gp = halopix[hp];
-            int c16 = lane & 7;
-            if (dense_swizzle) c16 ^= (hp >> 1) & 7;
-            else c16 ^= (lane >> 3);
-            const uint16_t* src = gdO + (size_t)(gp < 0 ? 0 : gp) * c_out + chunk * KC + c16 * 8;
-            if (gp < 0) src = reinterpret_cast<const uint16_t*>(kZeroRow) + c16 * 8;  // outside the image: zeros
-            copy16_to_lds(src, dst);
+            const u64_t a = haloaddr[u * 8 + (lane >> 3)];
+            // the dense layout swizzles with (hp >> 1) & 7 = (4 * (u & 1) + (lane >> 4)) & 7
+            const uint32_t c16 = dense_swizzle ? ((u & 1) ? c16_dense[1] : c16_dense[0]) : c16_raw;
+            copy16_to_lds(reinterpret_cast<const void*>((uintptr_t)(a + (u64_t)(c16 + (uint32_t)chunk * (KC * 2)))), dst);
         };
         auto copy_sink = [&]() { copy16_to_lds(gW + lane * 8, smem_base + L::off_sink()); };
 
@@ -253,18 +266,19 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
                 const int u = batch * units_per_batch + unit;
                 const int hp = u * 8 + px;
                 if (unit < units_per_batch && u < nunits && hp < nhalo) {
-                    const int gp = max(halopix[hp], 0);  // an outside pixel is all zeros: any index gives zeros
+                    // flat element index of the pixel (an outside pixel is all zeros: any index gives zeros)
+                    const uint64_t pix_e = (uint64_t)(haloaddr[hp] - (u64_t)(uintptr_t)gdO) >> 1;
                     SDGP_LDS unsigned char* src = lds_raw + rslot * L::kRawSlot + unit * 1024 + px * 128;
                     u32x4_t v[2];
                     v[0] = *(SDGP_LDS u32x4_t*)(src + (((2 * part) ^ px) * 16));
                     v[1] = *(SDGP_LDS u32x4_t*)(src + (((2 * part + 1) ^ px) * 16));
-                    const uint64_t e0 = (uint64_t)gp * (uint64_t)c_out + (uint64_t)(chunk * KC + part * 16);
+                    const uint64_t e0 = pix_e + (uint64_t)(chunk * KC + part * 16);
                     halo_item_to_lds<KC, MODE, M, RK, 16>(v, hp, part, e0, p.n, p.mix, lds_a + (chunk & 1) * a_buf_bytes,
                                                           lds_meta + (chunk & 1) * meta_buf_bytes);
                 }
             }
         };
-        __syncthreads();  // halopix visible to all producers (the consumers join this barrier too)
+        __syncthreads();  // haloaddr visible to all producers (the consumers join this barrier too)
 
         // ---- prologue: first chunk's halo brought in synchronously
         if constexpr (MODE == 0) {

@@ -23,10 +23,10 @@ int bwd_conv3_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t
     else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
     else return 1;
     const int ntaps = R * S;
-    if (stride != 1 || ntaps < 4 || ntaps > kMaxTaps || (C_out % kC3KC) != 0 || (C_in % 8) != 0) return 1;
+    if (stride != 1 || ntaps < 4 || ntaps > kMaxTaps || (C_out % kC3KC) != 0 || C_out > kC3MaxCout || (C_in % 8) != 0) return 1;
     if (!is_aligned16(dO) || !is_aligned16(W)) return 1;
     const int64_t P = H + 2 * pad - R + 1, Q = Wd + 2 * pad - S + 1;
-    if (B * P * Q >= INT_MAX || B * H * Wd >= INT_MAX || (int64_t)ntaps * C_in >= INT_MAX || C_out >= INT_MAX / 2) return 1;
+    if (B * P * Q >= INT_MAX || B * H * Wd >= INT_MAX || (int64_t)ntaps * C_in >= (1 << 24) || C_out >= INT_MAX / 2) return 1;
 
     Conv3Params p{};
     p.dO = static_cast<const uint16_t*>(dO);

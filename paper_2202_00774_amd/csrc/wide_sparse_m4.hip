@@ -1,0 +1,7 @@
+// Instantiates the eight-wavefront stride-1 kernel for n <= 2 of m = 4 (structured-sparse matrix instruction).
+#include "bwd_wide_launch.h"
+namespace sdgp {
+int launch_wide_sparse_m4(const WideParams& p, int bn, int rk, hipStream_t stream) {
+    return launch_wide_rk<2, 4>(p, bn, rk, stream);
+}
+}  // namespace sdgp
