@@ -55,7 +55,7 @@ constexpr int kWideSlots = 5;      // W ring
 constexpr int kWideAhead = 4;      // a slab is requested this many stages before its stage
 constexpr int kWideRawSlots = 4;   // raw halo ring (pruning)
 constexpr int kWideRawAhead = 3;
-constexpr int kWideMaxTaps = 32;
+constexpr int kWideMaxTaps = 9;      // the per-(tap, row) address table lives in LDS
 
 template <int BN, int MODE>
 struct WideLayout {
@@ -67,18 +67,21 @@ struct WideLayout {
     static constexpr int kAPitch = kSparse ? 32 : 64;          // bytes per halo pixel in LDS
     static constexpr int kRawSlot = kHU * 1024;
     static constexpr int kOutPitch = BN * 2 + 16;
+    // halo pixels of a buffer: the copy units, then one all-zero pixel that taps outside the image read
     __host__ __device__ static int pad16(int halo) { return (halo + 15) & ~15; }
+    __host__ __device__ static int pixels(int halo) { return pad16(halo) + 16; }
+    __host__ __device__ static int zero_pixel(int halo) { return (halo + 15) & ~15; }
     __host__ __device__ static int off_rowpix() { return 0; }   // survives the epilogue: the result tile starts after it
     __host__ __device__ static int off_out() { return kWideRows * 4; }
     __host__ __device__ static int off_w() { return off_out(); }
     __host__ __device__ static int off_sink() { return off_w() + kWideSlots * kWSlab; }
-    __host__ __device__ static int off_zero() { return off_sink() + 1024; }
-    __host__ __device__ static int off_haloaddr() { return off_zero() + 128; }
-    __host__ __device__ static int off_raw(int halo) { return off_haloaddr() + pad16(halo) * 8; }
+    __host__ __device__ static int off_atab() { return off_sink() + 1024; }
+    __host__ __device__ static int off_haloaddr() { return off_atab() + kWideMaxTaps * kWideRows * 4; }
+    __host__ __device__ static int off_raw(int halo) { return off_haloaddr() + pixels(halo) * 8; }
     __host__ __device__ static int off_a(int halo) { return off_raw(halo) + (kSparse ? kWideRawSlots * kRawSlot : 0); }
-    __host__ __device__ static int a_bytes(int halo) { return pad16(halo) * kAPitch; }
+    __host__ __device__ static int a_bytes(int halo) { return pixels(halo) * kAPitch; }
     __host__ __device__ static int off_meta(int halo) { return off_a(halo) + 2 * a_bytes(halo); }
-    __host__ __device__ static int meta_bytes(int halo) { return kSparse ? pad16(halo) * 4 : 0; }
+    __host__ __device__ static int meta_bytes(int halo) { return kSparse ? pixels(halo) * 4 : 0; }
     __host__ __device__ static int total(int halo) {
         const int loop = off_meta(halo) + 2 * meta_bytes(halo);
         const int out = off_out() + kWideRows * kOutPitch;  // the result tile is staged here after the last stage
@@ -89,12 +92,18 @@ struct WideLayout {
 // 16 bytes per lane from global memory straight into LDS: lane i lands at lds_base + 16*i.  The compiler does not see
 // these as memory instructions; callers count copies and wait with wide_wait_copies.
 __device__ __forceinline__ void wide_copy16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);  // wave-uniform by construction
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
 }
 // Same, address = wave-uniform base + 32-bit byte offset per lane.
 __device__ __forceinline__ void wide_copy16(const void* sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
-                 : "memory");
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+    const uint64_t a = (uint64_t)(uintptr_t)sbase;
+    // (the builtin returns a signed int: go through uint32_t, or the low word sign-extends into the high one)
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+    const uint64_t ua = ((uint64_t)hi << 32) | (uint64_t)lo;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base), "v"(voff), "s"(ua) : "memory");
 }
 // Waits until at most N of this wavefront's vector-memory operations are outstanding.
 template <int N>
@@ -198,28 +207,44 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
     // (chunk, tap) is then wanted by a few workgroups at a time instead of by all of them at once: all compute units
     // reading the same 8 KB in the same microsecond queue up at the few L2 channels that hold it.
     const int c_rot = mtile % nchunks, t_rot = (mtile / nchunks) % ntaps;
-    auto phys_chunk = [&](int c) { const int x = c + c_rot; return x >= nchunks ? x - nchunks : x; };
-    auto phys_tap = [&](int t) { const int x = t + t_rot; return x >= ntaps ? x - ntaps : x; };
 
     SDGP_LDS int* rowpix = (SDGP_LDS int*)(smem + L::off_rowpix());
     typedef unsigned long long u64_t;
     SDGP_LDS u64_t* haloaddr = (SDGP_LDS u64_t*)(smem + L::off_haloaddr());
+    SDGP_LDS uint32_t* atab = (SDGP_LDS uint32_t*)(smem + L::off_atab());
     const uint32_t off_a = (uint32_t)L::off_a(p.halo_max), a_buf_bytes = (uint32_t)L::a_bytes(p.halo_max);
     const uint32_t off_meta = (uint32_t)L::off_meta(p.halo_max), meta_buf_bytes = (uint32_t)L::meta_bytes(p.halo_max);
     const uint32_t off_raw = (uint32_t)L::off_raw(p.halo_max);
+    const uint32_t zero_pix = (uint32_t)L::zero_pixel(p.halo_max);
     const uint16_t* const gdO = p.dO;
     const uint16_t* const gW = p.W;
 
-    // ---- tables: output pixel of every tile row, address of channel 0 of every halo pixel, the row of zeros
+    // ---- tables (one row of the tile per thread)
+    //   rowpix[m]        output pixel of tile row m (-1: none)
+    //   atab[tap][m]     byte offset, inside a halo buffer, of the gradient pixel that physical tap `tap` of row m reads
+    //                    (dense: with the pixel's swizzle; the zero pixel when the tap falls outside the image)
+    //   haloaddr[hp]     address of channel 0 of halo pixel hp
     {
         const int m = tid;
-        int pix = -1;
+        int pix = -1, rowbase = 0, h = 0, w = 0;
+        bool live = false;
         if (m < tile_rows) {
             const int tb = m / tile_hw, rem = m % tile_hw;
-            const int b = b0 + tb, hh = hh0 + rem / p.TW, ww = ww0 + rem % p.TW;
-            if (b < p.B && hh < p.H && ww < p.Wd) pix = (b * p.H + hh) * p.Wd + ww;
+            h = hh0 + rem / p.TW, w = ww0 + rem % p.TW;
+            if (b0 + tb < p.B && h < p.H && w < p.Wd) {
+                live = true;
+                pix = ((b0 + tb) * p.H + h) * p.Wd + w;
+                rowbase = (tb * HTH + (h - py0)) * HTW + (w - qx0);
+            }
         }
         rowpix[m] = pix;
+        for (int r = 0; r < p.R; ++r)
+            for (int sx = 0; sx < p.S; ++sx) {
+                const int pp = h + p.pad - r, qq = w + p.pad - sx;
+                const bool inside = live && pp >= 0 && pp < p.P && qq >= 0 && qq < p.Q;
+                const uint32_t hp = inside ? (uint32_t)(rowbase + (p.pad - r) * HTW + (p.pad - sx)) : zero_pix;
+                atab[(r * p.S + sx) * kWideRows + m] = SPARSE ? hp * 32u : hp * 64u + (((hp >> 2) & 3u) << 4);
+            }
     }
     for (int hp = tid; hp < L::pad16(nhalo); hp += 512) {
         size_t gp = 0;  // positions past the halo (tail of the last copy unit) copy pixel 0; nobody reads them
@@ -230,37 +255,12 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
         }
         haloaddr[hp] = (u64_t)(uintptr_t)(gdO + gp * p.C_out);
     }
-    if (tid < 32) {
-        // 64 bytes of zero values; for the compressed format, positions (0, 1) in every quad at byte 64
-        uint32_t z = 0;
-        if (tid == 16) z = 0x44444444u;
-        *(SDGP_LDS uint32_t*)(smem + L::off_zero() + tid * 4) = z;
+    if (tid < 64) {
+        // the zero pixel of both halo buffers; compressed format: values 0 and positions (0, 1) in every quad
+        const uint32_t buf = tid >> 5, i = tid & 31;
+        if (i < L::kAPitch / 4) *(SDGP_LDS uint32_t*)(smem + off_a + buf * a_buf_bytes + zero_pix * L::kAPitch + i * 4) = 0u;
+        if (SPARSE && i == 31) *(SDGP_LDS uint32_t*)(smem + off_meta + buf * meta_buf_bytes + zero_pix * 4) = 0x44444444u;
     }
-
-    // ---- per-lane row data: halo position of each row and the taps that fall inside the image
-    int rowbase[TM];
-    uint32_t tapmask[TM];
-#pragma unroll
-    for (int t = 0; t < TM; ++t) {
-        const int m = wm * WM + t * 32 + (lane & 31);
-        rowbase[t] = 0, tapmask[t] = 0;
-        if (m < tile_rows) {
-            const int tb = m / tile_hw, rem = m % tile_hw;
-            const int h = hh0 + rem / p.TW, w = ww0 + rem % p.TW;
-            if (b0 + tb < p.B && h < p.H && w < p.Wd) {
-                rowbase[t] = (tb * HTH + (h - py0)) * HTW + (w - qx0);
-                uint32_t mask = 0;
-                for (int r = 0; r < p.R; ++r)
-                    for (int s = 0; s < p.S; ++s) {
-                        const int pp = h + p.pad - r, qq = w + p.pad - s;
-                        if (pp >= 0 && pp < p.P && qq >= 0 && qq < p.Q) mask |= 1u << (r * p.S + s);
-                    }
-                tapmask[t] = mask;
-            }
-        }
-    }
-    int my_tap_off = 0;  // lane ti holds the halo offset of tap ti (fetched with readlane)
-    if (lane < ntaps) my_tap_off = (p.pad - lane / p.S) * HTW + (p.pad - lane % p.S);
 
     // ---- copy duties of this wavefront: two copies per stage
     // copy 0: a W unit (wavefronts below WU) or a halo unit; copy 1: a halo unit
@@ -278,39 +278,42 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
     // 16-byte column a lane copies: LDS position (lane & 3) of pixel (lane >> 2) holds the swizzled source column
     const uint32_t c16_halo = SPARSE ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
                                      : (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
+    const uint32_t haloaddr_lane = (uint32_t)L::off_haloaddr() + (uint32_t)(lane >> 2) * 8u;
 
-    auto copy_w = [&](int chunk, int ti, int slot) {  // logical (chunk, tap)
-        const uint16_t* src = gW + ((size_t)phys_chunk(chunk) * KC * p.w_row + (size_t)phys_tap(ti) * p.C_in);
-        wide_copy16(src, w_voff, smem_base + L::off_w() + (uint32_t)slot * L::kWSlab + (uint32_t)wave * 1024);
+    // unit u of the halo, channels at byte offset src_off of every pixel, to LDS address dst
+    auto copy_halo = [&](int u, uint32_t src_off, uint32_t dst) {
+        const u64_t a = *(SDGP_LDS u64_t*)(smem + haloaddr_lane + (uint32_t)u * 128u);
+        wide_copy16(reinterpret_cast<const void*>((uintptr_t)(a + (u64_t)(c16_halo + src_off))), dst);
     };
-    auto copy_halo = [&](int u, int chunk, uint32_t dst) {
-        const u64_t a = haloaddr[u * 16 + (lane >> 2)];
-        wide_copy16(reinterpret_cast<const void*>((uintptr_t)(a + (u64_t)(c16_halo + (uint32_t)phys_chunk(chunk) * (KC * 2)))), dst);
-    };
+    const uint32_t tapB = (uint32_t)p.C_in * 2u;                 // bytes between the slabs of consecutive taps
+    const uint32_t chunkB = (uint32_t)KC * (uint32_t)p.w_row * 2u;  // ... of consecutive chunks
+    const unsigned char* const gWb = reinterpret_cast<const unsigned char*>(gW);
     // keeps the copy count of a stage constant when there is no halo unit to bring: part of this workgroup's first slab
     auto copy_sink = [&]() {
-        wide_copy16(gW + ((size_t)c_rot * KC * p.w_row + (size_t)t_rot * p.C_in), w_voff, smem_base + L::off_sink());
+        wide_copy16(gWb + ((size_t)c_rot * chunkB + (size_t)t_rot * tapB), w_voff, smem_base + L::off_sink());
     };
 
-    // rank / prune / compress one raw batch (in ring slot rslot) into the halo buffer of `chunk`
-    auto prune_batch = [&](int batch, int chunk, int rslot, int units_per_batch, int rot) {
+    // rank / prune / compress 64 items (pixel, 16-channel half) of a raw batch into a halo buffer (Sec. III-B)
+    //   item0: first item of this wavefront; u0: first halo unit of the batch; raw: LDS offset of the batch
+    auto prune_items = [&](int item0, int nitems, int u0, uint32_t raw, uint32_t abuf, uint32_t mbuf, uint32_t chan0) {
         if constexpr (SPARSE) {
-            const int item = ((wave + rot) & 7) * 64 + lane;  // (unit, pixel, 16-channel half)
+            const int item = item0 + lane;
             const int j = item >> 5, px = (item >> 1) & 15, part = item & 1;
-            const int u = batch * units_per_batch + j;
-            const int hp = u * 16 + px;
-            if (j < units_per_batch && hp < nhalo) {
-                SDGP_LDS unsigned char* src = smem + off_raw + rslot * L::kRawSlot + j * 1024 + px * 64;
+            const int hp = (u0 + j) * 16 + px;
+            if (item < nitems && hp < nhalo) {
+                SDGP_LDS unsigned char* src = smem + raw + j * 1024 + px * 64;
                 const int sw = (px >> 2) & 1;
                 u32x4_t v[2];
                 v[0] = *(SDGP_LDS u32x4_t*)(src + (((2 * part) ^ sw) * 16));
                 v[1] = *(SDGP_LDS u32x4_t*)(src + (((2 * part + 1) ^ sw) * 16));
-                const uint64_t e0 = ((uint64_t)(haloaddr[hp] - (u64_t)(uintptr_t)gdO) >> 1) + (uint64_t)(phys_chunk(chunk) * KC + part * 16);
+                uint64_t e0 = 0;
+                if constexpr (RK == kRandom)
+                    e0 = ((uint64_t)(haloaddr[hp] - (u64_t)(uintptr_t)gdO) >> 1) + (uint64_t)(chan0 + part * 16);
                 uint32_t packed[4], meta;
                 wide_prune16<M, RK>(v, p.n, p.mix, e0, packed, meta);
                 const u32x4_t x = {packed[0], packed[1], packed[2], packed[3]};
-                *(SDGP_LDS u32x4_t*)(smem + off_a + (chunk & 1) * a_buf_bytes + hp * 32 + ((part ^ ((hp >> 3) & 1)) * 16)) = x;
-                *(SDGP_LDS uint16_t*)(smem + off_meta + (chunk & 1) * meta_buf_bytes + hp * 4 + part * 2) = (uint16_t)meta;
+                *(SDGP_LDS u32x4_t*)(smem + abuf + hp * 32 + part * 16) = x;
+                *(SDGP_LDS uint16_t*)(smem + mbuf + hp * 4 + part * 2) = (uint16_t)meta;
             }
         }
     };
@@ -325,72 +328,88 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
 
     __syncthreads();  // tables visible
 
-    // ---- prologue: the first chunk's halo, the first W slabs, the first raw batches
+    // ---- prologue: the first chunk's halo (physical chunk c_rot)
     const int nb = SPARSE ? ntaps - 1 : ntaps - 3;  // stages of a chunk that carry halo work
     const int hub = SPARSE ? p.hub : HU;             // copy units per stage / batch
     if constexpr (!SPARSE) {
-        for (int u = wave; u < nunits; u += 8) copy_halo(u, 0, smem_base + off_a + u * 1024);
+        for (int u = wave; u < nunits; u += 8) copy_halo(u, (uint32_t)c_rot * (KC * 2), smem_base + off_a + u * 1024);
     } else {
         const int rounds = (nunits + HU - 1) / HU;
         for (int r = 0; r < rounds; ++r) {
-            for (int j = wave; j < HU; j += 8) {
-                const int u = r * HU + j;
-                if (u < nunits) copy_halo(u, 0, smem_base + off_raw + j * 1024);
-            }
+            for (int j = wave; j < HU; j += 8)
+                if (r * HU + j < nunits) copy_halo(r * HU + j, (uint32_t)c_rot * (KC * 2), smem_base + off_raw + j * 1024);
             wide_wait_copies<0>();
             __syncthreads();
-            for (int rot = 0; rot < (HU * 32 + 511) / 512; ++rot) {
-                // every wavefront takes 64 items per pass
-                const int item = (rot * 8 + wave) * 64 + lane;
-                const int j = item >> 5, px = (item >> 1) & 15, part = item & 1;
-                const int hp = (r * HU + j) * 16 + px;
-                if (j < HU && hp < nhalo) {
-                    SDGP_LDS unsigned char* src = smem + off_raw + j * 1024 + px * 64;
-                    const int sw = (px >> 2) & 1;
-                    u32x4_t v[2];
-                    v[0] = *(SDGP_LDS u32x4_t*)(src + (((2 * part) ^ sw) * 16));
-                    v[1] = *(SDGP_LDS u32x4_t*)(src + (((2 * part + 1) ^ sw) * 16));
-                    const uint64_t e0 = ((uint64_t)(haloaddr[hp] - (u64_t)(uintptr_t)gdO) >> 1) + (uint64_t)(c_rot * KC + part * 16);
-                    uint32_t packed[4], meta;
-                    wide_prune16<M, RK>(v, p.n, p.mix, e0, packed, meta);
-                    const u32x4_t x = {packed[0], packed[1], packed[2], packed[3]};
-                    *(SDGP_LDS u32x4_t*)(smem + off_a + hp * 32 + ((part ^ ((hp >> 3) & 1)) * 16)) = x;
-                    *(SDGP_LDS uint16_t*)(smem + off_meta + hp * 4 + part * 2) = (uint16_t)meta;
-                }
-            }
+            prune_items(wave * 64, HU * 32, r * HU, off_raw, off_a, off_meta, (uint32_t)c_rot * KC);
+            static_assert(HU * 32 <= 512, "one pass of the eight wavefronts covers a batch");
             __syncthreads();
         }
     }
 
-    // Stage bookkeeping (all scalar): (wc, wt) = (chunk, tap) of the stage whose W slab is requested next,
-    // (rc, rt) = stage whose raw batch is requested next, (c, t) = current stage.
-    int wc = 0, wt = 0, wslot = 0;
-    int rc = 0, rt = 0, rslot = 0;
+    // ---- stage bookkeeping, all scalar and incremental.
+    // W stream: the slab requested next (kWideAhead stages ahead of the current stage).  Past the last stage it
+    // keeps walking valid slabs into slots nobody reads, so the copy count per stage stays constant.
+    uint32_t w_tap_off = (uint32_t)t_rot * tapB, w_chunk_off = (uint32_t)c_rot * chunkB;
+    const uint32_t w_tap_end = (uint32_t)ntaps * tapB, w_chunk_end = (uint32_t)nchunks * chunkB;
+    int w_t = 0;
+    uint32_t w_dst = smem_base + L::off_w() + (uint32_t)wave * 1024;
+    const uint32_t w_dst_end = smem_base + L::off_w() + kWideSlots * L::kWSlab + (uint32_t)wave * 1024;
     auto issue_w = [&]() {
-        if (w_duty) {
-            const bool live = wc < nchunks;  // past the end: the last slab again, into a slot nobody reads
-            copy_w(live ? wc : nchunks - 1, live ? wt : ntaps - 1, wslot);
+        if (w_duty) wide_copy16(gWb + ((size_t)w_chunk_off + w_tap_off), w_voff, w_dst);
+        w_tap_off += tapB;
+        if (w_tap_off == w_tap_end) w_tap_off = 0;
+        if (++w_t == ntaps) {
+            w_t = 0;
+            w_chunk_off += chunkB;
+            if (w_chunk_off == w_chunk_end) w_chunk_off = 0;
         }
-        if (++wt == ntaps) wt = 0, ++wc;
-        if (++wslot == kWideSlots) wslot = 0;
+        w_dst += L::kWSlab;
+        if (w_dst == w_dst_end) w_dst -= kWideSlots * L::kWSlab;
     };
-    // raw batch that is pruned during stage (rc, rt): batch rt of chunk rc + 1
-    auto issue_raw = [&](int j) {
-        const int u = rt * hub + j;
-        const bool real = rc + 1 < nchunks && rt < nb && j < hub && u < nunits;
-        if (real) copy_halo(u, rc + 1, smem_base + off_raw + rslot * L::kRawSlot + j * 1024);
+    // halo stream: dense -- units of the next chunk, requested during the current chunk's first nb stages;
+    // pruning -- the raw batch that is pruned kWideRawAhead stages later.  h_u0 = first unit of the stage's batch,
+    // h_lim = units to bring for the stream's chunk (0: none), h_src = byte offset of that chunk's channels.
+    int h_t = 0, h_c = 0;                 // stage the stream works for (pruning: ahead of the current one)
+    int h_u0 = 0;
+    int h_pc = c_rot + 1 == nchunks ? 0 : c_rot + 1;  // physical chunk after the stream's chunk
+    const int h_cap = nb * hub;
+    int h_lim = nchunks > 1 ? min(nunits, h_cap) : 0;
+    uint32_t h_raw = smem_base + off_raw;  // pruning: ring slot of the batch
+    const uint32_t h_raw_end = smem_base + off_raw + kWideRawSlots * L::kRawSlot;
+    uint32_t h_buf = smem_base + off_a + a_buf_bytes;  // dense: the halo buffer being filled
+    auto halo_copy = [&](int j) {  // returns whether a copy was issued
+        const int u = h_u0 + j;
+        const bool real = j < hub && u < h_lim;
+        if (real) copy_halo(u, (uint32_t)h_pc * (KC * 2), SPARSE ? h_raw + (uint32_t)j * 1024u : h_buf + (uint32_t)u * 1024u);
         return real;
     };
-    auto advance_raw = [&]() {
-        if (++rt == ntaps) rt = 0, ++rc;
-        rslot = (rslot + 1) & (kWideRawSlots - 1);
+    auto halo_advance = [&]() {
+        h_u0 += hub;
+        if (++h_t == ntaps) {
+            h_t = 0, h_u0 = 0, ++h_c;
+            h_pc = h_pc + 1 == nchunks ? 0 : h_pc + 1;
+            h_lim = h_c + 1 < nchunks ? min(nunits, h_cap) : 0;
+            h_buf = (h_c & 1) ? smem_base + off_a : smem_base + off_a + a_buf_bytes;
+        }
+        if constexpr (SPARSE) {
+            h_raw += L::kRawSlot;
+            if (h_raw == h_raw_end) h_raw -= kWideRawSlots * L::kRawSlot;
+        }
+    };
+    auto issue_halo = [&]() {
+        bool r0 = w_duty, r1;
+        if (!w_duty) r0 = halo_copy(hj0);
+        r1 = halo_copy(hj1);
+        halo_advance();
+        if (!r0) copy_sink();
+        if (!r1) copy_sink();
     };
     for (int i = 0; i < kWideAhead; ++i) issue_w();
     if constexpr (SPARSE) {
         for (int i = 0; i < kWideRawAhead; ++i) {
-            if (!w_duty) issue_raw(hj0);
-            issue_raw(hj1);
-            advance_raw();
+            if (!w_duty) halo_copy(hj0);
+            halo_copy(hj1);
+            halo_advance();
         }
     }
     wide_wait_copies<0>();
@@ -402,55 +421,43 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
     for (int u = 0; u < TN; ++u) {
         const int L16 = lane & 15;
         const int chunk = 8 * wn + 4 * u + 2 * ((lane >> 4) & 1) + ((L16 & 3) >> 1);
-        b_lane[u] = (uint32_t)((8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (2 * (L16 >> 2))) * 16) + (L16 & 1) * 8);
+        b_lane[u] = (uint32_t)(L::off_w() + (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (2 * (L16 >> 2))) * 16) +
+                               (L16 & 1) * 8);
     }
     struct Frags {
         u32x4_t a[TM];
         int meta[TM];
         typename std::conditional<SPARSE, bf16x16_t, bf16x8_t>::type b[TN];
     };
-    uint32_t a_addr[TM];   // LDS address of this lane's A fragment of the stage being loaded (k-step 0)
-    uint32_t m_addr[TM];
     const uint32_t half = (uint32_t)(lane >> 5);
-    // addresses for stage (chunk, ti)
-    auto stage_addr = [&](int chunk, int ti) {
-        const int pti = phys_tap(ti);
-        const int tap_off = __builtin_amdgcn_readlane(my_tap_off, pti);
-        const uint32_t abuf = off_a + (uint32_t)(chunk & 1) * a_buf_bytes;
+    const uint32_t atab_lane = (uint32_t)L::off_atab() + (uint32_t)(wm * WM + (lane & 31)) * 4u;
+    uint32_t a_ent[TM];    // table entries of the stage whose fragments are being loaded
+    uint32_t a_ent_n[TM];  // ... of the stage after it (requested a k-step early)
+    auto read_entries = [&](int ptap) {
 #pragma unroll
-        for (int t = 0; t < TM; ++t) {
-            const uint32_t hp = (uint32_t)(rowbase[t] + tap_off);
-            const bool inside = (tapmask[t] >> pti) & 1u;
-            if constexpr (SPARSE) {
-                const uint32_t a = abuf + hp * 32u + ((half ^ ((hp >> 3) & 1u)) << 4);
-                const uint32_t mm = off_meta + (uint32_t)(chunk & 1) * meta_buf_bytes + hp * 4u + half * 2u;
-                a_addr[t] = inside ? a : (uint32_t)L::off_zero();
-                m_addr[t] = inside ? mm : (uint32_t)L::off_zero() + 64u;
-            } else {
-                const uint32_t a = abuf + hp * 64u + ((half ^ ((hp >> 2) & 3u)) << 4);
-                a_addr[t] = inside ? a : (uint32_t)L::off_zero();
-            }
-        }
+        for (int t = 0; t < TM; ++t) a_ent_n[t] = *(SDGP_LDS uint32_t*)(smem + atab_lane + (uint32_t)ptap * (kWideRows * 4) + t * 128);
     };
-    auto load_frags = [&](Frags& f, int slot, int ks) {
-        SDGP_LDS unsigned char* wbuf = smem + L::off_w() + slot * L::kWSlab;
+    // dense: a_lo = lane part of the address (half, k-step); pruning: value and position addresses
+    const uint32_t a_k0 = SPARSE ? half * 16u : half << 4;
+    const uint32_t m_k0 = half * 2u;
+    auto load_frags = [&](Frags& f, uint32_t abuf, uint32_t mbuf, uint32_t wslot_off, int ks) {
 #pragma unroll
         for (int t = 0; t < TM; ++t) {
             if constexpr (SPARSE) {
-                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + a_addr[t]);
-                f.meta[t] = *(SDGP_LDS uint16_t*)(smem + m_addr[t]);
+                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] | a_k0) + abuf));
+                f.meta[t] = *(SDGP_LDS uint16_t*)(smem + (((a_ent[t] >> 3) | m_k0) + mbuf));
             } else {
-                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + (a_addr[t] ^ (uint32_t)(ks * 32)));
+                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] ^ (a_k0 | (uint32_t)(ks * 32))) + abuf));
             }
         }
 #pragma unroll
         for (int u = 0; u < TN; ++u) {
+            SDGP_LDS unsigned char* wb = smem + b_lane[u] + wslot_off;
             if constexpr (SPARSE) {
                 s16x4_t q[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (SDGP_LDS s16x4_t*)(wbuf + b_lane[u] + ((i >> 1) * 16 + (i & 1) * 4) * L::kWRow));
+                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + ((i >> 1) * 16 + (i & 1) * 4) * L::kWRow));
                 typedef short s16x16_t __attribute__((ext_vector_type(16)));
                 const s16x16_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3],
                                       q[2][0], q[2][1], q[2][2], q[2][3], q[3][0], q[3][1], q[3][2], q[3][3]};
@@ -459,8 +466,7 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
                 s16x4_t q[2];
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (SDGP_LDS s16x4_t*)(wbuf + b_lane[u] + (ks * 16 + i * 4) * L::kWRow));
+                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + (ks * 16 + i * 4) * L::kWRow));
                 typedef short s16x8_t __attribute__((ext_vector_type(8)));
                 const s16x8_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3]};
                 f.b[u] = __builtin_bit_cast(bf16x8_t, all);
@@ -484,50 +490,38 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
 
     // ---- main loop.  Fragments of the next k-step are requested before the matrix instructions of the current
     // one; at a stage's last k-step that is the next stage, whose slab and halo are complete one barrier early.
-    int c = 0, t = 0, slot = 0;       // current stage
+    int t = 0, c = 0;                    // current stage: logical tap and chunk
+    int ptap_next = t_rot + 1 == ntaps ? 0 : t_rot + 1;   // physical tap of the next stage
+    int pc_next = c_rot + 1 == nchunks ? 0 : c_rot + 1;   // physical chunk of the next chunk
+    uint32_t abuf = off_a, mbuf = off_meta;               // halo buffer of the current chunk
+    uint32_t abuf_other = off_a + a_buf_bytes, mbuf_other = off_meta + meta_buf_bytes;
+    uint32_t wslot_off = 0;                                // byte offset of the current stage's slab in the ring
+    uint32_t p_raw = off_raw;                              // pruning: ring slot read during the current stage
     Frags fr[2];
-    stage_addr(0, 0);
-    load_frags(fr[0], 0, 0);
-    // one k-step; CUR selects the fragment set (compile-time)
+    read_entries(t_rot);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a_ent[i] = a_ent_n[i];
+    load_frags(fr[0], abuf, mbuf, 0, 0);
     auto kstep = [&](Frags& cur, Frags& nxt, int ks, int s) {
+        const bool last = ks == NKS - 1;
+        const uint32_t wslot_next = wslot_off + L::kWSlab == kWideSlots * L::kWSlab ? 0u : wslot_off + L::kWSlab;
+        const bool chunk_ends = t + 1 == ntaps;
         if (ks == 0) {
-            // this stage's copies: the W slab four stages ahead, and halo work
+            if (s + 1 < nstages) read_entries(ptap_next);  // used at this stage's last k-step
             issue_w();
+            issue_halo();
             if constexpr (SPARSE) {
-                bool r0 = w_duty, r1;
-                if (!w_duty) r0 = issue_raw(hj0);
-                r1 = issue_raw(hj1);
-                advance_raw();
-                if (!r0) copy_sink();
-                if (!r1) copy_sink();
-                if (t < nb && c + 1 < nchunks) prune_batch(t, c + 1, s & (kWideRawSlots - 1), hub, s);
-            } else {
-                // dense: units of the next chunk straight into the other halo buffer
-                const bool on = t < nb && c + 1 < nchunks;
-                const uint32_t dstb = smem_base + off_a + (uint32_t)((c + 1) & 1) * a_buf_bytes;
-                bool r0 = w_duty, r1 = false;
-                if (!w_duty) {
-                    const int u = t * HU + hj0;
-                    r0 = on && u < nunits;
-                    if (r0) copy_halo(u, c + 1, dstb + u * 1024);
-                }
-                {
-                    const int u = t * HU + hj1;
-                    r1 = on && u < nunits;
-                    if (r1) copy_halo(u, c + 1, dstb + u * 1024);
-                }
-                if (!r0) copy_sink();
-                if (!r1) copy_sink();
+                // batch t of the next chunk, in wavefront-sized pieces that move round the SIMDs from stage to stage
+                if (t < nb && c + 1 < nchunks)
+                    prune_items(((wave + s) & 7) * 64, hub * 32, t * hub, p_raw, abuf_other, mbuf_other, (uint32_t)pc_next * KC);
             }
         }
-        const bool last = ks == NKS - 1;
         if (!last) {
-            load_frags(nxt, slot, ks + 1);
+            load_frags(nxt, abuf, mbuf, wslot_off, ks + 1);
         } else if (s + 1 < nstages) {
-            int nt = t + 1, nc = c;
-            if (nt == ntaps) nt = 0, ++nc;
-            stage_addr(nc, nt);
-            load_frags(nxt, slot + 1 == kWideSlots ? 0 : slot + 1, 0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a_ent[i] = a_ent_n[i];
+            load_frags(nxt, chunk_ends ? abuf_other : abuf, chunk_ends ? mbuf_other : mbuf, wslot_next, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
         mma(cur);
@@ -535,8 +529,17 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
         if (last) {
             wide_wait_copies<4>();  // everything requested two stages ago has landed
             __syncthreads();
-            if (++t == ntaps) t = 0, ++c;
-            if (++slot == kWideSlots) slot = 0;
+            ptap_next = ptap_next + 1 == ntaps ? 0 : ptap_next + 1;
+            wslot_off = wslot_next;
+            if constexpr (SPARSE) p_raw = p_raw + L::kRawSlot == off_raw + kWideRawSlots * L::kRawSlot ? off_raw : p_raw + L::kRawSlot;
+            if (chunk_ends) {
+                t = 0, ++c;
+                pc_next = pc_next + 1 == nchunks ? 0 : pc_next + 1;
+                const uint32_t x = abuf; abuf = abuf_other; abuf_other = x;
+                const uint32_t y = mbuf; mbuf = mbuf_other; mbuf_other = y;
+            } else {
+                ++t;
+            }
         }
     };
     if constexpr (NKS == 2) {

@@ -28,7 +28,7 @@ int bwd_wide_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t 
     if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
     const int64_t P = H + 2 * pad - R + 1, Q = Wd + 2 * pad - S + 1;
     if (P < 1 || Q < 1 || pad < 0) return 1;
-    if (B * P * Q >= INT_MAX || B * H * Wd >= INT_MAX || (int64_t)ntaps * C_in >= (1 << 24) || C_out >= INT_MAX / 2) return 1;
+    if (B * P * Q >= INT_MAX || B * H * Wd >= INT_MAX || (int64_t)ntaps * C_in >= (1 << 24) || C_out * (int64_t)ntaps * C_in >= (1 << 30) || C_out >= INT_MAX / 2) return 1;
 
     WideParams p{};
     p.dO = static_cast<const uint16_t*>(dO);

@@ -115,3 +115,50 @@ def test_conv_2_16_and_dense():
     dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=43, dtype=oracle.BF16)
     for n, m in ((2, 16), (16, 16), (4, 16), (2, 32)):
         check_conv(layer, dO, W, n, m, oracle.GREEDY, 0, oracle.BF16)
+
+
+# ------------------------------------------------- many-tile problems (the 512-row stride-1 kernel)
+# Enough workgroups (>= 192 tiles of 512 rows) for the dispatcher to pick the eight-wavefront kernel.  The oracle
+# prunes the whole gradient and evaluates a seeded sample of output pixels plus the corners of the batch.
+
+MANY_TILE_CONVS = [
+    wl.ConvLayer("w16_n64", 400, 16, 16, 64, 64, 3, 3, 1, 1),        # two images per tile, one 64-column tile
+    wl.ConvLayer("w16_n136", 392, 16, 16, 136, 32, 3, 3, 1, 1),      # two 128-column tiles, the second one ragged
+    wl.ConvLayer("w8", 1608, 8, 8, 16, 32, 3, 3, 1, 1),              # eight images per tile, batch not a multiple
+    wl.ConvLayer("w30x28", 100, 30, 28, 8, 32, 3, 3, 1, 1),          # image split into tiles, odd sizes
+    wl.ConvLayer("w16_valid", 400, 16, 16, 24, 32, 3, 3, 1, 0),      # no padding: the gradient is 14 x 14
+    wl.ConvLayer("w2x2", 400, 16, 16, 8, 32, 2, 2, 1, 1),            # four taps
+]
+
+
+def sample_pixels(layer, count, seed):
+    total = layer.B * layer.H * layer.Wd
+    rng = np.random.default_rng(seed)
+    hw = layer.H * layer.Wd
+    fixed = [0, layer.Wd - 1, hw - layer.Wd, hw - 1, total - hw, total - 1, total - layer.Wd]
+    return np.unique(np.concatenate([np.array(fixed, dtype=np.int64), rng.integers(0, total, count)]))
+
+
+@pytest.mark.parametrize("layer", MANY_TILE_CONVS, ids=lambda l: l.name)
+def test_many_tile_conv_matches_oracle(layer):
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=77, dtype=oracle.BF16)
+    pixels = sample_pixels(layer, 700, 5)
+    for n, m, ranker in ((4, 4, oracle.GREEDY), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED),
+                         (2, 4, oracle.RANDOM), (1, 4, oracle.GREEDY), (2, 8, oracle.GREEDY_ADJUSTED),
+                         (2, 16, oracle.RANDOM), (2, 16, oracle.GREEDY)):
+        check_conv(layer, dO, W, n, m, ranker, 11, oracle.BF16, pixels=pixels)
+
+
+def test_many_tile_fused_equals_prune_then_dense():
+    """The fused kernel and (standalone prune, then the dense kernel) see the same pruned values."""
+    layer = wl.ConvLayer("w16_n128", 400, 16, 16, 128, 64, 3, 3, 1, 1)
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=78, dtype=oracle.BF16)
+    d, w = to_gpu(dO), to_gpu(W)
+    for n, m, ranker in ((2, 4, sdgp.GREEDY), (2, 8, sdgp.GREEDY_ADJUSTED), (2, 4, sdgp.RANDOM)):
+        pruned = sdgp.sdgp_prune(d, n, m, ranker, 21)[0]
+        a = sdgp.sdgp_conv_bwd_data(pruned, w, layer.H, layer.Wd, 1, 1, m, m, sdgp.GREEDY, 0)
+        b = sdgp.sdgp_conv_bwd_data(d, w, layer.H, layer.Wd, 1, 1, n, m, ranker, 21)
+        torch.cuda.synchronize()
+        diff = (a.float() - b.float()).abs().max().item()
+        scale = a.float().abs().max().item()
+        assert diff <= 2e-2 * scale, (n, m, ranker, diff, scale)
