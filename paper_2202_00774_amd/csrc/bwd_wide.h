@@ -47,6 +47,7 @@ struct WideParams {
     int halo_max;                // upper bound of the halo pixels of any tile (LDS sizing)
     int hub;                     // pruning: copy units per raw batch
     int ntiles_n, nblocks;
+    int exp;                     // development aid (builds with SDGP_TRACE only): switches parts of the kernel off
 };
 
 constexpr int kWideRows = 512;
@@ -152,6 +153,12 @@ __device__ __forceinline__ void wide_prune16(const u32x4_t (&v)[2], int n, uint3
         }
     }
 }
+
+#ifdef SDGP_TRACE
+#define SDGP_EXP(bit) (p.exp & (bit))
+#else
+#define SDGP_EXP(bit) false
+#endif
 
 template <int BN, int MODE, int M, int RK>
 __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
@@ -355,7 +362,7 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
     uint32_t w_dst = smem_base + L::off_w() + (uint32_t)wave * 1024;
     const uint32_t w_dst_end = smem_base + L::off_w() + kWideSlots * L::kWSlab + (uint32_t)wave * 1024;
     auto issue_w = [&]() {
-        if (w_duty) wide_copy16(gWb + ((size_t)w_chunk_off + w_tap_off), w_voff, w_dst);
+        if (w_duty && !SDGP_EXP(4)) wide_copy16(gWb + ((size_t)w_chunk_off + w_tap_off), w_voff, w_dst);
         w_tap_off += tapB;
         if (w_tap_off == w_tap_end) w_tap_off = 0;
         if (++w_t == ntaps) {
@@ -377,10 +384,20 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
     uint32_t h_raw = smem_base + off_raw;  // pruning: ring slot of the batch
     const uint32_t h_raw_end = smem_base + off_raw + kWideRawSlots * L::kRawSlot;
     uint32_t h_buf = smem_base + off_a + a_buf_bytes;  // dense: the halo buffer being filled
-    auto halo_copy = [&](int j) {  // returns whether a copy was issued
+    // The pixel addresses of the units a wavefront copies next are fetched from the table one stage early
+    // (slot 0: unit-in-stage hj0, slot 1: hj1), so the copy itself never waits for LDS.
+    u64_t h_addr[2] = {0, 0};
+    auto halo_prefetch = [&]() {
+        if (!w_duty && hj0 < hub && h_u0 + hj0 < h_lim) h_addr[0] = *(SDGP_LDS u64_t*)(smem + haloaddr_lane + (uint32_t)(h_u0 + hj0) * 128u);
+        if (hj1 < hub && h_u0 + hj1 < h_lim) h_addr[1] = *(SDGP_LDS u64_t*)(smem + haloaddr_lane + (uint32_t)(h_u0 + hj1) * 128u);
+    };
+    auto halo_copy = [&](int slot) {  // returns whether a copy was issued
+        const int j = slot ? hj1 : hj0;
         const int u = h_u0 + j;
-        const bool real = j < hub && u < h_lim;
-        if (real) copy_halo(u, (uint32_t)h_pc * (KC * 2), SPARSE ? h_raw + (uint32_t)j * 1024u : h_buf + (uint32_t)u * 1024u);
+        const bool real = j < hub && u < h_lim && !SDGP_EXP(4);
+        if (real)
+            wide_copy16(reinterpret_cast<const void*>((uintptr_t)(h_addr[slot] + (u64_t)(c16_halo + (uint32_t)h_pc * (KC * 2)))),
+                        SPARSE ? h_raw + (uint32_t)j * 1024u : h_buf + (uint32_t)u * 1024u);
         return real;
     };
     auto halo_advance = [&]() {
@@ -395,20 +412,23 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
             h_raw += L::kRawSlot;
             if (h_raw == h_raw_end) h_raw -= kWideRawSlots * L::kRawSlot;
         }
+        halo_prefetch();
     };
-    auto issue_halo = [&]() {
-        bool r0 = w_duty, r1;
-        if (!w_duty) r0 = halo_copy(hj0);
-        r1 = halo_copy(hj1);
+    // the stage's copy 0 when it is not a W unit, and copy 1; a stand-in copy keeps the count per stage constant
+    auto issue_halo0 = [&]() {
+        if (!w_duty && !halo_copy(0) && !SDGP_EXP(4)) copy_sink();
+    };
+    auto issue_halo1 = [&]() {
+        const bool r1 = halo_copy(1);
         halo_advance();
-        if (!r0) copy_sink();
-        if (!r1) copy_sink();
+        if (!r1 && !SDGP_EXP(4)) copy_sink();
     };
     for (int i = 0; i < kWideAhead; ++i) issue_w();
+    halo_prefetch();
     if constexpr (SPARSE) {
         for (int i = 0; i < kWideRawAhead; ++i) {
-            if (!w_duty) halo_copy(hj0);
-            halo_copy(hj1);
+            if (!w_duty) halo_copy(0);
+            halo_copy(1);
             halo_advance();
         }
     }
@@ -440,56 +460,58 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
     // dense: a_lo = lane part of the address (half, k-step); pruning: value and position addresses
     const uint32_t a_k0 = SPARSE ? half * 16u : half << 4;
     const uint32_t m_k0 = half * 2u;
+    // fragment requests, in pieces small enough to sit between two matrix instructions
+    auto load_a = [&](Frags& f, int t, uint32_t abuf, uint32_t mbuf, int ks) {
+        if (SDGP_EXP(8)) return;
+        if constexpr (SPARSE) {
+            f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] | a_k0) + abuf));
+            f.meta[t] = *(SDGP_LDS uint16_t*)(smem + (((a_ent[t] >> 3) | m_k0) + mbuf));
+        } else {
+            f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] ^ (a_k0 | (uint32_t)(ks * 32))) + abuf));
+        }
+    };
+    auto load_b = [&](Frags& f, int u, uint32_t wslot_off, int ks) {
+        if (SDGP_EXP(8)) return;
+        SDGP_LDS unsigned char* wb = smem + b_lane[u] + wslot_off;
+        if constexpr (SPARSE) {
+            s16x4_t q[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + ((i >> 1) * 16 + (i & 1) * 4) * L::kWRow));
+            typedef short s16x16_t __attribute__((ext_vector_type(16)));
+            const s16x16_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3],
+                                  q[2][0], q[2][1], q[2][2], q[2][3], q[3][0], q[3][1], q[3][2], q[3][3]};
+            f.b[u] = __builtin_bit_cast(bf16x16_t, all);
+        } else {
+            s16x4_t q[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + (ks * 16 + i * 4) * L::kWRow));
+            typedef short s16x8_t __attribute__((ext_vector_type(8)));
+            const s16x8_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3]};
+            f.b[u] = __builtin_bit_cast(bf16x8_t, all);
+        }
+    };
     auto load_frags = [&](Frags& f, uint32_t abuf, uint32_t mbuf, uint32_t wslot_off, int ks) {
 #pragma unroll
-        for (int t = 0; t < TM; ++t) {
-            if constexpr (SPARSE) {
-                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] | a_k0) + abuf));
-                f.meta[t] = *(SDGP_LDS uint16_t*)(smem + (((a_ent[t] >> 3) | m_k0) + mbuf));
-            } else {
-                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] ^ (a_k0 | (uint32_t)(ks * 32))) + abuf));
-            }
-        }
+        for (int t = 0; t < TM; ++t) load_a(f, t, abuf, mbuf, ks);
 #pragma unroll
-        for (int u = 0; u < TN; ++u) {
-            SDGP_LDS unsigned char* wb = smem + b_lane[u] + wslot_off;
-            if constexpr (SPARSE) {
-                s16x4_t q[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + ((i >> 1) * 16 + (i & 1) * 4) * L::kWRow));
-                typedef short s16x16_t __attribute__((ext_vector_type(16)));
-                const s16x16_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3],
-                                      q[2][0], q[2][1], q[2][2], q[2][3], q[3][0], q[3][1], q[3][2], q[3][3]};
-                f.b[u] = __builtin_bit_cast(bf16x16_t, all);
-            } else {
-                s16x4_t q[2];
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + (ks * 16 + i * 4) * L::kWRow));
-                typedef short s16x8_t __attribute__((ext_vector_type(8)));
-                const s16x8_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3]};
-                f.b[u] = __builtin_bit_cast(bf16x8_t, all);
-            }
-        }
+        for (int u = 0; u < TN; ++u) load_b(f, u, wslot_off, ks);
     };
-    auto mma = [&](const Frags& f) {
-        bf16x8_t a[TM];
-#pragma unroll
-        for (int t = 0; t < TM; ++t) a[t] = __builtin_bit_cast(bf16x8_t, f.a[t]);
-#pragma unroll
-        for (int t = 0; t < TM; ++t)
-#pragma unroll
-            for (int u = 0; u < TN; ++u) {
-                if constexpr (SPARSE)
-                    acc[t][u] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[t], f.b[u], acc[t][u], f.meta[t], 0, 0);
-                else
-                    acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], f.b[u], acc[t][u], 0, 0, 0);
-            }
+    auto mma_one = [&](const Frags& f, int t, int u) {
+        if (SDGP_EXP(2)) return;
+        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, f.a[t]);
+        if constexpr (SPARSE)
+            acc[t][u] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, f.b[u], acc[t][u], f.meta[t], 0, 0);
+        else
+            acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, f.b[u], acc[t][u], 0, 0, 0);
     };
 
-    // ---- main loop.  Fragments of the next k-step are requested before the matrix instructions of the current
-    // one; at a stage's last k-step that is the next stage, whose slab and halo are complete one barrier early.
+    // ---- main loop.  A matrix instruction occupies the pipe for 32 cycles; a wavefront issues in order, one
+    // instruction every four to five cycles.  Everything else a stage needs -- the copies, their bookkeeping, the
+    // requests for the next k-step's fragments -- is therefore cut into pieces of a few instructions and placed
+    // BETWEEN the matrix instructions, where it costs nothing.  Fragments are requested one k-step ahead; at a
+    // stage's last k-step that is the next stage, whose slab and halo are complete one barrier early.
     int t = 0, c = 0;                    // current stage: logical tap and chunk
     int ptap_next = t_rot + 1 == ntaps ? 0 : t_rot + 1;   // physical tap of the next stage
     int pc_next = c_rot + 1 == nchunks ? 0 : c_rot + 1;   // physical chunk of the next chunk
@@ -502,33 +524,71 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) a_ent[i] = a_ent_n[i];
     load_frags(fr[0], abuf, mbuf, 0, 0);
+    constexpr int GAPS = TM * TN;        // matrix instructions of a k-step
+    constexpr int APIECES = (TM + 1) / 2;
     auto kstep = [&](Frags& cur, Frags& nxt, int ks, int s) {
         const bool last = ks == NKS - 1;
+        const bool more = s + 1 < nstages;
         const uint32_t wslot_next = wslot_off + L::kWSlab == kWideSlots * L::kWSlab ? 0u : wslot_off + L::kWSlab;
         const bool chunk_ends = t + 1 == ntaps;
-        if (ks == 0) {
-            if (s + 1 < nstages) read_entries(ptap_next);  // used at this stage's last k-step
-            issue_w();
-            issue_halo();
-            if constexpr (SPARSE) {
-                // batch t of the next chunk, in wavefront-sized pieces that move round the SIMDs from stage to stage
-                if (t < nb && c + 1 < nchunks)
-                    prune_items(((wave + s) & 7) * 64, hub * 32, t * hub, p_raw, abuf_other, mbuf_other, (uint32_t)pc_next * KC);
-            }
-        }
-        if (!last) {
-            load_frags(nxt, abuf, mbuf, wslot_off, ks + 1);
-        } else if (s + 1 < nstages) {
+        // where this k-step's fragment requests go: the next k-step of this stage, or the first one of the next stage
+        const uint32_t la = (last && chunk_ends) ? abuf_other : abuf, lm = (last && chunk_ends) ? mbuf_other : mbuf;
+        const uint32_t lw = last ? wslot_next : wslot_off;
+        const int lks = last ? 0 : ks + 1;
+        const bool do_load = !last || more;
+        const bool copies = ks == 0;     // the stage's copies ride on its first k-step
+        if (SPARSE && more) read_entries(ptap_next);
+        // pieces, in issue order
+        //   0            table entries: dense first k-step requests them, a last k-step takes them over
+        //   1..APIECES   A fragments of two row tiles each
+        //   then TN      B fragments of one column tile each
+        //   then 3       the W copy, halo copy 0, halo copy 1 (first k-step only)
+        const int npieces = 1 + APIECES + TN + (copies ? 3 : 0);
+        auto piece = [&](int i) {
+            if (i == 0) {
+                if (last) {
+                    if (more) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a_ent[i] = a_ent_n[i];
-            load_frags(nxt, chunk_ends ? abuf_other : abuf, chunk_ends ? mbuf_other : mbuf, wslot_next, 0);
+                        for (int k = 0; k < TM; ++k) a_ent[k] = a_ent_n[k];
+                    }
+                } else if (more) {
+                    read_entries(ptap_next);
+                }
+            } else if (i <= APIECES) {
+                if (do_load) {
+                    const int t0 = 2 * (i - 1);
+                    load_a(nxt, t0, la, lm, lks);
+                    if (t0 + 1 < TM) load_a(nxt, t0 + 1, la, lm, lks);
+                }
+            } else if (i <= APIECES + TN) {
+                if (do_load) load_b(nxt, i - APIECES - 1, lw, lks);
+            } else if (i == APIECES + TN + 1) {
+                issue_w();
+            } else if (i == APIECES + TN + 2) {
+                issue_halo0();
+            } else {
+                issue_halo1();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        __builtin_amdgcn_sched_barrier(0);
+        int done = 0;
+#pragma unroll
+        for (int g = 0; g < GAPS; ++g) {
+            mma_one(cur, g / TN, g % TN);
+            __builtin_amdgcn_sched_barrier(0);
+            // after matrix instruction g, as many pieces as keep them evenly spread
+            const int upto = ((g + 1) * npieces + GAPS - 1) / GAPS;
+            for (; done < upto && done < npieces; ++done) piece(done);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        mma(cur);
-        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (SPARSE) {
+            // batch t of the next chunk, in wavefront-sized pieces that move round the SIMDs from stage to stage
+            if (t < nb && c + 1 < nchunks)
+                prune_items(((wave + s) & 7) * 64, hub * 32, t * hub, p_raw, abuf_other, mbuf_other, (uint32_t)pc_next * KC);
+        }
         if (last) {
             wide_wait_copies<4>();  // everything requested two stages ago has landed
-            __syncthreads();
+            if (!SDGP_EXP(16)) __syncthreads();
             ptap_next = ptap_next + 1 == ntaps ? 0 : ptap_next + 1;
             wslot_off = wslot_next;
             if constexpr (SPARSE) p_raw = p_raw + L::kRawSlot == off_raw + kWideRawSlots * L::kRawSlot ? off_raw : p_raw + L::kRawSlot;
@@ -556,6 +616,7 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
         if (s < nstages) kstep(fr[0], fr[1], 0, s);
     }
 
+    if (SDGP_EXP(1)) return;
     // ---- epilogue: fp32 -> bf16 (RNE) into LDS, then whole pixel rows with 16-byte stores
     wide_wait_copies<0>();
     __syncthreads();  // nobody reads or copies into the loop's buffers any more

@@ -2,6 +2,7 @@
 // (C_out a multiple of 32, C_in a multiple of 8), chooses the tile and launches.
 #include <algorithm>
 #include <climits>
+#include <cstdlib>
 
 #include "bwd_wide.h"
 
@@ -39,6 +40,9 @@ int bwd_wide_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t 
     p.w_row = ntaps * (int)C_in;
     p.n = n;
     p.mix = seed_mix(seed);
+#ifdef SDGP_TRACE
+    if (const char* e = getenv("SDGP_EXP")) p.exp = atoi(e);
+#endif
 
     const int bn = (C_in > 64) ? 128 : 64;
     p.ntiles_n = ((int)C_in + bn - 1) / bn;
