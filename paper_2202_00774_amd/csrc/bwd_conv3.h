@@ -7,8 +7,8 @@
 // (global_load_lds_dwordx4: lane i of a wavefront writes 16 bytes at LDS base + 16*i).
 // They need no destination registers, so a wavefront keeps three stages of copies in
 // flight and waits with an explicit counter: each producer wavefront issues exactly
-// kPer copies per stage, hence "all but the last 2*kPer copies have landed" means "everything
-// issued two stages ago is in LDS".
+// kPer copies per stage, hence "all but the last kPer copies have landed" means "everything
+// issued before this stage is in LDS".
 //
 //   * W slabs (64 x BN, the layout W has in memory) go into a ring of 4 slots, requested
 //     three stages ahead.  Rows are unpadded; the 16-byte chunk index is XOR-swizzled with
@@ -353,7 +353,10 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
                 if (pt < nb && pc + 1 < nchunks) prune_batch(pt, pc + 1, g & (kC3RawSlots - 1), upb, g);
             }
             stamp(3 + 2 * g);
-            wait_copies<2 * kPer>();
+            // Only this stage's requests may still be in flight: the consumers read the fragments of stage g+1
+            // before the barrier that ends stage g, so its slab (requested at stage g-2) must be complete one
+            // barrier early.
+            wait_copies<kPer>();
             __syncthreads();
             stamp(4 + 2 * g);
         }

@@ -16,10 +16,12 @@
 //     was issued, so fragments of stage s+1 can be read before the barrier that ends stage s.
 //   * The gradient halo of a tile (the pixels its taps reach, clipped to the image) is brought in ONCE per chunk and
 //     shared by all taps.  Dense: copied straight into the other halo buffer while the current chunk is multiplied.
-//     Pruning (Sec. III-B): the raw halo streams through a ring of 4 batches; three stages after a batch was
-//     requested the wavefronts rank / prune / compress it into the next chunk's halo buffer, two values and two
-//     2-bit positions per aligned quad of channels -- the operand of v_smfmac_f32_32x32x32_bf16.  A gradient
-//     element is ranked once per tile and chunk, not once per tap.
+//     Pruning (Sec. III-B, 3x3 filters): the raw halo of the next chunk streams into a ring of two 16 KB slots, a
+//     third of the halo at a time; at taps 1, 4 and 7 all wavefronts together rank / prune / compress one third
+//     (one 16-channel item per lane) into the next chunk's halo buffer, two values and two 2-bit positions per
+//     aligned quad of channels -- the operand of v_smfmac_f32_32x32x32_bf16.  Whole-workgroup passes keep the
+//     lanes full and the wavefronts level at the barrier; a gradient element is ranked once per tile and chunk,
+//     not once per tap.
 //   * Taps that fall outside the image read a row of zeros in LDS (one select per fragment address); nothing is
 //     stored or copied for the padding.
 //   * The result leaves through LDS: fp32 -> bf16, then 16-byte stores of whole pixel rows.
@@ -45,7 +47,7 @@ struct WideParams {
     int TB, TH, TW;              // tile: TB images x TH x TW pixels (<= 512)
     int tiles_h, tiles_w;
     int halo_max;                // upper bound of the halo pixels of any tile (LDS sizing)
-    int hub;                     // pruning: copy units per raw batch
+    int hub;                     // pruning: copy units per pass (a third of the halo, at most 16)
     int ntiles_n, nblocks;
     int exp;                     // development aid (builds with SDGP_TRACE only): switches parts of the kernel off
 };
@@ -54,8 +56,10 @@ constexpr int kWideRows = 512;
 constexpr int kWideKC = 32;        // reduction channels per chunk
 constexpr int kWideSlots = 5;      // W ring
 constexpr int kWideAhead = 4;      // a slab is requested this many stages before its stage
-constexpr int kWideRawSlots = 4;   // raw halo ring (pruning)
-constexpr int kWideRawAhead = 3;
+constexpr int kWideRawSlots = 2;   // raw halo ring (pruning): two passes of up to 16 copy units
+constexpr int kWidePassUnits = 16; // 16 units = 256 pixels = 512 items of 16 channels: one item per lane of the workgroup
+constexpr int kWidePasses = 3;     // pruning passes per chunk, at taps 1, 4 and 7 of a 9-tap filter
+constexpr int kWideRawAhead = 4;   // the raw stream runs this many stages ahead of the current stage
 constexpr int kWideMaxTaps = 9;      // the per-(tap, row) address table lives in LDS
 
 template <int BN, int MODE>
@@ -66,7 +70,7 @@ struct WideLayout {
     static constexpr int kWUnits = kWSlab / 1024;             // 1 KB copy units per slab (8 or 4)
     static constexpr int kHU = 16 - kWUnits;                   // halo copy units per stage (every wavefront issues two copies)
     static constexpr int kAPitch = kSparse ? 32 : 64;          // bytes per halo pixel in LDS
-    static constexpr int kRawSlot = kHU * 1024;
+    static constexpr int kRawSlot = kWidePassUnits * 1024;
     static constexpr int kOutPitch = BN * 2 + 16;
     // halo pixels of a buffer: the copy units, then one all-zero pixel that taps outside the image read
     __host__ __device__ static int pad16(int halo) { return (halo + 15) & ~15; }
@@ -341,14 +345,14 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
     if constexpr (!SPARSE) {
         for (int u = wave; u < nunits; u += 8) copy_halo(u, (uint32_t)c_rot * (KC * 2), smem_base + off_a + u * 1024);
     } else {
-        const int rounds = (nunits + HU - 1) / HU;
+        const int rounds = (nunits + kWidePassUnits - 1) / kWidePassUnits;
         for (int r = 0; r < rounds; ++r) {
-            for (int j = wave; j < HU; j += 8)
-                if (r * HU + j < nunits) copy_halo(r * HU + j, (uint32_t)c_rot * (KC * 2), smem_base + off_raw + j * 1024);
+            for (int j = wave; j < kWidePassUnits; j += 8)
+                if (r * kWidePassUnits + j < nunits)
+                    copy_halo(r * kWidePassUnits + j, (uint32_t)c_rot * (KC * 2), smem_base + off_raw + j * 1024);
             wide_wait_copies<0>();
             __syncthreads();
-            prune_items(wave * 64, HU * 32, r * HU, off_raw, off_a, off_meta, (uint32_t)c_rot * KC);
-            static_assert(HU * 32 <= 512, "one pass of the eight wavefronts covers a batch");
+            prune_items(wave * 64, kWidePassUnits * 32, r * kWidePassUnits, off_raw, off_a, off_meta, (uint32_t)c_rot * KC);
             __syncthreads();
         }
     }
@@ -373,44 +377,62 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
         w_dst += L::kWSlab;
         if (w_dst == w_dst_end) w_dst -= kWideSlots * L::kWSlab;
     };
-    // halo stream: dense -- units of the next chunk, requested during the current chunk's first nb stages;
-    // pruning -- the raw batch that is pruned kWideRawAhead stages later.  h_u0 = first unit of the stage's batch,
-    // h_lim = units to bring for the stream's chunk (0: none), h_src = byte offset of that chunk's channels.
-    int h_t = 0, h_c = 0;                 // stage the stream works for (pruning: ahead of the current one)
+    // halo stream.  Dense: units of the next chunk, requested during the current chunk's first nb stages, straight
+    // into the other halo buffer.  Pruning: the raw stream runs kWideRawAhead stages ahead in a cycle of three steps
+    // per pass -- first half of the pass's units, second half, nothing -- into ring slot (pass & 1).
+    // h_u0 = first unit of the step, h_lim = one past the last unit to bring (0: none), h_pc = physical chunk.
+    int h_t = 0, h_c = 0;                 // dense: stage the stream works for.  pruning: step in the cycle, pass in the chunk
     int h_u0 = 0;
-    int h_pc = c_rot + 1 == nchunks ? 0 : c_rot + 1;  // physical chunk after the stream's chunk
+    int h_pc = c_rot + 1 == nchunks ? 0 : c_rot + 1;  // physical chunk the stream fetches
     const int h_cap = nb * hub;
-    int h_lim = nchunks > 1 ? min(nunits, h_cap) : 0;
-    uint32_t h_raw = smem_base + off_raw;  // pruning: ring slot of the batch
-    const uint32_t h_raw_end = smem_base + off_raw + kWideRawSlots * L::kRawSlot;
+    int h_lim = nchunks > 1 ? min(nunits, SPARSE ? hub : h_cap) : 0;
+    int h_chunk = 1;                       // pruning: logical chunk the stream fetches
+    uint32_t h_raw = smem_base + off_raw;  // pruning: where unit h_u0 of the step lands
+    uint32_t h_slot = 0;
     uint32_t h_buf = smem_base + off_a + a_buf_bytes;  // dense: the halo buffer being filled
     // The pixel addresses of the units a wavefront copies next are fetched from the table one stage early
     // (slot 0: unit-in-stage hj0, slot 1: hj1), so the copy itself never waits for LDS.
     u64_t h_addr[2] = {0, 0};
     auto halo_prefetch = [&]() {
-        if (!w_duty && hj0 < hub && h_u0 + hj0 < h_lim) h_addr[0] = *(SDGP_LDS u64_t*)(smem + haloaddr_lane + (uint32_t)(h_u0 + hj0) * 128u);
-        if (hj1 < hub && h_u0 + hj1 < h_lim) h_addr[1] = *(SDGP_LDS u64_t*)(smem + haloaddr_lane + (uint32_t)(h_u0 + hj1) * 128u);
+        if (!w_duty && h_u0 + hj0 < h_lim) h_addr[0] = *(SDGP_LDS u64_t*)(smem + haloaddr_lane + (uint32_t)(h_u0 + hj0) * 128u);
+        if (h_u0 + hj1 < h_lim) h_addr[1] = *(SDGP_LDS u64_t*)(smem + haloaddr_lane + (uint32_t)(h_u0 + hj1) * 128u);
     };
     auto halo_copy = [&](int slot) {  // returns whether a copy was issued
         const int j = slot ? hj1 : hj0;
         const int u = h_u0 + j;
-        const bool real = j < hub && u < h_lim && !SDGP_EXP(4);
+        const bool real = u < h_lim && !SDGP_EXP(4);
         if (real)
             wide_copy16(reinterpret_cast<const void*>((uintptr_t)(h_addr[slot] + (u64_t)(c16_halo + (uint32_t)h_pc * (KC * 2)))),
                         SPARSE ? h_raw + (uint32_t)j * 1024u : h_buf + (uint32_t)u * 1024u);
         return real;
     };
     auto halo_advance = [&]() {
-        h_u0 += hub;
-        if (++h_t == ntaps) {
-            h_t = 0, h_u0 = 0, ++h_c;
-            h_pc = h_pc + 1 == nchunks ? 0 : h_pc + 1;
-            h_lim = h_c + 1 < nchunks ? min(nunits, h_cap) : 0;
-            h_buf = (h_c & 1) ? smem_base + off_a : smem_base + off_a + a_buf_bytes;
-        }
         if constexpr (SPARSE) {
-            h_raw += L::kRawSlot;
-            if (h_raw == h_raw_end) h_raw -= kWideRawSlots * L::kRawSlot;
+            // h_t: step in the cycle (0, 1: halves of the pass; 2: idle), h_c: pass in the chunk
+            ++h_t;
+            if (h_t == 1) {
+                h_u0 += HU, h_raw += HU * 1024;       // second half: the pass's remaining units
+            } else if (h_t == 2) {
+                h_lim = 0;                            // idle step
+            } else {
+                h_t = 0;
+                h_slot ^= 1u;
+                if (++h_c == kWidePasses) {
+                    h_c = 0, ++h_chunk;
+                    h_pc = h_pc + 1 == nchunks ? 0 : h_pc + 1;
+                }
+                h_u0 = h_c * hub;
+                h_raw = smem_base + off_raw + h_slot * L::kRawSlot;
+                h_lim = h_chunk < nchunks ? min(nunits, h_u0 + hub) : 0;
+            }
+        } else {
+            h_u0 += hub;
+            if (++h_t == ntaps) {
+                h_t = 0, h_u0 = 0, ++h_c;
+                h_pc = h_pc + 1 == nchunks ? 0 : h_pc + 1;
+                h_lim = h_c + 1 < nchunks ? min(nunits, h_cap) : 0;
+                h_buf = (h_c & 1) ? smem_base + off_a : smem_base + off_a + a_buf_bytes;
+            }
         }
         halo_prefetch();
     };
@@ -518,7 +540,6 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
     uint32_t abuf = off_a, mbuf = off_meta;               // halo buffer of the current chunk
     uint32_t abuf_other = off_a + a_buf_bytes, mbuf_other = off_meta + meta_buf_bytes;
     uint32_t wslot_off = 0;                                // byte offset of the current stage's slab in the ring
-    uint32_t p_raw = off_raw;                              // pruning: ring slot read during the current stage
     Frags fr[2];
     read_entries(t_rot);
 #pragma unroll
@@ -582,16 +603,21 @@ __global__ void __launch_bounds__(512) bwd_wide(const WideParams p) {
             for (; done < upto && done < npieces; ++done) piece(done);
         }
         if constexpr (SPARSE) {
-            // batch t of the next chunk, in wavefront-sized pieces that move round the SIMDs from stage to stage
-            if (t < nb && c + 1 < nchunks)
-                prune_items(((wave + s) & 7) * 64, hub * 32, t * hub, p_raw, abuf_other, mbuf_other, (uint32_t)pc_next * KC);
+            // at taps 1, 4, 7: one third of the next chunk's halo, one item per lane of the whole workgroup
+            if ((t == 1 || t == 4 || t == 7) && c + 1 < nchunks && !SDGP_EXP(32)) {
+                const int k = t == 1 ? 0 : (t == 4 ? 1 : 2);
+                const int u0 = k * hub;
+                const int cnt = min(hub, nunits - u0);
+                if (cnt > 0)
+                    prune_items(((wave + k + c) & 7) * 64, cnt * 32, u0, off_raw + (uint32_t)((c + k) & 1) * L::kRawSlot, abuf_other,
+                                mbuf_other, (uint32_t)pc_next * KC);
+            }
         }
         if (last) {
             wide_wait_copies<4>();  // everything requested two stages ago has landed
             if (!SDGP_EXP(16)) __syncthreads();
             ptap_next = ptap_next + 1 == ntaps ? 0 : ptap_next + 1;
             wslot_off = wslot_next;
-            if constexpr (SPARSE) p_raw = p_raw + L::kRawSlot == off_raw + kWideRawSlots * L::kRawSlot ? off_raw : p_raw + L::kRawSlot;
             if (chunk_ends) {
                 t = 0, ++c;
                 pc_next = pc_next + 1 == nchunks ? 0 : pc_next + 1;

@@ -25,7 +25,7 @@ int bwd_wide_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t 
     else return 1;
     const int ntaps = R * S;
     if (stride != 1 || ntaps < 4 || ntaps > kWideMaxTaps || (C_out % kWideKC) != 0 || (C_in % 8) != 0) return 1;
-    if (mode == 2 && (C_out % m) != 0) return 1;
+    if (mode == 2 && ((C_out % m) != 0 || ntaps != 9)) return 1;  // the pruning passes are scheduled for nine taps
     if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
     const int64_t P = H + 2 * pad - R + 1, Q = Wd + 2 * pad - S + 1;
     if (P < 1 || Q < 1 || pad < 0) return 1;
@@ -59,7 +59,7 @@ int bwd_wide_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t 
                 // the halo is clipped to the image
                 const int halo = TB * (int)std::min<int64_t>(TH + R - 1, P) * (int)std::min<int64_t>(TW + S - 1, Q);
                 const int units = (halo + 15) / 16;
-                if (units > hu * nb) continue;
+                if (mode == 2 ? units > kWidePasses * kWidePassUnits : units > hu * nb) continue;
                 if (wide_lds_bytes(mode, bn, halo) > 160 * 1024) continue;
                 const double tiles = (double)((B + TB - 1) / TB) * ((H + TH - 1) / TH) * ((Wd + TW - 1) / TW);
                 const double cost = tiles * (kWideRows * (double)ntaps + 2.0 * halo + 64.0);
@@ -72,12 +72,12 @@ int bwd_wide_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t 
     p.tiles_h = ((int)H + p.TH - 1) / p.TH;
     p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
     p.halo_max = bhalo;
-    p.hub = (((bhalo + 15) / 16) + nb - 1) / nb;
+    p.hub = (((bhalo + 15) / 16) + kWidePasses - 1) / kWidePasses;
     const int64_t tiles = (int64_t)((B + p.TB - 1) / p.TB) * p.tiles_h * p.tiles_w;
     if (tiles * p.ntiles_n >= INT_MAX) return 1;
     p.nblocks = (int)tiles * p.ntiles_n;
     if (p.nblocks == 0) return SDGP_OK;
-    if (p.nblocks < 192) return 1;  // too few 512-row tiles to fill the chip: the 256-row kernel takes it
+    if (p.nblocks < 128) return 1;  // too few 512-row tiles to keep half the chip busy: the 256-row kernel takes it
 
     if (mode == 0) return launch_wide_dense(p, bn, stream);
     if (m == 4) return launch_wide_sparse_m4(p, bn, rk, stream);
