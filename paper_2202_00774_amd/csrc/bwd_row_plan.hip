@@ -1,0 +1,83 @@
+// Host side of the row-per-stage kernel: stride-1 filters three taps wide and at most three rows high, with
+// enough 512-row tiles to fill the chip; chooses the tile and launches.
+#include <algorithm>
+#include <climits>
+
+#include "bwd_row.h"
+
+namespace sdgp {
+
+int launch_row_dense(const RowParams& p, int bn, hipStream_t stream);
+int launch_row_sparse_m4(const RowParams& p, int bn, int rk, hipStream_t stream);
+int launch_row_sparse_m8(const RowParams& p, int bn, int rk, hipStream_t stream);
+int launch_row_sparse_m16(const RowParams& p, int bn, int rk, hipStream_t stream);
+int row_lds_bytes(int mode, int bn, int halo);
+
+// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
+int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                   int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
+                   hipStream_t stream) {
+    int mode;
+    if (n == m) mode = 0;
+    else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
+    else return 1;
+    if (stride != 1 || S != kRowTaps || R < 1 || R > kRowMaxRows || (C_out % kWideKC) != 0 || (C_in % 8) != 0) return 1;
+    if (mode == 2 && (C_out % m) != 0) return 1;
+    if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
+    const int ntaps = R * S;
+    const int64_t P = H + 2 * pad - R + 1, Q = Wd + 2 * pad - S + 1;
+    if (P < 1 || Q < 1 || pad < 0) return 1;
+    if (B * P * Q >= INT_MAX || B * H * Wd >= INT_MAX || (int64_t)ntaps * C_in >= (1 << 24) ||
+        C_out * (int64_t)ntaps * C_in >= (1 << 30) || C_out >= INT_MAX / 2)
+        return 1;
+
+    RowParams p{};
+    p.dO = static_cast<const uint16_t*>(dO);
+    p.W = static_cast<const uint16_t*>(W);
+    p.dD = static_cast<uint16_t*>(dD);
+    p.B = (int)B, p.P = (int)P, p.Q = (int)Q, p.C_out = (int)C_out, p.C_in = (int)C_in, p.H = (int)H, p.Wd = (int)Wd;
+    p.R = R, p.pad = pad;
+    p.w_row = ntaps * (int)C_in;
+    p.n = n;
+    p.mix = seed_mix(seed);
+
+    const int bn = (C_in > 64) ? 128 : 64;
+    p.ntiles_n = ((int)C_in + bn - 1) / bn;
+
+    // tile shape: fewest tiles, then least halo, under the LDS budget and the copy schedule (16 units per stage)
+    double best = 1e300;
+    int bTB = 0, bTH = 0, bTW = 0, bhalo = 0;
+    for (int TH = 1; TH <= std::min((int)H, kWideRows); ++TH) {
+        for (int TW = 1; TW <= std::min((int)Wd, kWideRows / TH); ++TW) {
+            const int tb_max = std::max(1, std::min((int)B, kWideRows / (TH * TW)));
+            for (int TB = tb_max; TB >= 1; TB = (TB > 1 ? TB / 2 : 0)) {
+                // the halo is clipped to the image
+                const int halo = TB * (int)std::min<int64_t>(TH + R - 1, P) * (int)std::min<int64_t>(TW + S - 1, Q);
+                const int units = (halo + 15) / 16;
+                if (units > 16 * R) continue;
+                if (row_lds_bytes(mode, bn, halo) > 160 * 1024) continue;
+                const double tiles = (double)((B + TB - 1) / TB) * ((H + TH - 1) / TH) * ((Wd + TW - 1) / TW);
+                const double cost = tiles * (kWideRows * (double)ntaps + 2.0 * halo + 64.0);
+                if (cost < best || (cost == best && TW > bTW)) best = cost, bTB = TB, bTH = TH, bTW = TW, bhalo = halo;
+            }
+        }
+    }
+    if (bTB == 0) return 1;
+    p.TB = bTB, p.TH = bTH, p.TW = bTW;
+    p.tiles_h = ((int)H + p.TH - 1) / p.TH;
+    p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
+    p.halo_max = bhalo;
+    p.ups = (((bhalo + 15) / 16) + R - 1) / R;
+    const int64_t tiles = (int64_t)((B + p.TB - 1) / p.TB) * p.tiles_h * p.tiles_w;
+    if (tiles * p.ntiles_n >= INT_MAX) return 1;
+    p.nblocks = (int)tiles * p.ntiles_n;
+    if (p.nblocks == 0) return SDGP_OK;
+    if (p.nblocks < 128) return 1;  // too few 512-row tiles to keep half the chip busy: the 256-row kernel takes it
+
+    if (mode == 0) return launch_row_dense(p, bn, stream);
+    if (m == 4) return launch_row_sparse_m4(p, bn, rk, stream);
+    if (m == 8) return launch_row_sparse_m8(p, bn, rk, stream);
+    return launch_row_sparse_m16(p, bn, rk, stream);
+}
+
+}  // namespace sdgp

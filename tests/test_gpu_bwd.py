@@ -128,6 +128,8 @@ MANY_TILE_CONVS = [
     wl.ConvLayer("w30x28", 100, 30, 28, 8, 32, 3, 3, 1, 1),          # image split into tiles, odd sizes
     wl.ConvLayer("w16_valid", 400, 16, 16, 24, 32, 3, 3, 1, 0),      # no padding: the gradient is 14 x 14
     wl.ConvLayer("w2x2", 400, 16, 16, 8, 32, 2, 2, 1, 1),            # four taps
+    wl.ConvLayer("w2x3", 400, 16, 16, 16, 64, 2, 3, 1, 1),           # two filter rows of three taps
+    wl.ConvLayer("w1x3", 400, 16, 16, 72, 32, 1, 3, 1, 0),           # one filter row, no padding; 72 columns of a 128-wide tile
 ]
 
 
