@@ -37,6 +37,7 @@ struct RowParams {
     int halo_max;                // upper bound of the halo pixels of any tile (LDS sizing)
     int ups;                     // halo copy units per stage: a 1/R share of the halo, at most 16
     int ntiles_n, nblocks;
+    int exp;                     // development aid (builds with SDGP_TRACE only): switches parts of the kernel off
 };
 
 constexpr int kRowTaps = 3;        // taps per stage (filter width)
@@ -326,6 +327,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         }
     };
     auto mma_one = [&](const Frags& f, int t, int u) {
+        if (SDGP_EXP(2)) return;
         const bf16x8_t a = __builtin_bit_cast(bf16x8_t, f.a[t]);
         if constexpr (SPARSE)
             acc[t][u] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, f.b[u], acc[t][u], f.meta[t], 0, 0);
@@ -353,15 +355,17 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         const int npc = row_last ? pc_next : pc;
         const bool more = x + 1 < nstages;
         // first k-step: nothing of this stage was requested before the barrier except the table entries
-        read_entries(pr * TS);
-        take_entries();
+        if (!SDGP_EXP(8) || x == 0) {
+            read_entries(pr * TS);
+            take_entries();
 #pragma unroll
-        for (int t = 0; t < TM; ++t) load_a(f0, t, abuf, mbuf, 0);
+            for (int t = 0; t < TM; ++t) load_a(f0, t, abuf, mbuf, 0);
 #pragma unroll
-        for (int u = 0; u < TN; ++u) load_b(f0, u, set_off, 0);
+            for (int u = 0; u < TN; ++u) load_b(f0, u, set_off, 0);
+        }
         if constexpr (SPARSE) {
             // share r of the next chunk's halo: one item per lane of the whole workgroup
-            if (c + 1 < nchunks) {
+            if (c + 1 < nchunks && !SDGP_EXP(32)) {
                 const int u0 = r * ups;
                 const int cnt = min(ups, nunits - u0);
                 if (cnt > 0)
@@ -395,6 +399,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                     }
                 } else if (i <= APIECES + TN) {
                     if (has_next) load_b(nxt, i - APIECES - 1, set_off + (uint32_t)ntap * L::kWSlab, nks);
+                } else if (SDGP_EXP(4)) {
                 } else if (i == APIECES + TN + 1) {
                     if (more) copy_w_set(npc, npr, (x + 1) & 1);
                 } else if (i == APIECES + TN + 2) {
@@ -425,7 +430,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
             }
         }
         wide_wait_copies<0>();
-        __syncthreads();
+        __syncthreads();  // never optional: the epilogue reuses the tables' LDS as soon as a wavefront leaves the loop
         if (row_last) {
             r = 0, ++c, pc = pc_next;
             const uint32_t xa = abuf; abuf = abuf_other; abuf_other = xa;
@@ -446,6 +451,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         if (x < nstages) stage(fr[0], fr[1], x);
     }
 
+    if (SDGP_EXP(1)) return;
     // ---- epilogue: fp32 -> bf16 (RNE) into LDS, then whole pixel rows with 16-byte stores
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));

@@ -2,6 +2,7 @@
 // enough 512-row tiles to fill the chip; chooses the tile and launches.
 #include <algorithm>
 #include <climits>
+#include <cstdlib>
 
 #include "bwd_row.h"
 
@@ -40,6 +41,9 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
     p.w_row = ntaps * (int)C_in;
     p.n = n;
     p.mix = seed_mix(seed);
+#ifdef SDGP_TRACE
+    if (const char* e = getenv("SDGP_EXP")) p.exp = atoi(e);
+#endif
 
     const int bn = (C_in > 64) ? 128 : 64;
     p.ntiles_n = ((int)C_in + bn - 1) / bn;
