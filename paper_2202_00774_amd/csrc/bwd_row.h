@@ -2,7 +2,7 @@
 // dL/dD = prune(dL/dO) (*) W as an implicit GEMM (Fig. 3 left; Sec. II-A): rows = input pixels, columns = input
 // channels, reduction = taps x output channels, the pruned axis (Fig. 1).
 //
-// Same tiles, copies and tables as bwd_wide.h (eight wavefronts of one kind, 512 rows x BN columns per workgroup,
+// Same tiles, copies and tables as bwd_wide.h (eight wavefronts of one kind, 512 or 256 rows x BN columns per workgroup,
 // 32-channel chunks, direct-to-LDS copies, clipped halo, per-(tap, row) address table, result staged through LDS),
 // but a stage is a (chunk, filter row) pair: three taps, 48 dense or 24 sparse matrix instructions per wavefront
 // between two barriers instead of 16 or 8.  What a stage costs besides its matrix instructions -- the barrier and
@@ -32,7 +32,7 @@ struct RowParams {
     int w_row;                   // elements per W row: R*3*C_in
     int n;
     uint32_t mix;
-    int TB, TH, TW;              // tile: TB images x TH x TW pixels (<= 512)
+    int TB, TH, TW;              // tile: TB images x TH x TW pixels (<= the kernel's ROWS)
     int tiles_h, tiles_w;
     int halo_max;                // upper bound of the halo pixels of any tile (LDS sizing)
     int ups;                     // halo copy units per stage: a 1/R share of the halo, at most 16
@@ -43,7 +43,7 @@ struct RowParams {
 constexpr int kRowTaps = 3;        // taps per stage (filter width)
 constexpr int kRowMaxRows = 3;
 
-template <int BN, int MODE>
+template <int BN, int MODE, int ROWS>
 struct RowLayout {
     static constexpr bool kSparse = MODE == 2;
     static constexpr int kWRow = BN * 2;
@@ -57,10 +57,10 @@ struct RowLayout {
     __host__ __device__ static int pixels(int halo) { return pad16(halo) + 16; }  // + one all-zero pixel
     __host__ __device__ static int zero_pixel(int halo) { return pad16(halo); }
     __host__ __device__ static int off_rowpix() { return 0; }
-    __host__ __device__ static int off_out() { return kWideRows * 4; }
+    __host__ __device__ static int off_out() { return ROWS * 4; }
     __host__ __device__ static int off_w() { return off_out(); }
     __host__ __device__ static int off_atab() { return off_w() + 2 * kWSet; }
-    __host__ __device__ static int off_haloaddr() { return off_atab() + kRowMaxRows * kRowTaps * kWideRows * 4; }
+    __host__ __device__ static int off_haloaddr() { return off_atab() + kRowMaxRows * kRowTaps * ROWS * 4; }
     __host__ __device__ static int off_raw(int halo) { return off_haloaddr() + pixels(halo) * 8; }
     __host__ __device__ static int off_a(int halo) { return off_raw(halo) + (kSparse ? 2 * kRawSlot : 0); }
     __host__ __device__ static int a_bytes(int halo) { return pixels(halo) * kAPitch; }
@@ -68,20 +68,21 @@ struct RowLayout {
     __host__ __device__ static int meta_bytes(int halo) { return kSparse ? pixels(halo) * 4 : 0; }
     __host__ __device__ static int total(int halo) {
         const int loop = off_meta(halo) + 2 * meta_bytes(halo);
-        const int out = off_out() + kWideRows * kOutPitch;
+        const int out = off_out() + ROWS * kOutPitch;
         return loop > out ? loop : out;
     }
 };
 
-template <int BN, int MODE, int M, int RK>
+template <int BN, int MODE, int M, int RK, int ROWS>
 __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
-    using L = RowLayout<BN, MODE>;
+    using L = RowLayout<BN, MODE, ROWS>;
+    static_assert(ROWS == 512 || ROWS == 256, "rows of a workgroup tile");
     constexpr bool SPARSE = MODE == 2;
     constexpr int KC = kWideKC;
     constexpr int TS = kRowTaps;
     constexpr int WAVES_N = BN / 64;
     constexpr int WAVES_M = 8 / WAVES_N;
-    constexpr int WM = kWideRows / WAVES_M;
+    constexpr int WM = ROWS / WAVES_M;
     constexpr int TM = WM / 32;
     constexpr int TN = 2;
     constexpr int KSTEP = SPARSE ? 32 : 16;
@@ -144,7 +145,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     //   atab[tap][m]     byte offset, inside a halo buffer, of the gradient pixel that tap `tap` of row m reads
     //                    (dense: with the pixel's swizzle; the zero pixel when the tap falls outside the image)
     //   haloaddr[hp]     address of channel 0 of halo pixel hp
-    {
+    if (tid < ROWS) {
         const int m = tid;
         int pix = -1, rowbase = 0, h = 0, w = 0;
         bool live = false;
@@ -163,7 +164,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 const int pp = h + p.pad - r, qq = w + p.pad - sx;
                 const bool inside = live && pp >= 0 && pp < p.P && qq >= 0 && qq < p.Q;
                 const uint32_t hp = inside ? (uint32_t)(rowbase + (p.pad - r) * HTW + (p.pad - sx)) : zero_pix;
-                atab[(r * TS + sx) * kWideRows + m] = SPARSE ? hp * 32u : hp * 64u + (((hp >> 2) & 3u) << 4);
+                atab[(r * TS + sx) * ROWS + m] = SPARSE ? hp * 32u : hp * 64u + (((hp >> 2) & 3u) << 4);
             }
     }
     for (int hp = tid; hp < L::pad16(nhalo); hp += 512) {
@@ -289,7 +290,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     uint32_t a_ent_n[TM];  // ... of the tap after it (requested early)
     auto read_entries = [&](int tap) {
 #pragma unroll
-        for (int t = 0; t < TM; ++t) a_ent_n[t] = *(SDGP_LDS uint32_t*)(smem + atab_lane + (uint32_t)tap * (kWideRows * 4) + t * 128);
+        for (int t = 0; t < TM; ++t) a_ent_n[t] = *(SDGP_LDS uint32_t*)(smem + atab_lane + (uint32_t)tap * (ROWS * 4) + t * 128);
     };
     auto take_entries = [&]() {
 #pragma unroll
@@ -472,7 +473,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
             }
     __syncthreads();
 #pragma unroll 4
-    for (int idx = tid; idx < kWideRows * CPR; idx += 512) {
+    for (int idx = tid; idx < ROWS * CPR; idx += 512) {
         const int m = idx / CPR, cc = idx % CPR;
         const int pix = rowpix[m];
         if (pix >= 0 && n0 + cc * 8 < p.C_in) {

@@ -5,12 +5,12 @@
 
 namespace sdgp {
 
-template <int BN, int MODE, int M, int RK>
+template <int BN, int MODE, int M, int RK, int ROWS>
 int launch_row_one(const RowParams& p, hipStream_t stream) {
-    using L = RowLayout<BN, MODE>;
+    using L = RowLayout<BN, MODE, ROWS>;
     const int lds = L::total(p.halo_max);
     if (lds > 160 * 1024) return SDGP_ERR_SHAPE;
-    auto kern = bwd_row<BN, MODE, M, RK>;
+    auto kern = bwd_row<BN, MODE, M, RK, ROWS>;
     static const hipError_t attr =
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return SDGP_ERR_HIP;
@@ -19,16 +19,17 @@ int launch_row_one(const RowParams& p, hipStream_t stream) {
 }
 
 template <int MODE, int M, int RK>
-int launch_row_bn(const RowParams& p, int bn, hipStream_t stream) {
-    return bn == 128 ? launch_row_one<128, MODE, M, RK>(p, stream) : launch_row_one<64, MODE, M, RK>(p, stream);
+int launch_row_bn(const RowParams& p, int bn, int rows, hipStream_t stream) {
+    if (rows == 512) return bn == 128 ? launch_row_one<128, MODE, M, RK, 512>(p, stream) : launch_row_one<64, MODE, M, RK, 512>(p, stream);
+    return bn == 128 ? launch_row_one<128, MODE, M, RK, 256>(p, stream) : launch_row_one<64, MODE, M, RK, 256>(p, stream);
 }
 
 template <int MODE, int M>
-int launch_row_rk(const RowParams& p, int bn, int rk, hipStream_t stream) {
+int launch_row_rk(const RowParams& p, int bn, int rows, int rk, hipStream_t stream) {
     switch (rk) {
-        case kRandom: return launch_row_bn<MODE, M, kRandom>(p, bn, stream);
-        case kGreedy: return launch_row_bn<MODE, M, kGreedy>(p, bn, stream);
-        default: return launch_row_bn<MODE, M, kAdjusted>(p, bn, stream);
+        case kRandom: return launch_row_bn<MODE, M, kRandom>(p, bn, rows, stream);
+        case kGreedy: return launch_row_bn<MODE, M, kGreedy>(p, bn, rows, stream);
+        default: return launch_row_bn<MODE, M, kAdjusted>(p, bn, rows, stream);
     }
 }
 

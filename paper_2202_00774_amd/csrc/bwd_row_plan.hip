@@ -8,11 +8,45 @@
 
 namespace sdgp {
 
-int launch_row_dense(const RowParams& p, int bn, hipStream_t stream);
-int launch_row_sparse_m4(const RowParams& p, int bn, int rk, hipStream_t stream);
-int launch_row_sparse_m8(const RowParams& p, int bn, int rk, hipStream_t stream);
-int launch_row_sparse_m16(const RowParams& p, int bn, int rk, hipStream_t stream);
-int row_lds_bytes(int mode, int bn, int halo);
+int launch_row_dense(const RowParams& p, int bn, int rows, hipStream_t stream);
+int launch_row_sparse_m4(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
+int launch_row_sparse_m8(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
+int launch_row_sparse_m16(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
+int row_lds_bytes(int mode, int bn, int rows, int halo);
+
+namespace {
+
+// Tile shape for workgroup tiles of `rows` rows: fewest tiles, then least halo, under the LDS budget and the copy
+// schedule (16 units per stage).  Returns the number of workgroups, 0 when nothing fits.
+int64_t plan_tiles(RowParams& p, int rows, int mode, int bn, int64_t B, int64_t H, int64_t Wd, int R, int S, int64_t P, int64_t Q) {
+    const int ntaps = R * S;
+    double best = 1e300;
+    int bTB = 0, bTH = 0, bTW = 0, bhalo = 0;
+    for (int TH = 1; TH <= std::min((int)H, rows); ++TH) {
+        for (int TW = 1; TW <= std::min((int)Wd, rows / TH); ++TW) {
+            const int tb_max = std::max(1, std::min((int)B, rows / (TH * TW)));
+            for (int TB = tb_max; TB >= 1; TB = (TB > 1 ? TB / 2 : 0)) {
+                // the halo is clipped to the image
+                const int halo = TB * (int)std::min<int64_t>(TH + R - 1, P) * (int)std::min<int64_t>(TW + S - 1, Q);
+                const int units = (halo + 15) / 16;
+                if (units > 16 * R) continue;
+                if (row_lds_bytes(mode, bn, rows, halo) > 160 * 1024) continue;
+                const double tiles = (double)((B + TB - 1) / TB) * ((H + TH - 1) / TH) * ((Wd + TW - 1) / TW);
+                const double cost = tiles * (rows * (double)ntaps + 2.0 * halo + 64.0);
+                if (cost < best || (cost == best && TW > bTW)) best = cost, bTB = TB, bTH = TH, bTW = TW, bhalo = halo;
+            }
+        }
+    }
+    if (bTB == 0) return 0;
+    p.TB = bTB, p.TH = bTH, p.TW = bTW;
+    p.tiles_h = ((int)H + p.TH - 1) / p.TH;
+    p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
+    p.halo_max = bhalo;
+    p.ups = (((bhalo + 15) / 16) + R - 1) / R;
+    return (int64_t)((B + p.TB - 1) / p.TB) * p.tiles_h * p.tiles_w * p.ntiles_n;
+}
+
+}  // namespace
 
 // SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
 int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
@@ -48,40 +82,22 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
     const int bn = (C_in > 64) ? 128 : 64;
     p.ntiles_n = ((int)C_in + bn - 1) / bn;
 
-    // tile shape: fewest tiles, then least halo, under the LDS budget and the copy schedule (16 units per stage)
-    double best = 1e300;
-    int bTB = 0, bTH = 0, bTW = 0, bhalo = 0;
-    for (int TH = 1; TH <= std::min((int)H, kWideRows); ++TH) {
-        for (int TW = 1; TW <= std::min((int)Wd, kWideRows / TH); ++TW) {
-            const int tb_max = std::max(1, std::min((int)B, kWideRows / (TH * TW)));
-            for (int TB = tb_max; TB >= 1; TB = (TB > 1 ? TB / 2 : 0)) {
-                // the halo is clipped to the image
-                const int halo = TB * (int)std::min<int64_t>(TH + R - 1, P) * (int)std::min<int64_t>(TW + S - 1, Q);
-                const int units = (halo + 15) / 16;
-                if (units > 16 * R) continue;
-                if (row_lds_bytes(mode, bn, halo) > 160 * 1024) continue;
-                const double tiles = (double)((B + TB - 1) / TB) * ((H + TH - 1) / TH) * ((Wd + TW - 1) / TW);
-                const double cost = tiles * (kWideRows * (double)ntaps + 2.0 * halo + 64.0);
-                if (cost < best || (cost == best && TW > bTW)) best = cost, bTB = TB, bTH = TH, bTW = TW, bhalo = halo;
-            }
-        }
-    }
-    if (bTB == 0) return 1;
-    p.TB = bTB, p.TH = bTH, p.TW = bTW;
-    p.tiles_h = ((int)H + p.TH - 1) / p.TH;
-    p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
-    p.halo_max = bhalo;
-    p.ups = (((bhalo + 15) / 16) + R - 1) / R;
-    const int64_t tiles = (int64_t)((B + p.TB - 1) / p.TB) * p.tiles_h * p.tiles_w;
-    if (tiles * p.ntiles_n >= INT_MAX) return 1;
-    p.nblocks = (int)tiles * p.ntiles_n;
-    if (p.nblocks == 0) return SDGP_OK;
-    if (p.nblocks < 128) return 1;  // too few 512-row tiles to keep half the chip busy: the 256-row kernel takes it
+    // 512-row tiles when they fill the chip, else 256-row tiles (twice the workgroups, half the matrix work per stage)
+    int rows = 512;
+    RowParams p512 = p, p256 = p;
+    const int64_t n512 = plan_tiles(p512, 512, mode, bn, B, H, Wd, R, S, P, Q);
+    const int64_t n256 = plan_tiles(p256, 256, mode, bn, B, H, Wd, R, S, P, Q);
+    int64_t blocks;
+    if (n512 >= 192 || (n512 >= 128 && n256 < 128) || n256 == 0) rows = 512, p = p512, blocks = n512;
+    else rows = 256, p = p256, blocks = n256;
+    if (blocks == 0 && (B == 0 || H == 0 || Wd == 0)) return SDGP_OK;
+    if (blocks < 128 || blocks >= INT_MAX) return 1;  // too few tiles to keep half the chip busy: another kernel takes it
+    p.nblocks = (int)blocks;
 
-    if (mode == 0) return launch_row_dense(p, bn, stream);
-    if (m == 4) return launch_row_sparse_m4(p, bn, rk, stream);
-    if (m == 8) return launch_row_sparse_m8(p, bn, rk, stream);
-    return launch_row_sparse_m16(p, bn, rk, stream);
+    if (mode == 0) return launch_row_dense(p, bn, rows, stream);
+    if (m == 4) return launch_row_sparse_m4(p, bn, rows, rk, stream);
+    if (m == 8) return launch_row_sparse_m8(p, bn, rows, rk, stream);
+    return launch_row_sparse_m16(p, bn, rows, rk, stream);
 }
 
 }  // namespace sdgp

@@ -1,7 +1,7 @@
 // Instantiates the row-per-stage kernel for n <= 2 of m = 8 (structured-sparse matrix instruction).
 #include "bwd_row_launch.h"
 namespace sdgp {
-int launch_row_sparse_m8(const RowParams& p, int bn, int rk, hipStream_t stream) {
-    return launch_row_rk<2, 8>(p, bn, rk, stream);
+int launch_row_sparse_m8(const RowParams& p, int bn, int rows, int rk, hipStream_t stream) {
+    return launch_row_rk<2, 8>(p, bn, rows, rk, stream);
 }
 }  // namespace sdgp

@@ -129,6 +129,8 @@ MANY_TILE_CONVS = [
     wl.ConvLayer("w16_valid", 400, 16, 16, 24, 32, 3, 3, 1, 0),      # no padding: the gradient is 14 x 14
     wl.ConvLayer("w2x2", 400, 16, 16, 8, 32, 2, 2, 1, 1),            # four taps
     wl.ConvLayer("w2x3", 400, 16, 16, 16, 64, 2, 3, 1, 1),           # two filter rows of three taps
+    wl.ConvLayer("w16_r256_n64", 200, 16, 16, 64, 64, 3, 3, 1, 1),    # too few 512-row tiles: 256-row tiles, 64 columns
+    wl.ConvLayer("w8_r256_n136", 808, 8, 8, 136, 32, 3, 3, 1, 1),     # 256-row tiles of four images, ragged second column tile
     wl.ConvLayer("w1x3", 400, 16, 16, 72, 32, 1, 3, 1, 0),           # one filter row, no padding; 72 columns of a 128-wide tile
 ]
 
@@ -164,3 +166,16 @@ def test_many_tile_fused_equals_prune_then_dense():
         diff = (a.float() - b.float()).abs().max().item()
         scale = a.float().abs().max().item()
         assert diff <= 2e-2 * scale, (n, m, ranker, diff, scale)
+
+
+# ------------------------------------------------- full-size workload (the shapes and launches bench.py times)
+
+@pytest.mark.parametrize("index", range(6))
+def test_resnet9_batch512_sampled(index):
+    """Every ResNet-9 layer at batch 512: the fused 2:4 kernels and the dense kernel against the oracle on 4096 sampled
+    output pixels (plus the corners of the first and last image); the oracle prunes the whole gradient."""
+    layer = wl.resnet9_layers(512)[index]
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=2000 + index, dtype=oracle.BF16)
+    pixels = sample_pixels(layer, 4096, 100 + index)
+    for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (2, 4, oracle.RANDOM), (4, 4, oracle.GREEDY)):
+        check_conv(layer, dO, W, n, m, ranker, 0, oracle.BF16, pixels=pixels)
