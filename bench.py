@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the fused 2:4 kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what
-# the same counters read for a plain 256 MiB device copy (x2.0 and x1.0); see profiles/bwd_wide_traffic.md.
+# the same counters read for a plain 256 MiB device copy (x2.0 and x1.0); see profiles/bwd_row_traffic.md.
 MEASURED_TRAFFIC_BYTES = {"r9_128x256_16": 114.0e6, "r9_64x128_32": 228.3e6}
 PAPER_CONTEXT = ("the paper reports no measured rate for this path; it estimates a 15-25 % cut of total training time "
                  "assuming 2:4 sparse tensor-core support on an A100 (abstract, Sec. IV-C)")
@@ -129,7 +129,7 @@ def main():
     dom_ms = td["greedy"]
     issued = 0.5 * Ld.dense_flops  # the structured-sparse instruction issues half of the dense multiply-adds
     result["roofline"] = {
-        "bound": "mfma", "kernel": "bwd_wide (fused 2:4 greedy, structured-sparse MFMA) on %s" % Ld.name,
+        "bound": "mfma", "kernel": "bwd_row (fused 2:4 greedy, structured-sparse MFMA) on %s" % Ld.name,
         "achieved": round(issued / (dom_ms * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": round(issued / (dom_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         "traffic": MEASURED_TRAFFIC_BYTES.get(Ld.name),
@@ -141,7 +141,7 @@ def main():
     # the dense hand-written kernel (n == m) on the same layer: all of its FLOPs are issued
     dense_ms = time_call(lambda: call(*data[dom_i], 4, 4, sdgp.GREEDY))
     result["roofline_dense"] = {
-        "bound": "mfma", "kernel": "bwd_wide (dense, n == m) on %s" % Ld.name,
+        "bound": "mfma", "kernel": "bwd_row (dense, n == m) on %s" % Ld.name,
         "achieved": round(Ld.dense_flops / (dense_ms * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
         "unit": "TFLOP/s", "frac": round(Ld.dense_flops / (dense_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         "launch_us": round(dense_ms * 1e3, 2),

@@ -364,16 +364,21 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
 #pragma unroll
             for (int u = 0; u < TN; ++u) load_b(f0, u, set_off, 0);
         }
-        if constexpr (SPARSE) {
-            // share r of the next chunk's halo: one item per lane of the whole workgroup
-            if (c + 1 < nchunks && !SDGP_EXP(32)) {
-                const int u0 = r * ups;
-                const int cnt = min(ups, nunits - u0);
-                if (cnt > 0)
-                    prune_items(wave * 64, cnt * 32, u0, off_raw + (uint32_t)(x & 1) * L::kRawSlot, abuf_other, mbuf_other,
-                                (uint32_t)pc_next * KC);
+        // share r of the next chunk's halo: one item per lane of the whole workgroup.  The two wavefronts of a SIMD
+        // (w and w + 4) rank at different times -- one before the stage's first k-step, the other after it -- so
+        // that one's vector work runs under the other's matrix instructions.
+        auto prune_share = [&]() {
+            if constexpr (SPARSE) {
+                if (c + 1 < nchunks && !SDGP_EXP(32)) {
+                    const int u0 = r * ups;
+                    const int cnt = min(ups, nunits - u0);
+                    if (cnt > 0)
+                        prune_items(wave * 64, cnt * 32, u0, off_raw + (uint32_t)(x & 1) * L::kRawSlot, abuf_other, mbuf_other,
+                                    (uint32_t)pc_next * KC);
+                }
             }
-        }
+        };
+        if (wave < 4) prune_share();
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
@@ -384,6 +389,10 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
             const int ntap = (q + 1) / NKS, nks = (q + 1) % NKS;
             const bool entries_now = has_next && ks == 0 && tap + 1 < TS && NKS > 1;   // read the next tap's entries early
             const bool new_tap = has_next && ntap != tap;
+            if (q == 1) {
+                if (wave >= 4) prune_share();
+                __builtin_amdgcn_sched_barrier(0);
+            }
             // pieces: 0 table entries; 1..APIECES A fragments (two row tiles each); then TN B fragments;
             // in the first k-step also 3 copy pieces
             const int npieces = 1 + APIECES + TN + (q == 0 ? 3 : 0);
