@@ -170,7 +170,9 @@ __host__ __device__ __forceinline__ void prune_compress16_bf16(const uint32_t (&
     static_assert(RK == kGreedy || RK == kAdjusted, "magnitude rankers only");
     constexpr uint32_t kKeyMask = 0xFFFE0001u;  // magnitude and sign
     constexpr uint32_t kCodeMask = 0x1Eu;       // what remains of a dropped key: its position
-    constexpr uint32_t kMark = 0x200u;
+    // the mark tells a kept zero from a dropped slot, which only the rescale has to know; without it the
+    // position code is an inline constant and a key costs two instructions
+    constexpr uint32_t kMark = (RK == kAdjusted) ? 0x200u : 0u;
     const bool two = n >= 2;
     uint32_t f[4], s[4];
 #pragma unroll
