@@ -2,12 +2,22 @@
 // dL/dD = prune(dL/dO) (*) W as an implicit GEMM (Fig. 3 left; Sec. II-A): rows = input pixels, columns = input
 // channels, reduction = taps x output channels, the pruned axis (Fig. 1).
 //
-// Same tiles, copies and tables as bwd_wide.h (eight wavefronts of one kind, 512 or 256 rows x BN columns per workgroup,
-// 32-channel chunks, direct-to-LDS copies, clipped halo, per-(tap, row) address table, result staged through LDS),
-// but a stage is a (chunk, filter row) pair: three taps, 48 dense or 24 sparse matrix instructions per wavefront
-// between two barriers instead of 16 or 8.  What a stage costs besides its matrix instructions -- the barrier and
-// the wait in front of it, the copies and their bookkeeping, the skew between wavefronts -- is paid a third as often,
-// which is what the pruning kernels need: their matrix work per tap is half the dense kernel's.
+// Design, from measurements on gfx950:
+//   * Eight wavefronts, all of one kind: each owns a 128 x 64 register tile of a 512-row x 128-column workgroup tile
+//     (smaller tiles: 256 rows when 512-row tiles cannot fill the chip, 64 columns when C_in <= 64) and issues its
+//     share of the copies itself.  Two matrix wavefronts per SIMD keep the matrix pipe fed while the other one waits
+//     for LDS; tiles of this size keep the LDS read traffic (about 96 KB per 1024 matrix cycles) below what the LDS
+//     delivers.  Dedicated copy wavefronts would cost the registers that such tiles need.
+//   * Every byte from global memory moves with direct-to-LDS loads (lane i of a wavefront writes 16 bytes at LDS
+//     base + 16 i); they need no registers.
+//   * The reduction runs in chunks of 32 channels.  One stage = (chunk, filter row): three taps, 48 dense or 24
+//     sparse matrix instructions per wavefront between two barriers.  What a stage costs besides its matrix
+//     instructions -- the barrier and the wait in front of it, the copies and their bookkeeping, the skew between
+//     wavefronts -- is paid once per three taps.
+//   * The gradient halo of a tile (the pixels its taps reach, clipped to the image) is brought in ONCE per chunk and
+//     shared by all taps; a per-(tap, row) table in LDS maps a tile row to its halo pixel (a zero pixel for taps
+//     outside the image), so nothing is stored or copied for the padding.
+//   * The result leaves through LDS: fp32 -> bf16, then 16-byte stores of whole pixel rows.
 //   * W: the three slabs of the next stage's filter row are requested at the start of a stage into the other half of
 //     a two-set ring and are complete at the barrier that ends it (a stage lasts several copy latencies).
 //   * Dense: the next chunk's halo is copied into the other halo buffer, a share per stage.
@@ -19,7 +29,9 @@
 //     (s_waitcnt vmcnt(0)) before the barrier: no copy has to be counted, no stand-in copies are needed.
 #pragma once
 
-#include "bwd_wide.h"
+#include <type_traits>
+
+#include "lds_copy.h"
 
 namespace sdgp {
 
@@ -40,6 +52,7 @@ struct RowParams {
     int exp;                     // development aid (builds with SDGP_TRACE only): switches parts of the kernel off
 };
 
+constexpr int kRowKC = 32;         // reduction channels per chunk
 constexpr int kRowTaps = 3;        // taps per stage (filter width)
 constexpr int kRowMaxRows = 3;
 
@@ -47,7 +60,7 @@ template <int BN, int MODE, int ROWS>
 struct RowLayout {
     static constexpr bool kSparse = MODE == 2;
     static constexpr int kWRow = BN * 2;
-    static constexpr int kWSlab = kWideKC * kWRow;
+    static constexpr int kWSlab = kRowKC * kWRow;
     static constexpr int kWUnits = kWSlab / 1024;
     static constexpr int kWSet = kRowTaps * kWSlab;            // the slabs of one filter row
     static constexpr int kAPitch = kSparse ? 32 : 64;
@@ -78,7 +91,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     using L = RowLayout<BN, MODE, ROWS>;
     static_assert(ROWS == 512 || ROWS == 256, "rows of a workgroup tile");
     constexpr bool SPARSE = MODE == 2;
-    constexpr int KC = kWideKC;
+    constexpr int KC = kRowKC;
     constexpr int TS = kRowTaps;
     constexpr int WAVES_N = BN / 64;
     constexpr int WAVES_M = 8 / WAVES_N;
@@ -145,7 +158,18 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     //   atab[tap][m]     byte offset, inside a halo buffer, of the gradient pixel that tap `tap` of row m reads
     //                    (dense: with the pixel's swizzle; the zero pixel when the tap falls outside the image)
     //   haloaddr[hp]     address of channel 0 of halo pixel hp
-    if (tid < ROWS) {
+    // The address table of the halo comes first: the first copies need nothing else and fly while the rest is built.
+    for (int hp = tid; hp < L::pad16(nhalo); hp += 512) {
+        size_t gp = 0;  // positions past the halo (tail of the last copy unit) copy pixel 0; nobody reads them
+        if (hp < nhalo) {
+            const int tb = hp / halo_hw, rem = hp % halo_hw;
+            const int b = min(b0 + tb, p.B - 1);  // images past the batch: valid memory, rows never stored
+            gp = ((size_t)b * p.P + (py0 + rem / HTW)) * p.Q + (qx0 + rem % HTW);
+        }
+        haloaddr[hp] = (u64_t)(uintptr_t)(gdO + gp * p.C_out);
+    }
+    auto build_row_tables = [&]() {
+      if (tid < ROWS) {
         const int m = tid;
         int pix = -1, rowbase = 0, h = 0, w = 0;
         bool live = false;
@@ -166,22 +190,14 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 const uint32_t hp = inside ? (uint32_t)(rowbase + (p.pad - r) * HTW + (p.pad - sx)) : zero_pix;
                 atab[(r * TS + sx) * ROWS + m] = SPARSE ? hp * 32u : hp * 64u + (((hp >> 2) & 3u) << 4);
             }
-    }
-    for (int hp = tid; hp < L::pad16(nhalo); hp += 512) {
-        size_t gp = 0;  // positions past the halo (tail of the last copy unit) copy pixel 0; nobody reads them
-        if (hp < nhalo) {
-            const int tb = hp / halo_hw, rem = hp % halo_hw;
-            const int b = min(b0 + tb, p.B - 1);  // images past the batch: valid memory, rows never stored
-            gp = ((size_t)b * p.P + (py0 + rem / HTW)) * p.Q + (qx0 + rem % HTW);
-        }
-        haloaddr[hp] = (u64_t)(uintptr_t)(gdO + gp * p.C_out);
-    }
-    if (tid < 64) {
+      }
+      if (tid < 64) {
         // the zero pixel of both halo buffers; compressed format: values 0 and positions (0, 1) in every quad
         const uint32_t buf = tid >> 5, i = tid & 31;
         if (i < L::kAPitch / 4) *(SDGP_LDS uint32_t*)(smem + off_a + buf * a_buf_bytes + zero_pix * L::kAPitch + i * 4) = 0u;
         if (SPARSE && i == 31) *(SDGP_LDS uint32_t*)(smem + off_meta + buf * meta_buf_bytes + zero_pix * 4) = 0x44444444u;
-    }
+      }
+    };
 
     // ---- copies
     uint32_t w_voff;  // this lane's byte offset inside a slab's source: the wavefront copies unit (wave % WU) of a slab
@@ -198,7 +214,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     auto copy_w_set = [&](int pc, int pr, int set) {
         for (int i = wave; i < TS * WU; i += 8) {
             const int j = i / WU;
-            wide_copy16(gWb + ((size_t)pc * chunkB + (size_t)(pr * TS + j) * tapB), w_voff,
+            lds_copy16(gWb + ((size_t)pc * chunkB + (size_t)(pr * TS + j) * tapB), w_voff,
                         smem_base + L::off_w() + (uint32_t)set * L::kWSet + (uint32_t)j * L::kWSlab + (uint32_t)(wave % WU) * 1024u);
         }
     };
@@ -209,7 +225,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     // unit u of the halo, channels at byte offset src_off of every pixel, to LDS address dst
     auto copy_halo = [&](int u, uint32_t src_off, uint32_t dst) {
         const u64_t a = *(SDGP_LDS u64_t*)(smem + haloaddr_lane + (uint32_t)u * 128u);
-        wide_copy16(reinterpret_cast<const void*>((uintptr_t)(a + (u64_t)(c16_halo + src_off))), dst);
+        lds_copy16(reinterpret_cast<const void*>((uintptr_t)(a + (u64_t)(c16_halo + src_off))), dst);
     };
     // up to two units per wavefront of the share [u0, u0 + cnt) of a chunk's halo; unit u0 + i lands at dst0 + i KB
     auto copy_halo_share = [&](int u0, int cnt, int pc, uint32_t dst0) {
@@ -232,7 +248,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 if constexpr (RK == kRandom)
                     e0 = ((uint64_t)(haloaddr[hp] - (u64_t)(uintptr_t)gdO) >> 1) + (uint64_t)(chan0 + part * 16);
                 uint32_t packed[4], meta;
-                wide_prune16<M, RK>(v, p.n, p.mix, e0, packed, meta);
+                prune16_compressed<M, RK>(v, p.n, p.mix, e0, packed, meta);
                 const u32x4_t x = {packed[0], packed[1], packed[2], packed[3]};
                 *(SDGP_LDS u32x4_t*)(smem + abuf + hp * 32 + part * 16) = x;
                 *(SDGP_LDS uint16_t*)(smem + mbuf + hp * 4 + part * 2) = (uint16_t)meta;
@@ -248,26 +264,33 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
 
-    __syncthreads();  // tables visible
+    __syncthreads();  // halo address table visible
 
-    // ---- prologue: the first chunk's halo, the first stage's slabs, the raw share the first stage prunes
+    // ---- prologue: the first chunk's halo, the first stage's slabs, the raw share the first stage prunes; the row
+    // tables are built while the first copies are in flight
     const int ups = p.ups;
     const int pc1 = c_rot + 1 == nchunks ? 0 : c_rot + 1;  // physical chunk of logical chunk 1
+    copy_w_set(c_rot, r_rot, 0);
     if constexpr (!SPARSE) {
         for (int u = wave; u < nunits; u += 8) copy_halo(u, (uint32_t)c_rot * (KC * 2), smem_base + off_a + u * 1024);
+        build_row_tables();
     } else {
+        // rounds of 16 units through the two raw slots: round r + 1 is in flight while round r is ranked
         const int rounds = (nunits + 15) / 16;
+        copy_halo_share(0, min(16, nunits), c_rot, smem_base + off_raw);
+        build_row_tables();
         for (int r = 0; r < rounds; ++r) {
-            copy_halo_share(r * 16, min(16, nunits - r * 16), c_rot, smem_base + off_raw);
-            wide_wait_copies<0>();
-            __syncthreads();
-            prune_items(wave * 64, 512, r * 16, off_raw, off_a, off_meta, (uint32_t)c_rot * KC);
-            __syncthreads();
+            wait_lds_copies<0>();
+            __syncthreads();  // round r has landed; everybody is done with the slot round r + 1 goes into
+            if (r + 1 < rounds)
+                copy_halo_share((r + 1) * 16, min(16, nunits - (r + 1) * 16), c_rot,
+                                smem_base + off_raw + (uint32_t)((r + 1) & 1) * L::kRawSlot);
+            prune_items(wave * 64, 512, r * 16, off_raw + (uint32_t)(r & 1) * L::kRawSlot, off_a, off_meta, (uint32_t)c_rot * KC);
         }
+        __syncthreads();  // the last round is ranked: raw slot 0 is free again
         if (nchunks > 1) copy_halo_share(0, min(ups, nunits), pc1, smem_base + off_raw);
     }
-    copy_w_set(c_rot, r_rot, 0);
-    wide_wait_copies<0>();
+    wait_lds_copies<0>();
     __syncthreads();
 
     // ---- fragments
@@ -439,7 +462,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 for (; done < upto && done < npieces; ++done) piece(done);
             }
         }
-        wide_wait_copies<0>();
+        wait_lds_copies<0>();
         __syncthreads();  // never optional: the epilogue reuses the tables' LDS as soon as a wavefront leaves the loop
         if (row_last) {
             r = 0, ++c, pc = pc_next;

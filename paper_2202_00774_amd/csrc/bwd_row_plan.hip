@@ -56,7 +56,7 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
     if (n == m) mode = 0;
     else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
     else return 1;
-    if (stride != 1 || S != kRowTaps || R < 1 || R > kRowMaxRows || (C_out % kWideKC) != 0 || (C_in % 8) != 0) return 1;
+    if (stride != 1 || S != kRowTaps || R < 1 || R > kRowMaxRows || (C_out % kRowKC) != 0 || (C_in % 8) != 0) return 1;
     if (mode == 2 && (C_out % m) != 0) return 1;
     if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
     const int ntaps = R * S;
