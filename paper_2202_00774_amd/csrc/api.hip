@@ -11,6 +11,8 @@ int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
 int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                       int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                       hipStream_t stream);
+int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                  int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream);
 int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                    int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                    hipStream_t stream);
@@ -76,7 +78,9 @@ int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, 
         if (rc <= 0) return rc;
     }
     if (dt == SDGP_BF16 && sdgp::is_aligned16(dD)) {
-        int rc = sdgp::bwd_row_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
+        int rc = sdgp::bwd_pw_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
+        if (rc <= 0) return rc;
+        rc = sdgp::bwd_row_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
         if (rc <= 0) return rc;
         rc = sdgp::bwd_conv3_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
         if (rc <= 0) return rc;

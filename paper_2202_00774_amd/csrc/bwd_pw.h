@@ -1,0 +1,302 @@
+// Backward-data kernel for 1x1 stride-1 convolutions and linear layers: dL/dD[rows, C_in] = prune(dL/dO)[rows, C_out] . W
+// (Fig. 2; Sec. II-A).  A plain GEMM whose reduction axis is the pruned one (Fig. 1).  With C_out <= 2048 these layers
+// are bound by reading dL/dO and writing dL/dD once (arithmetic intensity 50-200 FLOP/B), so the kernel is built to
+// stream: a workgroup takes 512 (256) consecutive rows and up to 128 (256) columns -- all of C_in when C_in <= 256,
+// so the gradient is read from HBM exactly once -- and walks the reduction in chunks of 32 channels:
+//   * every byte from global memory moves with direct-to-LDS loads; the chunk after the current one is in flight
+//     while the current one is multiplied (two buffers each for the gradient rows and the 32 x BN slab of W); the
+//     request counter drains in front of the one barrier per chunk;
+//   * pruning (Sec. III-B): the raw rows of chunk s+2 stream in while chunk s+1 is ranked / pruned / compressed (two
+//     values + two 2-bit positions per aligned quad, the operand of v_smfmac_f32_32x32x32_bf16; every n <= 2 pattern
+//     fits it) and chunk s is multiplied;
+//   * eight wavefronts of one kind, register tiles of up to 128 x 64; fragments as in bwd_row.h (swizzled 16-byte
+//     reads for the gradient, transpose reads for W in its native layout);
+//   * the result leaves through LDS as whole rows with 16-byte stores.
+#pragma once
+
+#include <type_traits>
+
+#include "lds_copy.h"
+
+namespace sdgp {
+
+struct PwParams {
+    const uint16_t* dO;
+    const uint16_t* W;
+    uint16_t* dD;
+    long long rows;              // B*H*W
+    int C_out, C_in;
+    int n;
+    uint32_t mix;
+    int ntiles_n, nblocks;
+};
+
+constexpr int kPwKC = 32;  // reduction channels per chunk
+
+template <int BN, int MODE, int ROWS>
+struct PwLayout {
+    static constexpr bool kSparse = MODE == 2;
+    static constexpr int kWRow = BN * 2;
+    static constexpr int kWSlab = kPwKC * kWRow;
+    static constexpr int kWUnits = kWSlab / 1024;
+    static constexpr int kAUnits = ROWS / 16;                  // 1 KB copy units (16 rows x 64 B) of a gradient chunk
+    static constexpr int kABytes = ROWS * (kSparse ? 32 : 64);  // one gradient buffer as the matrix instructions read it
+    static constexpr int kRawBytes = ROWS * 64;
+    static constexpr int kMetaBytes = kSparse ? ROWS * 4 : 0;
+    static constexpr int kOutPitch = BN * 2 + 16;
+    static constexpr int off_w() { return 0; }
+    static constexpr int off_raw() { return off_w() + 2 * kWSlab; }
+    static constexpr int off_a() { return off_raw() + (kSparse ? 2 * kRawBytes : 0); }
+    static constexpr int off_meta() { return off_a() + 2 * kABytes; }
+    static constexpr int loop_bytes() { return off_meta() + 2 * kMetaBytes; }
+    static constexpr int out_bytes() { return ROWS * kOutPitch; }
+    static constexpr int total() { return loop_bytes() > out_bytes() ? loop_bytes() : out_bytes(); }
+};
+
+template <int BN, int MODE, int M, int RK, int ROWS>
+__global__ void __launch_bounds__(512) bwd_pw(const PwParams p) {
+    using L = PwLayout<BN, MODE, ROWS>;
+    static_assert(L::total() <= 160 * 1024, "LDS budget");
+    constexpr bool SPARSE = MODE == 2;
+    constexpr int KC = kPwKC;
+    constexpr int WAVES_N = BN / 64;
+    constexpr int WAVES_M = 8 / WAVES_N;
+    constexpr int WM = ROWS / WAVES_M;
+    constexpr int TM = WM / 32;
+    constexpr int TN = 2;
+    static_assert(TM >= 1 && TM * 32 * WAVES_M == ROWS, "row tiles");
+    constexpr int KSTEP = SPARSE ? 32 : 16;
+    constexpr int NKS = KC / KSTEP;
+    constexpr int CPR = BN / 8;                 // 16-byte columns per W row
+    constexpr int RPU = 1024 / L::kWRow > 0 ? 1024 / L::kWRow : 1;  // W rows per copy unit (BN <= 256: at least two)
+    constexpr int WU = L::kWUnits;
+    constexpr int AU = L::kAUnits;
+
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    SDGP_LDS unsigned char* smem = (SDGP_LDS unsigned char*)smem_generic;
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    // consecutive logical ids stay on one XCD (workgroups are dealt round-robin over 8 XCDs): the column tiles of one
+    // row tile then find the gradient rows in that XCD's L2
+    int lid = blockIdx.x;
+    {
+        const int per = p.nblocks >> 3;
+        if (lid < (per << 3)) lid = (lid & 7) * per + (lid >> 3);
+    }
+    const int ntile = lid % p.ntiles_n;
+    const long long m0 = (long long)(lid / p.ntiles_n) * ROWS;
+    const int n0 = ntile * BN;
+    const int nchunks = p.C_out / KC;
+    const long long last_row = p.rows - 1;
+    const unsigned char* const gdO = reinterpret_cast<const unsigned char*>(p.dO);
+    const unsigned char* const gWb = reinterpret_cast<const unsigned char*>(p.W);
+    const uint32_t rowB = (uint32_t)p.C_out * 2u;      // bytes per gradient row
+    const uint32_t wrowB = (uint32_t)p.C_in * 2u;      // bytes per W row
+
+    // ---- copies.  Gradient: unit u = rows 16u .. 16u+15 of the tile, 64 bytes each; LDS position (lane & 3) of row
+    // (lane >> 2) holds the swizzled source column.  Rows past the tensor re-read the last row (never stored).
+    const uint32_t c16_a = SPARSE ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
+                                  : (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
+    auto copy_a_unit = [&](int u, int chunk, uint32_t dst) {
+        long long row = m0 + u * 16 + (lane >> 2);
+        if (row > last_row) row = last_row;
+        lds_copy16(gdO + ((size_t)row * rowB + (size_t)chunk * (KC * 2) + c16_a), dst);
+    };
+    // W: unit u = rows u*RPU .. of the 32 x BN slab of a chunk, columns swizzled for the transpose reads
+    auto copy_w_unit = [&](int u, int chunk, uint32_t dst) {
+        const int row = u * RPU + lane / CPR;
+        const int lchunk = (lane % CPR) ^ (2 * (row & 3));
+        int col = n0 + lchunk * 8;
+        if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
+        lds_copy16(gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)col * 2u), dst);
+    };
+    // everything chunk `chunk` needs, into buffer set `set` (pruning: the gradient goes to raw slot `set`)
+    auto copy_chunk = [&](int chunk, int set, bool with_w) {
+        const uint32_t a_dst = smem_base + (SPARSE ? L::off_raw() + set * L::kRawBytes : L::off_a() + set * L::kABytes);
+        for (int i = wave; i < AU; i += 8) copy_a_unit(i, chunk, a_dst + (uint32_t)i * 1024u);
+        if (with_w)
+            for (int i = wave; i < WU; i += 8) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
+    };
+    auto copy_w_chunk = [&](int chunk, int set) {
+        for (int i = wave; i < WU; i += 8) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
+    };
+
+    // rank / prune / compress raw slot `set` (chunk `chunk`) into gradient buffer `set`: ROWS * 2 items of 16 channels
+    auto prune_chunk = [&](int chunk, int set) {
+        if constexpr (SPARSE) {
+#pragma unroll 1
+            for (int item = tid; item < ROWS * 2; item += 512) {
+                const int row = item >> 1, part = item & 1;
+                SDGP_LDS unsigned char* src = smem + L::off_raw() + set * L::kRawBytes + row * 64;
+                const int sw = (row >> 2) & 1;
+                u32x4_t v[2];
+                v[0] = *(SDGP_LDS u32x4_t*)(src + (((2 * part) ^ sw) * 16));
+                v[1] = *(SDGP_LDS u32x4_t*)(src + (((2 * part + 1) ^ sw) * 16));
+                uint64_t e0 = 0;
+                if constexpr (RK == kRandom) {
+                    long long grow = m0 + row;
+                    if (grow > last_row) grow = last_row;
+                    e0 = (uint64_t)grow * (uint64_t)p.C_out + (uint64_t)(chunk * KC + part * 16);
+                }
+                uint32_t packed[4], meta;
+                prune16_compressed<M, RK>(v, p.n, p.mix, e0, packed, meta);
+                const u32x4_t x = {packed[0], packed[1], packed[2], packed[3]};
+                *(SDGP_LDS u32x4_t*)(smem + L::off_a() + set * L::kABytes + row * 32 + part * 16) = x;
+                *(SDGP_LDS uint16_t*)(smem + L::off_meta() + set * L::kMetaBytes + row * 4 + part * 2) = (uint16_t)meta;
+            }
+        }
+    };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int t = 0; t < TM; ++t)
+#pragma unroll
+        for (int u = 0; u < TN; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
+
+    // ---- prologue
+    copy_chunk(0, 0, true);
+    if constexpr (SPARSE) {
+        if (nchunks > 1) copy_chunk(1, 1, false);
+        wait_lds_copies<0>();
+        __syncthreads();
+        prune_chunk(0, 0);
+    }
+    wait_lds_copies<0>();
+    __syncthreads();
+
+    // ---- fragments
+    uint32_t b_lane[TN];  // transpose reads from the swizzled slab, one lane address per 32-column tile
+#pragma unroll
+    for (int u = 0; u < TN; ++u) {
+        const int L16 = lane & 15;
+        const int chunk = 8 * wn + 4 * u + 2 * ((lane >> 4) & 1) + ((L16 & 3) >> 1);
+        b_lane[u] = (uint32_t)(L::off_w() + (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (2 * (L16 >> 2))) * 16) +
+                               (L16 & 1) * 8);
+    }
+    const uint32_t half = (uint32_t)(lane >> 5);
+    uint32_t a_lane[TM];  // this lane's row of each row tile inside a gradient buffer (swizzle included)
+    uint32_t m_lane[TM];
+#pragma unroll
+    for (int t = 0; t < TM; ++t) {
+        const uint32_t row = (uint32_t)(wm * WM + t * 32 + (lane & 31));
+        a_lane[t] = SPARSE ? row * 32u + half * 16u : row * 64u + (((half ^ (row >> 2)) & 3u) << 4);
+        m_lane[t] = row * 4u + half * 2u;
+    }
+    struct Frags {
+        u32x4_t a[TM];
+        int meta[TM];
+        typename std::conditional<SPARSE, bf16x16_t, bf16x8_t>::type b[TN];
+    };
+    auto load_frags = [&](Frags& f, int set, int ks) {
+#pragma unroll
+        for (int t = 0; t < TM; ++t) {
+            if constexpr (SPARSE) {
+                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + L::off_a() + set * L::kABytes + a_lane[t]);
+                f.meta[t] = *(SDGP_LDS uint16_t*)(smem + L::off_meta() + set * L::kMetaBytes + m_lane[t]);
+            } else {
+                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + L::off_a() + set * L::kABytes + (a_lane[t] ^ (uint32_t)(ks * 32)));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < TN; ++u) {
+            SDGP_LDS unsigned char* wb = smem + b_lane[u] + set * L::kWSlab;
+            if constexpr (SPARSE) {
+                s16x4_t q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + ((i >> 1) * 16 + (i & 1) * 4) * L::kWRow));
+                typedef short s16x16_t __attribute__((ext_vector_type(16)));
+                const s16x16_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3],
+                                      q[2][0], q[2][1], q[2][2], q[2][3], q[3][0], q[3][1], q[3][2], q[3][3]};
+                f.b[u] = __builtin_bit_cast(bf16x16_t, all);
+            } else {
+                s16x4_t q[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + (ks * 16 + i * 4) * L::kWRow));
+                typedef short s16x8_t __attribute__((ext_vector_type(8)));
+                const s16x8_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3]};
+                f.b[u] = __builtin_bit_cast(bf16x8_t, all);
+            }
+        }
+    };
+    auto mma = [&](const Frags& f) {
+#pragma unroll
+        for (int t = 0; t < TM; ++t) {
+            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, f.a[t]);
+#pragma unroll
+            for (int u = 0; u < TN; ++u) {
+                if constexpr (SPARSE)
+                    acc[t][u] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, f.b[u], acc[t][u], f.meta[t], 0, 0);
+                else
+                    acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, f.b[u], acc[t][u], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- main loop: one chunk per stage
+    Frags fr[2];
+    for (int s = 0; s < nchunks; ++s) {
+        const int set = s & 1;
+        // requests for what comes next: dense -- chunk s+1 into the other buffers; pruning -- W of chunk s+1 and the
+        // raw rows of chunk s+2 (into the slot whose rows were ranked during the previous stage)
+        if constexpr (SPARSE) {
+            if (s + 1 < nchunks) copy_w_chunk(s + 1, set ^ 1);
+            if (s + 2 < nchunks) {
+                const uint32_t a_dst = smem_base + L::off_raw() + set * L::kRawBytes;
+                for (int i = wave; i < AU; i += 8) copy_a_unit(i, s + 2, a_dst + (uint32_t)i * 1024u);
+            }
+        } else {
+            if (s + 1 < nchunks) copy_chunk(s + 1, set ^ 1, true);
+        }
+        load_frags(fr[0], set, 0);
+        if constexpr (SPARSE) {
+            if (s + 1 < nchunks) prune_chunk(s + 1, set ^ 1);  // its raw rows landed before the last barrier
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            if (ks + 1 < NKS) load_frags(fr[(ks + 1) & 1], set, ks + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(fr[ks & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wait_lds_copies<0>();
+        __syncthreads();
+    }
+
+    // ---- epilogue: fp32 -> bf16 (RNE) into LDS, then whole rows with 16-byte stores
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int tt = 0; tt < TM; ++tt)
+#pragma unroll
+        for (int u = 0; u < TN; ++u)
+#pragma unroll
+            for (int rr = 0; rr < 16; rr += 2) {
+                // registers rr and rr + 1 are two consecutive rows of one column
+                const int m = wm * WM + tt * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
+                const int col = wn * 64 + u * 32 + (lane & 31);
+                const f32x2_t v = {acc[tt][u][rr], acc[tt][u][rr + 1]};
+                const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+                *(SDGP_LDS uint16_t*)(smem + m * L::kOutPitch + col * 2) = (uint16_t)pk;
+                *(SDGP_LDS uint16_t*)(smem + (m + 1) * L::kOutPitch + col * 2) = (uint16_t)(pk >> 16);
+            }
+    __syncthreads();
+#pragma unroll 4
+    for (int idx = tid; idx < ROWS * CPR; idx += 512) {
+        const int m = idx / CPR, cc = idx % CPR;
+        const long long row = m0 + m;
+        if (row <= last_row && n0 + cc * 8 < p.C_in) {
+            const u32x4_t v = *(SDGP_LDS u32x4_t*)(smem + m * L::kOutPitch + cc * 16);
+            *reinterpret_cast<u32x4_t*>(p.dD + (size_t)row * p.C_in + n0 + cc * 8) = v;
+        }
+    }
+}
+
+}  // namespace sdgp

@@ -1,0 +1,7 @@
+// Instantiates the pointwise kernel without pruning (n == m): the dense baseline of the 1x1 and linear layers.
+#include "bwd_pw_launch.h"
+namespace sdgp {
+int launch_pw_dense(const PwParams& p, int shape, hipStream_t stream) {
+    return launch_pw_shape<0, 4, kGreedy>(p, shape, stream);
+}
+}  // namespace sdgp

@@ -1,0 +1,7 @@
+// Instantiates the pointwise kernel for n <= 2 of m = 4 (structured-sparse matrix instruction).
+#include "bwd_pw_launch.h"
+namespace sdgp {
+int launch_pw_sparse_m4(const PwParams& p, int shape, int rk, hipStream_t stream) {
+    return launch_pw_rk<2, 4>(p, shape, rk, stream);
+}
+}  // namespace sdgp

@@ -179,3 +179,38 @@ def test_resnet9_batch512_sampled(index):
     pixels = sample_pixels(layer, 4096, 100 + index)
     for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (2, 4, oracle.RANDOM), (4, 4, oracle.GREEDY)):
         check_conv(layer, dO, W, n, m, ranker, 0, oracle.BF16, pixels=pixels)
+
+
+# ------------------------------------------------- pointwise kernel (1x1 convolutions and linear layers with many rows)
+
+POINTWISE_CONVS = [
+    wl.ConvLayer("pw_256x256_n264", 64, 23, 23, 264, 64, 1, 1, 1, 0),   # 256-row x 256-column tiles, ragged rows and columns
+    wl.ConvLayer("pw_256x128_n264", 32, 16, 16, 264, 96, 1, 1, 1, 0),   # fewer rows: 256 x 128 tiles, three column tiles
+    wl.ConvLayer("pw_512x128", 128, 32, 32, 128, 32, 1, 1, 1, 0),       # 512-row x 128-column tiles, one chunk
+    wl.ConvLayer("pw_512x64_n24", 129, 16, 16, 24, 96, 1, 1, 1, 0),     # 64-column tiles, 24 live columns, ragged rows
+]
+
+
+@pytest.mark.parametrize("layer", POINTWISE_CONVS, ids=lambda l: l.name)
+def test_pointwise_conv_matches_oracle(layer):
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=91, dtype=oracle.BF16)
+    pixels = sample_pixels(layer, 1500, 7)
+    for n, m, ranker in ((4, 4, oracle.GREEDY), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED),
+                         (2, 4, oracle.RANDOM), (1, 4, oracle.GREEDY), (2, 8, oracle.RANDOM),
+                         (2, 16, oracle.GREEDY_ADJUSTED), (2, 16, oracle.GREEDY)):
+        check_conv(layer, dO, W, n, m, ranker, 13, oracle.BF16, pixels=pixels)
+
+
+def test_pointwise_linear_matches_oracle():
+    rows, C_out, C_in = 40001, 64, 136
+    dO = wl.laplace_with_zeros((rows, C_out), 1e-3, 0.3, seed=17, dtype=oracle.BF16)
+    W = wl.normal((C_out, C_in), 0.1, 18, oracle.BF16)
+    sample = np.unique(np.concatenate([np.array([0, rows - 1, rows - 2]), np.random.default_rng(3).integers(0, rows, 3000)]))
+    d, w = to_gpu(dO), to_gpu(W)
+    for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 8, oracle.GREEDY_ADJUSTED), (2, 4, oracle.RANDOM), (4, 4, oracle.GREEDY)):
+        pruned = oracle.prune(dO, n, m, ranker, seed=5)[0]
+        ref, ab = oracle.linear_bwd_data(pruned[sample], W)
+        out = sdgp.sdgp_linear_bwd_data(d, w, n, m, ranker, 5)
+        torch.cuda.synchronize()
+        err = rel_error(got_f64(out)[sample], ref, ab)
+        assert err <= TOL[oracle.BF16], (n, m, ranker, err)
