@@ -1,15 +1,15 @@
 // Backward-data kernel for 1x1 stride-1 convolutions and linear layers: dL/dD[rows, C_in] = prune(dL/dO)[rows, C_out] . W
 // (Fig. 2; Sec. II-A).  A plain GEMM whose reduction axis is the pruned one (Fig. 1).  With C_out <= 2048 these layers
 // are bound by reading dL/dO and writing dL/dD once (arithmetic intensity 50-200 FLOP/B), so the kernel is built to
-// stream: a workgroup takes 512 (256) consecutive rows and up to 128 (256) columns -- all of C_in when C_in <= 256,
-// so the gradient is read from HBM exactly once -- and walks the reduction in chunks of 32 channels:
+// stream: a workgroup takes 128 or 256 consecutive rows and 64 to 256 columns (the host picks the shape) and walks the
+// reduction in chunks of 32 channels:
 //   * every byte from global memory moves with direct-to-LDS loads; the chunk after the current one is in flight
 //     while the current one is multiplied (two buffers each for the gradient rows and the 32 x BN slab of W); the
 //     request counter drains in front of the one barrier per chunk;
 //   * pruning (Sec. III-B): the raw rows of chunk s+2 stream in while chunk s+1 is ranked / pruned / compressed (two
 //     values + two 2-bit positions per aligned quad, the operand of v_smfmac_f32_32x32x32_bf16; every n <= 2 pattern
 //     fits it) and chunk s is multiplied;
-//   * eight wavefronts of one kind, register tiles of up to 128 x 64; fragments as in bwd_row.h (swizzled 16-byte
+//   * wavefronts of one kind, register tiles of up to 128 x 64, two workgroups to a CU; fragments as in bwd_row.h (swizzled 16-byte
 //     reads for the gradient, transpose reads for W in its native layout);
 //   * the result leaves through LDS as whole rows with 16-byte stores.
 #pragma once
@@ -53,18 +53,19 @@ struct PwLayout {
     static constexpr int total() { return loop_bytes() > out_bytes() ? loop_bytes() : out_bytes(); }
 };
 
-template <int BN, int MODE, int M, int RK, int ROWS>
-__global__ void __launch_bounds__(512) bwd_pw(const PwParams p) {
+template <int BN, int MODE, int M, int RK, int ROWS, int NW>
+__global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     using L = PwLayout<BN, MODE, ROWS>;
     static_assert(L::total() <= 160 * 1024, "LDS budget");
     constexpr bool SPARSE = MODE == 2;
     constexpr int KC = kPwKC;
     constexpr int WAVES_N = BN / 64;
-    constexpr int WAVES_M = 8 / WAVES_N;
+    constexpr int WAVES_M = NW / WAVES_N;
+    constexpr int NT = NW * 64;
     constexpr int WM = ROWS / WAVES_M;
     constexpr int TM = WM / 32;
     constexpr int TN = 2;
-    static_assert(TM >= 1 && TM * 32 * WAVES_M == ROWS, "row tiles");
+    static_assert(WAVES_M >= 1 && TM >= 1 && TM * 32 * WAVES_M == ROWS, "row tiles");
     constexpr int KSTEP = SPARSE ? 32 : 16;
     constexpr int NKS = KC / KSTEP;
     constexpr int CPR = BN / 8;                 // 16-byte columns per W row
@@ -117,19 +118,19 @@ __global__ void __launch_bounds__(512) bwd_pw(const PwParams p) {
     // everything chunk `chunk` needs, into buffer set `set` (pruning: the gradient goes to raw slot `set`)
     auto copy_chunk = [&](int chunk, int set, bool with_w) {
         const uint32_t a_dst = smem_base + (SPARSE ? L::off_raw() + set * L::kRawBytes : L::off_a() + set * L::kABytes);
-        for (int i = wave; i < AU; i += 8) copy_a_unit(i, chunk, a_dst + (uint32_t)i * 1024u);
+        for (int i = wave; i < AU; i += NW) copy_a_unit(i, chunk, a_dst + (uint32_t)i * 1024u);
         if (with_w)
-            for (int i = wave; i < WU; i += 8) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
+            for (int i = wave; i < WU; i += NW) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
     };
     auto copy_w_chunk = [&](int chunk, int set) {
-        for (int i = wave; i < WU; i += 8) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
+        for (int i = wave; i < WU; i += NW) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
     };
 
     // rank / prune / compress raw slot `set` (chunk `chunk`) into gradient buffer `set`: ROWS * 2 items of 16 channels
     auto prune_chunk = [&](int chunk, int set) {
         if constexpr (SPARSE) {
 #pragma unroll 1
-            for (int item = tid; item < ROWS * 2; item += 512) {
+            for (int item = tid; item < ROWS * 2; item += NT) {
                 const int row = item >> 1, part = item & 1;
                 SDGP_LDS unsigned char* src = smem + L::off_raw() + set * L::kRawBytes + row * 64;
                 const int sw = (row >> 2) & 1;
@@ -250,7 +251,7 @@ __global__ void __launch_bounds__(512) bwd_pw(const PwParams p) {
             if (s + 1 < nchunks) copy_w_chunk(s + 1, set ^ 1);
             if (s + 2 < nchunks) {
                 const uint32_t a_dst = smem_base + L::off_raw() + set * L::kRawBytes;
-                for (int i = wave; i < AU; i += 8) copy_a_unit(i, s + 2, a_dst + (uint32_t)i * 1024u);
+                for (int i = wave; i < AU; i += NW) copy_a_unit(i, s + 2, a_dst + (uint32_t)i * 1024u);
             }
         } else {
             if (s + 1 < nchunks) copy_chunk(s + 1, set ^ 1, true);
@@ -289,7 +290,7 @@ __global__ void __launch_bounds__(512) bwd_pw(const PwParams p) {
             }
     __syncthreads();
 #pragma unroll 4
-    for (int idx = tid; idx < ROWS * CPR; idx += 512) {
+    for (int idx = tid; idx < ROWS * CPR; idx += NT) {
         const int m = idx / CPR, cc = idx % CPR;
         const long long row = m0 + m;
         if (row <= last_row && n0 + cc * 8 < p.C_in) {

@@ -5,25 +5,34 @@
 
 namespace sdgp {
 
-template <int BN, int MODE, int M, int RK, int ROWS>
+template <int BN, int MODE, int M, int RK, int ROWS, int NW>
 int launch_pw_one(const PwParams& p, hipStream_t stream) {
     using L = PwLayout<BN, MODE, ROWS>;
-    auto kern = bwd_pw<BN, MODE, M, RK, ROWS>;
+    auto kern = bwd_pw<BN, MODE, M, RK, ROWS, NW>;
     static const hipError_t attr =
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return SDGP_ERR_HIP;
-    hipLaunchKernelGGL(kern, dim3(p.nblocks), dim3(512), L::total(), stream, p);
+    hipLaunchKernelGGL(kern, dim3(p.nblocks), dim3(NW * 64), L::total(), stream, p);
     return launch_status();
 }
 
-// shape: 0 = 256 rows x 256 columns, 1 = 512 x 128, 2 = 256 x 128, 3 = 512 x 64
+// tile shapes: columns, rows, wavefronts
+struct PwShape {
+    int bn, rows, waves;
+};
+constexpr PwShape kPwShapes[] = {{256, 128, 4}, {128, 128, 4}, {64, 256, 4}};
+constexpr int kPwNumShapes = sizeof(kPwShapes) / sizeof(kPwShapes[0]);
+
 template <int MODE, int M, int RK>
 int launch_pw_shape(const PwParams& p, int shape, hipStream_t stream) {
     switch (shape) {
-        case 0: return launch_pw_one<256, MODE, M, RK, 256>(p, stream);
-        case 1: return launch_pw_one<128, MODE, M, RK, 512>(p, stream);
-        case 2: return launch_pw_one<128, MODE, M, RK, 256>(p, stream);
-        default: return launch_pw_one<64, MODE, M, RK, 512>(p, stream);
+#define SDGP_PW_CASE(i) \
+    case i: return launch_pw_one<kPwShapes[i].bn, MODE, M, RK, kPwShapes[i].rows, kPwShapes[i].waves>(p, stream);
+        SDGP_PW_CASE(0)
+        SDGP_PW_CASE(1)
+        SDGP_PW_CASE(2)
+#undef SDGP_PW_CASE
+        default: return SDGP_ERR_SHAPE;
     }
 }
 

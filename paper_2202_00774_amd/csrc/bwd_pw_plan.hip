@@ -1,8 +1,9 @@
 // Host side of the pointwise kernel: 1x1 stride-1 convolutions without padding and linear layers whose channel
 // counts fit (C_out a multiple of 32, C_in a multiple of 8); chooses the tile shape and launches.
 #include <climits>
+#include <cstdlib>
 
-#include "bwd_pw.h"
+#include "bwd_pw_launch.h"
 
 namespace sdgp {
 
@@ -32,19 +33,22 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     p.n = n;
     p.mix = seed_mix(seed);
 
-    // tile shape: all of C_in in one workgroup when it fits (the gradient is then read from HBM once); the larger
-    // row tile when it still gives every CU a workgroup
+    // tile shape.  Workgroups of four wavefronts, two to a CU, so that one's loads and stores overlap the other's
+    // arithmetic.  Pruning: all of C_in (up to 256 columns) in one workgroup, so every gradient row is ranked once;
+    // dense: 128 x 128 tiles measured fastest (column tiles of one row tile run side by side on one XCD and find
+    // the gradient rows in its L2).
     auto blocks_of = [&](int rows_per, int bn) { return ((rows + rows_per - 1) / rows_per) * ((C_in + bn - 1) / bn); };
-    int shape, bn, rows_per;
-    if (C_in > 128) {
-        if (blocks_of(256, 256) >= 256) shape = 0, bn = 256, rows_per = 256;
-        else shape = 2, bn = 128, rows_per = 256;
-    } else if (C_in > 64) {
-        if (blocks_of(512, 128) >= 256) shape = 1, bn = 128, rows_per = 512;
-        else shape = 2, bn = 128, rows_per = 256;
-    } else {
-        shape = 3, bn = 64, rows_per = 512;
+    int shape;
+    if (C_in <= 64) shape = 2;
+    else if (mode == 2 && C_in > 128) shape = 0;
+    else shape = 1;
+#ifdef SDGP_TRACE
+    if (const char* e = getenv("SDGP_PW_SHAPE")) {
+        const int v = atoi(e);
+        if (v >= 0 && v < kPwNumShapes) shape = v;
     }
+#endif
+    const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
     const int64_t blocks = blocks_of(rows_per, bn);
     if (blocks < 64 || blocks >= INT_MAX) return 1;  // too small to be worth a matrix-core launch of this shape
     p.ntiles_n = (int)((C_in + bn - 1) / bn);

@@ -184,10 +184,10 @@ def test_resnet9_batch512_sampled(index):
 # ------------------------------------------------- pointwise kernel (1x1 convolutions and linear layers with many rows)
 
 POINTWISE_CONVS = [
-    wl.ConvLayer("pw_256x256_n264", 64, 23, 23, 264, 64, 1, 1, 1, 0),   # 256-row x 256-column tiles, ragged rows and columns
-    wl.ConvLayer("pw_256x128_n264", 32, 16, 16, 264, 96, 1, 1, 1, 0),   # fewer rows: 256 x 128 tiles, three column tiles
-    wl.ConvLayer("pw_512x128", 128, 32, 32, 128, 32, 1, 1, 1, 0),       # 512-row x 128-column tiles, one chunk
-    wl.ConvLayer("pw_512x64_n24", 129, 16, 16, 24, 96, 1, 1, 1, 0),     # 64-column tiles, 24 live columns, ragged rows
+    wl.ConvLayer("pw_n264", 64, 23, 23, 264, 64, 1, 1, 1, 0),     # several column tiles, ragged rows and columns
+    wl.ConvLayer("pw_n264_few_rows", 32, 16, 16, 264, 96, 1, 1, 1, 0),
+    wl.ConvLayer("pw_n128", 128, 32, 32, 128, 32, 1, 1, 1, 0),    # one column tile, one reduction chunk
+    wl.ConvLayer("pw_n24", 129, 16, 16, 24, 96, 1, 1, 1, 0),      # 24 live columns of a 64-column tile, ragged rows
 ]
 
 
