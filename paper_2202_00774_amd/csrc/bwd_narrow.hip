@@ -1,10 +1,13 @@
-// Backward-data for layers with very few input channels (C_in <= 4: the first convolution of a network).
-//
-// With three columns the product is not matrix-core work: it is bound by reading dL/dO once.  A workgroup owns a
-// TH x TW tile of input pixels of one image.  It brings every gradient pixel its taps can reach into LDS once,
-// pruning each m-group with the register ranker on the way (Sec. III-B; stored dense with zeros), converts the
-// filter to fp32 in LDS, and then every thread accumulates its own pixel over taps and channels on the vector
-// ALU (Fig. 3 left, any filter size, stride and padding).  bf16 storage, fp32 accumulation.
+// Backward-data for layers with very few input channels (C_in <= 4: the first convolution of a network); the layer
+// is bound by reading dL/dO once.  A workgroup owns a TH x TW tile of input pixels of one image and brings every
+// gradient pixel its taps can reach into LDS once, pruning each m-group with the register ranker on the way
+// (Sec. III-B; stored dense with zeros).  Two kernels (Fig. 3 left, any filter size, stride and padding; bf16 storage,
+// fp32 accumulation):
+//   * bwd_narrow_mm, when taps x C_in <= 64: with so few columns per tap the product is turned around.  The matrix
+//     cores compute T[gradient pixel][tap, c] = sum_k prune(dL/dO)[pixel][k] W[k][tap][c] -- a plain GEMM with
+//     taps x C_in columns (27 for a 3x3 filter on RGB, padded to 32) -- into LDS, and every thread then sums, for
+//     its input pixel, the one entry per tap that belongs to it.
+//   * bwd_narrow, otherwise: every thread accumulates its own pixel over taps and channels on the vector ALU.
 #include "ranker.h"
 
 namespace sdgp {
@@ -143,8 +146,188 @@ __global__ void __launch_bounds__(256) bwd_narrow(const NarrowParams p) {
     }
 }
 
+typedef __bf16 bf16x8n __attribute__((ext_vector_type(8)));
+typedef float f32x16n __attribute__((ext_vector_type(16)));
+
+constexpr int kMmRowTiles = 3;  // 32-pixel row tiles per wavefront: four wavefronts cover up to 384 gradient pixels
+
+// Matrix-core variant; NT = 32-column tiles of (tap, c) pairs.
+template <int M, int RK, bool PRUNE, bool NLE2, int NT>
+__global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    SDGP_LDSN unsigned char* smem = (SDGP_LDSN unsigned char*)smem_generic;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile = blockIdx.x;
+    const int tw_i = tile % p.tiles_w, th_i = (tile / p.tiles_w) % p.tiles_h, b = tile / (p.tiles_w * p.tiles_h);
+    const int h0 = th_i * p.TH, w0 = tw_i * p.TW;
+    const int lo_h = h0 + p.pad - (p.R - 1), lo_w = w0 + p.pad - (p.S - 1);
+    const int pmin = lo_h <= 0 ? 0 : (lo_h + p.stride - 1) / p.stride;
+    const int qmin = lo_w <= 0 ? 0 : (lo_w + p.stride - 1) / p.stride;
+    const int npix = p.HP * p.HQ;
+    const int nrt = (npix + 31) >> 5;           // row tiles; rows past npix hold whatever LDS held: nobody reads their results
+    const int taps = p.R * p.S;
+    const int J = taps * p.C_in;                // live columns
+    constexpr int TP = NT * 32 + 1;             // floats per row of T (odd: the gather walks rows)
+
+    SDGP_LDSN unsigned char* lds_a = smem;                          // [nrt * 32][kAPitchN]   gradient, 64 channels
+    SDGP_LDSN unsigned char* lds_wt = smem + nrt * 32 * kAPitchN;   // [NT * 32][kAPitchN]    filter slice, transposed
+    SDGP_LDSN float* lds_t = (SDGP_LDSN float*)smem;                // [nrt * 32][TP]         after the last chunk
+
+    f32x16n acc[kMmRowTiles][NT];
+#pragma unroll
+    for (int t = 0; t < kMmRowTiles; ++t)
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
+
+    for (int kc0 = 0; kc0 < p.C_out; kc0 += kNarrowKC) {
+        __syncthreads();
+        // ---- gradient halo, pruned, into LDS (16 channels per item)
+        for (int it = tid; it < npix * (kNarrowKC / 16); it += 256) {
+            const int hp = it >> 2, part = it & 3;
+            const int pp = pmin + hp / p.HQ, qq = qmin + hp % p.HQ;
+            const int k = kc0 + part * 16;
+            u32x4n v[2] = {u32x4n{0u, 0u, 0u, 0u}, u32x4n{0u, 0u, 0u, 0u}};
+            const bool ok = pp < p.P && qq < p.Q;
+            const size_t gp = ok ? ((size_t)(b * p.P + pp) * p.Q + qq) : 0;
+            if (ok) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    if (k + i * 8 < p.C_out)
+                        v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4n*>(p.dO + gp * p.C_out + k + i * 8));
+            }
+            if constexpr (PRUNE) {
+                uint32_t raw[16], out[16];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
+                        raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
+                    }
+                const uint64_t e0 = (uint64_t)gp * (uint64_t)p.C_out + (uint64_t)k;
+#pragma unroll
+                for (int g = 0; g < 16 / M; ++g) {
+                    uint32_t r[M], o[M];
+                    bool kk[M];
+#pragma unroll
+                    for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
+                    const uint64_t eg = e0 + (uint64_t)(g * M);
+                    prune_group<kBF16, M, RK, NLE2>(r, p.n, hash_row(p.mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+#pragma unroll
+                    for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) v[i][x] = out[i * 8 + 2 * x] | (out[i * 8 + 2 * x + 1] << 16);
+            }
+            *(SDGP_LDSN u32x4n*)(lds_a + hp * kAPitchN + part * 32) = v[0];
+            *(SDGP_LDSN u32x4n*)(lds_a + hp * kAPitchN + part * 32 + 16) = v[1];
+        }
+        // ---- filter slice [kc0, kc0 + 64) x (tap, c), transposed: column j = tap * C_in + c, channels contiguous
+        for (int it = tid; it < kNarrowKC * NT * 32; it += 256) {
+            const int kk = it / (NT * 32), j = it % (NT * 32);
+            uint16_t wv = 0;
+            if (j < J && kc0 + kk < p.C_out) wv = p.W[(size_t)(kc0 + kk) * J + j];
+            *(SDGP_LDSN uint16_t*)(lds_wt + j * kAPitchN + kk * 2) = wv;
+        }
+        __syncthreads();
+
+        // ---- T += gradient x filter slice; wavefront w owns row tiles w, w + 4, w + 8
+        const int frag = (lane & 31) * kAPitchN + (lane >> 5) * 16;
+#pragma unroll
+        for (int ks = 0; ks < kNarrowKC / 16; ++ks) {
+            bf16x8n bfr[NT];
+#pragma unroll
+            for (int u = 0; u < NT; ++u)
+                bfr[u] = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(lds_wt + u * 32 * kAPitchN + frag + ks * 32));
+#pragma unroll
+            for (int t = 0; t < kMmRowTiles; ++t) {
+                const int rt = wave + 4 * t;
+                if (rt < nrt) {
+                    const bf16x8n afr = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(lds_a + rt * 32 * kAPitchN + frag + ks * 32));
+#pragma unroll
+                    for (int u = 0; u < NT; ++u) acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afr, bfr[u], acc[t][u], 0, 0, 0);
+                }
+            }
+        }
+    }
+    __syncthreads();  // every fragment is read: T takes the place of the gradient
+#pragma unroll
+    for (int t = 0; t < kMmRowTiles; ++t) {
+        const int rt = wave + 4 * t;
+        if (rt < nrt) {
+#pragma unroll
+            for (int u = 0; u < NT; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = rt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    lds_t[row * TP + u * 32 + (lane & 31)] = acc[t][u][r];
+                }
+        }
+    }
+    __syncthreads();
+
+    // ---- every input pixel sums the entry of each tap that reaches it
+    const int th = tid / p.TW, tw = tid % p.TW;
+    const int h = h0 + th, w = w0 + tw;
+    if (tid < p.TH * p.TW && h < p.H && w < p.Wd) {
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < p.R; ++r) {
+            const int hr = h + p.pad - r;
+            if (hr < 0 || hr % p.stride != 0) continue;
+            const int pp = hr / p.stride;
+            if (pp >= p.P) continue;
+            for (int s = 0; s < p.S; ++s) {
+                const int ws = w + p.pad - s;
+                if (ws < 0 || ws % p.stride != 0) continue;
+                const int qq = ws / p.stride;
+                if (qq >= p.Q) continue;
+                const int hp = (pp - pmin) * p.HQ + (qq - qmin);
+                const SDGP_LDSN float* trow = lds_t + hp * TP + (r * p.S + s) * p.C_in;
+                for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
+            }
+        }
+        uint16_t* dst = p.dD + ((size_t)(b * p.H + h) * p.Wd + w) * p.C_in;
+        for (int c = 0; c < p.C_in; ++c) dst[c] = (uint16_t)float_to_bf16(sum[c]);
+    }
+}
+
+// LDS bytes of bwd_narrow_mm for a tile of npix gradient pixels and nt column tiles.
+int narrow_mm_lds(int npix, int nt) {
+    const int rows = ((npix + 31) / 32) * 32;
+    const int loop = rows * kAPitchN + nt * 32 * kAPitchN;
+    const int t = rows * (nt * 32 + 1) * 4;
+    return loop > t ? loop : t;
+}
+
+template <int M, int RK, bool PRUNE, bool NLE2>
+int launch_narrow_mm(const NarrowParams& p, int nt, int grid, hipStream_t stream) {
+    const int lds = narrow_mm_lds(p.HP * p.HQ, nt);
+#define SDGP_NARROW_MM(NTV)                                                                                           \
+    {                                                                                                                 \
+        auto kern = bwd_narrow_mm<M, RK, PRUNE, NLE2, NTV>;                                                           \
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);   \
+        if (attr != hipSuccess) return SDGP_ERR_HIP;                                                                  \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, p);                                              \
+    }
+    if (nt == 1) SDGP_NARROW_MM(1)
+    else SDGP_NARROW_MM(2)
+#undef SDGP_NARROW_MM
+    return launch_status();
+}
+
 template <int M, bool NLE2>
-int launch_narrow_rk(const NarrowParams& p, int rk, int grid, int lds, hipStream_t stream) {
+int launch_narrow_rk(const NarrowParams& p, int rk, int nt, int grid, int lds, hipStream_t stream) {
+    if (nt > 0) {
+        if (rk == kRandom) return launch_narrow_mm<M, kRandom, true, NLE2>(p, nt, grid, stream);
+        if (rk == kGreedy) return launch_narrow_mm<M, kGreedy, true, NLE2>(p, nt, grid, stream);
+        return launch_narrow_mm<M, kAdjusted, true, NLE2>(p, nt, grid, stream);
+    }
 #define SDGP_NARROW(RKV)                                                                                              \
     {                                                                                                                 \
         auto kern = bwd_narrow<M, RKV, true, NLE2>;                                                                   \
@@ -181,9 +364,14 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
     p.HP = (p.TH - 1 + R - 1) / stride + 2, p.HQ = (p.TW - 1 + S - 1) / stride + 2;
     const int64_t grid = (int64_t)B * p.tiles_h * p.tiles_w;
     if (grid >= INT32_MAX) return 1;
-    const int lds = ((p.HP * p.HQ * kAPitchN + 15) & ~15) + kNarrowKC * R * S * 16;
-    if (lds > 160 * 1024) return 1;
     if (grid == 0) return SDGP_OK;
+    // the matrix-core variant when its columns, row tiles and LDS fit; else the vector-ALU one
+    const int J = R * S * (int)C_in, npix = p.HP * p.HQ;
+    int nt = J <= 32 ? 1 : (J <= 64 ? 2 : 0);
+    if (nt > 0 && ((npix + 31) / 32 > 4 * kMmRowTiles || narrow_mm_lds(npix, nt) > 160 * 1024)) nt = 0;
+    const int lds = ((npix * kAPitchN + 15) & ~15) + kNarrowKC * R * S * 16;
+    if (nt == 0 && lds > 160 * 1024) return 1;
+    if (dense && nt > 0) return launch_narrow_mm<4, kGreedy, false, true>(p, nt, (int)grid, stream);
     if (dense) {
         auto kern = bwd_narrow<4, kGreedy, false, true>;
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -193,9 +381,9 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
         return launch_status();
     }
     const bool nle2 = n <= 2;
-    if (m == 4) return nle2 ? launch_narrow_rk<4, true>(p, rk, (int)grid, lds, stream) : launch_narrow_rk<4, false>(p, rk, (int)grid, lds, stream);
-    if (m == 8) return nle2 ? launch_narrow_rk<8, true>(p, rk, (int)grid, lds, stream) : launch_narrow_rk<8, false>(p, rk, (int)grid, lds, stream);
-    return nle2 ? launch_narrow_rk<16, true>(p, rk, (int)grid, lds, stream) : launch_narrow_rk<16, false>(p, rk, (int)grid, lds, stream);
+    if (m == 4) return nle2 ? launch_narrow_rk<4, true>(p, rk, nt, (int)grid, lds, stream) : launch_narrow_rk<4, false>(p, rk, nt, (int)grid, lds, stream);
+    if (m == 8) return nle2 ? launch_narrow_rk<8, true>(p, rk, nt, (int)grid, lds, stream) : launch_narrow_rk<8, false>(p, rk, nt, (int)grid, lds, stream);
+    return nle2 ? launch_narrow_rk<16, true>(p, rk, nt, (int)grid, lds, stream) : launch_narrow_rk<16, false>(p, rk, nt, (int)grid, lds, stream);
 }
 
 }  // namespace sdgp

@@ -98,6 +98,12 @@ SMALL_CONVS = [
     wl.ConvLayer("c4x4img", 20, 4, 4, 64, 64, 3, 3, 1, 1),
     wl.ConvLayer("c7x7img", 5, 7, 7, 64, 64, 3, 3, 1, 1),
     wl.ConvLayer("c5x3", 1, 11, 9, 8, 16, 5, 3, 1, 2),
+    # few input channels: tap x channel columns on the matrix cores (one and two column tiles), ragged tiles,
+    # a channel count that is not a multiple of the 64-channel pass, stride 2, a 1x1 filter
+    wl.ConvLayer("c3x3_cin4", 2, 19, 21, 4, 72, 3, 3, 1, 1),
+    wl.ConvLayer("c5x5_cin2", 2, 17, 16, 2, 32, 5, 5, 1, 2),
+    wl.ConvLayer("c3x3s2_cin3", 2, 32, 32, 3, 136, 3, 3, 2, 1),
+    wl.ConvLayer("c1x1_cin1", 3, 16, 16, 1, 16, 1, 1, 1, 0),
 ]
 
 
