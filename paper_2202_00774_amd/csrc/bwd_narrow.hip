@@ -8,7 +8,7 @@
 //     taps x C_in columns (27 for a 3x3 filter on RGB, padded to 32) -- into LDS, and every thread then sums, for
 //     its input pixel, the one entry per tap that belongs to it.
 //   * bwd_narrow, otherwise: every thread accumulates its own pixel over taps and channels on the vector ALU.
-#include "ranker.h"
+#include "lds_copy.h"
 
 namespace sdgp {
 
@@ -26,6 +26,7 @@ struct NarrowParams {
     int B, H, Wd, P, Q, C_in, C_out, R, S, stride, pad;
     int TH, TW, tiles_h, tiles_w;
     int HP, HQ;  // gradient pixels per tile (rows, columns), upper bound
+    uint32_t hq_magic;  // floor(2^32 / HQ) + 1: x / HQ == umulhi(x, hq_magic) for the pixel counts of a tile
     int n;
     uint32_t mix;
 };
@@ -149,6 +150,7 @@ __global__ void __launch_bounds__(256) bwd_narrow(const NarrowParams p) {
 typedef __bf16 bf16x8n __attribute__((ext_vector_type(8)));
 typedef float f32x16n __attribute__((ext_vector_type(16)));
 
+constexpr int kMmRowB = 128;    // bytes per gradient pixel in LDS: 64 channels
 constexpr int kMmRowTiles = 3;  // 32-pixel row tiles per wavefront: four wavefronts cover up to 384 gradient pixels
 
 // Matrix-core variant; NT = 32-column tiles of (tap, c) pairs.
@@ -170,9 +172,13 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
     const int J = taps * p.C_in;                // live columns
     constexpr int TP = NT * 32 + 1;             // floats per row of T (odd: the gather walks rows)
 
-    SDGP_LDSN unsigned char* lds_a = smem;                          // [nrt * 32][kAPitchN]   gradient, 64 channels
-    SDGP_LDSN unsigned char* lds_wt = smem + nrt * 32 * kAPitchN;   // [NT * 32][kAPitchN]    filter slice, transposed
+    // gradient: 128 bytes per pixel (64 channels); 16-byte group g of pixel hp sits at position g ^ ((hp >> 1) & 7),
+    // which spreads the fragment reads of 16 consecutive pixels over all banks
+    SDGP_LDSN unsigned char* lds_a = smem;                          // [nrt * 32][128]
+    SDGP_LDSN unsigned char* lds_wt = smem + nrt * 32 * kMmRowB;    // [NT * 32][kAPitchN]    filter slice, transposed
     SDGP_LDSN float* lds_t = (SDGP_LDSN float*)smem;                // [nrt * 32][TP]         after the last chunk
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+    const int nunits = (npix + 7) >> 3;         // copy units: 8 pixels x 128 bytes
 
     f32x16n acc[kMmRowTiles][NT];
 #pragma unroll
@@ -184,60 +190,106 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
 
     for (int kc0 = 0; kc0 < p.C_out; kc0 += kNarrowKC) {
         __syncthreads();
-        // ---- gradient halo, pruned, into LDS (16 channels per item)
-        for (int it = tid; it < npix * (kNarrowKC / 16); it += 256) {
-            const int hp = it >> 2, part = it & 3;
-            const int pp = pmin + hp / p.HQ, qq = qmin + hp % p.HQ;
-            const int k = kc0 + part * 16;
-            u32x4n v[2] = {u32x4n{0u, 0u, 0u, 0u}, u32x4n{0u, 0u, 0u, 0u}};
-            const bool ok = pp < p.P && qq < p.Q;
-            const size_t gp = ok ? ((size_t)(b * p.P + pp) * p.Q + qq) : 0;
-            if (ok) {
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    if (k + i * 8 < p.C_out)
-                        v[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4n*>(p.dO + gp * p.C_out + k + i * 8));
-            }
-            if constexpr (PRUNE) {
-                uint32_t raw[16], out[16];
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
-                        raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
-                    }
-                const uint64_t e0 = (uint64_t)gp * (uint64_t)p.C_out + (uint64_t)k;
-#pragma unroll
-                for (int g = 0; g < 16 / M; ++g) {
-                    uint32_t r[M], o[M];
-                    bool kk[M];
-#pragma unroll
-                    for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
-                    const uint64_t eg = e0 + (uint64_t)(g * M);
-                    prune_group<kBF16, M, RK, NLE2>(r, p.n, hash_row(p.mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
-#pragma unroll
-                    for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
-                }
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) v[i][x] = out[i * 8 + 2 * x] | (out[i * 8 + 2 * x + 1] << 16);
-            }
-            *(SDGP_LDSN u32x4n*)(lds_a + hp * kAPitchN + part * 32) = v[0];
-            *(SDGP_LDSN u32x4n*)(lds_a + hp * kAPitchN + part * 32 + 16) = v[1];
+        // ---- gradient halo straight into LDS, every request of the tile in flight at once.  Pixels outside the
+        // gradient, the tail of the last unit and channels past C_out copy some valid bytes; the pass below clears them.
+        for (int u = wave; u < nunits; u += 4) {
+            const int hp = u * 8 + (lane >> 3);
+            const int hpc = min(hp, npix - 1);
+            const int hrow = (int)__umulhi((uint32_t)hpc, p.hq_magic);
+            const int pp = min(pmin + hrow, p.P - 1), qq = min(qmin + (hpc - hrow * p.HQ), p.Q - 1);
+            int k = kc0 + (((lane & 7) ^ ((hp >> 1) & 7)) << 3);
+            if (k >= p.C_out) k = kc0;
+            lds_copy16(p.dO + ((size_t)(b * p.P + pp) * p.Q + qq) * p.C_out + k, smem_base + (uint32_t)u * 1024u);
         }
         // ---- filter slice [kc0, kc0 + 64) x (tap, c), transposed: column j = tap * C_in + c, channels contiguous
-        for (int it = tid; it < kNarrowKC * NT * 32; it += 256) {
-            const int kk = it / (NT * 32), j = it % (NT * 32);
-            uint16_t wv = 0;
-            if (j < J && kc0 + kk < p.C_out) wv = p.W[(size_t)(kc0 + kk) * J + j];
-            *(SDGP_LDSN uint16_t*)(lds_wt + j * kAPitchN + kk * 2) = wv;
+        {
+            constexpr int kPer = kNarrowKC * NT * 32 / 256;  // elements per thread: all loads first, then the LDS writes
+            uint16_t wv[kPer];
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int it = tid + i * 256;
+                const int kk = it / (NT * 32), j = it % (NT * 32);
+                wv[i] = 0;
+                if (j < J && kc0 + kk < p.C_out) wv[i] = p.W[(size_t)(kc0 + kk) * J + j];
+            }
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int it = tid + i * 256;
+                const int kk = it / (NT * 32), j = it % (NT * 32);
+                *(SDGP_LDSN uint16_t*)(lds_wt + j * kAPitchN + kk * 2) = wv[i];
+            }
+        }
+        wait_lds_copies<0>();
+        __syncthreads();
+        // ---- in place: clear what is not gradient, prune the rest (16 channels per item); nothing to do for a dense
+        // tile whose gradient pixels and channels all exist
+        const bool all_there = pmin + p.HP <= p.P && qmin + p.HQ <= p.Q && kc0 + kNarrowKC <= p.C_out;
+        if (PRUNE || !all_there) {
+            for (int it = tid; it < npix * (kNarrowKC / 16); it += 256) {
+                const int hp = it >> 2, part = it & 3;
+                const int hrow = (int)__umulhi((uint32_t)hp, p.hq_magic);
+                const int pp = pmin + hrow, qq = qmin + (hp - hrow * p.HQ);
+                const int k = kc0 + part * 16;
+                const int sw = (hp >> 1) & 7;
+                SDGP_LDSN u32x4n* g0 = (SDGP_LDSN u32x4n*)(lds_a + hp * kMmRowB + (((2 * part) ^ sw) << 4));
+                SDGP_LDSN u32x4n* g1 = (SDGP_LDSN u32x4n*)(lds_a + hp * kMmRowB + (((2 * part + 1) ^ sw) << 4));
+                const u32x4n zero = {0u, 0u, 0u, 0u};
+                if (!(pp < p.P && qq < p.Q) || k >= p.C_out) {
+                    *g0 = zero;
+                    *g1 = zero;
+                } else if (PRUNE || k + 8 >= p.C_out) {
+                    u32x4n v[2] = {*g0, k + 8 < p.C_out ? *g1 : zero};
+                    if constexpr (PRUNE && NLE2 && RK != kRandom) {
+                        // magnitude rankers, n <= 2: rank on packed keys, then spread the two kept values of every
+                        // quad back to their positions
+                        const uint32_t w[8] = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
+                        uint32_t packed[4], meta;
+                        prune_compress16_bf16<M, RK>(w, p.n, packed, meta);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t i0 = (meta >> (4 * q)) & 3u, i1 = (meta >> (4 * q + 2)) & 3u;
+                            const uint64_t x = ((uint64_t)(packed[q] & 0xFFFFu) << (16 * i0)) | ((uint64_t)(packed[q] >> 16) << (16 * i1));
+                            v[q >> 1][2 * (q & 1)] = (uint32_t)x;
+                            v[q >> 1][2 * (q & 1) + 1] = (uint32_t)(x >> 32);
+                        }
+                    } else if constexpr (PRUNE) {
+                        uint32_t raw[16], out[16];
+#pragma unroll
+                        for (int i = 0; i < 2; ++i)
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) {
+                                raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
+                                raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
+                            }
+                        const size_t gp = (size_t)(b * p.P + pp) * p.Q + qq;
+                        const uint64_t e0 = (uint64_t)gp * (uint64_t)p.C_out + (uint64_t)k;
+#pragma unroll
+                        for (int g = 0; g < 16 / M; ++g) {
+                            uint32_t r[M], o[M];
+                            bool kk[M];
+#pragma unroll
+                            for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
+                            const uint64_t eg = e0 + (uint64_t)(g * M);
+                            prune_group<kBF16, M, RK, NLE2>(r, p.n, hash_row(p.mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+#pragma unroll
+                            for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
+                        }
+#pragma unroll
+                        for (int i = 0; i < 2; ++i)
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) v[i][x] = out[i * 8 + 2 * x] | (out[i * 8 + 2 * x + 1] << 16);
+                    }
+                    *g0 = v[0];
+                    *g1 = v[1];
+                }
+            }
         }
         __syncthreads();
 
         // ---- T += gradient x filter slice; wavefront w owns row tiles w, w + 4, w + 8
         const int frag = (lane & 31) * kAPitchN + (lane >> 5) * 16;
+        const int arow = (lane & 31) * kMmRowB;                              // row tiles start at multiples of 32 pixels:
+        const int aswz = ((lane & 31) >> 1) & 7, ahalf = lane >> 5;          // the swizzle depends on the lane only
 #pragma unroll
         for (int ks = 0; ks < kNarrowKC / 16; ++ks) {
             bf16x8n bfr[NT];
@@ -248,7 +300,7 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
             for (int t = 0; t < kMmRowTiles; ++t) {
                 const int rt = wave + 4 * t;
                 if (rt < nrt) {
-                    const bf16x8n afr = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(lds_a + rt * 32 * kAPitchN + frag + ks * 32));
+                    const bf16x8n afr = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(lds_a + rt * 32 * kMmRowB + arow + (((2 * ks + ahalf) ^ aswz) << 4)));
 #pragma unroll
                     for (int u = 0; u < NT; ++u) acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afr, bfr[u], acc[t][u], 0, 0, 0);
                 }
@@ -276,19 +328,33 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
     const int h = h0 + th, w = w0 + tw;
     if (tid < p.TH * p.TW && h < p.H && w < p.Wd) {
         float sum[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int r = 0; r < p.R; ++r) {
-            const int hr = h + p.pad - r;
-            if (hr < 0 || hr % p.stride != 0) continue;
-            const int pp = hr / p.stride;
-            if (pp >= p.P) continue;
-            for (int s = 0; s < p.S; ++s) {
-                const int ws = w + p.pad - s;
-                if (ws < 0 || ws % p.stride != 0) continue;
-                const int qq = ws / p.stride;
-                if (qq >= p.Q) continue;
-                const int hp = (pp - pmin) * p.HQ + (qq - qmin);
-                const SDGP_LDSN float* trow = lds_t + hp * TP + (r * p.S + s) * p.C_in;
-                for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
+        if (p.stride == 1) {
+            for (int r = 0; r < p.R; ++r) {
+                const int pp = h + p.pad - r;
+                if (pp < 0 || pp >= p.P) continue;
+                const SDGP_LDSN float* trow = lds_t + ((pp - pmin) * p.HQ + (w + p.pad - qmin)) * TP + r * p.S * p.C_in;
+                for (int s = 0; s < p.S; ++s) {
+                    const int qq = w + p.pad - s;
+                    if (qq >= 0 && qq < p.Q)
+                        for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
+                    trow += p.C_in - TP;  // next tap, previous gradient pixel
+                }
+            }
+        } else {
+            for (int r = 0; r < p.R; ++r) {
+                const int hr = h + p.pad - r;
+                if (hr < 0 || hr % p.stride != 0) continue;
+                const int pp = hr / p.stride;
+                if (pp >= p.P) continue;
+                for (int s = 0; s < p.S; ++s) {
+                    const int ws = w + p.pad - s;
+                    if (ws < 0 || ws % p.stride != 0) continue;
+                    const int qq = ws / p.stride;
+                    if (qq >= p.Q) continue;
+                    const int hp = (pp - pmin) * p.HQ + (qq - qmin);
+                    const SDGP_LDSN float* trow = lds_t + hp * TP + (r * p.S + s) * p.C_in;
+                    for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
+                }
             }
         }
         uint16_t* dst = p.dD + ((size_t)(b * p.H + h) * p.Wd + w) * p.C_in;
@@ -299,7 +365,7 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
 // LDS bytes of bwd_narrow_mm for a tile of npix gradient pixels and nt column tiles.
 int narrow_mm_lds(int npix, int nt) {
     const int rows = ((npix + 31) / 32) * 32;
-    const int loop = rows * kAPitchN + nt * 32 * kAPitchN;
+    const int loop = rows * kMmRowB + nt * 32 * kAPitchN;
     const int t = rows * (nt * 32 + 1) * 4;
     return loop > t ? loop : t;
 }
@@ -362,6 +428,7 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
     p.TH = (int)(H < 256 / p.TW ? H : 256 / p.TW);
     p.tiles_h = ((int)H + p.TH - 1) / p.TH, p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
     p.HP = (p.TH - 1 + R - 1) / stride + 2, p.HQ = (p.TW - 1 + S - 1) / stride + 2;
+    p.hq_magic = (uint32_t)((1ull << 32) / (uint64_t)p.HQ) + 1u;
     const int64_t grid = (int64_t)B * p.tiles_h * p.tiles_w;
     if (grid >= INT32_MAX) return 1;
     if (grid == 0) return SDGP_OK;
