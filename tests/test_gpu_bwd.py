@@ -40,9 +40,9 @@ def check_conv(layer, dO, W, n, m, ranker, seed, dtype, pixels=None):
     ref, ab = oracle.conv_bwd_data(pruned, W, layer.H, layer.Wd, layer.stride, layer.pad, pixels=pixels)
     out = sdgp.sdgp_conv_bwd_data(to_gpu(dO), to_gpu(W), layer.H, layer.Wd, layer.stride, layer.pad, n, m, ranker, seed)
     torch.cuda.synchronize()
-    got = got_f64(out)
     if pixels is not None:
-        got = got.reshape(-1, layer.C_in)[pixels]
+        out = out.reshape(-1, layer.C_in)[torch.from_numpy(pixels).to(out.device)]  # sample before the copy to the host
+    got = got_f64(out)
     err = rel_error(got, ref, ab)
     assert err <= TOL[dtype], (layer.name, n, m, ranker, err)
     # pixels that no tap reaches must be exactly zero
@@ -185,6 +185,39 @@ def test_resnet9_batch512_sampled(index):
     pixels = sample_pixels(layer, 4096, 100 + index)
     for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (2, 4, oracle.RANDOM), (4, 4, oracle.GREEDY)):
         check_conv(layer, dO, W, n, m, ranker, 0, oracle.BF16, pixels=pixels)
+
+
+@pytest.mark.parametrize("index", range(6))
+def test_resnet50_bottleneck_batch128_sampled(index):
+    """The bottleneck convolutions of ResNet-50 at 56x56 and 14x14, batch 128 (gradients of scale 1e-4 with 40 % zeros):
+    2:4 greedy and greedy-adjusted, 2:8 and 2:16 greedy, and the dense kernel, on 4096 sampled output pixels."""
+    layer = wl.resnet50_bottleneck_layers(128)[index]
+    dO, W = wl.layer_inputs(layer, 1e-4, 0.4, seed=3000 + index, dtype=oracle.BF16)
+    pixels = sample_pixels(layer, 4096, 200 + index)
+    for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (2, 8, oracle.GREEDY),
+                         (2, 16, oracle.GREEDY), (4, 4, oracle.GREEDY)):
+        check_conv(layer, dO, W, n, m, ranker, 0, oracle.BF16, pixels=pixels)
+
+
+def _resnet50_distinct_layers():
+    """(index, layer) of the first layer of every distinct shape among the 54 layers of ResNet-50 at batch 256."""
+    seen = {}
+    for index, l in enumerate(wl.resnet50_all_layers(256)):
+        seen.setdefault((l.H, l.Wd, l.C_in, l.C_out, l.R, l.S, l.stride, l.pad), (index, l))
+    return list(seen.values())
+
+
+@pytest.mark.parametrize("index,layer", _resnet50_distinct_layers(), ids=lambda v: v.name if hasattr(v, "name") else str(v))
+def test_resnet50_batch256_every_layer_shape_sampled(index, layer):
+    """Every distinct layer shape of the whole ResNet-50 at batch 256 and 224 x 224 input (stem 7x7 stride 2 with three
+    input channels, stride-2 3x3 and 1x1 layers, 1x1 layers up to 2048 channels, 7x7 images, the classifier): random
+    ranker seeded with the layer index at 2:4 and 2:8 and the dense kernel, per-layer gradient scale and zero fraction as
+    drawn for the whole-network sweep, on 1024 sampled output pixels."""
+    scale, zero_frac = wl.resnet50_layer_stats(index)
+    dO, W = wl.layer_inputs(layer, scale, zero_frac, seed=5000 + index, dtype=oracle.BF16)
+    pixels = sample_pixels(layer, 1024, 300 + index)
+    for n, m in ((2, 4), (2, 8), (4, 4)):
+        check_conv(layer, dO, W, n, m, oracle.RANDOM, index, oracle.BF16, pixels=pixels)
 
 
 # ------------------------------------------------- pointwise kernel (1x1 convolutions and linear layers with many rows)
