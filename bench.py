@@ -165,6 +165,60 @@ def main():
             table.append(row)
         result["layers"] = table
 
+        # ---- the other named workloads, timed only (their parity is the business of the GPU tests): inputs drawn on
+        # the GPU, Laplace magnitudes with exact zeros
+        def gpu_inputs(L, scale, zero_frac):
+            g = torch.Generator(device=dev)
+            g.manual_seed(7)
+            mag = torch.empty(L.dO_shape, device=dev).exponential_(generator=g) * scale
+            u = torch.rand(L.dO_shape, device=dev, generator=g)
+            x = torch.where(u < zero_frac, torch.zeros_like(mag), torch.where(u < zero_frac + (1 - zero_frac) / 2, -mag, mag))
+            w = torch.randn(L.W_shape, device=dev, generator=g) * (2.0 / (L.R * L.S * L.C_in)) ** 0.5
+            return x.to(torch.bfloat16), w.to(torch.bfloat16), torch.empty(L.dD_shape, dtype=torch.bfloat16, device=dev)
+
+        table = []
+        for L in wl.resnet50_bottleneck_layers(128):
+            dO, W, out = gpu_inputs(L, 1e-4, 0.4)
+            t = {}
+            for name, n, m, rk in (("dense", 4, 4, sdgp.GREEDY), ("2:4_greedy", 2, 4, sdgp.GREEDY),
+                                   ("2:4_greedy-adjusted", 2, 4, sdgp.GREEDY_ADJUSTED), ("2:8_greedy", 2, 8, sdgp.GREEDY),
+                                   ("2:16_greedy", 2, 16, sdgp.GREEDY)):
+                t[name] = time_call(lambda: call(L, dO, W, out, n, m, rk))
+            row = {"layer": L.name, "gflop_dense": round(L.dense_flops / 1e9, 2)}
+            row.update({k + "_us": round(v * 1e3, 1) for k, v in t.items()})
+            row["speedup_2:4"] = round(t["dense"] / t["2:4_greedy"], 3)
+            row["hbm_floor_us"] = round(L.bytes_moved() / (HBM_PEAK_GBS * 1e9) * 1e6, 1)
+            row["frac_of_hbm_peak_dense"] = round(L.bytes_moved() / (t["dense"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 3)
+            table.append(row)
+            del dO, W, out
+        result["resnet50_bottleneck_batch128"] = table
+
+        # the whole ResNet-50 at batch 256 and 224 x 224: every layer once per distinct shape, summed over the 54 layers
+        seen, tot = {}, {"dense": 0.0, "2:4_random": 0.0, "2:8_random": 0.0}
+        r50 = wl.resnet50_all_layers(256)
+        for i, L in enumerate(r50):
+            key = (L.H, L.Wd, L.C_in, L.C_out, L.R, L.S, L.stride, L.pad)
+            if key not in seen:
+                scale, zero_frac = wl.resnet50_layer_stats(i)
+                dO, W, out = gpu_inputs(L, scale, zero_frac)
+                seen[key] = {name: time_call(lambda: sdgp.sdgp_conv_bwd_data(dO, W, L.H, L.Wd, L.stride, L.pad, n, m, sdgp.RANDOM,
+                                                                             i, out=out), reps=5, warm=1)
+                             for name, n, m in (("dense", 4, 4), ("2:4_random", 2, 4), ("2:8_random", 2, 8))}
+                del dO, W, out
+            for name in tot:
+                tot[name] += seen[key][name]
+        flops = sum(L.dense_flops for L in r50)
+        result["resnet50_whole_batch256"] = {
+            "layers": len(r50), "distinct_shapes": len(seen), "gflop_dense": round(flops / 1e9, 1),
+            **{k + "_ms": round(v, 3) for k, v in tot.items()},
+            "speedup_2:4": round(tot["dense"] / tot["2:4_random"], 3), "speedup_2:8": round(tot["dense"] / tot["2:8_random"], 3),
+            "effective_tflops_2:4": round(flops / tot["2:4_random"] / 1e9, 1),
+            "ideal_ms": round(sum(max(L.bytes_moved() / (HBM_PEAK_GBS * 1e9), L.dense_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+                                  for L in r50) * 1e3, 3),
+            "note": "sum of per-layer launch times (random ranker seeded with the layer index); ideal = sum over layers of "
+                    "max(bytes / HBM peak, dense FLOPs / bf16 MFMA peak)",
+        }
+
         # ---- prune pass: dense-shaped output, tensors too large for the 256 MB last-level cache, rotated
         nelem = 256 * 112 * 112 * 64
         srcs = [gpu(wl.laplace_with_zeros((nelem // 64, 64), 1e-3, 0.3, seed=9000 + i, dtype=wl.BF16)) for i in range(2)]

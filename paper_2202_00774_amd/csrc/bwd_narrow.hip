@@ -3,7 +3,7 @@
 // gradient pixel its taps can reach into LDS once, pruning each m-group with the register ranker on the way
 // (Sec. III-B; stored dense with zeros).  Two kernels (Fig. 3 left, any filter size, stride and padding; bf16 storage,
 // fp32 accumulation):
-//   * bwd_narrow_mm, when taps x C_in <= 64: with so few columns per tap the product is turned around.  The matrix
+//   * bwd_narrow_mm, when the tile's (row tile, column tile) pairs and LDS fit (up to 7x7 filters on RGB): with so few columns per tap the product is turned around.  The matrix
 //     cores compute T[gradient pixel][tap, c] = sum_k prune(dL/dO)[pixel][k] W[k][tap][c] -- a plain GEMM with
 //     taps x C_in columns (27 for a 3x3 filter on RGB, padded to 32) -- into LDS, and every thread then sums, for
 //     its input pixel, the one entry per tap that belongs to it.
@@ -26,6 +26,7 @@ struct NarrowParams {
     int B, H, Wd, P, Q, C_in, C_out, R, S, stride, pad;
     int TH, TW, tiles_h, tiles_w;
     int HP, HQ;  // gradient pixels per tile (rows, columns), upper bound
+    int nt;             // 32-column tiles of (tap, c) pairs (matrix-core variant)
     uint32_t hq_magic;  // floor(2^32 / HQ) + 1: x / HQ == umulhi(x, hq_magic) for the pixel counts of a tile
     int n;
     uint32_t mix;
@@ -151,11 +152,12 @@ typedef __bf16 bf16x8n __attribute__((ext_vector_type(8)));
 typedef float f32x16n __attribute__((ext_vector_type(16)));
 
 constexpr int kMmRowB = 128;    // bytes per gradient pixel in LDS: 64 channels
-constexpr int kMmRowTiles = 3;  // 32-pixel row tiles per wavefront: four wavefronts cover up to 384 gradient pixels
+constexpr int kMmMaxNt = 5;     // column tiles: up to 160 (tap, c) columns, a 7x7 filter on three channels
+constexpr int kMmMaxPairs = 8;  // (32-pixel row tile, 32-column tile) pairs per wavefront: at most 32 per workgroup
 
-// Matrix-core variant; NT = 32-column tiles of (tap, c) pairs.
-template <int M, int RK, bool PRUNE, bool NLE2, int NT>
-__global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
+// Matrix-core variant; p.nt = 32-column tiles of (tap, c) pairs; kMmPairs = pairs per wavefront (accumulator registers).
+template <int M, int RK, bool PRUNE, bool NLE2, int kMmPairs>
+__global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     SDGP_LDSN unsigned char* smem = (SDGP_LDSN unsigned char*)smem_generic;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -168,25 +170,33 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
     const int qmin = lo_w <= 0 ? 0 : (lo_w + p.stride - 1) / p.stride;
     const int npix = p.HP * p.HQ;
     const int nrt = (npix + 31) >> 5;           // row tiles; rows past npix hold whatever LDS held: nobody reads their results
-    const int taps = p.R * p.S;
-    const int J = taps * p.C_in;                // live columns
-    constexpr int TP = NT * 32 + 1;             // floats per row of T (odd: the gather walks rows)
+    const int nt = p.nt;
+    const int npairs = nrt * nt;
+    const int J = p.R * p.S * p.C_in;           // live columns
+    const int TP = J | 1;                       // floats per row of T (odd: the gather walks rows)
 
     // gradient: 128 bytes per pixel (64 channels); 16-byte group g of pixel hp sits at position g ^ ((hp >> 1) & 7),
     // which spreads the fragment reads of 16 consecutive pixels over all banks
     SDGP_LDSN unsigned char* lds_a = smem;                          // [nrt * 32][128]
-    SDGP_LDSN unsigned char* lds_wt = smem + nrt * 32 * kMmRowB;    // [NT * 32][kAPitchN]    filter slice, transposed
+    SDGP_LDSN unsigned char* lds_wt = smem + nrt * 32 * kMmRowB;    // [nt * 32][kAPitchN]    filter slice, transposed
     SDGP_LDSN float* lds_t = (SDGP_LDSN float*)smem;                // [nrt * 32][TP]         after the last chunk
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
     const int nunits = (npix + 7) >> 3;         // copy units: 8 pixels x 128 bytes
 
-    f32x16n acc[kMmRowTiles][NT];
+    // this wavefront's pairs: wave, wave + 4, ...
+    int pair_a[kMmPairs], pair_b[kMmPairs];     // LDS offsets of the pair's row tile and column tile
+    int pair_rt[kMmPairs], pair_u[kMmPairs];
 #pragma unroll
-    for (int t = 0; t < kMmRowTiles; ++t)
+    for (int i = 0; i < kMmPairs; ++i) {
+        const int pr = min(wave + 4 * i, npairs - 1);
+        pair_rt[i] = pr / nt, pair_u[i] = pr - pair_rt[i] * nt;
+        pair_a[i] = pair_rt[i] * 32 * kMmRowB, pair_b[i] = pair_u[i] * 32 * kAPitchN;
+    }
+    f32x16n acc[kMmPairs];
 #pragma unroll
-        for (int u = 0; u < NT; ++u)
+    for (int i = 0; i < kMmPairs; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
 
     for (int kc0 = 0; kc0 < p.C_out; kc0 += kNarrowKC) {
         __syncthreads();
@@ -203,21 +213,27 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
         }
         // ---- filter slice [kc0, kc0 + 64) x (tap, c), transposed: column j = tap * C_in + c, channels contiguous
         {
-            constexpr int kPer = kNarrowKC * NT * 32 / 256;  // elements per thread: all loads first, then the LDS writes
-            uint16_t wv[kPer];
+            constexpr int kPer = kNarrowKC * 32 / 256;  // elements per thread and column tile
+            uint16_t wv[kMmMaxNt][kPer];                // every load first, then the LDS writes
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) {
-                const int it = tid + i * 256;
-                const int kk = it / (NT * 32), j = it % (NT * 32);
-                wv[i] = 0;
-                if (j < J && kc0 + kk < p.C_out) wv[i] = p.W[(size_t)(kc0 + kk) * J + j];
-            }
+            for (int u = 0; u < kMmMaxNt; ++u)
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) {
-                const int it = tid + i * 256;
-                const int kk = it / (NT * 32), j = it % (NT * 32);
-                *(SDGP_LDSN uint16_t*)(lds_wt + j * kAPitchN + kk * 2) = wv[i];
-            }
+                for (int i = 0; i < kPer; ++i) {
+                    const int it = tid + i * 256;
+                    const int kk = it >> 5, j = u * 32 + (it & 31);
+                    wv[u][i] = 0;
+                    if (u < nt && j < J && kc0 + kk < p.C_out) wv[u][i] = p.W[(size_t)(kc0 + kk) * J + j];
+                }
+#pragma unroll
+            for (int u = 0; u < kMmMaxNt; ++u)
+                if (u < nt) {
+#pragma unroll
+                    for (int i = 0; i < kPer; ++i) {
+                        const int it = tid + i * 256;
+                        const int kk = it >> 5, j = u * 32 + (it & 31);
+                        *(SDGP_LDSN uint16_t*)(lds_wt + j * kAPitchN + kk * 2) = wv[u][i];
+                    }
+                }
         }
         wait_lds_copies<0>();
         __syncthreads();
@@ -286,75 +302,51 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
         }
         __syncthreads();
 
-        // ---- T += gradient x filter slice; wavefront w owns row tiles w, w + 4, w + 8
-        const int frag = (lane & 31) * kAPitchN + (lane >> 5) * 16;
+        // ---- T += gradient x filter slice
+        const int bfrag = (lane & 31) * kAPitchN + (lane >> 5) * 16;
         const int arow = (lane & 31) * kMmRowB;                              // row tiles start at multiples of 32 pixels:
         const int aswz = ((lane & 31) >> 1) & 7, ahalf = lane >> 5;          // the swizzle depends on the lane only
 #pragma unroll
         for (int ks = 0; ks < kNarrowKC / 16; ++ks) {
-            bf16x8n bfr[NT];
 #pragma unroll
-            for (int u = 0; u < NT; ++u)
-                bfr[u] = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(lds_wt + u * 32 * kAPitchN + frag + ks * 32));
-#pragma unroll
-            for (int t = 0; t < kMmRowTiles; ++t) {
-                const int rt = wave + 4 * t;
-                if (rt < nrt) {
-                    const bf16x8n afr = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(lds_a + rt * 32 * kMmRowB + arow + (((2 * ks + ahalf) ^ aswz) << 4)));
-#pragma unroll
-                    for (int u = 0; u < NT; ++u) acc[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afr, bfr[u], acc[t][u], 0, 0, 0);
+            for (int i = 0; i < kMmPairs; ++i) {
+                if (wave + 4 * i < npairs) {
+                    const bf16x8n afr = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(lds_a + pair_a[i] + arow + (((2 * ks + ahalf) ^ aswz) << 4)));
+                    const bf16x8n bfr = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(lds_wt + pair_b[i] + bfrag + ks * 32));
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afr, bfr, acc[i], 0, 0, 0);
                 }
             }
         }
     }
     __syncthreads();  // every fragment is read: T takes the place of the gradient
 #pragma unroll
-    for (int t = 0; t < kMmRowTiles; ++t) {
-        const int rt = wave + 4 * t;
-        if (rt < nrt) {
+    for (int i = 0; i < kMmPairs; ++i) {
+        if (wave + 4 * i < npairs) {
 #pragma unroll
-            for (int u = 0; u < NT; ++u)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = rt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    lds_t[row * TP + u * 32 + (lane & 31)] = acc[t][u][r];
-                }
+            for (int r = 0; r < 16; ++r) {
+                const int row = pair_rt[i] * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int col = pair_u[i] * 32 + (lane & 31);
+                if (col < J) lds_t[row * TP + col] = acc[i][r];
+            }
         }
     }
     __syncthreads();
 
-    // ---- every input pixel sums the entry of each tap that reaches it
+    // ---- every input pixel sums the entry of each tap that reaches it: tap r reaches row h when h + pad - r is a
+    // multiple of the stride, so r starts at (h + pad) mod stride and steps by the stride while the gradient row falls
     const int th = tid / p.TW, tw = tid % p.TW;
     const int h = h0 + th, w = w0 + tw;
     if (tid < p.TH * p.TW && h < p.H && w < p.Wd) {
         float sum[4] = {0.f, 0.f, 0.f, 0.f};
-        if (p.stride == 1) {
-            for (int r = 0; r < p.R; ++r) {
-                const int pp = h + p.pad - r;
-                if (pp < 0 || pp >= p.P) continue;
-                const SDGP_LDSN float* trow = lds_t + ((pp - pmin) * p.HQ + (w + p.pad - qmin)) * TP + r * p.S * p.C_in;
-                for (int s = 0; s < p.S; ++s) {
-                    const int qq = w + p.pad - s;
-                    if (qq >= 0 && qq < p.Q)
-                        for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
-                    trow += p.C_in - TP;  // next tap, previous gradient pixel
-                }
-            }
-        } else {
-            for (int r = 0; r < p.R; ++r) {
-                const int hr = h + p.pad - r;
-                if (hr < 0 || hr % p.stride != 0) continue;
-                const int pp = hr / p.stride;
-                if (pp >= p.P) continue;
-                for (int s = 0; s < p.S; ++s) {
-                    const int ws = w + p.pad - s;
-                    if (ws < 0 || ws % p.stride != 0) continue;
-                    const int qq = ws / p.stride;
-                    if (qq >= p.Q) continue;
-                    const int hp = (pp - pmin) * p.HQ + (qq - qmin);
-                    const SDGP_LDSN float* trow = lds_t + hp * TP + (r * p.S + s) * p.C_in;
+        const int r0 = (h + p.pad) % p.stride, s0 = (w + p.pad) % p.stride;
+        const int pp0 = (h + p.pad - r0) / p.stride, qq0 = (w + p.pad - s0) / p.stride;
+        for (int r = r0, pp = pp0; r < p.R && pp >= 0; r += p.stride, --pp) {
+            if (pp >= p.P) continue;
+            const SDGP_LDSN float* trow = lds_t + ((pp - pmin) * p.HQ + (qq0 - qmin)) * TP + (r * p.S + s0) * p.C_in;
+            for (int s = s0, qq = qq0; s < p.S && qq >= 0; s += p.stride, --qq) {
+                if (qq < p.Q)
                     for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
-                }
+                trow += p.stride * p.C_in - TP;  // next tap of this phase, previous gradient pixel
             }
         }
         uint16_t* dst = p.dD + ((size_t)(b * p.H + h) * p.Wd + w) * p.C_in;
@@ -362,27 +354,28 @@ __global__ void __launch_bounds__(256) bwd_narrow_mm(const NarrowParams p) {
     }
 }
 
-// LDS bytes of bwd_narrow_mm for a tile of npix gradient pixels and nt column tiles.
-int narrow_mm_lds(int npix, int nt) {
+// LDS bytes of bwd_narrow_mm for a tile of npix gradient pixels, nt column tiles and J live columns.
+int narrow_mm_lds(int npix, int nt, int J) {
     const int rows = ((npix + 31) / 32) * 32;
     const int loop = rows * kMmRowB + nt * 32 * kAPitchN;
-    const int t = rows * (nt * 32 + 1) * 4;
+    const int t = rows * (J | 1) * 4;
     return loop > t ? loop : t;
 }
 
 template <int M, int RK, bool PRUNE, bool NLE2>
-int launch_narrow_mm(const NarrowParams& p, int nt, int grid, hipStream_t stream) {
-    const int lds = narrow_mm_lds(p.HP * p.HQ, nt);
-#define SDGP_NARROW_MM(NTV)                                                                                           \
+int launch_narrow_mm(const NarrowParams& p, int grid, hipStream_t stream) {
+    const int lds = narrow_mm_lds(p.HP * p.HQ, p.nt, p.R * p.S * p.C_in);
+    const int npairs = ((p.HP * p.HQ + 31) / 32) * p.nt;
+#define SDGP_NARROW_MM(PAIRS)                                                                                         \
     {                                                                                                                 \
-        auto kern = bwd_narrow_mm<M, RK, PRUNE, NLE2, NTV>;                                                           \
+        auto kern = bwd_narrow_mm<M, RK, PRUNE, NLE2, PAIRS>;                                                         \
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);   \
         if (attr != hipSuccess) return SDGP_ERR_HIP;                                                                  \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, p);                                              \
     }
-    if (nt == 1) SDGP_NARROW_MM(1)
-    else SDGP_NARROW_MM(2)
+    if (npairs <= 12) SDGP_NARROW_MM(3)   // few accumulators: three workgroups share a CU
+    else SDGP_NARROW_MM(kMmMaxPairs)
 #undef SDGP_NARROW_MM
     return launch_status();
 }
@@ -390,9 +383,9 @@ int launch_narrow_mm(const NarrowParams& p, int nt, int grid, hipStream_t stream
 template <int M, bool NLE2>
 int launch_narrow_rk(const NarrowParams& p, int rk, int nt, int grid, int lds, hipStream_t stream) {
     if (nt > 0) {
-        if (rk == kRandom) return launch_narrow_mm<M, kRandom, true, NLE2>(p, nt, grid, stream);
-        if (rk == kGreedy) return launch_narrow_mm<M, kGreedy, true, NLE2>(p, nt, grid, stream);
-        return launch_narrow_mm<M, kAdjusted, true, NLE2>(p, nt, grid, stream);
+        if (rk == kRandom) return launch_narrow_mm<M, kRandom, true, NLE2>(p, grid, stream);
+        if (rk == kGreedy) return launch_narrow_mm<M, kGreedy, true, NLE2>(p, grid, stream);
+        return launch_narrow_mm<M, kAdjusted, true, NLE2>(p, grid, stream);
     }
 #define SDGP_NARROW(RKV)                                                                                              \
     {                                                                                                                 \
@@ -427,18 +420,21 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
     p.TW = (int)(Wd < 16 ? Wd : 16);
     p.TH = (int)(H < 256 / p.TW ? H : 256 / p.TW);
     p.tiles_h = ((int)H + p.TH - 1) / p.TH, p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
-    p.HP = (p.TH - 1 + R - 1) / stride + 2, p.HQ = (p.TW - 1 + S - 1) / stride + 2;
+    // gradient rows (columns) a tile's taps can reach: those whose multiple of the stride falls into a span of TH + R - 1
+    p.HP = (p.TH - 1 + R - 1) / stride + 1, p.HQ = (p.TW - 1 + S - 1) / stride + 1;
+    if (p.HQ < 2) p.HQ = 2;  // the reciprocal below needs a divisor above one
     p.hq_magic = (uint32_t)((1ull << 32) / (uint64_t)p.HQ) + 1u;
     const int64_t grid = (int64_t)B * p.tiles_h * p.tiles_w;
     if (grid >= INT32_MAX) return 1;
     if (grid == 0) return SDGP_OK;
-    // the matrix-core variant when its columns, row tiles and LDS fit; else the vector-ALU one
+    // the matrix-core variant when its (row tile, column tile) pairs and LDS fit; else the vector-ALU one
     const int J = R * S * (int)C_in, npix = p.HP * p.HQ;
-    int nt = J <= 32 ? 1 : (J <= 64 ? 2 : 0);
-    if (nt > 0 && ((npix + 31) / 32 > 4 * kMmRowTiles || narrow_mm_lds(npix, nt) > 160 * 1024)) nt = 0;
+    int nt = (J + 31) / 32;
+    if (nt > kMmMaxNt || ((npix + 31) / 32) * nt > 4 * kMmMaxPairs || narrow_mm_lds(npix, nt, J) > 160 * 1024) nt = 0;
+    p.nt = nt;
     const int lds = ((npix * kAPitchN + 15) & ~15) + kNarrowKC * R * S * 16;
     if (nt == 0 && lds > 160 * 1024) return 1;
-    if (dense && nt > 0) return launch_narrow_mm<4, kGreedy, false, true>(p, nt, (int)grid, stream);
+    if (dense && nt > 0) return launch_narrow_mm<4, kGreedy, false, true>(p, (int)grid, stream);
     if (dense) {
         auto kern = bwd_narrow<4, kGreedy, false, true>;
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

@@ -1,4 +1,4 @@
-// Backward-data kernel for 1x1 stride-1 convolutions and linear layers: dL/dD[rows, C_in] = prune(dL/dO)[rows, C_out] . W
+// Backward-data kernel for 1x1 convolutions without padding (any stride) and linear layers: dL/dD[rows, C_in] = prune(dL/dO)[rows, C_out] . W
 // (Fig. 2; Sec. II-A).  A plain GEMM whose reduction axis is the pruned one (Fig. 1).  With C_out <= 2048 these layers
 // are bound by reading dL/dO and writing dL/dD once (arithmetic intensity 50-200 FLOP/B), so the kernel is built to
 // stream: a workgroup takes 128 or 256 consecutive rows and 64 to 256 columns (the host picks the shape) and walks the
@@ -11,7 +11,9 @@
 //     fits it) and chunk s is multiplied;
 //   * wavefronts of one kind, register tiles of up to 128 x 64, two workgroups to a CU; fragments as in bwd_row.h (swizzled 16-byte
 //     reads for the gradient, transpose reads for W in its native layout);
-//   * the result leaves through LDS as whole rows with 16-byte stores.
+//   * the result leaves through LDS as whole rows with 16-byte stores; with a stride, a gradient pixel's row goes to
+//     input pixel (p * stride, q * stride) and the other pixels of its stride x stride block receive zeros (no tap
+//     reaches them).
 #pragma once
 
 #include <type_traits>
@@ -24,8 +26,9 @@ struct PwParams {
     const uint16_t* dO;
     const uint16_t* W;
     uint16_t* dD;
-    long long rows;              // B*H*W
+    long long rows;              // gradient pixels: B*P*Q
     int C_out, C_in;
+    int stride, P, Q, H, Wd;     // stride > 1: gradient pixel (p, q) is input pixel (p*stride, q*stride); the others get zeros
     int n;
     uint32_t mix;
     int ntiles_n, nblocks;
@@ -50,7 +53,8 @@ struct PwLayout {
     static constexpr int off_meta() { return off_a() + 2 * kABytes; }
     static constexpr int loop_bytes() { return off_meta() + 2 * kMetaBytes; }
     static constexpr int out_bytes() { return ROWS * kOutPitch; }
-    static constexpr int total() { return loop_bytes() > out_bytes() ? loop_bytes() : out_bytes(); }
+    static constexpr int off_rowtab() { return loop_bytes() > out_bytes() ? loop_bytes() : out_bytes(); }  // stride > 1 only
+    static constexpr int total() { return off_rowtab() + ROWS * 8; }
 };
 
 template <int BN, int MODE, int M, int RK, int ROWS, int NW>
@@ -288,14 +292,48 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                 *(SDGP_LDS uint16_t*)(smem + m * L::kOutPitch + col * 2) = (uint16_t)pk;
                 *(SDGP_LDS uint16_t*)(smem + (m + 1) * L::kOutPitch + col * 2) = (uint16_t)(pk >> 16);
             }
+    if (p.stride > 1) {
+        // where each row of the tile goes: its input pixel and how many of the stride x stride pixels it owns exist
+        SDGP_LDS int* rowtab = (SDGP_LDS int*)(smem + L::off_rowtab());
+        for (int m = tid; m < ROWS; m += NT) {
+            const long long row = m0 + m;
+            int pix = -1, lim = 0;
+            if (row <= last_row) {
+                const int pq = p.P * p.Q;
+                const int b = (int)(row / pq), rem = (int)(row - (long long)b * pq);
+                const int pp = rem / p.Q, qq = rem - pp * p.Q;
+                const int h = pp * p.stride, w = qq * p.stride;
+                pix = (b * p.H + h) * p.Wd + w;
+                lim = (min(p.stride, p.H - h) << 8) | min(p.stride, p.Wd - w);
+            }
+            rowtab[2 * m] = pix, rowtab[2 * m + 1] = lim;
+        }
+    }
     __syncthreads();
+    if (p.stride == 1) {
 #pragma unroll 4
-    for (int idx = tid; idx < ROWS * CPR; idx += NT) {
-        const int m = idx / CPR, cc = idx % CPR;
-        const long long row = m0 + m;
-        if (row <= last_row && n0 + cc * 8 < p.C_in) {
-            const u32x4_t v = *(SDGP_LDS u32x4_t*)(smem + m * L::kOutPitch + cc * 16);
-            *reinterpret_cast<u32x4_t*>(p.dD + (size_t)row * p.C_in + n0 + cc * 8) = v;
+        for (int idx = tid; idx < ROWS * CPR; idx += NT) {
+            const int m = idx / CPR, cc = idx % CPR;
+            const long long row = m0 + m;
+            if (row <= last_row && n0 + cc * 8 < p.C_in) {
+                const u32x4_t v = *(SDGP_LDS u32x4_t*)(smem + m * L::kOutPitch + cc * 16);
+                *reinterpret_cast<u32x4_t*>(p.dD + (size_t)row * p.C_in + n0 + cc * 8) = v;
+            }
+        }
+    } else {
+        const SDGP_LDS int* rowtab = (const SDGP_LDS int*)(smem + L::off_rowtab());
+        const u32x4_t zero = {0u, 0u, 0u, 0u};
+        for (int idx = tid; idx < ROWS * CPR; idx += NT) {
+            const int m = idx / CPR, cc = idx % CPR;
+            const int pix = rowtab[2 * m], lim = rowtab[2 * m + 1];
+            if (pix >= 0 && n0 + cc * 8 < p.C_in) {
+                const u32x4_t v = *(SDGP_LDS u32x4_t*)(smem + m * L::kOutPitch + cc * 16);
+                uint16_t* dst = p.dD + (size_t)pix * p.C_in + n0 + cc * 8;
+                const int ny = lim >> 8, nx = lim & 255;
+                for (int dy = 0; dy < ny; ++dy)
+                    for (int dx = 0; dx < nx; ++dx)
+                        *reinterpret_cast<u32x4_t*>(dst + (size_t)(dy * p.Wd + dx) * p.C_in) = (dy | dx) ? zero : v;
+            }
         }
     }
 }

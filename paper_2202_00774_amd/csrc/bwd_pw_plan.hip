@@ -1,4 +1,4 @@
-// Host side of the pointwise kernel: 1x1 stride-1 convolutions without padding and linear layers whose channel
+// Host side of the pointwise kernel: 1x1 convolutions without padding (any stride) and linear layers whose channel
 // counts fit (C_out a multiple of 32, C_in a multiple of 8); chooses the tile shape and launches.
 #include <climits>
 #include <cstdlib>
@@ -19,10 +19,12 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     if (n == m) mode = 0;
     else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
     else return 1;
-    if (R != 1 || S != 1 || stride != 1 || pad != 0 || (C_out % kPwKC) != 0 || (C_in % 8) != 0) return 1;
+    if (R != 1 || S != 1 || stride < 1 || stride > 255 || pad != 0 || (C_out % kPwKC) != 0 || (C_in % 8) != 0) return 1;
     if (mode == 2 && (C_out % m) != 0) return 1;
     if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
-    const int64_t rows = B * H * Wd;
+    const int64_t P = (H - 1) / stride + 1, Q = (Wd - 1) / stride + 1;  // gradient image
+    const int64_t rows = B * P * Q;
+    if (stride > 1 && (B * H * Wd >= INT_MAX || H < 1 || Wd < 1)) return 1;
     if (rows < 1 || C_out < kPwKC || C_in < 8 || C_out >= (1 << 24) || C_in >= (1 << 24)) return 1;
 
     PwParams p{};
@@ -31,6 +33,7 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     p.dD = static_cast<uint16_t*>(dD);
     p.rows = rows, p.C_out = (int)C_out, p.C_in = (int)C_in;
     p.n = n;
+    p.stride = stride, p.P = (int)P, p.Q = (int)Q, p.H = (int)H, p.Wd = (int)Wd;
     p.mix = seed_mix(seed);
 
     // tile shape.  Workgroups of four wavefronts, two to a CU, so that one's loads and stores overlap the other's

@@ -85,6 +85,14 @@ def test_linear_classifier_shape():
         sdgp.sdgp_linear_bwd_data(to_gpu(dO), to_gpu(W), 2, 16, sdgp.GREEDY)
 
 
+def test_linear_with_few_input_features():
+    """A linear layer with three input features takes the first-layer kernel (one-pixel images)."""
+    dO = wl.laplace_with_zeros((300, 64), 1e-3, 0.3, seed=31, dtype=oracle.BF16)
+    W = wl.normal((64, 3), 0.2, 32, oracle.BF16)
+    for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 8, oracle.RANDOM), (4, 4, oracle.GREEDY)):
+        check_linear(dO, W, n, m, ranker, 5, oracle.BF16)
+
+
 # -------------------------------------------------------------------- conv
 
 SMALL_CONVS = [
@@ -227,6 +235,8 @@ POINTWISE_CONVS = [
     wl.ConvLayer("pw_n264_few_rows", 32, 16, 16, 264, 96, 1, 1, 1, 0),
     wl.ConvLayer("pw_n128", 128, 32, 32, 128, 32, 1, 1, 1, 0),    # one column tile, one reduction chunk
     wl.ConvLayer("pw_n24", 129, 16, 16, 24, 96, 1, 1, 1, 0),      # 24 live columns of a 64-column tile, ragged rows
+    wl.ConvLayer("pw_s2", 64, 31, 29, 72, 64, 1, 1, 2, 0),        # stride 2, odd image: the last row and column stand alone
+    wl.ConvLayer("pw_s3_n264", 160, 20, 22, 264, 32, 1, 1, 3, 0),  # stride 3, several column tiles
 ]
 
 
