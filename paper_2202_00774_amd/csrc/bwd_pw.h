@@ -47,10 +47,14 @@ struct PwLayout {
     static constexpr int kRawBytes = ROWS * 64;
     static constexpr int kMetaBytes = kSparse ? ROWS * 4 : 0;
     static constexpr int kOutPitch = BN * 2 + 16;
+    // buffer sets in the request ring: the dense kernel requests kSets - 1 chunks ahead.  Two: with three or four
+    // sets the 128 x 128 dense tile drops from four workgroups per CU to two and runs 20-30 % slower -- more
+    // workgroups hide the copy latency better than a deeper ring does.
+    static constexpr int kSets = 2;
     static constexpr int off_w() { return 0; }
-    static constexpr int off_raw() { return off_w() + 2 * kWSlab; }
+    static constexpr int off_raw() { return off_w() + kSets * kWSlab; }
     static constexpr int off_a() { return off_raw() + (kSparse ? 2 * kRawBytes : 0); }
-    static constexpr int off_meta() { return off_a() + 2 * kABytes; }
+    static constexpr int off_meta() { return off_a() + kSets * kABytes; }
     static constexpr int loop_bytes() { return off_meta() + 2 * kMetaBytes; }
     static constexpr int out_bytes() { return ROWS * kOutPitch; }
     static constexpr int off_rowtab() { return loop_bytes() > out_bytes() ? loop_bytes() : out_bytes(); }  // stride > 1 only
@@ -165,12 +169,19 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
             for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
 
     // ---- prologue
-    copy_chunk(0, 0, true);
+    constexpr int SETS = L::kSets;
+    static_assert(AU % NW == 0 && WU % NW == 0, "every wavefront issues the same number of copies per chunk");
+    constexpr int kCopiesPerChunk = AU / NW + WU / NW;
     if constexpr (SPARSE) {
+        copy_chunk(0, 0, true);
         if (nchunks > 1) copy_chunk(1, 1, false);
         wait_lds_copies<0>();
         __syncthreads();
         prune_chunk(0, 0);
+    } else {
+#pragma unroll
+        for (int i = 0; i < SETS - 1; ++i)
+            if (i < nchunks) copy_chunk(i, i, true);
     }
     wait_lds_copies<0>();
     __syncthreads();
@@ -247,10 +258,12 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
 
     // ---- main loop: one chunk per stage
     Frags fr[2];
+    int set = 0, set_req = SETS - 1;  // dense: ring positions of chunk s and of the chunk requested during stage s
     for (int s = 0; s < nchunks; ++s) {
-        const int set = s & 1;
-        // requests for what comes next: dense -- chunk s+1 into the other buffers; pruning -- W of chunk s+1 and the
-        // raw rows of chunk s+2 (into the slot whose rows were ranked during the previous stage)
+        if constexpr (SPARSE) set = s & 1;
+        // requests for what comes next: dense -- chunk s + SETS - 1 into the set that the previous stage read;
+        // pruning -- W of chunk s+1 and the raw rows of chunk s+2 (into the slot whose rows were ranked during the
+        // previous stage)
         if constexpr (SPARSE) {
             if (s + 1 < nchunks) copy_w_chunk(s + 1, set ^ 1);
             if (s + 2 < nchunks) {
@@ -258,7 +271,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                 for (int i = wave; i < AU; i += NW) copy_a_unit(i, s + 2, a_dst + (uint32_t)i * 1024u);
             }
         } else {
-            if (s + 1 < nchunks) copy_chunk(s + 1, set ^ 1, true);
+            if (s + SETS - 1 < nchunks) copy_chunk(s + SETS - 1, set_req, true);
         }
         load_frags(fr[0], set, 0);
         if constexpr (SPARSE) {
@@ -271,7 +284,16 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
             mma(fr[ks & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        wait_lds_copies<0>();
+        if constexpr (SPARSE) {
+            wait_lds_copies<0>();
+        } else {
+            // chunk s + 1 has to be there; the requests of the chunks after it (issued in order, the same number by
+            // every wavefront) may stay in flight.  Near the end fewer are outstanding: drain.
+            if (s + SETS - 1 < nchunks) wait_lds_copies<(SETS - 2) * kCopiesPerChunk>();
+            else wait_lds_copies<0>();
+            set = set + 1 == SETS ? 0 : set + 1;
+            set_req = set_req + 1 == SETS ? 0 : set_req + 1;
+        }
         __syncthreads();
     }
 
