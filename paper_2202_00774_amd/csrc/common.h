@@ -23,6 +23,19 @@ __host__ __device__ __forceinline__ uint32_t float_to_bf16(float f) {
     return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? ((u >> 16) | 0x40u) : r;
 }
 
+// Two binary32 values -> two bfloat16 in one dword (first value in the low half), round to nearest even.  On the
+// device this is one v_cvt_pk_bf16_f32; the same bits as float_to_bf16 for every finite input.
+__host__ __device__ __forceinline__ uint32_t float2_to_bf16x2(float lo, float hi) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef float sdgp_f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 sdgp_bf16x2 __attribute__((ext_vector_type(2)));
+    const sdgp_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, sdgp_bf16x2));
+#else
+    return float_to_bf16(lo) | (float_to_bf16(hi) << 16);
+#endif
+}
+
 // ------------------------------------------------------- counter-based hash
 //
 // Key of flat element e under `seed` for the random pruning function

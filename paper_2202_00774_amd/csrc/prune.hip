@@ -19,6 +19,9 @@ namespace sdgp {
 namespace {
 
 constexpr int kBlock = 256;
+// vector kernel: items per thread -- fewer, longer-lived wavefronts with more bytes in flight each, as far as the
+// registers allow (an item of a 32-group is 64 bytes of bf16; the hash keys of the random ranker cost registers too)
+constexpr int items_per_thread(int m, int rk) { return m >= 32 ? 1 : (m >= 16 || rk == SDGP_RANDOM ? 2 : 4); }
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int DT>
@@ -46,13 +49,31 @@ prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, v
     constexpr int VECS = ITEM / PV;          // 16-byte vectors per item
     constexpr int GROUPS = ITEM / M;         // groups per item
 
-    const int64_t item = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (item >= nitems) return;
-
-    const u32x4* src = reinterpret_cast<const u32x4*>(dO_) + item * VECS;
+    // kItemsPerThread items per thread, a workgroup apart (coalesced); every load is issued before the first use
+    constexpr int kItemsPerThread = items_per_thread(M, RK);
+    const int64_t item0 = (int64_t)blockIdx.x * (kBlock * kItemsPerThread) + threadIdx.x;
+    u32x4 vin[kItemsPerThread][VECS];
+#pragma unroll
+    for (int u = 0; u < kItemsPerThread; ++u) {
+        const int64_t it = item0 + (int64_t)u * kBlock;
+        if (it < nitems) {
+            const u32x4* src = reinterpret_cast<const u32x4*>(dO_) + it * VECS;
+#pragma unroll
+            for (int i = 0; i < VECS; ++i) {
+                // an item of several vectors leaves gaps between the lanes of one load; the vectors of the other loads
+                // fill them, so the cache line should stay until they have come by: no streaming hint then
+                if constexpr (VECS == 1) vin[u][i] = __builtin_nontemporal_load(src + i);
+                else vin[u][i] = src[i];
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kItemsPerThread; ++u) {
+    const int64_t item = item0 + (int64_t)u * kBlock;
+    if (item >= nitems) break;
     u32x4 v[VECS];
 #pragma unroll
-    for (int i = 0; i < VECS; ++i) v[i] = __builtin_nontemporal_load(src + i);
+    for (int i = 0; i < VECS; ++i) v[i] = vin[u][i];
 
     uint32_t raw[ITEM];
 #pragma unroll
@@ -119,6 +140,7 @@ prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, v
             }
         }
     }
+    }  // items of this thread
 }
 
 // ------------------------------------------------------------- group kernel
@@ -195,7 +217,8 @@ struct PruneArgs {
 
 template <int DT, int M, int RK, bool NLE2>
 void launch_items_out(const PruneArgs& a, int64_t nitems) {
-    const dim3 grid((unsigned)((nitems + kBlock - 1) / kBlock)), block(kBlock);
+    const int64_t per_block = (int64_t)kBlock * items_per_thread(M, RK);
+    const dim3 grid((unsigned)((nitems + per_block - 1) / per_block)), block(kBlock);
     if (a.pruned && a.vals)
         hipLaunchKernelGGL((prune_items<DT, M, RK, NLE2, true, true>), grid, block, 0, a.stream, a.dO, nitems, a.n, a.mix,
                            a.pruned, a.vals, a.idx);

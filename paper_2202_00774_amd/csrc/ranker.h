@@ -118,7 +118,8 @@ __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uin
         for (int j = 0; j < M; ++j) key[j] = (key[j] << 5) | (uint32_t)(31 - j);
         if constexpr (NLE2) select_top2_distinct<M>(key, n, keep);
         else select_by_rank<M>(key, n, keep);
-    } else if constexpr (NLE2 && M >= 8) {
+    } else if constexpr (NLE2 && M >= 16) {
+        // (for eight keys the 28 comparisons of the rank count measured faster than the multiset and its fallback)
         select_top2_ties<M>(key, n, keep);
     } else {
         select_by_rank<M>(key, n, keep);
@@ -135,11 +136,20 @@ __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uin
             kept = keep[j] ? __fadd_rn(kept, a) : kept;
         }
         const float scale = (kept == 0.0f) ? 1.0f : __fdiv_rn(total, kept);
+        if constexpr (DT == kBF16 && M % 2 == 0) {
 #pragma unroll
-        for (int j = 0; j < M; ++j) {
-            const float y = __fmul_rn(x[j], scale);
-            const uint32_t yb = (DT == kBF16) ? float_to_bf16(y) : float_to_bits(y);
-            out[j] = keep[j] ? yb : 0u;
+            for (int j = 0; j < M; j += 2) {
+                const uint32_t yb = float2_to_bf16x2(__fmul_rn(x[j], scale), __fmul_rn(x[j + 1], scale));
+                out[j] = keep[j] ? (yb & 0xFFFFu) : 0u;
+                out[j + 1] = keep[j + 1] ? (yb >> 16) : 0u;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < M; ++j) {
+                const float y = __fmul_rn(x[j], scale);
+                const uint32_t yb = (DT == kBF16) ? float_to_bf16(y) : float_to_bits(y);
+                out[j] = keep[j] ? yb : 0u;
+            }
         }
     } else {
 #pragma unroll
@@ -257,11 +267,11 @@ __host__ __device__ __forceinline__ void prune_compress16_bf16(const uint32_t (&
             for (int i = 0; i < QG; ++i) {
                 const int q = g * QG + i;
                 const uint32_t d = packed[q];
-                const uint32_t ylo = float_to_bf16(__fmul_rn(bits_to_float(d << 16), scale));
-                const uint32_t yhi = float_to_bf16(__fmul_rn(bits_to_float(d & 0xFFFF0000u), scale));
+                const uint32_t y = float2_to_bf16x2(__fmul_rn(bits_to_float(d << 16), scale),
+                                                    __fmul_rn(bits_to_float(d & 0xFFFF0000u), scale));
                 // a dropped slot stays +0 whatever the scale is (the mark went away with the value)
-                const uint32_t mlo = 0u - (lo_key[q] & 1u), mhi = 0u - (hi_key[q] & 1u);
-                packed[q] = (ylo & mlo) | ((yhi & mhi) << 16);
+                const uint32_t mlo = (0u - (lo_key[q] & 1u)) & 0xFFFFu, mhi = (0u - (hi_key[q] & 1u)) << 16;
+                packed[q] = y & (mlo | mhi);
             }
         }
     }
