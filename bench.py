@@ -238,7 +238,17 @@ def main():
             ms = time_call(f, reps=20, warm=3)
             prune[name] = {"us": round(ms * 1e3, 1), "GB/s": round(4.0 * nelem / (ms * 1e-3) / 1e9, 1),
                            "frac_of_hbm_peak": round(4.0 * nelem / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        result["prune_pass"] = {"tensor": "[%d, 64] bf16 (411 MB), 2:4, dense-shaped output, 4 B per element" % (nelem // 64),
+        for n_, m_ in ((2, 8), (2, 16)):
+            def g(n_=n_, m_=m_):
+                s, d = srcs[k[0] % 2], dsts[k[0] % 2]
+                k[0] += 1
+                rc = lib.sdgp_prune(ctypes.c_void_p(s.data_ptr()), s.shape[0], s.shape[1], sdgp.BF16, n_, m_, sdgp.GREEDY, 0,
+                                    ctypes.c_void_p(d.data_ptr()), None, None, stream)
+                assert rc == 0
+            ms = time_call(g, reps=20, warm=3)
+            prune["greedy_%d:%d" % (n_, m_)] = {"us": round(ms * 1e3, 1), "GB/s": round(4.0 * nelem / (ms * 1e-3) / 1e9, 1),
+                                                "frac_of_hbm_peak": round(4.0 * nelem / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        result["prune_pass"] = {"tensor": "[%d, 64] bf16 (411 MB), 2:4 unless named, dense-shaped output, 4 B per element" % (nelem // 64),
                                 **prune}
         result["roofline_prune"] = {"bound": "hbm", "kernel": "prune_items (2:4 greedy)",
                                     "achieved": prune["greedy"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -75,6 +75,26 @@ prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, v
 #pragma unroll
     for (int i = 0; i < VECS; ++i) v[i] = vin[u][i];
 
+    if constexpr (DT == kBF16 && M == 16 && NLE2 && RK != kRandom && MASKED && !COMPACT) {
+        // sixteen bf16 channels, one group, at most two survivors: rank on packed keys (ranker.h) and spread the two
+        // kept values of every quad back to their positions
+        const uint32_t w[8] = {v[0].x, v[0].y, v[0].z, v[0].w, v[1].x, v[1].y, v[1].z, v[1].w};
+        uint32_t packed[4], meta;
+        prune_compress16_bf16<16, RK>(w, n, packed, meta);
+        uint32_t o[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t i0 = (meta >> (4 * q)) & 3u, i1 = (meta >> (4 * q + 2)) & 3u;
+            const uint64_t x = ((uint64_t)(packed[q] & 0xFFFFu) << (16 * i0)) | ((uint64_t)(packed[q] >> 16) << (16 * i1));
+            o[2 * q] = (uint32_t)x, o[2 * q + 1] = (uint32_t)(x >> 32);
+        }
+        u32x4* dst = reinterpret_cast<u32x4*>(pruned_) + item * VECS;
+        const u32x4 p0 = {o[0], o[1], o[2], o[3]}, p1 = {o[4], o[5], o[6], o[7]};
+        __builtin_nontemporal_store(p0, dst);
+        __builtin_nontemporal_store(p1, dst + 1);
+        continue;
+    }
+
     uint32_t raw[ITEM];
 #pragma unroll
     for (int i = 0; i < VECS; ++i) {
