@@ -13,6 +13,8 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
                       hipStream_t stream);
 int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                   int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream);
+int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                      int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream);
 int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                    int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                    hipStream_t stream);
@@ -81,6 +83,8 @@ int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, 
         int rc = sdgp::bwd_pw_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
         if (rc <= 0) return rc;
         rc = sdgp::bwd_row_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
+        if (rc <= 0) return rc;
+        rc = sdgp::bwd_gather_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
         if (rc <= 0) return rc;
         rc = sdgp::bwd_conv3_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
         if (rc <= 0) return rc;

@@ -26,9 +26,15 @@ struct PwParams {
     const uint16_t* dO;
     const uint16_t* W;
     uint16_t* dD;
-    long long rows;              // gradient pixels: B*P*Q
+    long long rows;              // GEMM rows: gradient pixels B*P*Q (gather mode: B*Pc*Qc)
+    long long rows_dO;           // gradient pixels B*P*Q
     int C_out, C_in;
     int stride, P, Q, H, Wd;     // stride > 1: gradient pixel (p, q) is input pixel (p*stride, q*stride); the others get zeros
+    // gather mode (one output parity class of a strided filter; see bwd_pw_plan.hip): row (b, i, j) of the class grid
+    // Pc x Qc is input pixel (i*stride + oa, j*stride + ob) and sums ntaps taps; tap t reads gradient pixel
+    // (i + tap_dp[t], j + tap_dq[t]) -- zeros outside the gradient -- against filter tap tap_w[t] of w_taps
+    int gather, ntaps, w_taps, Pc, Qc, oa, ob;
+    int tap_dp[4], tap_dq[4], tap_w[4];
     int n;
     uint32_t mix;
     int ntiles_n, nblocks;
@@ -57,9 +63,12 @@ struct PwLayout {
     static constexpr int off_meta() { return off_a() + kSets * kABytes; }
     static constexpr int loop_bytes() { return off_meta() + 2 * kMetaBytes; }
     static constexpr int out_bytes() { return ROWS * kOutPitch; }
-    static constexpr int off_rowtab() { return loop_bytes() > out_bytes() ? loop_bytes() : out_bytes(); }  // stride > 1 only
-    static constexpr int total() { return off_rowtab() + ROWS * 8; }
+    static constexpr int off_rowtab() { return loop_bytes() > out_bytes() ? loop_bytes() : out_bytes(); }  // strided layers only
+    static constexpr int total() { return off_rowtab() + ROWS * 12; }
 };
+
+// what a tap outside the gradient copies (one 64-byte chunk row)
+__device__ __align__(64) const uint32_t kPwZeros[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
 template <int BN, int MODE, int M, int RK, int ROWS, int NW>
 __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
@@ -100,28 +109,47 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     const long long m0 = (long long)(lid / p.ntiles_n) * ROWS;
     const int n0 = ntile * BN;
     const int nchunks = p.C_out / KC;
+    const int nstages = nchunks * p.ntaps;   // reduction steps: (tap, chunk), the chunks of a tap in a row
     const long long last_row = p.rows - 1;
+    const long long last_pix = (long long)p.rows_dO - 1;
+    SDGP_LDS int* rowtab = (SDGP_LDS int*)(smem + L::off_rowtab());
+    auto tap_of = [&](int st) { return (st >= nchunks) + (st >= 2 * nchunks) + (st >= 3 * nchunks); };
     const unsigned char* const gdO = reinterpret_cast<const unsigned char*>(p.dO);
     const unsigned char* const gWb = reinterpret_cast<const unsigned char*>(p.W);
     const uint32_t rowB = (uint32_t)p.C_out * 2u;      // bytes per gradient row
-    const uint32_t wrowB = (uint32_t)p.C_in * 2u;      // bytes per W row
+    const uint32_t wrowB = (uint32_t)p.C_in * 2u * (uint32_t)p.w_taps;  // bytes per W row (all taps of one output channel)
 
     // ---- copies.  Gradient: unit u = rows 16u .. 16u+15 of the tile, 64 bytes each; LDS position (lane & 3) of row
     // (lane >> 2) holds the swizzled source column.  Rows past the tensor re-read the last row (never stored).
     const uint32_t c16_a = SPARSE ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
                                   : (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
-    auto copy_a_unit = [&](int u, int chunk, uint32_t dst) {
-        long long row = m0 + u * 16 + (lane >> 2);
-        if (row > last_row) row = last_row;
-        lds_copy16(gdO + ((size_t)row * rowB + (size_t)chunk * (KC * 2) + c16_a), dst);
+    // `st` is the reduction step: tap st / nchunks, chunk st % nchunks
+    auto copy_a_unit = [&](int u, int st, uint32_t dst) {
+        if (!p.gather) {
+            long long row = m0 + u * 16 + (lane >> 2);
+            if (row > last_row) row = last_row;
+            lds_copy16(gdO + ((size_t)row * rowB + (size_t)st * (KC * 2) + c16_a), dst);
+        } else {
+            const int t = tap_of(st), chunk = st - t * nchunks;
+            const int rl = u * 16 + (lane >> 2);
+            const int base = rowtab[3 * rl], ij = rowtab[3 * rl + 1];
+            const int i = (ij & 0xFFFF) + p.tap_dp[t], j = (ij >> 16) + p.tap_dq[t];
+            const bool ok = base >= 0 && i >= 0 && i < p.P && j >= 0 && j < p.Q;
+            long long src = (long long)base + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
+            src = src < 0 ? 0 : (src > last_pix ? last_pix : src);  // (a valid tap is inside anyway)
+            const unsigned char* a = ok ? gdO + ((size_t)src * rowB + (size_t)chunk * (KC * 2) + c16_a)
+                                        : reinterpret_cast<const unsigned char*>(kPwZeros) + c16_a;
+            lds_copy16(a, dst);
+        }
     };
     // W: unit u = rows u*RPU .. of the 32 x BN slab of a chunk, columns swizzled for the transpose reads
-    auto copy_w_unit = [&](int u, int chunk, uint32_t dst) {
+    auto copy_w_unit = [&](int u, int st, uint32_t dst) {
+        const int t = tap_of(st), chunk = st - t * nchunks;
         const int row = u * RPU + lane / CPR;
         const int lchunk = (lane % CPR) ^ (2 * (row & 3));
         int col = n0 + lchunk * 8;
         if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
-        lds_copy16(gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)col * 2u), dst);
+        lds_copy16(gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(p.tap_w[t] * p.C_in + col) * 2u), dst);
     };
     // everything chunk `chunk` needs, into buffer set `set` (pruning: the gradient goes to raw slot `set`)
     auto copy_chunk = [&](int chunk, int set, bool with_w) {
@@ -147,9 +175,11 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                 v[1] = *(SDGP_LDS u32x4_t*)(src + (((2 * part + 1) ^ sw) * 16));
                 uint64_t e0 = 0;
                 if constexpr (RK == kRandom) {
+                    const int t = tap_of(chunk), ch = chunk - t * nchunks;  // (`chunk` is the reduction step here)
                     long long grow = m0 + row;
-                    if (grow > last_row) grow = last_row;
-                    e0 = (uint64_t)grow * (uint64_t)p.C_out + (uint64_t)(chunk * KC + part * 16);
+                    if (p.gather) grow = (long long)rowtab[3 * row] + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
+                    grow = grow < 0 ? 0 : (grow > last_pix ? last_pix : grow);  // (rows of zeros: any index will do)
+                    e0 = (uint64_t)grow * (uint64_t)p.C_out + (uint64_t)(ch * KC + part * 16);
                 }
                 uint32_t packed[4], meta;
                 prune16_compressed<M, RK>(v, p.n, p.mix, e0, packed, meta);
@@ -169,19 +199,38 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
             for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
 
     // ---- prologue
+    if (p.gather) {
+        // per row of the tile: flat index of gradient pixel (b, i, j) (it may lie outside the gradient: the taps add
+        // their shifts), i and j, and the input pixel the row is stored to
+        for (int m = tid; m < ROWS; m += NT) {
+            const long long row = m0 + m;
+            int base = -1, ij = 0, opix = -1;
+            if (row <= last_row) {
+                const int pq = p.Pc * p.Qc;
+                const int b = (int)(row / pq), rem = (int)(row - (long long)b * pq);
+                const int i = rem / p.Qc, j = rem - i * p.Qc;
+                base = (b * p.P + i) * p.Q + j;
+                if (base < 0) base = 0;
+                ij = i | (j << 16);
+                opix = (b * p.H + i * p.stride + p.oa) * p.Wd + j * p.stride + p.ob;
+            }
+            rowtab[3 * m] = base, rowtab[3 * m + 1] = ij, rowtab[3 * m + 2] = opix;
+        }
+        __syncthreads();
+    }
     constexpr int SETS = L::kSets;
     static_assert(AU % NW == 0 && WU % NW == 0, "every wavefront issues the same number of copies per chunk");
     constexpr int kCopiesPerChunk = AU / NW + WU / NW;
     if constexpr (SPARSE) {
         copy_chunk(0, 0, true);
-        if (nchunks > 1) copy_chunk(1, 1, false);
+        if (nstages > 1) copy_chunk(1, 1, false);
         wait_lds_copies<0>();
         __syncthreads();
         prune_chunk(0, 0);
     } else {
 #pragma unroll
         for (int i = 0; i < SETS - 1; ++i)
-            if (i < nchunks) copy_chunk(i, i, true);
+            if (i < nstages) copy_chunk(i, i, true);
     }
     wait_lds_copies<0>();
     __syncthreads();
@@ -259,23 +308,23 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     // ---- main loop: one chunk per stage
     Frags fr[2];
     int set = 0, set_req = SETS - 1;  // dense: ring positions of chunk s and of the chunk requested during stage s
-    for (int s = 0; s < nchunks; ++s) {
+    for (int s = 0; s < nstages; ++s) {
         if constexpr (SPARSE) set = s & 1;
         // requests for what comes next: dense -- chunk s + SETS - 1 into the set that the previous stage read;
         // pruning -- W of chunk s+1 and the raw rows of chunk s+2 (into the slot whose rows were ranked during the
         // previous stage)
         if constexpr (SPARSE) {
-            if (s + 1 < nchunks) copy_w_chunk(s + 1, set ^ 1);
-            if (s + 2 < nchunks) {
+            if (s + 1 < nstages) copy_w_chunk(s + 1, set ^ 1);
+            if (s + 2 < nstages) {
                 const uint32_t a_dst = smem_base + L::off_raw() + set * L::kRawBytes;
                 for (int i = wave; i < AU; i += NW) copy_a_unit(i, s + 2, a_dst + (uint32_t)i * 1024u);
             }
         } else {
-            if (s + SETS - 1 < nchunks) copy_chunk(s + SETS - 1, set_req, true);
+            if (s + SETS - 1 < nstages) copy_chunk(s + SETS - 1, set_req, true);
         }
         load_frags(fr[0], set, 0);
         if constexpr (SPARSE) {
-            if (s + 1 < nchunks) prune_chunk(s + 1, set ^ 1);  // its raw rows landed before the last barrier
+            if (s + 1 < nstages) prune_chunk(s + 1, set ^ 1);  // its raw rows landed before the last barrier
         }
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
@@ -289,7 +338,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
         } else {
             // chunk s + 1 has to be there; the requests of the chunks after it (issued in order, the same number by
             // every wavefront) may stay in flight.  Near the end fewer are outstanding: drain.
-            if (s + SETS - 1 < nchunks) wait_lds_copies<(SETS - 2) * kCopiesPerChunk>();
+            if (s + SETS - 1 < nstages) wait_lds_copies<(SETS - 2) * kCopiesPerChunk>();
             else wait_lds_copies<0>();
             set = set + 1 == SETS ? 0 : set + 1;
             set_req = set_req + 1 == SETS ? 0 : set_req + 1;
@@ -314,9 +363,8 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                 *(SDGP_LDS uint16_t*)(smem + m * L::kOutPitch + col * 2) = (uint16_t)pk;
                 *(SDGP_LDS uint16_t*)(smem + (m + 1) * L::kOutPitch + col * 2) = (uint16_t)(pk >> 16);
             }
-    if (p.stride > 1) {
+    if (p.stride > 1 && !p.gather) {
         // where each row of the tile goes: its input pixel and how many of the stride x stride pixels it owns exist
-        SDGP_LDS int* rowtab = (SDGP_LDS int*)(smem + L::off_rowtab());
         for (int m = tid; m < ROWS; m += NT) {
             const long long row = m0 + m;
             int pix = -1, lim = 0;
@@ -342,8 +390,16 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                 *reinterpret_cast<u32x4_t*>(p.dD + (size_t)row * p.C_in + n0 + cc * 8) = v;
             }
         }
+    } else if (p.gather) {
+        for (int idx = tid; idx < ROWS * CPR; idx += NT) {
+            const int m = idx / CPR, cc = idx % CPR;
+            const int pix = rowtab[3 * m + 2];
+            if (pix >= 0 && n0 + cc * 8 < p.C_in) {
+                const u32x4_t v = *(SDGP_LDS u32x4_t*)(smem + m * L::kOutPitch + cc * 16);
+                *reinterpret_cast<u32x4_t*>(p.dD + (size_t)pix * p.C_in + n0 + cc * 8) = v;
+            }
+        }
     } else {
-        const SDGP_LDS int* rowtab = (const SDGP_LDS int*)(smem + L::off_rowtab());
         const u32x4_t zero = {0u, 0u, 0u, 0u};
         for (int idx = tid; idx < ROWS * CPR; idx += NT) {
             const int m = idx / CPR, cc = idx % CPR;

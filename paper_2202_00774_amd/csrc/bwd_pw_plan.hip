@@ -34,6 +34,7 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     p.rows = rows, p.C_out = (int)C_out, p.C_in = (int)C_in;
     p.n = n;
     p.stride = stride, p.P = (int)P, p.Q = (int)Q, p.H = (int)H, p.Wd = (int)Wd;
+    p.rows_dO = rows, p.gather = 0, p.ntaps = 1, p.w_taps = 1;
     p.mix = seed_mix(seed);
 
     // tile shape.  Workgroups of four wavefronts, two to a CU, so that one's loads and stores overlap the other's
@@ -61,6 +62,83 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     if (m == 4) return launch_pw_sparse_m4(p, shape, rk, stream);
     if (m == 8) return launch_pw_sparse_m8(p, shape, rk, stream);
     return launch_pw_sparse_m16(p, shape, rk, stream);
+}
+
+// Strided filters wider than 1x1 (the stride-2 3x3 layers of a ResNet): the input pixels split into stride x stride
+// parity classes; class (a, b) -- pixels (i*stride + a, j*stride + b) -- is a small stride-1 correlation over the
+// gradient with the taps r = a + pad (mod stride), s = b + pad (mod stride), at most four of them here.  One launch of
+// the pointwise kernel per class: a GEMM whose reduction runs over (tap, channel) and whose rows are gathered from the
+// gradient pixels (i + dp, j + dq) of each tap, zeros outside.  Each gradient element is ranked once per tap that
+// reads it (the kept set does not depend on who asks).
+// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
+int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                      int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
+    int mode;
+    if (n == m) mode = 0;
+    else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
+    else return 1;
+    if (stride < 2 || stride > 4 || R < stride || S < stride || R > 2 * stride || S > 2 * stride || pad < 0) return 1;
+    if (C_out < kPwKC || (C_out % kPwKC) != 0 || C_in < 8 || (C_in % 8) != 0) return 1;
+    if (mode == 2 && (C_out % m) != 0) return 1;
+    if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
+    if (H + 2 * pad < R || Wd + 2 * pad < S || H < stride || Wd < stride) return 1;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    if (B < 1 || P < 1 || Q < 1 || P >= 65536 || Q >= 32768 || H >= 65536 || Wd >= 32768 || B * (P + 8) * (Q + 8) >= (1 << 30) || B * H * Wd >= INT_MAX ||
+        C_out >= (1 << 20) || (int64_t)R * S * C_in >= (1 << 20))
+        return 1;
+
+    PwParams base{};
+    base.dO = static_cast<const uint16_t*>(dO);
+    base.W = static_cast<const uint16_t*>(W);
+    base.dD = static_cast<uint16_t*>(dD);
+    base.C_out = (int)C_out, base.C_in = (int)C_in;
+    base.n = n;
+    base.mix = seed_mix(seed);
+    base.stride = stride, base.P = (int)P, base.Q = (int)Q, base.H = (int)H, base.Wd = (int)Wd;
+    base.rows_dO = B * P * Q, base.gather = 1, base.w_taps = R * S;
+
+    int shape;
+    if (C_in <= 64) shape = 2;
+    else if (mode == 2 && C_in > 128) shape = 0;
+    else shape = 1;
+    const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
+    base.ntiles_n = (int)((C_in + bn - 1) / bn);
+
+    // all classes first: nothing is launched unless every one of them fits
+    PwParams cls[16];
+    int ncls = 0;
+    for (int a = 0; a < stride; ++a)
+        for (int b = 0; b < stride; ++b) {
+            PwParams q = base;
+            q.oa = a, q.ob = b;
+            q.Pc = (int)((H - a + stride - 1) / stride), q.Qc = (int)((Wd - b + stride - 1) / stride);
+            q.ntaps = 0;
+            for (int r = 0; r < R; ++r) {
+                if ((a + pad - r) % stride != 0) continue;
+                for (int sx = 0; sx < S; ++sx) {
+                    if ((b + pad - sx) % stride != 0) continue;
+                    if (q.ntaps == 4) return 1;
+                    q.tap_dp[q.ntaps] = (a + pad - r) / stride, q.tap_dq[q.ntaps] = (b + pad - sx) / stride;
+                    q.tap_w[q.ntaps] = r * S + sx;
+                    ++q.ntaps;
+                }
+            }
+            if (q.ntaps == 0) return 1;
+            q.rows = B * q.Pc * q.Qc;
+            const int64_t blocks = ((q.rows + rows_per - 1) / rows_per) * q.ntiles_n;
+            if (q.rows < 1 || blocks < 64 || blocks >= INT_MAX) return 1;
+            q.nblocks = (int)blocks;
+            cls[ncls++] = q;
+        }
+    for (int i = 0; i < ncls; ++i) {
+        int rc;
+        if (mode == 0) rc = launch_pw_dense(cls[i], shape, stream);
+        else if (m == 4) rc = launch_pw_sparse_m4(cls[i], shape, rk, stream);
+        else if (m == 8) rc = launch_pw_sparse_m8(cls[i], shape, rk, stream);
+        else rc = launch_pw_sparse_m16(cls[i], shape, rk, stream);
+        if (rc != SDGP_OK) return rc;
+    }
+    return SDGP_OK;
 }
 
 }  // namespace sdgp

@@ -240,6 +240,25 @@ POINTWISE_CONVS = [
 ]
 
 
+# strided filters wider than 1x1: one pointwise launch per parity class of the input pixels, rows gathered per tap
+STRIDED_CONVS = [
+    wl.ConvLayer("g_s2_3x3", 64, 30, 28, 72, 64, 3, 3, 2, 1),          # classes of 1, 2, 2 and 4 taps
+    wl.ConvLayer("g_s2_3x3_n264", 96, 17, 19, 264, 32, 3, 3, 2, 1),    # odd image, several column tiles
+    wl.ConvLayer("g_s2_4x4", 64, 32, 32, 64, 64, 4, 4, 2, 1),          # four taps in every class
+    wl.ConvLayer("g_s2_3x3_valid", 64, 31, 31, 40, 32, 3, 3, 2, 0),    # no padding
+    wl.ConvLayer("g_s3_3x3", 192, 30, 30, 32, 32, 3, 3, 3, 1),         # stride 3: nine classes of one tap
+]
+
+
+@pytest.mark.parametrize("layer", STRIDED_CONVS, ids=lambda l: l.name)
+def test_strided_conv_matches_oracle(layer):
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=93, dtype=oracle.BF16)
+    pixels = sample_pixels(layer, 2000, 9)
+    for n, m, ranker in ((4, 4, oracle.GREEDY), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED),
+                         (2, 4, oracle.RANDOM), (2, 8, oracle.RANDOM), (2, 16, oracle.GREEDY)):
+        check_conv(layer, dO, W, n, m, ranker, 17, oracle.BF16, pixels=pixels)
+
+
 @pytest.mark.parametrize("layer", POINTWISE_CONVS, ids=lambda l: l.name)
 def test_pointwise_conv_matches_oracle(layer):
     dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=91, dtype=oracle.BF16)
