@@ -70,7 +70,7 @@ struct PwLayout {
 // what a tap outside the gradient copies (one 64-byte chunk row)
 __device__ __align__(64) const uint32_t kPwZeros[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-template <int BN, int MODE, int M, int RK, int ROWS, int NW>
+template <int BN, int MODE, int M, int RK, int ROWS, int NW, bool GATHER>
 __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     using L = PwLayout<BN, MODE, ROWS>;
     static_assert(L::total() <= 160 * 1024, "LDS budget");
@@ -109,11 +109,11 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     const long long m0 = (long long)(lid / p.ntiles_n) * ROWS;
     const int n0 = ntile * BN;
     const int nchunks = p.C_out / KC;
-    const int nstages = nchunks * p.ntaps;   // reduction steps: (tap, chunk), the chunks of a tap in a row
+    const int nstages = GATHER ? nchunks * p.ntaps : nchunks;   // reduction steps: (tap, chunk), the chunks of a tap in a row
     const long long last_row = p.rows - 1;
     const long long last_pix = (long long)p.rows_dO - 1;
     SDGP_LDS int* rowtab = (SDGP_LDS int*)(smem + L::off_rowtab());
-    auto tap_of = [&](int st) { return (st >= nchunks) + (st >= 2 * nchunks) + (st >= 3 * nchunks); };
+    auto tap_of = [&](int st) { return GATHER ? (st >= nchunks) + (st >= 2 * nchunks) + (st >= 3 * nchunks) : 0; };
     const unsigned char* const gdO = reinterpret_cast<const unsigned char*>(p.dO);
     const unsigned char* const gWb = reinterpret_cast<const unsigned char*>(p.W);
     const uint32_t rowB = (uint32_t)p.C_out * 2u;      // bytes per gradient row
@@ -125,7 +125,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                                   : (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
     // `st` is the reduction step: tap st / nchunks, chunk st % nchunks
     auto copy_a_unit = [&](int u, int st, uint32_t dst) {
-        if (!p.gather) {
+        if constexpr (!GATHER) {
             long long row = m0 + u * 16 + (lane >> 2);
             if (row > last_row) row = last_row;
             lds_copy16(gdO + ((size_t)row * rowB + (size_t)st * (KC * 2) + c16_a), dst);
@@ -149,7 +149,8 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
         const int lchunk = (lane % CPR) ^ (2 * (row & 3));
         int col = n0 + lchunk * 8;
         if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
-        lds_copy16(gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(p.tap_w[t] * p.C_in + col) * 2u), dst);
+        const int wtap = GATHER ? p.tap_w[t] : 0;
+        lds_copy16(gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(wtap * p.C_in + col) * 2u), dst);
     };
     // everything chunk `chunk` needs, into buffer set `set` (pruning: the gradient goes to raw slot `set`)
     auto copy_chunk = [&](int chunk, int set, bool with_w) {
@@ -177,7 +178,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                 if constexpr (RK == kRandom) {
                     const int t = tap_of(chunk), ch = chunk - t * nchunks;  // (`chunk` is the reduction step here)
                     long long grow = m0 + row;
-                    if (p.gather) grow = (long long)rowtab[3 * row] + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
+                    if constexpr (GATHER) grow = (long long)rowtab[3 * row] + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
                     grow = grow < 0 ? 0 : (grow > last_pix ? last_pix : grow);  // (rows of zeros: any index will do)
                     e0 = (uint64_t)grow * (uint64_t)p.C_out + (uint64_t)(ch * KC + part * 16);
                 }
@@ -199,7 +200,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
             for (int r = 0; r < 16; ++r) acc[t][u][r] = 0.0f;
 
     // ---- prologue
-    if (p.gather) {
+    if constexpr (GATHER) {
         // per row of the tile: flat index of gradient pixel (b, i, j) (it may lie outside the gradient: the taps add
         // their shifts), i and j, and the input pixel the row is stored to
         for (int m = tid; m < ROWS; m += NT) {
@@ -363,7 +364,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                 *(SDGP_LDS uint16_t*)(smem + m * L::kOutPitch + col * 2) = (uint16_t)pk;
                 *(SDGP_LDS uint16_t*)(smem + (m + 1) * L::kOutPitch + col * 2) = (uint16_t)(pk >> 16);
             }
-    if (p.stride > 1 && !p.gather) {
+    if (!GATHER && p.stride > 1) {
         // where each row of the tile goes: its input pixel and how many of the stride x stride pixels it owns exist
         for (int m = tid; m < ROWS; m += NT) {
             const long long row = m0 + m;
@@ -380,7 +381,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
         }
     }
     __syncthreads();
-    if (p.stride == 1) {
+    if (!GATHER && p.stride == 1) {
 #pragma unroll 4
         for (int idx = tid; idx < ROWS * CPR; idx += NT) {
             const int m = idx / CPR, cc = idx % CPR;
@@ -390,7 +391,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
                 *reinterpret_cast<u32x4_t*>(p.dD + (size_t)row * p.C_in + n0 + cc * 8) = v;
             }
         }
-    } else if (p.gather) {
+    } else if (GATHER) {
         for (int idx = tid; idx < ROWS * CPR; idx += NT) {
             const int m = idx / CPR, cc = idx % CPR;
             const int pix = rowtab[3 * m + 2];

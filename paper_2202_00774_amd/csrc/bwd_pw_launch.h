@@ -5,10 +5,10 @@
 
 namespace sdgp {
 
-template <int BN, int MODE, int M, int RK, int ROWS, int NW>
+template <int BN, int MODE, int M, int RK, int ROWS, int NW, bool GATHER>
 int launch_pw_one(const PwParams& p, hipStream_t stream) {
     using L = PwLayout<BN, MODE, ROWS>;
-    auto kern = bwd_pw<BN, MODE, M, RK, ROWS, NW>;
+    auto kern = bwd_pw<BN, MODE, M, RK, ROWS, NW, GATHER>;
     static const hipError_t attr =
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return SDGP_ERR_HIP;
@@ -27,7 +27,9 @@ template <int MODE, int M, int RK>
 int launch_pw_shape(const PwParams& p, int shape, hipStream_t stream) {
     switch (shape) {
 #define SDGP_PW_CASE(i) \
-    case i: return launch_pw_one<kPwShapes[i].bn, MODE, M, RK, kPwShapes[i].rows, kPwShapes[i].waves>(p, stream);
+    case i:                                                                                                          \
+        return p.gather ? launch_pw_one<kPwShapes[i].bn, MODE, M, RK, kPwShapes[i].rows, kPwShapes[i].waves, true>(p, stream)  \
+                        : launch_pw_one<kPwShapes[i].bn, MODE, M, RK, kPwShapes[i].rows, kPwShapes[i].waves, false>(p, stream);
         SDGP_PW_CASE(0)
         SDGP_PW_CASE(1)
         SDGP_PW_CASE(2)

@@ -77,6 +77,7 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
     p.mix = seed_mix(seed);
 #ifdef SDGP_TRACE
     if (const char* e = getenv("SDGP_EXP")) p.exp = atoi(e);
+    if (const char* t = getenv("SDGP_TRACE_PTR")) p.trace = (unsigned long long*)strtoull(t, nullptr, 0);
 #endif
 
     const int bn = (C_in > 64) ? 128 : 64;
