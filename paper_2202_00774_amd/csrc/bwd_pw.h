@@ -45,6 +45,7 @@ constexpr int kPwKC = 32;  // reduction channels per chunk
 template <int BN, int MODE, int ROWS>
 struct PwLayout {
     static constexpr bool kSparse = MODE == 2;
+    static constexpr bool kPrunes = MODE != 0;  // raw rows are staged and ranked (MODE 1 stores them dense, zero-filled)
     static constexpr int kWRow = BN * 2;
     static constexpr int kWSlab = kPwKC * kWRow;
     static constexpr int kWUnits = kWSlab / 1024;
@@ -59,7 +60,7 @@ struct PwLayout {
     static constexpr int kSets = 2;
     static constexpr int off_w() { return 0; }
     static constexpr int off_raw() { return off_w() + kSets * kWSlab; }
-    static constexpr int off_a() { return off_raw() + (kSparse ? 2 * kRawBytes : 0); }
+    static constexpr int off_a() { return off_raw() + (kPrunes ? 2 * kRawBytes : 0); }
     static constexpr int off_meta() { return off_a() + kSets * kABytes; }
     static constexpr int loop_bytes() { return off_meta() + 2 * kMetaBytes; }
     static constexpr int out_bytes() { return ROWS * kOutPitch; }
@@ -75,6 +76,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     using L = PwLayout<BN, MODE, ROWS>;
     static_assert(L::total() <= 160 * 1024, "LDS budget");
     constexpr bool SPARSE = MODE == 2;
+    constexpr bool PRUNES = MODE != 0;
     constexpr int KC = kPwKC;
     constexpr int WAVES_N = BN / 64;
     constexpr int WAVES_M = NW / WAVES_N;
@@ -121,7 +123,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
 
     // ---- copies.  Gradient: unit u = rows 16u .. 16u+15 of the tile, 64 bytes each; LDS position (lane & 3) of row
     // (lane >> 2) holds the swizzled source column.  Rows past the tensor re-read the last row (never stored).
-    const uint32_t c16_a = SPARSE ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
+    const uint32_t c16_a = PRUNES ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
                                   : (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
     // `st` is the reduction step: tap st / nchunks, chunk st % nchunks
     auto copy_a_unit = [&](int u, int st, uint32_t dst) {
@@ -154,7 +156,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     };
     // everything chunk `chunk` needs, into buffer set `set` (pruning: the gradient goes to raw slot `set`)
     auto copy_chunk = [&](int chunk, int set, bool with_w) {
-        const uint32_t a_dst = smem_base + (SPARSE ? L::off_raw() + set * L::kRawBytes : L::off_a() + set * L::kABytes);
+        const uint32_t a_dst = smem_base + (PRUNES ? L::off_raw() + set * L::kRawBytes : L::off_a() + set * L::kABytes);
         for (int i = wave; i < AU; i += NW) copy_a_unit(i, chunk, a_dst + (uint32_t)i * 1024u);
         if (with_w)
             for (int i = wave; i < WU; i += NW) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
@@ -165,6 +167,51 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
 
     // rank / prune / compress raw slot `set` (chunk `chunk`) into gradient buffer `set`: ROWS * 2 items of 16 channels
     auto prune_chunk = [&](int chunk, int set) {
+        if constexpr (PRUNES && !SPARSE) {
+            // any n of m (m up to 32): the pruned rows are stored dense, zeros in the dropped positions, in the layout
+            // the dense matrix instruction reads.  One item = one m-group or sixteen channels, whichever is larger.
+            constexpr int IC = M > 16 ? M : 16;       // channels per item
+            constexpr int IPR = KC / IC;              // items per row of the chunk
+#pragma unroll 1
+            for (int item = tid; item < ROWS * IPR; item += NT) {
+                const int row = item / IPR, part = item % IPR;
+                SDGP_LDS unsigned char* src = smem + L::off_raw() + set * L::kRawBytes + row * 64;
+                SDGP_LDS unsigned char* dst = smem + L::off_a() + set * L::kABytes + row * 64;
+                const int sw = (row >> 2) & 1, sw2 = (row >> 2) & 3;
+                uint32_t raw[IC], out[IC];
+#pragma unroll
+                for (int g = 0; g < IC / 8; ++g) {
+                    const u32x4_t v = *(SDGP_LDS u32x4_t*)(src + (((part * (IC / 8) + g) ^ sw) * 16));
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) raw[g * 8 + 2 * x] = v[x] & 0xFFFFu, raw[g * 8 + 2 * x + 1] = v[x] >> 16;
+                }
+                uint64_t e0 = 0;
+                if constexpr (RK == kRandom) {
+                    const int t = tap_of(chunk), ch = chunk - t * nchunks;  // (`chunk` is the reduction step here)
+                    long long grow = m0 + row;
+                    if constexpr (GATHER) grow = (long long)rowtab[3 * row] + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
+                    grow = grow < 0 ? 0 : (grow > last_pix ? last_pix : grow);
+                    e0 = (uint64_t)grow * (uint64_t)p.C_out + (uint64_t)(ch * KC + part * IC);
+                }
+#pragma unroll
+                for (int g = 0; g < IC / M; ++g) {
+                    uint32_t r[M], o[M];
+                    bool kk[M];
+#pragma unroll
+                    for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
+                    const uint64_t eg = e0 + (uint64_t)(g * M);
+                    prune_group<kBF16, M, RK, false>(r, p.n, hash_row(p.mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+#pragma unroll
+                    for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
+                }
+#pragma unroll
+                for (int g = 0; g < IC / 8; ++g) {
+                    const u32x4_t x = {out[g * 8] | (out[g * 8 + 1] << 16), out[g * 8 + 2] | (out[g * 8 + 3] << 16),
+                                       out[g * 8 + 4] | (out[g * 8 + 5] << 16), out[g * 8 + 6] | (out[g * 8 + 7] << 16)};
+                    *(SDGP_LDS u32x4_t*)(dst + (((part * (IC / 8) + g) ^ sw2) << 4)) = x;
+                }
+            }
+        }
         if constexpr (SPARSE) {
 #pragma unroll 1
             for (int item = tid; item < ROWS * 2; item += NT) {
@@ -222,7 +269,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     constexpr int SETS = L::kSets;
     static_assert(AU % NW == 0 && WU % NW == 0, "every wavefront issues the same number of copies per chunk");
     constexpr int kCopiesPerChunk = AU / NW + WU / NW;
-    if constexpr (SPARSE) {
+    if constexpr (PRUNES) {
         copy_chunk(0, 0, true);
         if (nstages > 1) copy_chunk(1, 1, false);
         wait_lds_copies<0>();
@@ -310,11 +357,11 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
     Frags fr[2];
     int set = 0, set_req = SETS - 1;  // dense: ring positions of chunk s and of the chunk requested during stage s
     for (int s = 0; s < nstages; ++s) {
-        if constexpr (SPARSE) set = s & 1;
+        if constexpr (PRUNES) set = s & 1;
         // requests for what comes next: dense -- chunk s + SETS - 1 into the set that the previous stage read;
         // pruning -- W of chunk s+1 and the raw rows of chunk s+2 (into the slot whose rows were ranked during the
         // previous stage)
-        if constexpr (SPARSE) {
+        if constexpr (PRUNES) {
             if (s + 1 < nstages) copy_w_chunk(s + 1, set ^ 1);
             if (s + 2 < nstages) {
                 const uint32_t a_dst = smem_base + L::off_raw() + set * L::kRawBytes;
@@ -324,7 +371,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
             if (s + SETS - 1 < nstages) copy_chunk(s + SETS - 1, set_req, true);
         }
         load_frags(fr[0], set, 0);
-        if constexpr (SPARSE) {
+        if constexpr (PRUNES) {
             if (s + 1 < nstages) prune_chunk(s + 1, set ^ 1);  // its raw rows landed before the last barrier
         }
 #pragma unroll
@@ -334,7 +381,7 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
             mma(fr[ks & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (SPARSE) {
+        if constexpr (PRUNES) {
             wait_lds_copies<0>();
         } else {
             // chunk s + 1 has to be there; the requests of the chunks after it (issued in order, the same number by

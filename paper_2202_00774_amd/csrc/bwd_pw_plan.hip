@@ -11,16 +11,44 @@ int launch_pw_dense(const PwParams& p, int shape, hipStream_t stream);
 int launch_pw_sparse_m4(const PwParams& p, int shape, int rk, hipStream_t stream);
 int launch_pw_sparse_m8(const PwParams& p, int shape, int rk, hipStream_t stream);
 int launch_pw_sparse_m16(const PwParams& p, int shape, int rk, hipStream_t stream);
+int launch_pw_masked_m4(const PwParams& p, int shape, int rk, hipStream_t stream);
+int launch_pw_masked_m8(const PwParams& p, int shape, int rk, hipStream_t stream);
+int launch_pw_masked_m16(const PwParams& p, int shape, int rk, hipStream_t stream);
+int launch_pw_masked_m32(const PwParams& p, int shape, int rk, hipStream_t stream);
+
+namespace {
+
+// 0: dense (n == m); 2: at most two survivors per aligned quad, the structured-sparse instruction; 1: any other n of
+// m in {4, 8, 16, 32}, pruned rows stored dense with zeros; -1: not for this kernel
+int pw_mode(int n, int m) {
+    if (n == m) return 0;
+    if (n <= 2 && (m == 4 || m == 8 || m == 16)) return 2;
+    if (m == 4 || m == 8 || m == 16 || m == 32) return 1;
+    return -1;
+}
+
+int launch_pw_any(const PwParams& p, int mode, int m, int shape, int rk, hipStream_t stream) {
+    if (mode == 0) return launch_pw_dense(p, shape, stream);
+    if (mode == 2) {
+        if (m == 4) return launch_pw_sparse_m4(p, shape, rk, stream);
+        if (m == 8) return launch_pw_sparse_m8(p, shape, rk, stream);
+        return launch_pw_sparse_m16(p, shape, rk, stream);
+    }
+    if (m == 4) return launch_pw_masked_m4(p, shape, rk, stream);
+    if (m == 8) return launch_pw_masked_m8(p, shape, rk, stream);
+    if (m == 16) return launch_pw_masked_m16(p, shape, rk, stream);
+    return launch_pw_masked_m32(p, shape, rk, stream);
+}
+
+}  // namespace
 
 // SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
 int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                   int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
-    int mode;
-    if (n == m) mode = 0;
-    else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
-    else return 1;
+    const int mode = pw_mode(n, m);
+    if (mode < 0) return 1;
     if (R != 1 || S != 1 || stride < 1 || stride > 255 || pad != 0 || (C_out % kPwKC) != 0 || (C_in % 8) != 0) return 1;
-    if (mode == 2 && (C_out % m) != 0) return 1;
+    if (mode != 0 && (C_out % m) != 0) return 1;
     if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
     const int64_t P = (H - 1) / stride + 1, Q = (Wd - 1) / stride + 1;  // gradient image
     const int64_t rows = B * P * Q;
@@ -44,7 +72,7 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     auto blocks_of = [&](int rows_per, int bn) { return ((rows + rows_per - 1) / rows_per) * ((C_in + bn - 1) / bn); };
     int shape;
     if (C_in <= 64) shape = 2;
-    else if (mode == 2 && C_in > 128) shape = 0;
+    else if (mode != 0 && C_in > 128) shape = 0;
     else shape = 1;
 #ifdef SDGP_TRACE
     if (const char* e = getenv("SDGP_PW_SHAPE")) {
@@ -58,10 +86,7 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     p.ntiles_n = (int)((C_in + bn - 1) / bn);
     p.nblocks = (int)blocks;
 
-    if (mode == 0) return launch_pw_dense(p, shape, stream);
-    if (m == 4) return launch_pw_sparse_m4(p, shape, rk, stream);
-    if (m == 8) return launch_pw_sparse_m8(p, shape, rk, stream);
-    return launch_pw_sparse_m16(p, shape, rk, stream);
+    return launch_pw_any(p, mode, m, shape, rk, stream);
 }
 
 // Strided filters wider than 1x1 (the stride-2 3x3 layers of a ResNet): the input pixels split into stride x stride
@@ -73,13 +98,11 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
 // SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
 int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                       int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
-    int mode;
-    if (n == m) mode = 0;
-    else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
-    else return 1;
+    const int mode = pw_mode(n, m);
+    if (mode < 0) return 1;
     if (stride < 2 || stride > 4 || R < stride || S < stride || R > 2 * stride || S > 2 * stride || pad < 0) return 1;
     if (C_out < kPwKC || (C_out % kPwKC) != 0 || C_in < 8 || (C_in % 8) != 0) return 1;
-    if (mode == 2 && (C_out % m) != 0) return 1;
+    if (mode != 0 && (C_out % m) != 0) return 1;
     if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
     if (H + 2 * pad < R || Wd + 2 * pad < S || H < stride || Wd < stride) return 1;
     const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
@@ -99,7 +122,7 @@ int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
 
     int shape;
     if (C_in <= 64) shape = 2;
-    else if (mode == 2 && C_in > 128) shape = 0;
+    else if (mode != 0 && C_in > 128) shape = 0;
     else shape = 1;
     const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
     base.ntiles_n = (int)((C_in + bn - 1) / bn);
@@ -131,11 +154,7 @@ int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
             cls[ncls++] = q;
         }
     for (int i = 0; i < ncls; ++i) {
-        int rc;
-        if (mode == 0) rc = launch_pw_dense(cls[i], shape, stream);
-        else if (m == 4) rc = launch_pw_sparse_m4(cls[i], shape, rk, stream);
-        else if (m == 8) rc = launch_pw_sparse_m8(cls[i], shape, rk, stream);
-        else rc = launch_pw_sparse_m16(cls[i], shape, rk, stream);
+        const int rc = launch_pw_any(cls[i], mode, m, shape, rk, stream);
         if (rc != SDGP_OK) return rc;
     }
     return SDGP_OK;

@@ -1,0 +1,8 @@
+// Instantiates the pointwise kernel for any n of m = 32 that the structured-sparse instruction cannot take (n > 2, or any n at m = 32):
+// the pruned rows are stored dense with zeros and multiplied by the dense matrix instruction.
+#include "bwd_pw_launch.h"
+namespace sdgp {
+int launch_pw_masked_m32(const PwParams& p, int shape, int rk, hipStream_t stream) {
+    return launch_pw_rk<1, 32>(p, shape, rk, stream);
+}
+}  // namespace sdgp

@@ -255,7 +255,8 @@ def test_strided_conv_matches_oracle(layer):
     dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=93, dtype=oracle.BF16)
     pixels = sample_pixels(layer, 2000, 9)
     for n, m, ranker in ((4, 4, oracle.GREEDY), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED),
-                         (2, 4, oracle.RANDOM), (2, 8, oracle.RANDOM), (2, 16, oracle.GREEDY)):
+                         (2, 4, oracle.RANDOM), (2, 8, oracle.RANDOM), (2, 16, oracle.GREEDY),
+                         (4, 8, oracle.GREEDY), (8, 32, oracle.GREEDY_ADJUSTED)):
         check_conv(layer, dO, W, n, m, ranker, 17, oracle.BF16, pixels=pixels)
 
 
@@ -265,7 +266,10 @@ def test_pointwise_conv_matches_oracle(layer):
     pixels = sample_pixels(layer, 1500, 7)
     for n, m, ranker in ((4, 4, oracle.GREEDY), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED),
                          (2, 4, oracle.RANDOM), (1, 4, oracle.GREEDY), (2, 8, oracle.RANDOM),
-                         (2, 16, oracle.GREEDY_ADJUSTED), (2, 16, oracle.GREEDY)):
+                         (2, 16, oracle.GREEDY_ADJUSTED), (2, 16, oracle.GREEDY),
+                         # more than two survivors per group, or groups of 32: pruned rows stored dense with zeros
+                         (3, 4, oracle.GREEDY), (4, 8, oracle.RANDOM), (4, 16, oracle.GREEDY_ADJUSTED),
+                         (16, 32, oracle.GREEDY), (2, 32, oracle.RANDOM)):
         check_conv(layer, dO, W, n, m, ranker, 13, oracle.BF16, pixels=pixels)
 
 
