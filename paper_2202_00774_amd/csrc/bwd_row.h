@@ -60,6 +60,7 @@ constexpr int kRowMaxRows = 3;
 template <int BN, int MODE, int ROWS>
 struct RowLayout {
     static constexpr bool kSparse = MODE == 2;
+    static constexpr bool kPrunes = MODE != 0;  // raw halo shares are staged and ranked (MODE 1 stores them dense, zero-filled)
     static constexpr int kWRow = BN * 2;
     static constexpr int kWSlab = kRowKC * kWRow;
     static constexpr int kWUnits = kWSlab / 1024;
@@ -76,7 +77,7 @@ struct RowLayout {
     __host__ __device__ static int off_atab() { return off_w() + 2 * kWSet; }
     __host__ __device__ static int off_haloaddr() { return off_atab() + kRowMaxRows * kRowTaps * ROWS * 4; }
     __host__ __device__ static int off_raw(int halo) { return off_haloaddr() + pixels(halo) * 8; }
-    __host__ __device__ static int off_a(int halo) { return off_raw(halo) + (kSparse ? 2 * kRawSlot : 0); }
+    __host__ __device__ static int off_a(int halo) { return off_raw(halo) + (kPrunes ? 2 * kRawSlot : 0); }
     __host__ __device__ static int a_bytes(int halo) { return pixels(halo) * kAPitch; }
     __host__ __device__ static int off_meta(int halo) { return off_a(halo) + 2 * a_bytes(halo); }
     __host__ __device__ static int meta_bytes(int halo) { return kSparse ? pixels(halo) * 4 : 0; }
@@ -92,6 +93,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     using L = RowLayout<BN, MODE, ROWS>;
     static_assert(ROWS == 512 || ROWS == 256, "rows of a workgroup tile");
     constexpr bool SPARSE = MODE == 2;
+    constexpr bool PRUNES = MODE != 0;
     constexpr int KC = kRowKC;
     constexpr int TS = kRowTaps;
     constexpr int WAVES_N = BN / 64;
@@ -230,7 +232,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         }
     };
     // 16-byte column a lane copies: LDS position (lane & 3) of pixel (lane >> 2) holds the swizzled source column
-    const uint32_t c16_halo = SPARSE ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
+    const uint32_t c16_halo = PRUNES ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
                                      : (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
     const uint32_t haloaddr_lane = (uint32_t)L::off_haloaddr() + (uint32_t)(lane >> 2) * 8u;
     // unit u of the halo, channels at byte offset src_off of every pixel, to LDS address dst
@@ -245,6 +247,47 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
 
     // rank / prune / compress 64 items (pixel, 16-channel half) of a raw share into a halo buffer (Sec. III-B)
     auto prune_items = [&](int item0, int nitems, int u0, uint32_t raw, uint32_t abuf, uint32_t mbuf, uint32_t chan0) {
+        if constexpr (PRUNES && !SPARSE) {
+            // any n of m: the pruned pixels are stored dense, zeros in the dropped positions, in the layout the dense
+            // matrix instruction reads.  (A 32-group would be the whole chunk of a pixel, taken by the lane of its
+            // first half; no 32-group instantiation exists, see the planner.)
+            constexpr int IC = M > 16 ? 32 : 16;  // channels per item
+            const int item = item0 + lane;
+            const int j = item >> 5, px = (item >> 1) & 15, part = item & 1;
+            const int hp = (u0 + j) * 16 + px;
+            if (item < nitems && hp < nhalo && (IC == 16 || part == 0)) {
+                SDGP_LDS unsigned char* src = smem + raw + j * 1024 + px * 64;
+                SDGP_LDS unsigned char* dst = smem + abuf + hp * 64;
+                const int sw = (px >> 2) & 1, sw2 = (hp >> 2) & 3;
+                uint32_t rawv[IC], out[IC];
+#pragma unroll
+                for (int g = 0; g < IC / 8; ++g) {
+                    const u32x4_t v = *(SDGP_LDS u32x4_t*)(src + (((part * 2 + g) ^ sw) * 16));
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) rawv[g * 8 + 2 * x] = v[x] & 0xFFFFu, rawv[g * 8 + 2 * x + 1] = v[x] >> 16;
+                }
+                uint64_t e0 = 0;
+                if constexpr (RK == kRandom)
+                    e0 = ((uint64_t)(haloaddr[hp] - (u64_t)(uintptr_t)gdO) >> 1) + (uint64_t)(chan0 + part * 16);
+#pragma unroll
+                for (int g = 0; g < IC / M; ++g) {
+                    uint32_t rr[M], o[M];
+                    bool kk[M];
+#pragma unroll
+                    for (int jj = 0; jj < M; ++jj) rr[jj] = rawv[g * M + jj];
+                    const uint64_t eg = e0 + (uint64_t)(g * M);
+                    prune_group<kBF16, M, RK, false>(rr, p.n, hash_row(p.mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+#pragma unroll
+                    for (int jj = 0; jj < M; ++jj) out[g * M + jj] = o[jj];
+                }
+#pragma unroll
+                for (int g = 0; g < IC / 8; ++g) {
+                    const u32x4_t x = {out[g * 8] | (out[g * 8 + 1] << 16), out[g * 8 + 2] | (out[g * 8 + 3] << 16),
+                                       out[g * 8 + 4] | (out[g * 8 + 5] << 16), out[g * 8 + 6] | (out[g * 8 + 7] << 16)};
+                    *(SDGP_LDS u32x4_t*)(dst + (((part * 2 + g) ^ sw2) << 4)) = x;
+                }
+            }
+        }
         if constexpr (SPARSE) {
             const int item = item0 + lane;
             const int j = item >> 5, px = (item >> 1) & 15, part = item & 1;
@@ -282,7 +325,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     const int ups = p.ups;
     const int pc1 = c_rot + 1 == nchunks ? 0 : c_rot + 1;  // physical chunk of logical chunk 1
     copy_w_set(c_rot, r_rot, 0);
-    if constexpr (!SPARSE) {
+    if constexpr (!PRUNES) {
         for (int u = wave; u < nunits; u += 8) copy_halo(u, (uint32_t)c_rot * (KC * 2), smem_base + off_a + u * 1024);
         build_row_tables();
     } else {
@@ -408,7 +451,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         // (w and w + 4) rank at different times -- one before the stage's first k-step, the other after it -- so
         // that one's vector work runs under the other's matrix instructions.
         auto prune_share = [&]() {
-            if constexpr (SPARSE) {
+            if constexpr (PRUNES) {
                 if (c + 1 < nchunks && !SDGP_EXP(32)) {
                     const int u0 = r * ups;
                     const int cnt = min(ups, nunits - u0);
@@ -459,7 +502,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 } else if (i == APIECES + TN + 1) {
                     if (more) copy_w_set(npc, npr, (x + 1) & 1);
                 } else if (i == APIECES + TN + 2) {
-                    if constexpr (!SPARSE) {
+                    if constexpr (!PRUNES) {
                         // dense: share r of the next chunk's halo straight into the other buffer
                         if (c + 1 < nchunks) {
                             const int u0 = r * ups;

@@ -12,6 +12,9 @@ int launch_row_dense(const RowParams& p, int bn, int rows, hipStream_t stream);
 int launch_row_sparse_m4(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
 int launch_row_sparse_m8(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
 int launch_row_sparse_m16(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
+int launch_row_masked_m4(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
+int launch_row_masked_m8(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
+int launch_row_masked_m16(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
 int row_lds_bytes(int mode, int bn, int rows, int halo);
 
 namespace {
@@ -52,12 +55,16 @@ int64_t plan_tiles(RowParams& p, int rows, int mode, int bn, int64_t B, int64_t 
 int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                    int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                    hipStream_t stream) {
+    // 0: dense; 2: at most two survivors per aligned quad, the structured-sparse instruction; 1: any other n of m in
+    // {4, 8, 16}, the pruned halo stored dense with zeros (32-groups need more registers than eight wavefronts leave:
+    // the parity-class kernel keeps them)
     int mode;
     if (n == m) mode = 0;
     else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
+    else if (m == 4 || m == 8 || m == 16) mode = 1;
     else return 1;
     if (stride != 1 || S != kRowTaps || R < 1 || R > kRowMaxRows || (C_out % kRowKC) != 0 || (C_in % 8) != 0) return 1;
-    if (mode == 2 && (C_out % m) != 0) return 1;
+    if (mode != 0 && (C_out % m) != 0) return 1;
     if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
     const int ntaps = R * S;
     const int64_t P = H + 2 * pad - R + 1, Q = Wd + 2 * pad - S + 1;
@@ -96,6 +103,11 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
     p.nblocks = (int)blocks;
 
     if (mode == 0) return launch_row_dense(p, bn, rows, stream);
+    if (mode == 1) {
+        if (m == 4) return launch_row_masked_m4(p, bn, rows, rk, stream);
+        if (m == 8) return launch_row_masked_m8(p, bn, rows, rk, stream);
+        return launch_row_masked_m16(p, bn, rows, rk, stream);
+    }
     if (m == 4) return launch_row_sparse_m4(p, bn, rows, rk, stream);
     if (m == 8) return launch_row_sparse_m8(p, bn, rows, rk, stream);
     return launch_row_sparse_m16(p, bn, rows, rk, stream);

@@ -163,7 +163,10 @@ def test_many_tile_conv_matches_oracle(layer):
     pixels = sample_pixels(layer, 700, 5)
     for n, m, ranker in ((4, 4, oracle.GREEDY), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED),
                          (2, 4, oracle.RANDOM), (1, 4, oracle.GREEDY), (2, 8, oracle.GREEDY_ADJUSTED),
-                         (2, 16, oracle.RANDOM), (2, 16, oracle.GREEDY)):
+                         (2, 16, oracle.RANDOM), (2, 16, oracle.GREEDY),
+                         # more than two survivors per group, or groups of 32: the pruned halo stored dense with zeros
+                         (3, 4, oracle.GREEDY), (4, 8, oracle.RANDOM), (4, 16, oracle.GREEDY_ADJUSTED),
+                         (16, 32, oracle.GREEDY), (2, 32, oracle.RANDOM)):
         check_conv(layer, dO, W, n, m, ranker, 11, oracle.BF16, pixels=pixels)
 
 
