@@ -50,9 +50,9 @@ __host__ __device__ inline uint32_t seed_mix(uint64_t seed) {
     return 0xA54FF53Au ^ ((uint32_t)seed * 0x9E3779B9u) ^ ((uint32_t)(seed >> 32) * 0x510E527Fu);
 }
 
-__device__ __forceinline__ uint32_t hash_row(uint32_t mix, uint32_t e_hi) { return mix ^ (e_hi * 0xBB67AE85u); }
+__host__ __device__ __forceinline__ uint32_t hash_row(uint32_t mix, uint32_t e_hi) { return mix ^ (e_hi * 0xBB67AE85u); }
 
-__device__ __forceinline__ uint32_t hash_elem(uint32_t row, uint32_t e_lo) {
+__host__ __device__ __forceinline__ uint32_t hash_elem(uint32_t row, uint32_t e_lo) {
     uint32_t v = row ^ e_lo;
     v ^= v >> 16;
     v *= 0x6A09E667u;

@@ -38,6 +38,13 @@ __device__ __forceinline__ void prune16_compressed(const u32x4_t (&v)[2], int n,
         const uint32_t w[8] = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
         prune_compress16_bf16<M, RK>(w, n, packed, meta);
     } else {
+        {
+            // fast path; it says when it cannot be sure (two hashes of a group agreeing in 28 bits at the threshold)
+            const uint32_t w[8] = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
+            bool exact;
+            prune_compress16_random<M>(w, n, mix, e0, packed, meta, exact);
+            if (exact) return;
+        }
         uint32_t raw[16], out[16];
         bool keep[16];
 #pragma unroll

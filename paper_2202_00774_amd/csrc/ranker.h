@@ -277,4 +277,76 @@ __host__ __device__ __forceinline__ void prune_compress16_bf16(const uint32_t (&
     }
 }
 
+// Random with n <= 2 on sixteen consecutive bf16 channels, into the same operand format as prune_compress16_bf16.
+// Key of an element: the upper 28 bits of its hash with (15 - position in group) below them, so keys are distinct and
+// ordered like (hash, -position) unless two hashes agree in their upper 28 bits.  The kept set is {key >= n-th
+// largest}; it can differ from the exact one only if the n-th and the (n+1)-th largest keys of a group share those 28
+// bits (their low hash bits, not their positions, would decide): then `exact` comes back false and the caller takes
+// the generic path.  The values are fetched by position afterwards (they are not part of the key).  kPrefix (the
+// hash bits a key keeps; the low four bits are the position code's) is a parameter so that a test can shorten it and
+// exercise the `exact` flag.
+template <int M, uint32_t kPrefix = 0xFFFFFFF0u>
+__host__ __device__ __forceinline__ void prune_compress16_random(const uint32_t (&w)[8], int n, uint32_t mix, uint64_t e0,
+                                                                 uint32_t (&packed)[4], uint32_t& meta, bool& exact) {
+    static_assert(M == 4 || M == 8 || M == 16, "group sizes that tile sixteen channels");
+    const bool two = n >= 2;
+    uint32_t f[4], s[4], t[4];  // largest, second and third largest key of each quad
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint64_t eg = e0 + (uint64_t)((4 * q) / M * M);              // first element of the quad's group
+        const uint32_t hrow = hash_row(mix, (uint32_t)(eg >> 32));
+        const uint32_t e_lo = (uint32_t)eg + (uint32_t)((4 * q) % M);      // the quad's first element
+        const uint32_t c0 = (uint32_t)(15 - (4 * q) % M);
+        const uint32_t k0 = (hash_elem(hrow, e_lo) & kPrefix) | c0;
+        const uint32_t k1 = (hash_elem(hrow, e_lo + 1u) & kPrefix) | (c0 - 1u);
+        const uint32_t k2 = (hash_elem(hrow, e_lo + 2u) & kPrefix) | (c0 - 2u);
+        const uint32_t k3 = (hash_elem(hrow, e_lo + 3u) & kPrefix) | (c0 - 3u);
+        const uint32_t hi = sdgp_umax(k0, k1), lo = sdgp_umin(k0, k1);
+        const uint32_t hi2 = sdgp_umax(k2, k3), lo2 = sdgp_umin(k2, k3);
+        const uint32_t x = sdgp_umin(hi, hi2), y = sdgp_umax(lo, lo2), z = sdgp_umin(lo, lo2);
+        f[q] = sdgp_umax(hi, hi2);
+        s[q] = sdgp_umax(x, y);
+        t[q] = sdgp_umax(sdgp_umin(x, y), z);
+    }
+    exact = true;
+    uint32_t thr[4];  // the group's threshold, per quad
+#pragma unroll
+    for (int g = 0; g < 16 / M; ++g) {
+        constexpr int QG = M / 4;
+        // the three largest keys of the group: every candidate is among its quads' three largest
+        uint32_t v1 = f[g * QG], v2 = s[g * QG], v3 = t[g * QG];
+#pragma unroll
+        for (int i = 1; i < QG; ++i) {
+            const uint32_t cand[3] = {f[g * QG + i], s[g * QG + i], t[g * QG + i]};
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const uint32_t k = cand[c];
+                const uint32_t n3 = sdgp_umax(sdgp_umin(v2, k), v3);  // new third: median of (v2, v3, k) as v2 >= v3
+                const uint32_t n2 = sdgp_umax(sdgp_umin(v1, k), v2);
+                v1 = sdgp_umax(v1, k), v2 = n2, v3 = n3;
+            }
+        }
+        const uint32_t th = two ? v2 : v1, below = two ? v3 : v2;
+        exact = exact && ((th & kPrefix) != (below & kPrefix));
+#pragma unroll
+        for (int i = 0; i < QG; ++i) thr[g * QG + i] = th;
+    }
+    meta = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        // the quad's survivors are among its two largest keys; a slot without one keeps a (dropped) position, value +0
+        const bool keep_f = f[q] >= thr[q], keep_s = s[q] >= thr[q];
+        const uint32_t pf = (15u - (f[q] & 15u)) & 3u, ps = (15u - (s[q] & 15u)) & 3u;  // position in the quad
+        const uint32_t d01 = w[2 * q], d23 = w[2 * q + 1];
+        const uint32_t vf = ((pf & 2u) ? d23 : d01) >> (16u * (pf & 1u)) & 0xFFFFu;
+        const uint32_t vs = ((ps & 2u) ? d23 : d01) >> (16u * (ps & 1u)) & 0xFFFFu;
+        const uint32_t xf = keep_f ? vf : 0u, xs = keep_s ? vs : 0u;
+        const bool f_first = pf < ps;
+        const uint32_t p_lo = f_first ? pf : ps, p_hi = f_first ? ps : pf;
+        const uint32_t x_lo = f_first ? xf : xs, x_hi = f_first ? xs : xf;
+        packed[q] = x_lo | (x_hi << 16);
+        meta |= (p_lo | (p_hi << 2)) << (4 * q);
+    }
+}
+
 }  // namespace sdgp

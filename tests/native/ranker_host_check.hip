@@ -1,0 +1,173 @@
+// Host build of the register rankers (csrc/ranker.h is __host__ __device__ where it matters): the key-based rankers that
+// feed the structured-sparse matrix instruction against plain per-group selections written out here.
+//   * prune_compress16_bf16 (Magnitude, Rescaled Magnitude; Sec. III-B) against a rank count by (|x|, -position) and
+//     the rescale in fp32;
+//   * prune_compress16_random against a rank count by (H(seed, e), -position) with H written out from its definition;
+//     shortened hash prefixes make its "not sure" flag fire often, and every result it vouches for must be right.
+// Prints one line per configuration and returns the number of mismatches.  Test infrastructure, not product code.
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+__host__ inline float __fadd_rn(float a, float b) { volatile float r = a + b; return r; }
+__host__ inline float __fmul_rn(float a, float b) { volatile float r = a * b; return r; }
+__host__ inline float __fdiv_rn(float a, float b) { volatile float r = a / b; return r; }
+#define __forceinline__ inline
+#include "ranker.h"
+using namespace sdgp;
+
+static uint32_t f2bf(float f) {
+    uint32_t u; memcpy(&u, &f, 4);
+    uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? ((u >> 16) | 0x40u) : r;
+}
+// reference: straightforward per-group prune, then compaction per quad
+template <int M>
+static void ref(const uint16_t* x, int n, bool adjusted, uint32_t* packed, uint32_t* meta_out) {
+    uint16_t out[16]; bool keep[16];
+    for (int g = 0; g < 16 / M; ++g) {
+        const uint16_t* r = x + g * M;
+        for (int j = 0; j < M; ++j) {
+            int rank = 0;
+            for (int i = 0; i < M; ++i) {
+                uint32_t ki = r[i] & 0x7FFF, kj = r[j] & 0x7FFF;
+                if (ki > kj || (ki == kj && i < j)) ++rank;
+            }
+            keep[g * M + j] = rank < n;
+        }
+        float total = 0, kept = 0;
+        for (int j = 0; j < M; ++j) {
+            uint32_t b = (uint32_t)(r[j] & 0x7FFF) << 16; float a; memcpy(&a, &b, 4);
+            total = total + a; if (keep[g * M + j]) kept = kept + a;
+        }
+        float scale = kept == 0.0f ? 1.0f : total / kept;
+        for (int j = 0; j < M; ++j) {
+            uint32_t b = (uint32_t)r[j] << 16; float xv; memcpy(&xv, &b, 4);
+            uint16_t y = adjusted ? (uint16_t)f2bf(xv * scale) : r[j];
+            out[g * M + j] = keep[g * M + j] ? y : 0;
+        }
+    }
+    uint32_t meta = 0;
+    for (int q = 0; q < 4; ++q) {
+        int pos[2], cnt = 0;
+        for (int j = 0; j < 4; ++j) if (keep[4 * q + j]) pos[cnt++] = j;
+        // result check is semantic: decode instead of forcing one encoding
+        (void)pos; (void)cnt;
+    }
+    (void)meta;
+    for (int i = 0; i < 16; ++i) packed[i] = out[i];  // dense pruned values
+    *meta_out = 0;
+}
+template <int M, int RK>
+static int run_mag(int iters, unsigned seed) {
+    int bad = 0;
+    srand(seed);
+    for (int it = 0; it < iters; ++it) {
+        uint16_t x[16];
+        int kind = it % 6;
+        for (int i = 0; i < 16; ++i) {
+            uint32_t r = (uint32_t)rand();
+            switch (kind) {
+                case 0: x[i] = (uint16_t)r; break;                                   // anything incl. NaN/inf
+                case 1: x[i] = (uint16_t)((r & 0x8000) | 0x3F80 | (r & 3)); break;   // many ties, signs differ
+                case 2: x[i] = (r & 3) ? 0 : (uint16_t)(0x3C00 + (r >> 8) % 512 + ((r & 4) ? 0x8000 : 0)); break;  // zeros
+                case 3: x[i] = (uint16_t)((r & 0x8000) | 0x3F80); break;              // all equal magnitude
+                case 4: x[i] = (uint16_t)((r & 0x8000) | (0x7F00 + (r >> 4) % 256)); break;  // huge / inf / nan
+                default: x[i] = (uint16_t)((r & 0x8000) | ((r >> 3) % 64)); break;    // subnormal small
+            }
+        }
+        for (int n = 1; n <= 2; ++n) {
+            uint32_t w[8];
+            for (int i = 0; i < 8; ++i) w[i] = x[2 * i] | ((uint32_t)x[2 * i + 1] << 16);
+            uint32_t pk[4], meta;
+            prune_compress16_bf16<M, RK>(w, n, pk, meta);
+            uint32_t refv[16], dummy;
+            ref<M>(x, n, RK == kAdjusted, refv, &dummy);
+            // decode
+            uint32_t dec[16] = {0};
+            bool ok = true;
+            for (int q = 0; q < 4; ++q) {
+                int p0 = (meta >> (4 * q)) & 3, p1 = (meta >> (4 * q + 2)) & 3;
+                if (p0 >= p1) ok = false;
+                dec[4 * q + p0] = pk[q] & 0xFFFF;
+                dec[4 * q + p1] = pk[q] >> 16;
+            }
+            if ((meta >> 16) != 0) ok = false;
+            for (int i = 0; i < 16; ++i) if (dec[i] != refv[i]) ok = false;
+            if (!ok && bad++ < 5) {
+                printf("MISMATCH M=%d RK=%d n=%d kind=%d meta=%04x\n in :", M, RK, n, kind, meta);
+                for (int i = 0; i < 16; ++i) printf(" %04x", x[i]);
+                printf("\n ref:"); for (int i = 0; i < 16; ++i) printf(" %04x", refv[i]);
+                printf("\n got:"); for (int i = 0; i < 16; ++i) printf(" %04x", dec[i]);
+                printf("\n");
+            }
+        }
+    }
+    printf("M=%d RK=%d: %d mismatches of %d\n", M, RK, bad, 2 * iters);
+    return bad;
+}
+static uint32_t H(uint64_t seed, uint64_t e) {  // the definition, written out
+    uint32_t x = (uint32_t)e, y = (uint32_t)(e >> 32), s0 = (uint32_t)seed, s1 = (uint32_t)(seed >> 32);
+    uint32_t v = 0xA54FF53Au ^ x ^ (s0 * 0x9E3779B9u) ^ (y * 0xBB67AE85u) ^ (s1 * 0x510E527Fu);
+    v ^= v >> 16; v *= 0x6A09E667u; v ^= v >> 15; v *= 0xBB67AE85u; v ^= v >> 16;
+    return v;
+}
+template <int M, uint32_t PFX>
+static int run_rand(int iters, unsigned sd, bool narrow_hash) {
+    int bad = 0, inexact = 0;
+    srand(sd);
+    for (int it = 0; it < iters; ++it) {
+        uint16_t x[16];
+        for (int i = 0; i < 16; ++i) x[i] = (uint16_t)rand();
+        const uint64_t seed = ((uint64_t)rand() << 32) ^ (uint64_t)rand() ^ ((uint64_t)rand() << 17);
+        uint64_t e0 = ((uint64_t)(rand() & 0xFFFF) << 32 | (uint32_t)rand()) & ~15ull;
+        if (it % 7 == 0) e0 = (((uint64_t)(it % 5) << 32) | 0xFFFFFFF0u);  // groups right below a carry into the high word
+        for (int n = 1; n <= 2; ++n) {
+            uint32_t w[8];
+            for (int i = 0; i < 8; ++i) w[i] = x[2 * i] | ((uint32_t)x[2 * i + 1] << 16);
+            uint32_t pk[4], meta; bool exact;
+            prune_compress16_random<M, PFX>(w, n, seed_mix(seed), e0, pk, meta, exact);
+            if (!exact) { ++inexact; continue; }
+            uint32_t refv[16];
+            for (int g = 0; g < 16 / M; ++g)
+                for (int j = 0; j < M; ++j) {
+                    int rank = 0;
+                    for (int i = 0; i < M; ++i) {
+                        uint32_t hi_ = H(seed, e0 + g * M + i), hj = H(seed, e0 + g * M + j);
+                        if (hi_ > hj || (hi_ == hj && i < j)) ++rank;
+                    }
+                    refv[g * M + j] = rank < n ? x[g * M + j] : 0;
+                }
+            uint32_t dec[16] = {0};
+            bool ok = (meta >> 16) == 0;
+            for (int q = 0; q < 4; ++q) {
+                int p0 = (meta >> (4 * q)) & 3, p1 = (meta >> (4 * q + 2)) & 3;
+                if (p0 >= p1) ok = false;
+                dec[4 * q + p0] = pk[q] & 0xFFFF;
+                dec[4 * q + p1] = pk[q] >> 16;
+            }
+            // a kept zero and a dropped element look alike in the dense view: both are 0
+            for (int i = 0; i < 16; ++i) if (dec[i] != refv[i]) ok = false;
+            if (!ok && bad++ < 5) {
+                printf("MISMATCH M=%d n=%d meta=%04x e0=%llx\n ref:", M, n, meta, (unsigned long long)e0);
+                for (int i = 0; i < 16; ++i) printf(" %04x", refv[i]);
+                printf("\n got:"); for (int i = 0; i < 16; ++i) printf(" %04x", dec[i]);
+                printf("\n");
+            }
+        }
+    }
+    printf("M=%d prefix %08x: %d mismatches, %d inexact of %d\n", M, PFX, bad, inexact, 2 * iters);
+    (void)narrow_hash;
+    return bad;
+}
+int main() {
+    int bad = 0;
+    bad += run_mag<4, kGreedy>(100000, 1); bad += run_mag<8, kGreedy>(100000, 2); bad += run_mag<16, kGreedy>(100000, 3);
+    bad += run_mag<4, kAdjusted>(100000, 4); bad += run_mag<8, kAdjusted>(100000, 5); bad += run_mag<16, kAdjusted>(100000, 6);
+    bad += run_rand<4, 0xFFFFFFF0u>(100000, 1, false); bad += run_rand<8, 0xFFFFFFF0u>(100000, 2, false);
+    bad += run_rand<16, 0xFFFFFFF0u>(100000, 3, false);
+    bad += run_rand<4, 0xFF000000u>(100000, 4, false); bad += run_rand<8, 0xFF000000u>(100000, 5, false);
+    bad += run_rand<16, 0xFFC00000u>(100000, 6, false);
+    printf("total mismatches %d\n", bad);
+    return bad != 0;
+}
