@@ -2,6 +2,7 @@
 // enough 512-row tiles to fill the chip; chooses the tile and launches.
 #include <algorithm>
 #include <climits>
+#include <cstdio>
 #include <cstdlib>
 
 #include "bwd_row.h"
@@ -101,6 +102,20 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
         const int64_t n256 = plan_tiles(p256, 256, mode, bn, B, H, Wd, R, S, P, Q);
         if (n512 >= 192 || (n512 >= 128 && n256 < 128) || n256 == 0) rows = 512, chosen = p512, blocks = n512;
         else rows = 256, chosen = p256, blocks = n256;
+#ifdef SDGP_TRACE
+        if (const char* e = getenv("SDGP_ROW_SHAPE")) {  // "<rows>x<bn>"
+            int fr = 0, fb = 0;
+            if (sscanf(e, "%dx%d", &fr, &fb) == 2 && (fr == 512 || fr == 256) && (fb == 128 || fb == 64) && fb <= bn) {
+                if (fb != bn) {
+                    bn = fb;
+                    continue;
+                }
+                if (fr == 512 && n512 > 0) rows = 512, chosen = p512, blocks = n512;
+                if (fr == 256 && n256 > 0) rows = 256, chosen = p256, blocks = n256;
+                break;
+            }
+        }
+#endif
         if (bn == 128 && blocks < 192) {
             bn = 64;
             continue;
