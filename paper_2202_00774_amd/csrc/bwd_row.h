@@ -248,9 +248,9 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     // rank / prune / compress 64 items (pixel, 16-channel half) of a raw share into a halo buffer (Sec. III-B)
     auto prune_items = [&](int item0, int nitems, int u0, uint32_t raw, uint32_t abuf, uint32_t mbuf, uint32_t chan0) {
         if constexpr (PRUNES && !SPARSE) {
-            // any n of m: the pruned pixels are stored dense, zeros in the dropped positions, in the layout the dense
-            // matrix instruction reads.  (A 32-group would be the whole chunk of a pixel, taken by the lane of its
-            // first half; no 32-group instantiation exists, see the planner.)
+            // any n of m (m up to 32): the pruned pixels are stored dense, zeros in the dropped positions, in the
+            // layout the dense matrix instruction reads.  A 32-group is the whole chunk of a pixel: the lane of its
+            // first half takes it.
             constexpr int IC = M > 16 ? 32 : 16;  // channels per item
             const int item = item0 + lane;
             const int j = item >> 5, px = (item >> 1) & 15, part = item & 1;

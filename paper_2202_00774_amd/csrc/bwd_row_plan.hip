@@ -16,6 +16,7 @@ int launch_row_sparse_m16(const RowParams& p, int bn, int rows, int rk, hipStrea
 int launch_row_masked_m4(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
 int launch_row_masked_m8(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
 int launch_row_masked_m16(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
+int launch_row_masked_m32(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
 int row_lds_bytes(int mode, int bn, int rows, int halo);
 
 namespace {
@@ -57,12 +58,11 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
                    int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                    hipStream_t stream) {
     // 0: dense; 2: at most two survivors per aligned quad, the structured-sparse instruction; 1: any other n of m in
-    // {4, 8, 16}, the pruned halo stored dense with zeros (32-groups need more registers than eight wavefronts leave:
-    // the parity-class kernel keeps them)
+    // {4, 8, 16, 32}, the pruned halo stored dense with zeros
     int mode;
     if (n == m) mode = 0;
     else if (n <= 2 && (m == 4 || m == 8 || m == 16)) mode = 2;
-    else if (m == 4 || m == 8 || m == 16) mode = 1;
+    else if (m == 4 || m == 8 || m == 16 || m == 32) mode = 1;
     else return 1;
     if (stride != 1 || S != kRowTaps || R < 1 || R > kRowMaxRows || (C_out % kRowKC) != 0 || (C_in % 8) != 0) return 1;
     if (mode != 0 && (C_out % m) != 0) return 1;
@@ -92,6 +92,7 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
     // 128-column tiles unless they leave a quarter of the CUs without a workgroup: then 64-column tiles, twice as many
     // (measured on the 512 -> 512 layer at 4 x 4: 128 workgroups of 128 columns 57 us, 256 of 64 columns 45 us)
     int bn = (C_in > 64) ? 128 : 64;
+    if (mode == 1 && m == 32) bn = 64;  // the 32-key ranker leaves no registers for the 128-column tile's fragments
     int rows = 512;
     int64_t blocks = 0;
     RowParams chosen = p;
@@ -131,7 +132,8 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
     if (mode == 1) {
         if (m == 4) return launch_row_masked_m4(p, bn, rows, rk, stream);
         if (m == 8) return launch_row_masked_m8(p, bn, rows, rk, stream);
-        return launch_row_masked_m16(p, bn, rows, rk, stream);
+        if (m == 16) return launch_row_masked_m16(p, bn, rows, rk, stream);
+        return launch_row_masked_m32(p, bn, rows, rk, stream);
     }
     if (m == 4) return launch_row_sparse_m4(p, bn, rows, rk, stream);
     if (m == 8) return launch_row_sparse_m8(p, bn, rows, rk, stream);

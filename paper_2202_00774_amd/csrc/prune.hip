@@ -121,7 +121,7 @@ prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, v
         bool k[M];
 #pragma unroll
         for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
-        prune_group<DT, M, RK, NLE2>(r, n, hrow, (uint32_t)e0 + g * M, k, o);
+        prune_group<DT, M, RK, NLE2, false>(r, n, hrow, (uint32_t)e0 + g * M, k, o);
 #pragma unroll
         for (int j = 0; j < M; ++j) {
             out[g * M + j] = o[j];

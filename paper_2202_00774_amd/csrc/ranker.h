@@ -42,6 +42,38 @@ __device__ __forceinline__ void select_by_rank(const uint32_t (&key)[M], int n, 
     for (int j = 0; j < M; ++j) keep[j] = rank[j] < n;
 }
 
+// Any n, keys pairwise distinct: sort a copy of the keys (bitonic network, M/2 * log2(M) * (log2(M) + 1) / 2
+// compare-exchanges of one min and one max: 80 for sixteen keys, 240 for thirty-two -- a third of the rank count's
+// instructions, and no rank registers), take the n-th largest as the threshold.
+template <int M>
+__device__ __forceinline__ void select_by_sort(const uint32_t (&key)[M], int n, bool (&keep)[M]) {
+    static_assert((M & (M - 1)) == 0 && M >= 2, "power of two");
+    uint32_t s[M];
+#pragma unroll
+    for (int j = 0; j < M; ++j) s[j] = key[j];
+#pragma unroll
+    for (int k = 2; k <= M; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+            for (int i = 0; i < M; ++i) {
+                const int l = i ^ j;
+                if (l > i) {
+                    const uint32_t a = s[i], b = s[l];
+                    const bool desc = (i & k) == 0;  // descending runs first: s[0] ends up the largest
+                    s[i] = desc ? max(a, b) : min(a, b);
+                    s[l] = desc ? min(a, b) : max(a, b);
+                }
+            }
+        }
+    }
+    uint32_t thr = s[0];
+#pragma unroll
+    for (int i = 1; i < M; ++i) thr = (i == n - 1) ? s[i] : thr;  // n is wavefront-uniform: scalar selects
+#pragma unroll
+    for (int j = 0; j < M; ++j) keep[j] = key[j] >= thr;
+}
+
 // n <= 2, keys pairwise distinct: the threshold is the largest or second
 // largest key, found with one max and one median per element.
 template <int M>
@@ -94,9 +126,11 @@ __device__ __forceinline__ void select_top2_ties(const uint32_t (&key)[M], int n
 //   hrow     hash_row(mix, high word of the group's flat index)   (Random only)
 //   e_lo     low word of the flat index of element 0              (Random only)
 //   NLE2     compile-time promise that n <= 2 (enables the threshold selects)
+//   SORT     any n on distinct keys: sorting network (fewer instructions: the fused kernels) or rank count (measured
+//            faster in the streaming prune kernel)
 // Output: keep[j], and out[j] = stored bit pattern of the pruned element
 // (+0 where dropped).
-template <int DT, int M, int RK, bool NLE2>
+template <int DT, int M, int RK, bool NLE2, bool SORT = true>
 __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uint32_t hrow, uint32_t e_lo,
                                             bool (&keep)[M], uint32_t (&out)[M]) {
     constexpr uint32_t kMagMask = (DT == kBF16) ? 0x7FFFu : 0x7FFFFFFFu;
@@ -117,6 +151,7 @@ __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uin
 #pragma unroll
         for (int j = 0; j < M; ++j) key[j] = (key[j] << 5) | (uint32_t)(31 - j);
         if constexpr (NLE2) select_top2_distinct<M>(key, n, keep);
+        else if constexpr (SORT && M >= 8 && (M & (M - 1)) == 0) select_by_sort<M>(key, n, keep);
         else select_by_rank<M>(key, n, keep);
     } else if constexpr (NLE2 && M >= 16) {
         // (for eight keys the 28 comparisons of the rank count measured faster than the multiset and its fallback)
