@@ -193,6 +193,13 @@ def main():
             del dO, W, out
         result["resnet50_bottleneck_batch128"] = table
 
+        # general n of m (the accuracy study's settings, Sec. IV-B: Rescaled Magnitude): pruned rows stored dense with zeros
+        Lg, dOg, Wg, outg = data[3]
+        tg = {"dense": time_call(lambda: call(Lg, dOg, Wg, outg, 4, 4, sdgp.GREEDY))}
+        for n_, m_ in ((2, 4), (4, 8), (2, 8), (8, 16), (4, 16), (2, 16), (16, 32), (8, 32), (4, 32)):
+            tg["%d:%d" % (n_, m_)] = time_call(lambda: call(Lg, dOg, Wg, outg, n_, m_, sdgp.GREEDY_ADJUSTED))
+        result["general_nm_greedy_adjusted"] = {"layer": Lg.name, **{k + "_us": round(v * 1e3, 1) for k, v in tg.items()}}
+
         # the whole ResNet-50 at batch 256 and 224 x 224: every layer once per distinct shape, summed over the 54 layers
         seen, tot = {}, {"dense": 0.0, "2:4_random": 0.0, "2:8_random": 0.0}
         r50 = wl.resnet50_all_layers(256)
