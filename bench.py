@@ -255,8 +255,22 @@ def main():
             ms = time_call(g, reps=20, warm=3)
             prune["greedy_%d:%d" % (n_, m_)] = {"us": round(ms * 1e3, 1), "GB/s": round(4.0 * nelem / (ms * 1e-3) / 1e9, 1),
                                                 "frac_of_hbm_peak": round(4.0 * nelem / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        result["prune_pass"] = {"tensor": "[%d, 64] bf16 (411 MB), 2:4 unless named, dense-shaped output, 4 B per element" % (nelem // 64),
-                                **prune}
+        # compact output (values + uint8 positions, no dense-shaped copy): 2 + 3 n/m bytes per element
+        vals = torch.empty(nelem // 2, dtype=torch.bfloat16, device=dev)
+        idx = torch.empty(nelem // 2, dtype=torch.uint8, device=dev)
+
+        def compact():
+            s = srcs[k[0] % 2]
+            k[0] += 1
+            rc = lib.sdgp_prune(ctypes.c_void_p(s.data_ptr()), s.shape[0], s.shape[1], sdgp.BF16, 2, 4, sdgp.GREEDY, 0, None,
+                                ctypes.c_void_p(vals.data_ptr()), ctypes.c_void_p(idx.data_ptr()), stream)
+            assert rc == 0
+        ms = time_call(compact, reps=20, warm=3)
+        prune["greedy_compact_output"] = {"us": round(ms * 1e3, 1), "GB/s": round(3.5 * nelem / (ms * 1e-3) / 1e9, 1),
+                                          "frac_of_hbm_peak": round(3.5 * nelem / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del vals, idx
+        result["prune_pass"] = {"tensor": "[%d, 64] bf16 (411 MB), 2:4 unless named, dense-shaped output (4 B per element) unless "
+                                          "named" % (nelem // 64), **prune}
         result["roofline_prune"] = {"bound": "hbm", "kernel": "prune_items (2:4 greedy)",
                                     "achieved": prune["greedy"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                     "frac": prune["greedy"]["frac_of_hbm_peak"],

@@ -148,6 +148,43 @@ prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, v
         // Kept values and positions in ascending position; n per group.
         T* vals = reinterpret_cast<T*>(vals_);
         int64_t o = (int64_t)item * GROUPS * n;
+        if (n == 2) {
+            // exactly two survivors per group: the lowest and the highest kept position, found with select chains;
+            // an item's values and positions leave with one store each
+            uint32_t cv[GROUPS * 2], cp[GROUPS * 2];
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                uint32_t v0 = out[g * M + M - 1], p0 = M - 1, v1 = out[g * M], p1 = 0;
+#pragma unroll
+                for (int j = M - 2; j >= 0; --j) {
+                    v0 = keep[g * M + j] ? out[g * M + j] : v0;
+                    p0 = keep[g * M + j] ? (uint32_t)j : p0;
+                }
+#pragma unroll
+                for (int j = 1; j < M; ++j) {
+                    v1 = keep[g * M + j] ? out[g * M + j] : v1;
+                    p1 = keep[g * M + j] ? (uint32_t)j : p1;
+                }
+                cv[2 * g] = v0, cv[2 * g + 1] = v1, cp[2 * g] = p0, cp[2 * g + 1] = p1;
+            }
+            if constexpr (DT == kBF16 && GROUPS == 2) {
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 pv = {cv[0] | (cv[1] << 16), cv[2] | (cv[3] << 16)};
+                __builtin_nontemporal_store(pv, reinterpret_cast<u32x2*>(vals + o));
+                __builtin_nontemporal_store(cp[0] | (cp[1] << 8) | (cp[2] << 16) | (cp[3] << 24), reinterpret_cast<uint32_t*>(idx + o));
+            } else if constexpr (DT == kBF16) {
+                static_assert(GROUPS == 1, "one group per item");
+                __builtin_nontemporal_store(cv[0] | (cv[1] << 16), reinterpret_cast<uint32_t*>(vals + o));
+                __builtin_nontemporal_store((uint16_t)(cp[0] | (cp[1] << 8)), reinterpret_cast<uint16_t*>(idx + o));
+            } else {
+                static_assert(GROUPS == 1, "one group per item");
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 pv = {cv[0], cv[1]};
+                __builtin_nontemporal_store(pv, reinterpret_cast<u32x2*>(vals + o));
+                __builtin_nontemporal_store((uint16_t)(cp[0] | (cp[1] << 8)), reinterpret_cast<uint16_t*>(idx + o));
+            }
+            continue;
+        }
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) {
 #pragma unroll
@@ -283,7 +320,8 @@ template <int DT>
 void prune_dtype(const PruneArgs& a) {
     constexpr int PV = Storage<DT>::kPerVec;
     const bool vec_m = (a.m == 4 || a.m == 8 || a.m == 16 || a.m == 32);
-    const bool aligned = is_aligned16(a.dO) && (!a.pruned || is_aligned16(a.pruned));
+    const bool aligned = is_aligned16(a.dO) && (!a.pruned || is_aligned16(a.pruned)) &&
+                         (!a.vals || (is_aligned16(a.vals) && (reinterpret_cast<uintptr_t>(a.idx) & 3u) == 0));  // vector stores of the compact output
     int64_t done = 0;
     if (vec_m && aligned) {
         const int item = a.m > PV ? a.m : PV;
