@@ -201,8 +201,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 const int pp = h + p.pad - r, qq = w + p.pad - sx;
                 const bool inside = live && pp >= 0 && pp < p.P && qq >= 0 && qq < p.Q;
                 const uint32_t hp = inside ? (uint32_t)(rowbase + (p.pad - r) * HTW + (p.pad - sx)) : zero_pix;
-                // pruning: the pixel's offset in the meta buffer (4 bytes per pixel; eight times that in the value buffer)
-                atab[(r * TS + sx) * ROWS + m] = SPARSE ? hp * 4u : hp * 64u + (((hp >> 2) & 3u) << 4);
+                atab[(r * TS + sx) * ROWS + m] = SPARSE ? hp * 32u : hp * 64u + (((hp >> 2) & 3u) << 4);
             }
       }
       if (tid < 64) {
@@ -381,11 +380,10 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     const uint32_t m_k0 = half * 2u;
     auto load_a = [&](Frags& f, int t, uint32_t abuf, uint32_t mbuf, int ks) {
         if constexpr (SPARSE) {
-            // abuf / mbuf arrive with this lane's half already added: one shift-add and one add per entry
-            f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] << 3) + abuf));
-            f.meta[t] = *(SDGP_LDS uint16_t*)(smem + (a_ent[t] + mbuf));
+            f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] | a_k0) + abuf));
+            f.meta[t] = *(SDGP_LDS uint16_t*)(smem + (((a_ent[t] >> 3) | m_k0) + mbuf));
         } else {
-            f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] ^ (a_k0 | (uint32_t)(ks * 32))) + abuf));  // one xor-add
+            f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] ^ (a_k0 | (uint32_t)(ks * 32))) + abuf));
         }
     };
     auto load_b = [&](Frags& f, int u, uint32_t slab_off, int ks) {
@@ -437,8 +435,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         const int npr = pr + 1 == R ? 0 : pr + 1;
         const int npc = row_last ? pc_next : pc;
         const bool more = x + 1 < nstages;
-        // the halo buffers as this lane addresses them (pruning: its half of the 32 compressed bytes / 4 meta bytes)
-        const uint32_t abuf_l = SPARSE ? abuf + a_k0 : abuf, mbuf_l = mbuf + m_k0;
 #ifdef SDGP_TRACE
         const unsigned long long tr_s0 = __builtin_readcyclecounter();
 #endif
@@ -447,7 +443,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
             read_entries(pr * TS);
             take_entries();
 #pragma unroll
-            for (int t = 0; t < TM; ++t) load_a(f0, t, abuf_l, mbuf_l, 0);
+            for (int t = 0; t < TM; ++t) load_a(f0, t, abuf, mbuf, 0);
 #pragma unroll
             for (int u = 0; u < TN; ++u) load_b(f0, u, set_off, 0);
         }
@@ -497,8 +493,8 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                     if (has_next) {
                         if (i == 1 && new_tap) take_entries();
                         const int t0 = 2 * (i - 1);
-                        load_a(nxt, t0, abuf_l, mbuf_l, nks);
-                        if (t0 + 1 < TM) load_a(nxt, t0 + 1, abuf_l, mbuf_l, nks);
+                        load_a(nxt, t0, abuf, mbuf, nks);
+                        if (t0 + 1 < TM) load_a(nxt, t0 + 1, abuf, mbuf, nks);
                     }
                 } else if (i <= APIECES + TN) {
                     if (has_next) load_b(nxt, i - APIECES - 1, set_off + (uint32_t)ntap * L::kWSlab, nks);
