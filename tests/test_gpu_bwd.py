@@ -259,7 +259,7 @@ def test_strided_conv_matches_oracle(layer):
     pixels = sample_pixels(layer, 2000, 9)
     for n, m, ranker in ((4, 4, oracle.GREEDY), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED),
                          (2, 4, oracle.RANDOM), (2, 8, oracle.RANDOM), (2, 16, oracle.GREEDY),
-                         (4, 8, oracle.GREEDY), (8, 32, oracle.GREEDY_ADJUSTED)):
+                         (4, 8, oracle.GREEDY), (4, 8, oracle.RANDOM), (8, 32, oracle.GREEDY_ADJUSTED)):
         check_conv(layer, dO, W, n, m, ranker, 17, oracle.BF16, pixels=pixels)
 
 
