@@ -52,6 +52,8 @@ def _load():
             lib.sdgp_ref_bf16_to_float.argtypes = [ctypes.c_uint16]
             lib.sdgp_ref_prune.restype = i32
             lib.sdgp_ref_prune.argtypes = [vp, i64, i64, i32, i32, i32, i32, u64, vp, vp, vp]
+            lib.sdgp_ref_prune_channel_rescaled.restype = i32
+            lib.sdgp_ref_prune_channel_rescaled.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
             lib.sdgp_ref_linear_bwd_data.restype = i32
             lib.sdgp_ref_linear_bwd_data.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp]
             lib.sdgp_ref_conv_bwd_data.restype = i32
@@ -122,6 +124,30 @@ def prune(dO: np.ndarray, n: int, m: int, ranker: int, seed: int = 0, dtype: int
     if rc != 0:
         raise ValueError("sdgp_ref_prune rejected its arguments")
     return pruned, vals, idx
+
+
+def prune_channel_rescaled(dO: np.ndarray, n: int, m: int, dtype: int | None = None):
+    """Magnitude pruning with one rescaling factor per channel (second reading of Rescaled Magnitude).
+
+    ``dO`` is viewed as [rows, C].  Returns ``(pruned, scale, total, kept)``: the dense-shaped pruned copy,
+    the fp32 factor of every channel and the two fp64 column sums it is the quotient of.
+    """
+    if dtype is None:
+        dtype = F32 if dO.dtype == np.float32 else BF16
+    dO = _check(dO, dtype, "dO")
+    C = dO.shape[-1]
+    rows = dO.size // C if C else 0
+    if m < 1 or C % m:
+        raise ValueError("C must be a multiple of m")
+    pruned = np.empty_like(dO)
+    scale = np.empty(C, np.float32)
+    total = np.empty(C, np.float64)
+    kept = np.empty(C, np.float64)
+    rc = _load().sdgp_ref_prune_channel_rescaled(_ptr(dO), rows, C, dtype, n, m, _ptr(total), _ptr(kept),
+                                                 _ptr(scale), _ptr(pruned))
+    if rc != 0:
+        raise ValueError("sdgp_ref_prune_channel_rescaled rejected its arguments")
+    return pruned, scale, total, kept
 
 
 def linear_bwd_data(dOp: np.ndarray, W: np.ndarray, dtype: int | None = None):

@@ -11,7 +11,8 @@
  *     channels of dL/dO, apply the pruning function P to each, store the result
  *     at the same place of a zero-initialised copy.
  *   - the three P of Sec. III-B: Random, Magnitude ("greedy"), Rescaled
- *     Magnitude ("greedy-adjusted");
+ *     Magnitude ("greedy-adjusted"), and the second reading of the latter with
+ *     one factor per channel;
  *   - the backward-data product that consumes the pruned tensor (Fig. 1, Fig. 2,
  *     Fig. 3): a matrix product for a linear layer, the transposed correlation
  *     for a convolution layer.
@@ -194,6 +195,86 @@ int sdgp_ref_prune(const void* dO, int64_t rows, int64_t C, int dtype, int n, in
             }
         }
     }
+    return 0;
+}
+
+/* ------------------------------------- Rescaled Magnitude, per-channel norm */
+
+/*
+ * The captions of the figures that show the rescaled gradient (Sec. III-B) speak
+ * of an L1 norm preserved per channel across the batch and spatial dimensions,
+ * while Alg. 1 hands P one group.  Reading (the second one; the per-group reading
+ * above stays the default): the kept set is the Magnitude one, and channel c gets
+ * ONE factor for the whole tensor,
+ *     s[c] = (sum over rows of |dO[i,c]|) / (sum over rows where c was kept of |dO[i,c]|),
+ * so that the column's L1 norm after pruning equals the one before.  A column whose
+ * kept sum is zero (nothing but zeros survived) has s[c] = 1.
+ *
+ * Arithmetic: the two column sums in fp64, rows ascending; s[c] is their fp64
+ * quotient rounded once to fp32; a kept value is fp32(x) * s[c] in fp32, rounded to
+ * the storage type (round to nearest even).
+ *
+ * Outputs (each may be NULL): total[C] and kept[C] (the fp64 sums), scale[C],
+ * pruned [rows, C].  Returns 0, or -1 on bad arguments or out of memory.
+ */
+int sdgp_ref_prune_channel_rescaled(const void* dO, int64_t rows, int64_t C, int dtype, int n, int m,
+                                    double* total, double* kept, float* scale, void* pruned) {
+    if (n < 1 || n > m || m > 32 || C < 0 || rows < 0 || (C % m) != 0) return -1;
+    if (dtype != REF_F32 && dtype != REF_BF16) return -1;
+    const int64_t groups = C / m;
+    double* tot = (double*)calloc((size_t)(C > 0 ? C : 1), sizeof(double));
+    double* kep = (double*)calloc((size_t)(C > 0 ? C : 1), sizeof(double));
+    float* sc = (float*)malloc((size_t)(C > 0 ? C : 1) * sizeof(float));
+    unsigned char* mask = (unsigned char*)malloc((size_t)(rows * C > 0 ? rows * C : 1));
+    if (!tot || !kep || !sc || !mask) {
+        free(tot), free(kep), free(sc), free(mask);
+        return -1;
+    }
+    /* first sweep: Magnitude keep-set of every group, and the two sums of every column */
+    for (int64_t i = 0; i < rows; ++i) {
+        for (int64_t g = 0; g < groups; ++g) {
+            const int64_t base = i * C + g * m;
+            float x[32], unused;
+            uint32_t mag[32];
+            for (int j = 0; j < m; ++j) {
+                if (dtype == REF_BF16) {
+                    uint16_t h = ((const uint16_t*)dO)[base + j];
+                    x[j] = bf16_to_float(h);
+                    mag[j] = (uint32_t)(h & 0x7FFFu);
+                } else {
+                    uint32_t u = ((const uint32_t*)dO)[base + j];
+                    x[j] = bits_to_float(u);
+                    mag[j] = u & 0x7FFFFFFFu;
+                }
+            }
+            rank_group(x, mag, m, n, REF_GREEDY, 0, 0, mask + base, &unused);
+            for (int j = 0; j < m; ++j) {
+                double a = (double)bits_to_float(float_to_bits(x[j]) & 0x7FFFFFFFu);
+                tot[g * m + j] += a;
+                if (mask[base + j]) kep[g * m + j] += a;
+            }
+        }
+    }
+    for (int64_t c = 0; c < C; ++c) sc[c] = (kep[c] == 0.0) ? 1.0f : (float)(tot[c] / kep[c]);
+    /* second sweep: kept values times their column's factor */
+    if (pruned) {
+        for (int64_t i = 0; i < rows; ++i) {
+            for (int64_t c = 0; c < C; ++c) {
+                const int64_t e = i * C + c;
+                if (dtype == REF_BF16) {
+                    float y = bf16_to_float(((const uint16_t*)dO)[e]) * sc[c];
+                    ((uint16_t*)pruned)[e] = mask[e] ? float_to_bf16(y) : (uint16_t)0;
+                } else {
+                    float y = ((const float*)dO)[e] * sc[c];
+                    ((uint32_t*)pruned)[e] = mask[e] ? float_to_bits(y) : 0u;
+                }
+            }
+        }
+    }
+    if (total) memcpy(total, tot, (size_t)C * sizeof(double));
+    if (kept) memcpy(kept, kep, (size_t)C * sizeof(double));
+    if (scale) memcpy(scale, sc, (size_t)C * sizeof(float));
+    free(tot), free(kep), free(sc), free(mask);
     return 0;
 }
 
