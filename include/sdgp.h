@@ -10,7 +10,8 @@
  *
  * Conventions that hold for every entry point
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
- *     never allocates, frees or retains it.  Inputs are const and are never
+ *     never allocates, frees or retains memory; scratch space, where a call needs
+ *     it, is a workspace argument.  Inputs are const and are never
  *     written: dL/dO must survive because the weight gradient is computed from
  *     the unpruned tensor (Sec. III-A, last paragraph).
  *   - Tensors are contiguous, the pruned axis (channels) is the last one with
@@ -137,6 +138,59 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
  * call is fully fused); (size_t)-1 when the arguments are invalid. */
 size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                                     int R, int S, int stride, int pad, int dt, int n, int m);
+
+/*
+ * Rescaled Magnitude with one factor per channel.
+ *
+ * Sec. III-B defines Rescaled Magnitude on the group that P receives (what
+ * SDGP_GREEDY_ADJUSTED does); the captions of the figures that show the rescaled
+ * gradient instead state that the L1 norm is preserved per channel over the batch
+ * and spatial dimensions.  The entry points below implement that second reading:
+ * the kept set of every group is the Magnitude one, and channel c of the whole
+ * tensor is multiplied by
+ *     s[c] = (sum over rows of |dO[i,c]|) / (sum over the rows that kept c of |dO[i,c]|),
+ * s[c] = 1 when the divisor is 0.  Both sums are accumulated in fp64; s[c] is the
+ * fp64 quotient rounded to fp32.
+ *
+ * sdgp_channel_scales       one read of dO [rows, C]: writes scale [C] (fp32, device) and, when
+ *                           `sums` is not NULL, the two sums as sums[0..C) and sums[C..2C) (fp64,
+ *                           device).  The result does not depend on the launch and is the same
+ *                           from call to call (partial sums are added in a fixed order).
+ *                           workspace: sdgp_channel_scales_workspace(...) bytes, 8-byte aligned.
+ * sdgp_prune_channel_rescaled   Alg. 1 with P = Magnitude, kept values multiplied by scale[channel]
+ *                           in fp32 and rounded to `dt` (RNE); dropped positions hold +0.
+ *                           `scale` [C] is read from device memory (normally sdgp_channel_scales').
+ * sdgp_scale_filter         W_scaled[k, :] = W[k, :] * scale[k] for W [C_out, inner] (inner = C_in for
+ *                           a linear layer, R*S*C_in for a convolution), fp32 product rounded to
+ *                           `dt`.  With it the rescaled product needs no second sweep over dO:
+ *                           sum_k (x_k s_k) W[k,:] = sum_k x_k (s_k W[k,:]), so
+ *                           sdgp_conv_bwd_data(dO, W_scaled, ..., SDGP_GREEDY, ...) is the backward-data
+ *                           product of the rescaled gradient (rounding the filter instead of the
+ *                           gradient: the same error bound, not the same bits).  W_scaled may
+ *                           alias W.
+ * sdgp_conv_bwd_data_channel_rescaled   the three steps above in one call: factors from dO, filter
+ *                           rescaled into the workspace, fused Magnitude backward-data product.
+ *                           A linear layer is the case B = rows, H = Wd = R = S = stride = 1, pad = 0.
+ *                           workspace: sdgp_conv_bwd_data_channel_rescaled_workspace(...) bytes,
+ *                           16-byte aligned; contents undefined afterwards.
+ *
+ * Shapes, n, m, alignment and error behaviour are those of sdgp_prune and sdgp_conv_bwd_data.
+ * The workspace queries return (size_t)-1 for invalid arguments.
+ */
+size_t sdgp_channel_scales_workspace(int64_t rows, int64_t C, int dt, int n, int m);
+int sdgp_channel_scales(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, float* scale,
+                        double* sums, void* workspace, size_t workspace_bytes, void* hip_stream);
+int sdgp_prune_channel_rescaled(const void* dO, int64_t rows, int64_t C, int dt, int n, int m,
+                                const float* scale, void* pruned, void* hip_stream);
+int sdgp_scale_filter(const void* W, const float* scale, void* W_scaled, int64_t C_out, int64_t inner,
+                      int dt, void* hip_stream);
+size_t sdgp_conv_bwd_data_channel_rescaled_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                                                     int64_t C_out, int R, int S, int stride, int pad,
+                                                     int dt, int n, int m);
+int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
+                                        int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
+                                        int stride, int pad, int dt, int n, int m, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* sdgp_status_string(int status);

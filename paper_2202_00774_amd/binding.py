@@ -21,6 +21,8 @@ _lock = threading.Lock()
 _lib = None
 
 EXPORTS = ("sdgp_prune", "sdgp_linear_bwd_data", "sdgp_conv_bwd_data", "sdgp_conv_bwd_data_workspace",
+           "sdgp_channel_scales_workspace", "sdgp_channel_scales", "sdgp_prune_channel_rescaled", "sdgp_scale_filter",
+           "sdgp_conv_bwd_data_channel_rescaled_workspace", "sdgp_conv_bwd_data_channel_rescaled",
            "sdgp_status_string", "sdgp_version")
 
 
@@ -52,6 +54,20 @@ def load():
                                                i32, u64, vp, sz, vp]
             lib.sdgp_conv_bwd_data_workspace.restype = sz
             lib.sdgp_conv_bwd_data_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32]
+            lib.sdgp_channel_scales_workspace.restype = sz
+            lib.sdgp_channel_scales_workspace.argtypes = [i64, i64, i32, i32, i32]
+            lib.sdgp_channel_scales.restype = i32
+            lib.sdgp_channel_scales.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp, sz, vp]
+            lib.sdgp_prune_channel_rescaled.restype = i32
+            lib.sdgp_prune_channel_rescaled.argtypes = [vp, i64, i64, i32, i32, i32, vp, vp, vp]
+            lib.sdgp_scale_filter.restype = i32
+            lib.sdgp_scale_filter.argtypes = [vp, vp, vp, i64, i64, i32, vp]
+            lib.sdgp_conv_bwd_data_channel_rescaled_workspace.restype = sz
+            lib.sdgp_conv_bwd_data_channel_rescaled_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32, i32, i32,
+                                                                         i32, i32, i32]
+            lib.sdgp_conv_bwd_data_channel_rescaled.restype = i32
+            lib.sdgp_conv_bwd_data_channel_rescaled.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32,
+                                                               i32, i32, i32, vp, sz, vp]
             lib.sdgp_status_string.restype = ctypes.c_char_p
             lib.sdgp_status_string.argtypes = [i32]
             lib.sdgp_version.restype = i32
@@ -161,3 +177,101 @@ def sdgp_conv_bwd_data(dO: torch.Tensor, W: torch.Tensor, H: int, Wd: int, strid
     if rc != 0:
         raise SdgpError(rc, "sdgp_conv_bwd_data")
     return out
+
+
+# ---------------------------------------------- Rescaled Magnitude, one factor per channel
+
+_INVALID = 2**64 - 1
+
+
+def _workspace(need: int, workspace, device, where: str):
+    if need == _INVALID:
+        raise SdgpError(-3, where)
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def sdgp_channel_scales(dO: torch.Tensor, n: int, m: int, *, sums: bool = False, workspace: torch.Tensor | None = None):
+    """Per-channel factors of ``dO`` ([..., C]) under Magnitude n:m pruning: fp32 [C]; with ``sums`` also the two
+    fp64 column sums as a [2, C] tensor (all |x|, kept |x|)."""
+    _dev(dO, "dO")
+    C = dO.shape[-1]
+    rows = dO.numel() // C if C else 0
+    dt = _dtype_code(dO)
+    lib = load()
+    workspace, wbytes = _workspace(int(lib.sdgp_channel_scales_workspace(rows, C, dt, n, m)), workspace, dO.device,
+                                   "sdgp_channel_scales_workspace")
+    scale = torch.empty(C, dtype=torch.float32, device=dO.device)
+    both = torch.empty((2, C), dtype=torch.float64, device=dO.device) if sums else None
+    rc = lib.sdgp_channel_scales(_ptr(dO), rows, C, dt, n, m, _ptr(scale), _ptr(both), _ptr(workspace), wbytes, _stream(dO))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_channel_scales")
+    return (scale, both) if sums else scale
+
+
+def sdgp_prune_channel_rescaled(dO: torch.Tensor, n: int, m: int, scale: torch.Tensor | None = None) -> torch.Tensor:
+    """Magnitude n:m pruning of ``dO`` with kept values multiplied by their channel's factor (computed when not given)."""
+    _dev(dO, "dO")
+    C = dO.shape[-1]
+    rows = dO.numel() // C if C else 0
+    if scale is None:
+        scale = sdgp_channel_scales(dO, n, m)
+    _dev(scale, "scale")
+    if scale.dtype != torch.float32 or scale.numel() != C:
+        raise ValueError("scale must be float32 [C]")
+    out = torch.empty_like(dO)
+    rc = load().sdgp_prune_channel_rescaled(_ptr(dO), rows, C, _dtype_code(dO), n, m, _ptr(scale), _ptr(out), _stream(dO))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_prune_channel_rescaled")
+    return out
+
+
+def sdgp_scale_filter(W: torch.Tensor, scale: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``W[k, ...] * scale[k]`` for a filter whose first axis is C_out."""
+    _dev(W, "W"), _dev(scale, "scale")
+    C_out = W.shape[0]
+    if scale.dtype != torch.float32 or scale.numel() != C_out:
+        raise ValueError("scale must be float32 [C_out]")
+    if out is None:
+        out = torch.empty_like(W)
+    _dev(out, "out")
+    inner = W.numel() // C_out if C_out else 0
+    rc = load().sdgp_scale_filter(_ptr(W), _ptr(scale), _ptr(out), C_out, inner, _dtype_code(W), _stream(W))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_scale_filter")
+    return out
+
+
+def sdgp_conv_bwd_data_channel_rescaled(dO: torch.Tensor, W: torch.Tensor, H: int, Wd: int, stride: int, pad: int,
+                                        n: int, m: int, out: torch.Tensor | None = None,
+                                        workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """dD of a convolution from dO pruned by Magnitude and rescaled per channel, in one call."""
+    _dev(dO, "dO"), _dev(W, "W")
+    if dO.dim() != 4 or W.dim() != 4 or W.shape[0] != dO.shape[3] or W.dtype != dO.dtype:
+        raise ValueError("expected dO [B,P,Q,C_out] and W [C_out,R,S,C_in] of one dtype")
+    B, P, Q, C_out = dO.shape
+    _, R, S, C_in = W.shape
+    if (H + 2 * pad - R) // stride + 1 != P or (Wd + 2 * pad - S) // stride + 1 != Q:
+        raise ValueError("dO's spatial size does not match H, Wd, stride, pad")
+    if out is None:
+        out = torch.empty((B, H, Wd, C_in), dtype=dO.dtype, device=dO.device)
+    _dev(out, "out")
+    dt = _dtype_code(dO)
+    lib = load()
+    need = int(lib.sdgp_conv_bwd_data_channel_rescaled_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m))
+    workspace, wbytes = _workspace(need, workspace, dO.device, "sdgp_conv_bwd_data_channel_rescaled_workspace")
+    rc = lib.sdgp_conv_bwd_data_channel_rescaled(_ptr(dO), _ptr(W), _ptr(out), B, H, Wd, C_in, C_out, R, S, stride, pad,
+                                                 dt, n, m, _ptr(workspace), wbytes, _stream(dO))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_conv_bwd_data_channel_rescaled")
+    return out
+
+
+def sdgp_linear_bwd_data_channel_rescaled(dO: torch.Tensor, W: torch.Tensor, n: int, m: int) -> torch.Tensor:
+    """The same for a linear layer (dO [rows, C_out], W [C_out, C_in]): a 1x1 convolution over rows pixels."""
+    if dO.dim() != 2 or W.dim() != 2:
+        raise ValueError("expected dO [rows, C_out] and W [C_out, C_in]")
+    rows, C_out = dO.shape
+    out = sdgp_conv_bwd_data_channel_rescaled(dO.view(rows, 1, 1, C_out), W.view(C_out, 1, 1, W.shape[1]), 1, 1, 1, 0, n, m)
+    return out.view(rows, W.shape[1])

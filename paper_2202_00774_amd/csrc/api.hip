@@ -24,6 +24,12 @@ int bwd_conv3_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t
 int bwd_tiled_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                      int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                      hipStream_t stream);
+size_t channel_scales_workspace(int64_t rows, int64_t C, int dt, int m);
+int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, float* scale, double* sums,
+                          void* partial, hipStream_t stream);
+int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, const float* scale,
+                                  void* pruned, hipStream_t stream);
+int scale_rows_launch(const void* W, const float* scale, void* out, int64_t C_out, int64_t inner, int dt, hipStream_t stream);
 }  // namespace sdgp
 
 namespace {
@@ -94,6 +100,29 @@ int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, 
     return sdgp::bwd_simple_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, stream);
 }
 
+// [rows, C] pruned along C in groups of m: the checks sdgp_prune and the per-channel entry points share.
+int check_rows(int64_t rows, int64_t C, int dt, int n, int m, int64_t* total) {
+    if (!valid_dtype(dt)) return SDGP_ERR_DTYPE;
+    if (!valid_nm(n, m)) return SDGP_ERR_NM;
+    if (!mul_checked(rows, C, total) || (C % m) != 0) return SDGP_ERR_SHAPE;
+    return SDGP_OK;
+}
+
+size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+
+// Workspace of the fused per-channel call: partial sums | factors | rescaled filter.
+struct ChannelWorkspace {
+    size_t off_scale, off_filter, total;
+};
+
+ChannelWorkspace channel_workspace(int64_t rows, int64_t C_out, int64_t n_W, int dt, int m) {
+    ChannelWorkspace w;
+    w.off_scale = align256(rows > 0 && C_out > 0 ? sdgp::channel_scales_workspace(rows, C_out, dt, m) : 0);
+    w.off_filter = w.off_scale + align256((size_t)C_out * sizeof(float));
+    w.total = w.off_filter + align256((size_t)n_W * (dt == SDGP_BF16 ? 2u : 4u));
+    return w;
+}
+
 }  // namespace
 
 extern "C" {
@@ -147,6 +176,79 @@ int sdgp_linear_bwd_data(const void* dO, const void* W, void* dD, int64_t rows, 
                         static_cast<hipStream_t>(hip_stream));
 }
 
+size_t sdgp_channel_scales_workspace(int64_t rows, int64_t C, int dt, int n, int m) {
+    int64_t total = 0;
+    if (check_rows(rows, C, dt, n, m, &total) != SDGP_OK) return (size_t)-1;
+    return C == 0 ? 0 : sdgp::channel_scales_workspace(rows, C, dt, m);
+}
+
+int sdgp_channel_scales(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, float* scale, double* sums,
+                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int64_t total = 0;
+    const int rc = check_rows(rows, C, dt, n, m, &total);
+    if (rc != SDGP_OK) return rc;
+    if (C == 0) return SDGP_OK;  // no channel, no factor
+    if (scale == nullptr || (total > 0 && dO == nullptr)) return SDGP_ERR_NULL;
+    // a tensor without rows still defines every factor (1: the kept sum is 0); the kernels handle rows == 0
+    const size_t need = sdgp::channel_scales_workspace(rows, C, dt, m);
+    if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 7u) != 0)
+        return SDGP_ERR_WORKSPACE;
+    return sdgp::channel_scales_launch(dO, rows, C, dt, n, m, scale, sums, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int sdgp_prune_channel_rescaled(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, const float* scale,
+                                void* pruned, void* hip_stream) {
+    int64_t total = 0;
+    const int rc = check_rows(rows, C, dt, n, m, &total);
+    if (rc != SDGP_OK) return rc;
+    if (total == 0) return SDGP_OK;
+    if (dO == nullptr || scale == nullptr || pruned == nullptr) return SDGP_ERR_NULL;
+    return sdgp::prune_channel_rescaled_launch(dO, rows, C, dt, n, m, scale, pruned, static_cast<hipStream_t>(hip_stream));
+}
+
+int sdgp_scale_filter(const void* W, const float* scale, void* W_scaled, int64_t C_out, int64_t inner, int dt,
+                      void* hip_stream) {
+    if (!valid_dtype(dt)) return SDGP_ERR_DTYPE;
+    int64_t total = 0;
+    if (!mul_checked(C_out, inner, &total)) return SDGP_ERR_SHAPE;
+    if (total == 0) return SDGP_OK;
+    if (W == nullptr || scale == nullptr || W_scaled == nullptr) return SDGP_ERR_NULL;
+    return sdgp::scale_rows_launch(W, scale, W_scaled, C_out, inner, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t sdgp_conv_bwd_data_channel_rescaled_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R,
+                                                     int S, int stride, int pad, int dt, int n, int m) {
+    ConvGeom g;
+    if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g) != SDGP_OK) return (size_t)-1;
+    if (g.n_dD == 0) return 0;
+    return channel_workspace(B * g.P * g.Q, C_out, g.n_W, dt, m).total;
+}
+
+int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd,
+                                        int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dt, int n,
+                                        int m, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ConvGeom g;
+    int rc = check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g);
+    if (rc != SDGP_OK) return rc;
+    if (g.n_dD == 0) return SDGP_OK;
+    if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (g.n_dO == 0 || g.n_W == 0)  // nothing to rescale: the product of an empty sum, zeros
+        return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, stream);
+    const int64_t rows = B * g.P * g.Q;
+    const ChannelWorkspace w = channel_workspace(rows, C_out, g.n_W, dt, m);
+    if (workspace == nullptr || workspace_bytes < w.total || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0)
+        return SDGP_ERR_WORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    float* scale = reinterpret_cast<float*>(base + w.off_scale);
+    void* filter = base + w.off_filter;
+    rc = sdgp::channel_scales_launch(dO, rows, C_out, dt, n, m, scale, nullptr, base, stream);
+    if (rc != SDGP_OK) return rc;
+    rc = sdgp::scale_rows_launch(W, scale, filter, C_out, (int64_t)R * S * C_in, dt, stream);
+    if (rc != SDGP_OK) return rc;
+    return bwd_dispatch(dO, filter, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, stream);
+}
+
 const char* sdgp_status_string(int status) {
     switch (status) {
         case SDGP_OK: return "ok";
@@ -161,6 +263,6 @@ const char* sdgp_status_string(int status) {
     }
 }
 
-int sdgp_version(void) { return 100; }
+int sdgp_version(void) { return 200; }
 
 }  // extern "C"

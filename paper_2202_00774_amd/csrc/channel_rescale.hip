@@ -1,0 +1,400 @@
+// Rescaled Magnitude with one factor per channel (Sec. III-B; the captions of the figures showing the rescaled
+// gradient state that the L1 norm is preserved per channel over the batch and spatial dimensions).
+//
+// The kept set of every group is the Magnitude one.  Channel c of the whole tensor gets one factor
+//     s[c] = (sum over rows of |dO[i,c]|) / (sum over rows that kept c of |dO[i,c]|),   1 when the divisor is 0,
+// so the factor is known only after a sweep over the tensor.  Four kernels:
+//   channel_sums      one streaming read of dO: ranks every group, accumulates both column sums in fp64.  A thread
+//                     owns one 16-byte column slot (at least one group) and walks down the rows, so its 2 x slot
+//                     accumulators live in registers; the threads of a workgroup that share a slot are added up
+//                     in LDS in a fixed order, and every workgroup writes one row of partial sums
+//   channel_finish    adds the partial rows in order (deterministic: no atomics) and divides
+//   prune_scaled      Alg. 1 with kept values multiplied by their channel's factor (fp32 product, rounded to the
+//                     storage type): same thread-to-column mapping, the factors stay in registers
+//   scale_rows        W'[k,:] = W[k,:] * s[k]: folds the factors into the filter, after which the fused
+//                     Magnitude backward-data kernels compute the rescaled product without a second sweep of dO
+//                     (dD = sum_k x_k s_k W_k = sum_k x_k W'_k)
+// All of it is bound by HBM: 2 bytes per element read for the sums, 4 for prune_scaled.
+#include "ranker.h"
+
+namespace sdgp {
+
+namespace {
+
+constexpr int kBlock = 256;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT>
+struct Elem;
+template <>
+struct Elem<kF32> {
+    using type = uint32_t;
+    static constexpr int kPerVec = 4;
+};
+template <>
+struct Elem<kBF16> {
+    using type = uint16_t;
+    static constexpr int kPerVec = 8;
+};
+
+// How the tensor is dealt to threads.  A slot is `slot` consecutive channels (a whole number of groups); a workgroup
+// is tg slots wide and tr = 256 / tg rows tall; workgroup (x, y) starts at slot x*tg and row y*tr and walks down in
+// steps of nb*tr rows.
+struct Plan {
+    int slot;        // channels per slot
+    int64_t nslots;  // C / slot
+    int tg, tr;      // threads along the slots / along the rows
+    int gx;          // workgroups along the slots
+    int nb;          // workgroups along the rows = rows of partial sums
+    bool vec;        // compiled group size and 16-byte accesses
+};
+
+Plan make_plan(int64_t rows, int64_t C, int dt, int m, bool aligned) {
+    Plan p;
+    const int pv = (dt == kBF16) ? 8 : 4;
+    const int item = m > pv ? m : pv;
+    p.vec = aligned && (m == 4 || m == 8 || m == 16 || m == 32) && (C % item) == 0;
+    p.slot = p.vec ? item : m;
+    p.nslots = C / p.slot;
+    int tg = 1;
+    while (tg < kBlock && tg < p.nslots) tg <<= 1;
+    p.tg = tg;
+    p.tr = kBlock / tg;
+    p.gx = (int)((p.nslots + tg - 1) / tg);
+    // at least 64 rows per thread so that the partial sums stay a small fraction of the tensor; about 2048
+    // workgroups in all
+    int64_t nb = rows / ((int64_t)p.tr * 64);
+    const int64_t cap = 2048 / p.gx > 0 ? 2048 / p.gx : 1;
+    if (nb > cap) nb = cap;
+    if (nb < 1) nb = 1;
+    p.nb = (int)nb;
+    return p;
+}
+
+// Keep flags of one group by Magnitude; m compiled (M > 0) or at run time (M == 0, rank count).
+template <int DT, int M, bool NLE2>
+__device__ __forceinline__ void magnitude_keep(const uint32_t (&raw)[M ? M : 32], int m, int n, bool (&keep)[M ? M : 32]) {
+    if constexpr (M > 0) {
+        uint32_t out[M];
+        prune_group<DT, M, kGreedy, NLE2, false>(raw, n, 0u, 0u, keep, out);
+    } else {
+        constexpr uint32_t kMagMask = (DT == kBF16) ? 0x7FFFu : 0x7FFFFFFFu;
+        for (int j = 0; j < m; ++j) {
+            int rank = 0;
+            const uint32_t kj = raw[j] & kMagMask;
+            for (int i = 0; i < m; ++i) {
+                const uint32_t ki = raw[i] & kMagMask;
+                rank += (ki > kj || (ki == kj && i < j)) ? 1 : 0;
+            }
+            keep[j] = rank < n;
+        }
+    }
+}
+
+// Loads one slot of one row into raw[] (one stored bit pattern per element).
+template <int DT, int M>
+__device__ __forceinline__ void load_slot(const void* dO_, int64_t elem0, int slot, uint32_t (&raw)[(M ? (M > Elem<DT>::kPerVec ? M : Elem<DT>::kPerVec) : 32)]) {
+    using T = typename Elem<DT>::type;
+    if constexpr (M > 0) {
+        constexpr int PV = Elem<DT>::kPerVec;
+        constexpr int ITEM = M > PV ? M : PV;
+        const u32x4* src = reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(dO_) + elem0);
+#pragma unroll
+        for (int i = 0; i < ITEM / PV; ++i) {
+            const u32x4 v = src[i];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if constexpr (DT == kBF16) {
+                    raw[i * 8 + 2 * k] = w[k] & 0xFFFFu;
+                    raw[i * 8 + 2 * k + 1] = w[k] >> 16;
+                } else {
+                    raw[i * 4 + k] = w[k];
+                }
+            }
+        }
+    } else {
+        const T* src = reinterpret_cast<const T*>(dO_) + elem0;
+        for (int j = 0; j < slot; ++j) raw[j] = (uint32_t)src[j];
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ float abs_as_float(uint32_t raw) {
+    return (DT == kBF16) ? bits_to_float((raw & 0x7FFFu) << 16) : bits_to_float(raw & 0x7FFFFFFFu);
+}
+
+// ------------------------------------------------------------------ column sums
+
+template <int DT, int M, bool NLE2>
+__global__ void __launch_bounds__(kBlock)
+channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n, int slot, int64_t nslots, int tg, int tr,
+             double* __restrict__ partial) {
+    constexpr int PV = Elem<DT>::kPerVec;
+    constexpr int SLOT = M ? (M > PV ? M : PV) : 32;  // array size; the slot itself is `slot` channels
+    constexpr int GM = M ? M : 32;
+    __shared__ double red[kBlock];
+
+    const int tid = threadIdx.x;
+    const int sx = tid & (tg - 1), ry = tid / tg;
+    const int64_t s = (int64_t)blockIdx.x * tg + sx;
+    const bool active = s < nslots;
+    const int64_t step = (int64_t)gridDim.y * tr;
+
+    double tot[SLOT], kep[SLOT];
+#pragma unroll
+    for (int j = 0; j < SLOT; ++j) tot[j] = 0.0, kep[j] = 0.0;
+
+    if (active) {
+        const int groups = M ? SLOT / GM : 1;
+        for (int64_t r = (int64_t)blockIdx.y * tr + ry; r < rows; r += step) {
+            uint32_t raw[SLOT];
+            load_slot<DT, M>(dO_, r * C + s * slot, slot, raw);
+            if constexpr (M > 0) {
+#pragma unroll
+                for (int g = 0; g < groups; ++g) {
+                    uint32_t gr[GM];
+                    bool keep[GM];
+#pragma unroll
+                    for (int j = 0; j < GM; ++j) gr[j] = raw[g * GM + j];
+                    magnitude_keep<DT, M, NLE2>(gr, m, n, keep);
+#pragma unroll
+                    for (int j = 0; j < GM; ++j) {
+                        const float a = abs_as_float<DT>(gr[j]);
+                        tot[g * GM + j] += (double)a;
+                        kep[g * GM + j] += (double)(keep[j] ? a : 0.0f);
+                    }
+                }
+            } else {
+                bool keep[32];
+                magnitude_keep<DT, 0, false>(raw, m, n, keep);
+                for (int j = 0; j < m; ++j) {
+                    const float a = abs_as_float<DT>(raw[j]);
+                    tot[j] += (double)a;
+                    kep[j] += (double)(keep[j] ? a : 0.0f);
+                }
+            }
+        }
+    }
+
+    // Add the tr threads that share a slot, in ascending row-lane order, one accumulator at a time.
+    double* prow = partial + (int64_t)blockIdx.y * 2 * C;
+    auto reduce_one = [&](int j) {
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            double v = which ? kep[j] : tot[j];
+            if (tr > 1) {
+                __syncthreads();
+                red[tid] = v;
+                __syncthreads();
+                if (ry == 0) {
+                    v = red[sx];
+                    for (int y = 1; y < tr; ++y) v += red[y * tg + sx];
+                }
+            }
+            if (ry == 0 && active) prow[(int64_t)which * C + s * slot + j] = v;
+        }
+    };
+    if constexpr (M > 0) {
+#pragma unroll
+        for (int j = 0; j < SLOT; ++j) reduce_one(j);
+    } else {
+        for (int j = 0; j < slot; ++j) reduce_one(j);
+    }
+}
+
+// One thread per channel: partial rows added in ascending order, then the factor.
+__global__ void __launch_bounds__(kBlock)
+channel_finish(const double* __restrict__ partial, int nb, int64_t C, float* __restrict__ scale, double* __restrict__ sums) {
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= C) return;
+    double tot = 0.0, kep = 0.0;
+    for (int b = 0; b < nb; ++b) {
+        tot += partial[((int64_t)b * 2) * C + c];
+        kep += partial[((int64_t)b * 2 + 1) * C + c];
+    }
+    scale[c] = (kep == 0.0) ? 1.0f : (float)(tot / kep);
+    if (sums) {
+        sums[c] = tot;
+        sums[C + c] = kep;
+    }
+}
+
+// ------------------------------------------------------ prune with the factors
+
+template <int DT, int M, bool NLE2>
+__global__ void __launch_bounds__(kBlock)
+prune_scaled(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n, int slot, int64_t nslots, int tg, int tr,
+             const float* __restrict__ scale, void* __restrict__ pruned_) {
+    using T = typename Elem<DT>::type;
+    constexpr int PV = Elem<DT>::kPerVec;
+    constexpr int SLOT = M ? (M > PV ? M : PV) : 32;
+    constexpr int GM = M ? M : 32;
+
+    const int tid = threadIdx.x;
+    const int sx = tid & (tg - 1), ry = tid / tg;
+    const int64_t s = (int64_t)blockIdx.x * tg + sx;
+    if (s >= nslots) return;
+    const int64_t step = (int64_t)gridDim.y * tr;
+
+    float sc[SLOT];
+    if constexpr (M > 0) {
+#pragma unroll
+        for (int j = 0; j < SLOT; ++j) sc[j] = scale[s * slot + j];
+    } else {
+        for (int j = 0; j < slot; ++j) sc[j] = scale[s * slot + j];
+    }
+
+    for (int64_t r = (int64_t)blockIdx.y * tr + ry; r < rows; r += step) {
+        const int64_t e0 = r * C + s * slot;
+        uint32_t raw[SLOT];
+        load_slot<DT, M>(dO_, e0, slot, raw);
+        if constexpr (M > 0) {
+            uint32_t out[SLOT];
+#pragma unroll
+            for (int g = 0; g < SLOT / GM; ++g) {
+                uint32_t gr[GM];
+                bool keep[GM];
+#pragma unroll
+                for (int j = 0; j < GM; ++j) gr[j] = raw[g * GM + j];
+                magnitude_keep<DT, M, NLE2>(gr, m, n, keep);
+#pragma unroll
+                for (int j = 0; j < GM; ++j) {
+                    const float x = (DT == kBF16) ? bf16_to_float(gr[j]) : bits_to_float(gr[j]);
+                    const float y = __fmul_rn(x, sc[g * GM + j]);
+                    const uint32_t yb = (DT == kBF16) ? float_to_bf16(y) : float_to_bits(y);
+                    out[g * GM + j] = keep[j] ? yb : 0u;
+                }
+            }
+            u32x4* dst = reinterpret_cast<u32x4*>(reinterpret_cast<T*>(pruned_) + e0);
+#pragma unroll
+            for (int i = 0; i < SLOT / PV; ++i) {
+                uint32_t w[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if constexpr (DT == kBF16) w[k] = out[i * 8 + 2 * k] | (out[i * 8 + 2 * k + 1] << 16);
+                    else w[k] = out[i * 4 + k];
+                }
+                const u32x4 pk = {w[0], w[1], w[2], w[3]};
+                __builtin_nontemporal_store(pk, dst + i);
+            }
+        } else {
+            bool keep[32];
+            magnitude_keep<DT, 0, false>(raw, m, n, keep);
+            T* dst = reinterpret_cast<T*>(pruned_) + e0;
+            for (int j = 0; j < m; ++j) {
+                const float x = (DT == kBF16) ? bf16_to_float(raw[j]) : bits_to_float(raw[j]);
+                const float y = __fmul_rn(x, sc[j]);
+                const uint32_t yb = (DT == kBF16) ? float_to_bf16(y) : float_to_bits(y);
+                dst[j] = (T)(keep[j] ? yb : 0u);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------ filter rows * s
+
+// W [C_out, inner] -> W' [C_out, inner], row k multiplied by scale[k] in fp32 and rounded to the storage type.
+template <int DT>
+__global__ void __launch_bounds__(kBlock)
+scale_rows(const void* __restrict__ W_, const float* __restrict__ scale, void* __restrict__ out_, int64_t C_out, int64_t inner) {
+    using T = typename Elem<DT>::type;
+    const int64_t total = C_out * inner;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    const T* W = reinterpret_cast<const T*>(W_);
+    T* out = reinterpret_cast<T*>(out_);
+    for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < total; e += stride) {
+        const float s = scale[e / inner];
+        const uint32_t raw = (uint32_t)W[e];
+        const float x = (DT == kBF16) ? bf16_to_float(raw) : bits_to_float(raw);
+        const float y = __fmul_rn(x, s);
+        out[e] = (T)((DT == kBF16) ? float_to_bf16(y) : float_to_bits(y));
+    }
+}
+
+// --------------------------------------------------------------------- launch
+
+template <int DT, int M>
+void launch_sums(const Plan& p, const void* dO, int64_t rows, int64_t C, int m, int n, double* partial, hipStream_t st) {
+    const dim3 grid((unsigned)p.gx, (unsigned)p.nb), block(kBlock);
+    if (n <= 2)
+        hipLaunchKernelGGL((channel_sums<DT, M, true>), grid, block, 0, st, dO, rows, C, m, n, p.slot, p.nslots, p.tg, p.tr, partial);
+    else
+        hipLaunchKernelGGL((channel_sums<DT, M, false>), grid, block, 0, st, dO, rows, C, m, n, p.slot, p.nslots, p.tg, p.tr, partial);
+}
+
+template <int DT, int M>
+void launch_prune(const Plan& p, const void* dO, int64_t rows, int64_t C, int m, int n, const float* scale, void* pruned,
+                  hipStream_t st) {
+    const dim3 grid((unsigned)p.gx, (unsigned)p.nb), block(kBlock);
+    if (n <= 2)
+        hipLaunchKernelGGL((prune_scaled<DT, M, true>), grid, block, 0, st, dO, rows, C, m, n, p.slot, p.nslots, p.tg, p.tr, scale, pruned);
+    else
+        hipLaunchKernelGGL((prune_scaled<DT, M, false>), grid, block, 0, st, dO, rows, C, m, n, p.slot, p.nslots, p.tg, p.tr, scale, pruned);
+}
+
+template <int DT>
+void sums_dtype(const Plan& p, const void* dO, int64_t rows, int64_t C, int m, int n, double* partial, hipStream_t st) {
+    if (!p.vec) return launch_sums<DT, 0>(p, dO, rows, C, m, n, partial, st);
+    switch (m) {
+        case 4: return launch_sums<DT, 4>(p, dO, rows, C, m, n, partial, st);
+        case 8: return launch_sums<DT, 8>(p, dO, rows, C, m, n, partial, st);
+        case 16: return launch_sums<DT, 16>(p, dO, rows, C, m, n, partial, st);
+        default: return launch_sums<DT, 32>(p, dO, rows, C, m, n, partial, st);
+    }
+}
+
+template <int DT>
+void prune_dtype(const Plan& p, const void* dO, int64_t rows, int64_t C, int m, int n, const float* scale, void* pruned,
+                 hipStream_t st) {
+    if (!p.vec) return launch_prune<DT, 0>(p, dO, rows, C, m, n, scale, pruned, st);
+    switch (m) {
+        case 4: return launch_prune<DT, 4>(p, dO, rows, C, m, n, scale, pruned, st);
+        case 8: return launch_prune<DT, 8>(p, dO, rows, C, m, n, scale, pruned, st);
+        case 16: return launch_prune<DT, 16>(p, dO, rows, C, m, n, scale, pruned, st);
+        default: return launch_prune<DT, 32>(p, dO, rows, C, m, n, scale, pruned, st);
+    }
+}
+
+}  // namespace
+
+// Bytes of partial sums channel_scales_launch writes for these arguments (rows > 0, C > 0, C % m == 0).
+size_t channel_scales_workspace(int64_t rows, int64_t C, int dt, int m) {
+    const Plan p = make_plan(rows, C, dt, m, true);
+    // the unaligned plan never has more partial rows than this bound: nb depends on tr = 256 / tg, and the
+    // scalar plan's slots are no wider than the vector plan's, so take the larger of the two
+    const Plan q = make_plan(rows, C, dt, m, false);
+    const int nb = p.nb > q.nb ? p.nb : q.nb;
+    return (size_t)nb * 2u * (size_t)C * sizeof(double);
+}
+
+// Validated arguments in.  scale [C] floats, sums [2*C] doubles or NULL, partial = the workspace.
+int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, float* scale, double* sums,
+                          void* partial, hipStream_t stream) {
+    const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO));
+    double* part = static_cast<double*>(partial);
+    if (dt == kBF16) sums_dtype<kBF16>(p, dO, rows, C, m, n, part, stream);
+    else sums_dtype<kF32>(p, dO, rows, C, m, n, part, stream);
+    hipLaunchKernelGGL(channel_finish, dim3((unsigned)((C + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, part, p.nb, C,
+                       scale, sums);
+    return launch_status();
+}
+
+int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, const float* scale,
+                                  void* pruned, hipStream_t stream) {
+    const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO) && is_aligned16(pruned));
+    if (dt == kBF16) prune_dtype<kBF16>(p, dO, rows, C, m, n, scale, pruned, stream);
+    else prune_dtype<kF32>(p, dO, rows, C, m, n, scale, pruned, stream);
+    return launch_status();
+}
+
+int scale_rows_launch(const void* W, const float* scale, void* out, int64_t C_out, int64_t inner, int dt, hipStream_t stream) {
+    const int64_t total = C_out * inner;
+    int64_t blocks = (total + kBlock - 1) / kBlock;
+    if (blocks > 4096) blocks = 4096;
+    if (dt == kBF16) hipLaunchKernelGGL(scale_rows<kBF16>, dim3((unsigned)blocks), dim3(kBlock), 0, stream, W, scale, out, C_out, inner);
+    else hipLaunchKernelGGL(scale_rows<kF32>, dim3((unsigned)blocks), dim3(kBlock), 0, stream, W, scale, out, C_out, inner);
+    return launch_status();
+}
+
+}  // namespace sdgp

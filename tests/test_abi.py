@@ -119,3 +119,76 @@ def test_workspace_too_small_is_rejected(lib):
             if need:
                 assert conv(lib, B, H, Wd, C_in, C_out, R, S, st, pad, n=n, m=m) == E_WS
                 assert conv(lib, B, H, Wd, C_in, C_out, R, S, st, pad, n=n, m=m, ws=P, ws_bytes=need - 1) == E_WS
+
+
+# ------------------------------------------------ per-channel Rescaled Magnitude entry points
+
+BAD = ctypes.c_size_t(-1).value
+
+
+def test_channel_scales_argument_errors(lib):
+    def scales(rows=4, C=16, dt=1, n=2, m=4, dO=P, scale=P, ws=P, ws_bytes=1 << 20):
+        return lib.sdgp_channel_scales(dO, rows, C, dt, n, m, scale, None, ws, ws_bytes, None)
+
+    assert scales(dt=3) == E_DTYPE
+    assert scales(n=0) == E_NM
+    assert scales(m=33, C=66) == E_NM
+    assert scales(C=18) == E_SHAPE
+    assert scales(rows=-1) == E_SHAPE
+    assert scales(dO=None) == E_NULL
+    assert scales(scale=None) == E_NULL
+    assert scales(ws=None) == E_WS
+    assert scales(ws_bytes=8) == E_WS
+    assert scales(ws=ctypes.c_void_p(20)) == E_WS          # not 8-byte aligned
+    assert scales(C=0) == OK
+    assert lib.sdgp_channel_scales_workspace(4, 18, 1, 2, 4) == BAD
+    need = lib.sdgp_channel_scales_workspace(1 << 20, 256, 1, 2, 4)
+    assert need != BAD and need % 8 == 0 and 2 * 256 * 8 <= need <= (1 << 20) * 256 * 2 // 4   # far below the tensor
+    assert lib.sdgp_channel_scales_workspace(4, 0, 1, 2, 4) == 0
+
+
+def test_prune_channel_rescaled_and_scale_filter_argument_errors(lib):
+    def prune_cr(rows=4, C=16, dt=1, n=2, m=4, dO=P, scale=P, pruned=P):
+        return lib.sdgp_prune_channel_rescaled(dO, rows, C, dt, n, m, scale, pruned, None)
+
+    assert prune_cr(dt=2) == E_DTYPE
+    assert prune_cr(n=5) == E_NM
+    assert prune_cr(C=6) == E_SHAPE
+    assert prune_cr(dO=None) == E_NULL
+    assert prune_cr(scale=None) == E_NULL
+    assert prune_cr(pruned=None) == E_NULL
+    assert prune_cr(rows=0) == OK
+
+    def scale_filter(C_out=16, inner=72, dt=1, W=P, scale=P, out=P):
+        return lib.sdgp_scale_filter(W, scale, out, C_out, inner, dt, None)
+
+    assert scale_filter(dt=5) == E_DTYPE
+    assert scale_filter(C_out=-1) == E_SHAPE
+    assert scale_filter(inner=-1) == E_SHAPE
+    assert scale_filter(W=None) == E_NULL
+    assert scale_filter(scale=None) == E_NULL
+    assert scale_filter(out=None) == E_NULL
+    assert scale_filter(C_out=0) == OK
+    assert scale_filter(inner=0) == OK
+
+
+def test_conv_channel_rescaled_argument_errors(lib):
+    def conv_cr(B=2, H=8, Wd=8, C_in=8, C_out=16, R=3, S=3, stride=1, pad=1, dt=1, n=2, m=4, dO=P, W=P, dD=P, ws=P,
+                ws_bytes=1 << 24):
+        return lib.sdgp_conv_bwd_data_channel_rescaled(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m,
+                                                       ws, ws_bytes, None)
+
+    assert conv_cr(dt=-1) == E_DTYPE
+    assert conv_cr(n=0) == E_NM
+    assert conv_cr(C_out=10) == E_SHAPE
+    assert conv_cr(stride=5) == E_SHAPE
+    assert conv_cr(dO=None) == E_NULL
+    assert conv_cr(W=None) == E_NULL
+    assert conv_cr(dD=None) == E_NULL
+    assert conv_cr(ws=None) == E_WS
+    need = lib.sdgp_conv_bwd_data_channel_rescaled_workspace(2, 8, 8, 8, 16, 3, 3, 1, 1, 1, 2, 4)
+    assert need != BAD and need >= 16 * 4 + 16 * 9 * 8 * 2        # the factors and the rescaled filter at least
+    assert conv_cr(ws_bytes=need - 1) == E_WS
+    assert conv_cr(ws=ctypes.c_void_p(24)) == E_WS                # not 16-byte aligned
+    assert conv_cr(B=0) == OK
+    assert lib.sdgp_conv_bwd_data_channel_rescaled_workspace(2, 8, 8, 8, 10, 3, 3, 1, 1, 1, 2, 4) == BAD
