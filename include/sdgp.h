@@ -149,8 +149,9 @@ size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_
  * the kept set of every group is the Magnitude one, and channel c of the whole
  * tensor is multiplied by
  *     s[c] = (sum over rows of |dO[i,c]|) / (sum over the rows that kept c of |dO[i,c]|),
- * s[c] = 1 when the divisor is 0.  Both sums are accumulated in fp64; s[c] is the
- * fp64 quotient rounded to fp32.
+ * s[c] = 1 when the divisor is 0.  Both sums are accumulated in fp64 (in an order
+ * that is fixed for a given shape, not the row order); s[c] is the fp64 quotient
+ * rounded to fp32.
  *
  * sdgp_channel_scales       one read of dO [rows, C]: writes scale [C] (fp32, device) and, when
  *                           `sums` is not NULL, the two sums as sums[0..C) and sums[C..2C) (fp64,

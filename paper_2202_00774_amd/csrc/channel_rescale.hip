@@ -8,7 +8,7 @@
 //                     owns one 16-byte column slot (at least one group) and walks down the rows, so its 2 x slot
 //                     accumulators live in registers; the threads of a workgroup that share a slot are added up
 //                     in LDS in a fixed order, and every workgroup writes one row of partial sums
-//   channel_finish    adds the partial rows in order (deterministic: no atomics) and divides
+//   channel_finish    adds the partial rows in a fixed order (deterministic: no atomics) and divides
 //   prune_scaled      Alg. 1 with kept values multiplied by their channel's factor (fp32 product, rounded to the
 //                     storage type): same thread-to-column mapping, the factors stay in registers
 //   scale_rows        W'[k,:] = W[k,:] * s[k]: folds the factors into the filter, after which the fused
@@ -126,13 +126,18 @@ __device__ __forceinline__ float abs_as_float(uint32_t raw) {
 
 // ------------------------------------------------------------------ column sums
 
+// Accumulation is fp64 per thread: with at most 24 significant bits per addend the sums are exact until they span
+// more than 53 bits, and carrying each sum as a pair of floats (error-free additions, six fp32 operations per term)
+// measured a third slower than the fp64 additions.
 template <int DT, int M, bool NLE2>
 __global__ void __launch_bounds__(kBlock)
 channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n, int slot, int64_t nslots, int tg, int tr,
              double* __restrict__ partial) {
+    using T = typename Elem<DT>::type;
     constexpr int PV = Elem<DT>::kPerVec;
     constexpr int SLOT = M ? (M > PV ? M : PV) : 32;  // array size; the slot itself is `slot` channels
     constexpr int GM = M ? M : 32;
+    constexpr int VECS = SLOT / PV;
     __shared__ double red[kBlock];
 
     const int tid = threadIdx.x;
@@ -146,13 +151,37 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
     for (int j = 0; j < SLOT; ++j) tot[j] = 0.0, kep[j] = 0.0;
 
     if (active) {
-        const int groups = M ? SLOT / GM : 1;
-        for (int64_t r = (int64_t)blockIdx.y * tr + ry; r < rows; r += step) {
-            uint32_t raw[SLOT];
-            load_slot<DT, M>(dO_, r * C + s * slot, slot, raw);
-            if constexpr (M > 0) {
+        int64_t r = (int64_t)blockIdx.y * tr + ry;
+        if constexpr (M > 0) {
+            // the next row's vectors are requested before this row's are ranked
+            u32x4 cur[VECS], nxt[VECS];
+            const T* base = reinterpret_cast<const T*>(dO_) + s * slot;
+            if (r < rows) {
 #pragma unroll
-                for (int g = 0; g < groups; ++g) {
+                for (int i = 0; i < VECS; ++i) cur[i] = reinterpret_cast<const u32x4*>(base + r * C)[i];
+            }
+            for (; r < rows; r += step) {
+                const int64_t rn = r + step;
+                if (rn < rows) {
+#pragma unroll
+                    for (int i = 0; i < VECS; ++i) nxt[i] = reinterpret_cast<const u32x4*>(base + rn * C)[i];
+                }
+                uint32_t raw[SLOT];
+#pragma unroll
+                for (int i = 0; i < VECS; ++i) {
+                    const uint32_t w[4] = {cur[i].x, cur[i].y, cur[i].z, cur[i].w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        if constexpr (DT == kBF16) {
+                            raw[i * 8 + 2 * k] = w[k] & 0xFFFFu;
+                            raw[i * 8 + 2 * k + 1] = w[k] >> 16;
+                        } else {
+                            raw[i * 4 + k] = w[k];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int g = 0; g < SLOT / GM; ++g) {
                     uint32_t gr[GM];
                     bool keep[GM];
 #pragma unroll
@@ -161,17 +190,25 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
 #pragma unroll
                     for (int j = 0; j < GM; ++j) {
                         const float a = abs_as_float<DT>(gr[j]);
-                        tot[g * GM + j] += (double)a;
-                        kep[g * GM + j] += (double)(keep[j] ? a : 0.0f);
+                        const double ad = (double)a;
+                        tot[g * GM + j] += ad;
+                        kep[g * GM + j] += keep[j] ? ad : 0.0;
                     }
                 }
-            } else {
+#pragma unroll
+                for (int i = 0; i < VECS; ++i) cur[i] = nxt[i];
+            }
+        } else {
+            for (; r < rows; r += step) {
+                uint32_t raw[SLOT];
+                load_slot<DT, M>(dO_, r * C + s * slot, slot, raw);
                 bool keep[32];
                 magnitude_keep<DT, 0, false>(raw, m, n, keep);
                 for (int j = 0; j < m; ++j) {
                     const float a = abs_as_float<DT>(raw[j]);
-                    tot[j] += (double)a;
-                    kep[j] += (double)(keep[j] ? a : 0.0f);
+                    const double ad = (double)a;
+                    tot[j] += ad;
+                    kep[j] += keep[j] ? ad : 0.0;
                 }
             }
         }
@@ -203,15 +240,31 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
     }
 }
 
-// One thread per channel: partial rows added in ascending order, then the factor.
+// Adds the nb partial rows and divides.  A workgroup owns kFinC channels; kFinL threads per channel each add every
+// kFinL-th partial row in ascending order, then the kFinL sums are added in ascending order: a fixed order for a
+// given nb, with enough independent loads in flight that the pass is not a chain of memory latencies.
+constexpr int kFinC = 4, kFinL = kBlock / kFinC;
+
 __global__ void __launch_bounds__(kBlock)
 channel_finish(const double* __restrict__ partial, int nb, int64_t C, float* __restrict__ scale, double* __restrict__ sums) {
-    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (c >= C) return;
+    __shared__ double red[2][kFinL][kFinC];
+    const int cx = threadIdx.x % kFinC, l = threadIdx.x / kFinC;
+    const int64_t c = (int64_t)blockIdx.x * kFinC + cx;
     double tot = 0.0, kep = 0.0;
-    for (int b = 0; b < nb; ++b) {
-        tot += partial[((int64_t)b * 2) * C + c];
-        kep += partial[((int64_t)b * 2 + 1) * C + c];
+    if (c < C) {
+#pragma unroll 8
+        for (int b = l; b < nb; b += kFinL) {
+            tot += partial[((int64_t)b * 2) * C + c];
+            kep += partial[((int64_t)b * 2 + 1) * C + c];
+        }
+    }
+    red[0][l][cx] = tot;
+    red[1][l][cx] = kep;
+    __syncthreads();
+    if (l != 0 || c >= C) return;
+    for (int i = 1; i < kFinL; ++i) {
+        tot += red[0][i][cx];
+        kep += red[1][i][cx];
     }
     scale[c] = (kep == 0.0) ? 1.0f : (float)(tot / kep);
     if (sums) {
@@ -375,7 +428,7 @@ int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n
     double* part = static_cast<double*>(partial);
     if (dt == kBF16) sums_dtype<kBF16>(p, dO, rows, C, m, n, part, stream);
     else sums_dtype<kF32>(p, dO, rows, C, m, n, part, stream);
-    hipLaunchKernelGGL(channel_finish, dim3((unsigned)((C + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, part, p.nb, C,
+    hipLaunchKernelGGL(channel_finish, dim3((unsigned)((C + kFinC - 1) / kFinC)), dim3(kBlock), 0, stream, part, p.nb, C,
                        scale, sums);
     return launch_status();
 }
