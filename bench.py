@@ -275,7 +275,45 @@ def main():
                                     "achieved": prune["greedy"]["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                     "frac": prune["greedy"]["frac_of_hbm_peak"],
                                     "traffic": MEASURED_TRAFFIC_BYTES["prune_411MB"], "algorithmic_bytes": 4.0 * nelem}
-        del srcs, dsts
+        # ---- Rescaled Magnitude with one factor per channel (second reading of Sec. III-B): the sweep that makes the
+        # factors (2 bytes per element read), the prune pass with them (4), on the same 411 MB tensors; and the fused
+        # call (factors, filter rows times factors, Magnitude product) on the ResNet-9 layers against the per-group one
+        ws = torch.empty(int(lib.sdgp_channel_scales_workspace(nelem // 64, 64, sdgp.BF16, 2, 4)), dtype=torch.uint8, device=dev)
+        factors = torch.empty(64, dtype=torch.float32, device=dev)
+
+        def sums():
+            s = srcs[k[0] % 2]
+            k[0] += 1
+            rc = lib.sdgp_channel_scales(ctypes.c_void_p(s.data_ptr()), s.shape[0], s.shape[1], sdgp.BF16, 2, 4,
+                                         ctypes.c_void_p(factors.data_ptr()), None, ctypes.c_void_p(ws.data_ptr()), ws.numel(), stream)
+            assert rc == 0
+
+        def prune_scaled():
+            s, d = srcs[k[0] % 2], dsts[k[0] % 2]
+            k[0] += 1
+            rc = lib.sdgp_prune_channel_rescaled(ctypes.c_void_p(s.data_ptr()), s.shape[0], s.shape[1], sdgp.BF16, 2, 4,
+                                                 ctypes.c_void_p(factors.data_ptr()), ctypes.c_void_p(d.data_ptr()), stream)
+            assert rc == 0
+        ms_s, ms_p = time_call(sums, reps=20, warm=3), time_call(prune_scaled, reps=20, warm=3)
+        per_channel = {
+            "channel_scales": {"us": round(ms_s * 1e3, 1), "GB/s": round(2.0 * nelem / (ms_s * 1e-3) / 1e9, 1),
+                               "frac_of_hbm_peak": round(2.0 * nelem / (ms_s * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+            "prune_channel_rescaled": {"us": round(ms_p * 1e3, 1), "GB/s": round(4.0 * nelem / (ms_p * 1e-3) / 1e9, 1),
+                                       "frac_of_hbm_peak": round(4.0 * nelem / (ms_p * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+            "fused_layers": [],
+        }
+        for L, dO, W, out in data:
+            need = int(lib.sdgp_conv_bwd_data_channel_rescaled_workspace(L.B, L.H, L.Wd, L.C_in, L.C_out, L.R, L.S, L.stride,
+                                                                         L.pad, sdgp.BF16, 2, 4))
+            wsl = torch.empty(need, dtype=torch.uint8, device=dev)
+            t_pc = time_call(lambda: sdgp.sdgp_conv_bwd_data_channel_rescaled(dO, W, L.H, L.Wd, L.stride, L.pad, 2, 4, out=out,
+                                                                              workspace=wsl))
+            t_pg = time_call(lambda: call(L, dO, W, out, 2, 4, sdgp.GREEDY_ADJUSTED))
+            per_channel["fused_layers"].append({"layer": L.name, "per_channel_us": round(t_pc * 1e3, 1),
+                                                "per_group_us": round(t_pg * 1e3, 1)})
+            del wsl
+        result["rescaled_per_channel"] = per_channel
+        del srcs, dsts, ws
 
         # ---- the CPU oracle on a bounded sample of the same workload
         if args.cpu_batch > 0:

@@ -24,6 +24,15 @@ namespace {
 constexpr int kBlock = 256;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// One 16-byte load of a streamed tensor.  With one vector per thread the line is used up by the load and gets the
+// streaming hint; with several, the lanes of one load leave gaps that the thread's other loads fill, so the line
+// should stay until they have come by.
+template <bool kStream>
+__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+    if constexpr (kStream) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
 template <int DT>
 struct Elem;
 template <>
@@ -49,7 +58,9 @@ struct Plan {
     bool vec;        // compiled group size and 16-byte accesses
 };
 
-Plan make_plan(int64_t rows, int64_t C, int dt, int m, bool aligned) {
+// min_rows: fewest rows a thread should walk (the sums kernel writes one row of partial sums per workgroup, so its
+// threads must amortise it; the pruning kernel has no such cost).
+Plan make_plan(int64_t rows, int64_t C, int dt, int m, bool aligned, int min_rows) {
     Plan p;
     const int pv = (dt == kBF16) ? 8 : 4;
     const int item = m > pv ? m : pv;
@@ -61,15 +72,18 @@ Plan make_plan(int64_t rows, int64_t C, int dt, int m, bool aligned) {
     p.tg = tg;
     p.tr = kBlock / tg;
     p.gx = (int)((p.nslots + tg - 1) / tg);
-    // at least 64 rows per thread so that the partial sums stay a small fraction of the tensor; about 2048
-    // workgroups in all
-    int64_t nb = rows / ((int64_t)p.tr * 64);
+    // about 2048 workgroups in all; 64 rows per thread when the tensor is large enough for that many, fewer (down to
+    // min_rows) when it is not
     const int64_t cap = 2048 / p.gx > 0 ? 2048 / p.gx : 1;
+    int64_t nb = rows / ((int64_t)p.tr * 64);
+    if (nb < cap) nb = rows / ((int64_t)p.tr * min_rows);
     if (nb > cap) nb = cap;
     if (nb < 1) nb = 1;
     p.nb = (int)nb;
     return p;
 }
+
+constexpr int kSumsMinRows = 16, kPruneMinRows = 2;
 
 // Keep flags of one group by Magnitude; m compiled (M > 0) or at run time (M == 0, rank count).
 template <int DT, int M, bool NLE2>
@@ -91,32 +105,12 @@ __device__ __forceinline__ void magnitude_keep(const uint32_t (&raw)[M ? M : 32]
     }
 }
 
-// Loads one slot of one row into raw[] (one stored bit pattern per element).
-template <int DT, int M>
-__device__ __forceinline__ void load_slot(const void* dO_, int64_t elem0, int slot, uint32_t (&raw)[(M ? (M > Elem<DT>::kPerVec ? M : Elem<DT>::kPerVec) : 32)]) {
+// Scalar path: loads the m elements of one group into raw[] (one stored bit pattern per element).
+template <int DT>
+__device__ __forceinline__ void load_group_scalar(const void* dO_, int64_t elem0, int m, uint32_t (&raw)[32]) {
     using T = typename Elem<DT>::type;
-    if constexpr (M > 0) {
-        constexpr int PV = Elem<DT>::kPerVec;
-        constexpr int ITEM = M > PV ? M : PV;
-        const u32x4* src = reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(dO_) + elem0);
-#pragma unroll
-        for (int i = 0; i < ITEM / PV; ++i) {
-            const u32x4 v = src[i];
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if constexpr (DT == kBF16) {
-                    raw[i * 8 + 2 * k] = w[k] & 0xFFFFu;
-                    raw[i * 8 + 2 * k + 1] = w[k] >> 16;
-                } else {
-                    raw[i * 4 + k] = w[k];
-                }
-            }
-        }
-    } else {
-        const T* src = reinterpret_cast<const T*>(dO_) + elem0;
-        for (int j = 0; j < slot; ++j) raw[j] = (uint32_t)src[j];
-    }
+    const T* src = reinterpret_cast<const T*>(dO_) + elem0;
+    for (int j = 0; j < m; ++j) raw[j] = (uint32_t)src[j];
 }
 
 template <int DT>
@@ -158,13 +152,13 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
             const T* base = reinterpret_cast<const T*>(dO_) + s * slot;
             if (r < rows) {
 #pragma unroll
-                for (int i = 0; i < VECS; ++i) cur[i] = reinterpret_cast<const u32x4*>(base + r * C)[i];
+                for (int i = 0; i < VECS; ++i) cur[i] = load16<VECS == 1>(reinterpret_cast<const u32x4*>(base + r * C) + i);
             }
             for (; r < rows; r += step) {
                 const int64_t rn = r + step;
                 if (rn < rows) {
 #pragma unroll
-                    for (int i = 0; i < VECS; ++i) nxt[i] = reinterpret_cast<const u32x4*>(base + rn * C)[i];
+                    for (int i = 0; i < VECS; ++i) nxt[i] = load16<VECS == 1>(reinterpret_cast<const u32x4*>(base + rn * C) + i);
                 }
                 uint32_t raw[SLOT];
 #pragma unroll
@@ -201,7 +195,7 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
         } else {
             for (; r < rows; r += step) {
                 uint32_t raw[SLOT];
-                load_slot<DT, M>(dO_, r * C + s * slot, slot, raw);
+                load_group_scalar<DT>(dO_, r * C + s * slot, slot, raw);
                 bool keep[32];
                 magnitude_keep<DT, 0, false>(raw, m, n, keep);
                 for (int j = 0; j < m; ++j) {
@@ -298,12 +292,42 @@ prune_scaled(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
         for (int j = 0; j < slot; ++j) sc[j] = scale[s * slot + j];
     }
 
-    for (int64_t r = (int64_t)blockIdx.y * tr + ry; r < rows; r += step) {
-        const int64_t e0 = r * C + s * slot;
-        uint32_t raw[SLOT];
-        load_slot<DT, M>(dO_, e0, slot, raw);
-        if constexpr (M > 0) {
-            uint32_t out[SLOT];
+    int64_t r = (int64_t)blockIdx.y * tr + ry;
+    if constexpr (M > 0) {
+        constexpr int VECS = SLOT / PV;
+        // the next row's vectors are requested before this row's are ranked (measured: faster with one and with
+        // four vectors per slot, slower with two, where the row is loaded when its turn comes)
+        constexpr bool kAhead = VECS != 2;
+        u32x4 cur[VECS], nxt[VECS];
+        const T* base = reinterpret_cast<const T*>(dO_) + s * slot;
+        if (kAhead && r < rows) {
+#pragma unroll
+            for (int i = 0; i < VECS; ++i) cur[i] = load16<VECS == 1>(reinterpret_cast<const u32x4*>(base + r * C) + i);
+        }
+        for (; r < rows; r += step) {
+            const int64_t rn = kAhead ? r + step : r;
+            if (rn < rows) {
+#pragma unroll
+                for (int i = 0; i < VECS; ++i) nxt[i] = load16<VECS == 1>(reinterpret_cast<const u32x4*>(base + rn * C) + i);
+            }
+            if constexpr (!kAhead) {
+#pragma unroll
+                for (int i = 0; i < VECS; ++i) cur[i] = nxt[i];
+            }
+            uint32_t raw[SLOT], out[SLOT];
+#pragma unroll
+            for (int i = 0; i < VECS; ++i) {
+                const uint32_t w[4] = {cur[i].x, cur[i].y, cur[i].z, cur[i].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if constexpr (DT == kBF16) {
+                        raw[i * 8 + 2 * k] = w[k] & 0xFFFFu;
+                        raw[i * 8 + 2 * k + 1] = w[k] >> 16;
+                    } else {
+                        raw[i * 4 + k] = w[k];
+                    }
+                }
+            }
 #pragma unroll
             for (int g = 0; g < SLOT / GM; ++g) {
                 uint32_t gr[GM];
@@ -319,9 +343,9 @@ prune_scaled(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
                     out[g * GM + j] = keep[j] ? yb : 0u;
                 }
             }
-            u32x4* dst = reinterpret_cast<u32x4*>(reinterpret_cast<T*>(pruned_) + e0);
+            u32x4* dst = reinterpret_cast<u32x4*>(reinterpret_cast<T*>(pruned_) + r * C + s * slot);
 #pragma unroll
-            for (int i = 0; i < SLOT / PV; ++i) {
+            for (int i = 0; i < VECS; ++i) {
                 uint32_t w[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
@@ -331,7 +355,14 @@ prune_scaled(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
                 const u32x4 pk = {w[0], w[1], w[2], w[3]};
                 __builtin_nontemporal_store(pk, dst + i);
             }
-        } else {
+#pragma unroll
+            for (int i = 0; i < VECS; ++i) cur[i] = nxt[i];
+        }
+    } else {
+        for (; r < rows; r += step) {
+            const int64_t e0 = r * C + s * slot;
+            uint32_t raw[SLOT];
+            load_group_scalar<DT>(dO_, e0, slot, raw);
             bool keep[32];
             magnitude_keep<DT, 0, false>(raw, m, n, keep);
             T* dst = reinterpret_cast<T*>(pruned_) + e0;
@@ -413,10 +444,10 @@ void prune_dtype(const Plan& p, const void* dO, int64_t rows, int64_t C, int m, 
 
 // Bytes of partial sums channel_scales_launch writes for these arguments (rows > 0, C > 0, C % m == 0).
 size_t channel_scales_workspace(int64_t rows, int64_t C, int dt, int m) {
-    const Plan p = make_plan(rows, C, dt, m, true);
+    const Plan p = make_plan(rows, C, dt, m, true, kSumsMinRows);
     // the unaligned plan never has more partial rows than this bound: nb depends on tr = 256 / tg, and the
     // scalar plan's slots are no wider than the vector plan's, so take the larger of the two
-    const Plan q = make_plan(rows, C, dt, m, false);
+    const Plan q = make_plan(rows, C, dt, m, false, kSumsMinRows);
     const int nb = p.nb > q.nb ? p.nb : q.nb;
     return (size_t)nb * 2u * (size_t)C * sizeof(double);
 }
@@ -424,7 +455,7 @@ size_t channel_scales_workspace(int64_t rows, int64_t C, int dt, int m) {
 // Validated arguments in.  scale [C] floats, sums [2*C] doubles or NULL, partial = the workspace.
 int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, float* scale, double* sums,
                           void* partial, hipStream_t stream) {
-    const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO));
+    const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO), kSumsMinRows);
     double* part = static_cast<double*>(partial);
     if (dt == kBF16) sums_dtype<kBF16>(p, dO, rows, C, m, n, part, stream);
     else sums_dtype<kF32>(p, dO, rows, C, m, n, part, stream);
@@ -435,7 +466,7 @@ int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n
 
 int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, const float* scale,
                                   void* pruned, hipStream_t stream) {
-    const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO) && is_aligned16(pruned));
+    const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO) && is_aligned16(pruned), kPruneMinRows);
     if (dt == kBF16) prune_dtype<kBF16>(p, dO, rows, C, m, n, scale, pruned, stream);
     else prune_dtype<kF32>(p, dO, rows, C, m, n, scale, pruned, stream);
     return launch_status();
