@@ -8,7 +8,9 @@ PyTorch's own kernels (outside this library's path); ``backward`` hands dL/dO (N
     y = sdgp_conv2d(x, weight, stride=1, padding=1, n=2, m=4, ranker=GREEDY, seed=step)
     y = sdgp_linear(x, weight, n=2, m=4, ranker=GREEDY_ADJUSTED)
 
-``n == m`` gives the dense data gradient from the same kernels.
+``n == m`` gives the dense data gradient from the same kernels.  ``per_channel=True`` selects the second reading of
+Rescaled Magnitude (Sec. III-B figure captions): Magnitude pruning with one rescaling factor per output channel taken
+over the whole gradient tensor; ``ranker`` and ``seed`` are then not used.
 """
 from __future__ import annotations
 
@@ -20,53 +22,59 @@ from . import binding
 
 class _Conv2dFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, stride, padding, n, m, ranker, seed):
+    def forward(ctx, x, weight, stride, padding, n, m, ranker, seed, per_channel):
         ctx.save_for_backward(x, weight)
-        ctx.cfg = (int(stride), int(padding), int(n), int(m), int(ranker), int(seed))
+        ctx.cfg = (int(stride), int(padding), int(n), int(m), int(ranker), int(seed), bool(per_channel))
         return F.conv2d(x, weight, None, stride, padding)
 
     @staticmethod
     def backward(ctx, gy):
         x, weight = ctx.saved_tensors
-        stride, padding, n, m, ranker, seed = ctx.cfg
+        stride, padding, n, m, ranker, seed, per_channel = ctx.cfg
         gx = gw = None
         if ctx.needs_input_grad[1]:
             gw = torch.nn.grad.conv2d_weight(x, weight.shape, gy, stride, padding)  # dense dL/dO
         if ctx.needs_input_grad[0]:
             dO = gy.permute(0, 2, 3, 1).contiguous()          # [B, P, Q, C_out]; a view when gy is channels_last
             Wk = weight.permute(0, 2, 3, 1).contiguous()      # [C_out, R, S, C_in]
-            dD = binding.sdgp_conv_bwd_data(dO, Wk, x.shape[2], x.shape[3], stride, padding, n, m, ranker, seed)
+            if per_channel:
+                dD = binding.sdgp_conv_bwd_data_channel_rescaled(dO, Wk, x.shape[2], x.shape[3], stride, padding, n, m)
+            else:
+                dD = binding.sdgp_conv_bwd_data(dO, Wk, x.shape[2], x.shape[3], stride, padding, n, m, ranker, seed)
             gx = dD.permute(0, 3, 1, 2)                       # NCHW view of NHWC memory (channels_last)
-        return gx, gw, None, None, None, None, None, None
+        return gx, gw, None, None, None, None, None, None, None
 
 
 class _LinearFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, n, m, ranker, seed):
+    def forward(ctx, x, weight, n, m, ranker, seed, per_channel):
         ctx.save_for_backward(x, weight)
-        ctx.cfg = (int(n), int(m), int(ranker), int(seed))
+        ctx.cfg = (int(n), int(m), int(ranker), int(seed), bool(per_channel))
         return F.linear(x, weight)
 
     @staticmethod
     def backward(ctx, gy):
         x, weight = ctx.saved_tensors
-        n, m, ranker, seed = ctx.cfg
+        n, m, ranker, seed, per_channel = ctx.cfg
         gx = gw = None
         g2 = gy.reshape(-1, gy.shape[-1])
         if ctx.needs_input_grad[1]:
             gw = g2.t() @ x.reshape(-1, x.shape[-1])          # dense dL/dO
         if ctx.needs_input_grad[0]:
-            gx = binding.sdgp_linear_bwd_data(g2.contiguous(), weight.contiguous(), n, m, ranker, seed).reshape(x.shape)
-        return gx, gw, None, None, None, None
+            if per_channel:
+                gx = binding.sdgp_linear_bwd_data_channel_rescaled(g2.contiguous(), weight.contiguous(), n, m).reshape(x.shape)
+            else:
+                gx = binding.sdgp_linear_bwd_data(g2.contiguous(), weight.contiguous(), n, m, ranker, seed).reshape(x.shape)
+        return gx, gw, None, None, None, None, None
 
 
 def sdgp_conv2d(x: torch.Tensor, weight: torch.Tensor, stride: int = 1, padding: int = 0, n: int = 2, m: int = 4,
-                ranker: int = binding.GREEDY, seed: int = 0) -> torch.Tensor:
+                ranker: int = binding.GREEDY, seed: int = 0, per_channel: bool = False) -> torch.Tensor:
     """conv2d (no bias, dilation 1, one group; x [B,C,H,W], weight [K,C,R,S]) whose input gradient is SDGP-pruned."""
-    return _Conv2dFn.apply(x, weight, stride, padding, n, m, ranker, seed)
+    return _Conv2dFn.apply(x, weight, stride, padding, n, m, ranker, seed, per_channel)
 
 
 def sdgp_linear(x: torch.Tensor, weight: torch.Tensor, n: int = 2, m: int = 4, ranker: int = binding.GREEDY,
-                seed: int = 0) -> torch.Tensor:
+                seed: int = 0, per_channel: bool = False) -> torch.Tensor:
     """x @ weight.T (x [..., in], weight [out, in]) whose input gradient is SDGP-pruned along the `out` axis."""
-    return _LinearFn.apply(x, weight, n, m, ranker, seed)
+    return _LinearFn.apply(x, weight, n, m, ranker, seed, per_channel)

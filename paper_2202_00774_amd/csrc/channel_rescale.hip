@@ -235,9 +235,9 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
 }
 
 // Adds the nb partial rows and divides.  A workgroup owns kFinC channels; kFinL threads per channel each add every
-// kFinL-th partial row in ascending order, then the kFinL sums are added in ascending order: a fixed order for a
-// given nb, with enough independent loads in flight that the pass is not a chain of memory latencies.
-constexpr int kFinC = 4, kFinL = kBlock / kFinC;
+// kFinL-th partial row in ascending order, then a halving tree in LDS adds the kFinL sums: a fixed order for a given
+// nb, with enough independent loads in flight that the pass is not a chain of memory latencies.
+constexpr int kFinC = 2, kFinL = kBlock / kFinC;
 
 __global__ void __launch_bounds__(kBlock)
 channel_finish(const double* __restrict__ partial, int nb, int64_t C, float* __restrict__ scale, double* __restrict__ sums) {
@@ -255,11 +255,16 @@ channel_finish(const double* __restrict__ partial, int nb, int64_t C, float* __r
     red[0][l][cx] = tot;
     red[1][l][cx] = kep;
     __syncthreads();
-    if (l != 0 || c >= C) return;
-    for (int i = 1; i < kFinL; ++i) {
-        tot += red[0][i][cx];
-        kep += red[1][i][cx];
+    for (int half = kFinL / 2; half >= 1; half >>= 1) {
+        if (l < half) {
+            red[0][l][cx] += red[0][l + half][cx];
+            red[1][l][cx] += red[1][l + half][cx];
+        }
+        __syncthreads();
     }
+    if (l != 0 || c >= C) return;
+    tot = red[0][0][cx];
+    kep = red[1][0][cx];
     scale[c] = (kep == 0.0) ? 1.0f : (float)(tot / kep);
     if (sums) {
         sums[c] = tot;

@@ -59,3 +59,29 @@ def test_linear_gradients():
     assert rel_error(wl.to_f64(bits(x.grad.reshape(-1, 24))), ref, ab) <= 1e-2
     gw_ref = gy.reshape(-1, 64).float().t() @ x.detach().reshape(-1, 24).float()
     assert torch.allclose(w.grad.float(), gw_ref, rtol=2e-2, atol=2e-2 * gw_ref.abs().max().item())
+
+
+def test_per_channel_rescale_through_autograd():
+    torch.manual_seed(5)
+    B, C, K, H = 6, 16, 32, 13
+    x = torch.randn(B, C, H, H, device="cuda", dtype=torch.bfloat16).contiguous(memory_format=torch.channels_last).requires_grad_()
+    w = (torch.randn(K, C, 3, 3, device="cuda", dtype=torch.bfloat16) * 0.2).requires_grad_()
+    y = sa.sdgp_conv2d(x, w, 1, 1, 2, 4, per_channel=True)
+    gy = (torch.randn_like(y) * 1e-2).contiguous(memory_format=torch.channels_last)
+    y.backward(gy)
+    dO = bits(gy.permute(0, 2, 3, 1))
+    pruned = oracle.prune_channel_rescaled(dO.reshape(-1, K), 2, 4)[0].reshape(dO.shape)
+    ref, ab = oracle.conv_bwd_data(pruned, bits(w.permute(0, 2, 3, 1)), H, H, 1, 1)
+    assert rel_error(wl.to_f64(bits(x.grad.permute(0, 2, 3, 1))), ref, ab) <= 1e-2
+    wr = w.detach().clone().requires_grad_()
+    torch.nn.functional.conv2d(x.detach(), wr, None, 1, 1).backward(gy)
+    assert torch.allclose(w.grad.float(), wr.grad.float(), rtol=2e-2, atol=2e-2 * wr.grad.float().abs().max().item())
+
+    xl = torch.randn(7, 30, 24, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    wl_ = (torch.randn(64, 24, device="cuda", dtype=torch.bfloat16) * 0.2).requires_grad_()
+    yl = sa.sdgp_linear(xl, wl_, 2, 4, per_channel=True)
+    gl = torch.randn_like(yl) * 1e-2
+    yl.backward(gl)
+    pruned = oracle.prune_channel_rescaled(bits(gl.reshape(-1, 64)), 2, 4)[0]
+    ref, ab = oracle.linear_bwd_data(pruned, bits(wl_))
+    assert rel_error(wl.to_f64(bits(xl.grad.reshape(-1, 24))), ref, ab) <= 1e-2
