@@ -7,7 +7,7 @@
 //   channel_sums      one streaming read of dO: ranks every group, accumulates both column sums in fp64.  A thread
 //                     owns one 16-byte column slot (at least one group) and walks down the rows, so its 2 x slot
 //                     accumulators live in registers; the threads of a workgroup that share a slot are added up
-//                     in LDS in a fixed order, and every workgroup writes one row of partial sums
+//                     in LDS in a fixed order, and every workgroup writes one partial sum per channel and kind
 //   channel_finish    adds the partial rows in a fixed order (deterministic: no atomics) and divides
 //   prune_scaled      Alg. 1 with kept values multiplied by their channel's factor (fp32 product, rounded to the
 //                     storage type): same thread-to-column mapping, the factors stay in registers
@@ -209,7 +209,8 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
     }
 
     // Add the tr threads that share a slot, in ascending row-lane order, one accumulator at a time.
-    double* prow = partial + (int64_t)blockIdx.y * 2 * C;
+    // partial sums are stored [which][channel][workgroup row] so that the finishing pass reads a channel's run
+    const int64_t nbl = gridDim.y;
     auto reduce_one = [&](int j) {
 #pragma unroll
         for (int which = 0; which < 2; ++which) {
@@ -223,7 +224,7 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
                     for (int y = 1; y < tr; ++y) v += red[y * tg + sx];
                 }
             }
-            if (ry == 0 && active) prow[(int64_t)which * C + s * slot + j] = v;
+            if (ry == 0 && active) partial[((int64_t)which * C + s * slot + j) * nbl + blockIdx.y] = v;
         }
     };
     if constexpr (M > 0) {
@@ -248,8 +249,8 @@ channel_finish(const double* __restrict__ partial, int nb, int64_t C, float* __r
     if (c < C) {
 #pragma unroll 8
         for (int b = l; b < nb; b += kFinL) {
-            tot += partial[((int64_t)b * 2) * C + c];
-            kep += partial[((int64_t)b * 2 + 1) * C + c];
+            tot += partial[c * nb + b];
+            kep += partial[(C + c) * nb + b];
         }
     }
     red[0][l][cx] = tot;
