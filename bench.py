@@ -315,6 +315,40 @@ def main():
         result["rescaled_per_channel"] = per_channel
         del srcs, dsts, ws
 
+        # ---- where backward-data sits in a training step (Sec. IV-C, Fig. 9: forward, weight gradient and data gradient
+        # take about a third each on the paper's hardware): forward and weight gradient by PyTorch's library kernels
+        # (outside this library's path; context only), data gradient by this library, same layers, same layout
+        try:
+            split = []
+            for L, dO, W, out in data:
+                x = torch.randn(L.B, L.H, L.Wd, L.C_in, device=dev, dtype=torch.bfloat16).permute(0, 3, 1, 2)  # NHWC memory
+                wt = W.permute(0, 3, 1, 2)                      # [K, C, R, S] view of the KRSC filter
+                gy = dO.permute(0, 3, 1, 2)
+                t_f = time_call(lambda: torch.nn.functional.conv2d(x, wt, None, L.stride, L.pad), reps=5, warm=2)
+                t_w = time_call(lambda: torch.nn.grad.conv2d_weight(x, wt.shape, gy, L.stride, L.pad), reps=5, warm=2)
+                t_l = time_call(lambda: torch.nn.grad.conv2d_input(x.shape, wt, gy, L.stride, L.pad), reps=5, warm=2)
+                t_d = time_call(lambda: call(L, dO, W, out, 4, 4, sdgp.GREEDY), reps=5)
+                t_s = time_call(lambda: call(L, dO, W, out, 2, 4, sdgp.GREEDY), reps=5)
+                split.append({"layer": L.name, "forward_us": round(t_f * 1e3, 1), "weight_grad_us": round(t_w * 1e3, 1),
+                              "data_grad_library_us": round(t_l * 1e3, 1), "data_grad_dense_us": round(t_d * 1e3, 1),
+                              "data_grad_2:4_us": round(t_s * 1e3, 1)})
+                del x
+            tf, tw = sum(r["forward_us"] for r in split), sum(r["weight_grad_us"] for r in split)
+            td, ts = sum(r["data_grad_dense_us"] for r in split), sum(r["data_grad_2:4_us"] for r in split)
+            tl = sum(r["data_grad_library_us"] for r in split)
+            result["training_step_split"] = {
+                "layers": split, "data_grad_share_library": round(tl / (tf + tw + tl), 3),
+                "data_grad_share_dense": round(td / (tf + tw + td), 3),
+                "step_time_ratio_2:4_vs_dense": round((tf + tw + ts) / (tf + tw + td), 3),
+                "step_time_ratio_2:4_vs_library": round((tf + tw + ts) / (tf + tw + tl), 3),
+                "note": "forward, weight gradient and data_grad_library: torch (library kernels, bf16 channels-last), not part "
+                        "of this library; data_grad_dense and data_grad_2:4: this library (n == m, and fused 2:4 greedy); the "
+                        "ratios are what the three convolution passes of these six layers would take with the fused 2:4 data "
+                        "gradient instead of this library's dense one / instead of the library's",
+            }
+        except Exception as e:  # the library convolution is context, not the product: report and go on
+            result["training_step_split"] = {"error": repr(e)[:200]}
+
         # ---- the CPU oracle on a bounded sample of the same workload
         if args.cpu_batch > 0:
             import oracle
