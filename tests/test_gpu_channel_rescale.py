@@ -23,8 +23,9 @@ pytestmark = pytest.mark.gpu
 
 DTYPES = [oracle.BF16, oracle.F32]
 NM = [(2, 4), (1, 4), (2, 8), (4, 8), (2, 16), (4, 16), (2, 32), (16, 32), (3, 5), (2, 6), (4, 4)]
-# rows x C: one workgroup, several, more slots than a workgroup is wide, a slot count that is no power of two
-SHAPES = [(37, 1), (1000, 3), (4099, 16), (300, 47)]
+# rows x groups: one group per row, several workgroups down the rows, a slot count that is no power of two, and more
+# slots than a workgroup is wide (two workgroups side by side, the second one partly idle)
+SHAPES = [(37, 1), (1000, 3), (4099, 16), (300, 47), (70, 600)]
 
 
 def ulp_distance_f32(a, b):
