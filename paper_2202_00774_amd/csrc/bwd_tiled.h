@@ -116,20 +116,6 @@ struct TiledLayout {
 
 constexpr int kMaxHaloItems = 8;  // halo items (16 channels of one pixel) a producer lane holds in flight
 
-// Two survivors (value, position) of one aligned quad, positions ascending.
-// out[] holds the pruned values (zero where dropped), so a slot that has no
-// survivor may point at any dropped position.
-__device__ __forceinline__ void compress_quad(const bool (&k)[4], const uint32_t (&o)[4], uint32_t& v0, uint32_t& v1,
-                                              uint32_t& pos) {
-    const uint32_t p0 = k[0] ? 0u : (k[1] ? 1u : (k[2] ? 2u : 0u));
-    v0 = k[0] ? o[0] : (k[1] ? o[1] : (k[2] ? o[2] : o[0]));
-    const bool two_low = k[2] && (k[0] || k[1]);
-    const bool both01 = k[1] && k[0];
-    const uint32_t p1 = k[3] ? 3u : (two_low ? 2u : (both01 ? 1u : 3u));
-    v1 = k[3] ? o[3] : (two_low ? o[2] : (both01 ? o[1] : o[3]));
-    pos = p0 | (p1 << 2);
-}
-
 // One halo item (ITEM channels of one gradient pixel, already in registers) -> LDS:
 // verbatim (MODE 0), pruned with zeros (MODE 1) or pruned and compressed (MODE 2).
 template <int KC, int MODE, int M, int RK, int ITEM>
@@ -142,11 +128,11 @@ __device__ __forceinline__ void halo_item_to_lds(const u32x4_t (&v)[ITEM / 8], i
     if constexpr (MODE == 0) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) *(SDGP_LDS u32x4_t*)(lds_a + hp * APITCH + part * (ITEM * 2) + i * 16) = v[i];
-    } else if constexpr (SPARSE && RK != kRandom) {
-        static_assert(ITEM == 16, "the compressing ranker takes sixteen channels");
+    } else if constexpr (SPARSE) {
+        static_assert(ITEM == 16, "the compressing rankers take sixteen channels");
         const uint32_t w[8] = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
         uint32_t packed[4], meta;
-        prune_compress16_bf16<M, RK>(w, n, packed, meta);
+        prune_compress16<M, RK>(w, n, mix, e0, packed, meta);
         const u32x4_t x = {packed[0], packed[1], packed[2], packed[3]};
         *(SDGP_LDS u32x4_t*)(lds_a + hp * APITCH + part * 16) = x;
         *(SDGP_LDS uint16_t*)(lds_meta + hp * (KC / 8) + part * 2) = (uint16_t)meta;
@@ -167,34 +153,20 @@ __device__ __forceinline__ void halo_item_to_lds(const u32x4_t (&v)[ITEM / 8], i
 #pragma unroll
             for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
             const uint64_t eg = e0 + (uint64_t)(g * M);  // a group never straddles a 2^32 boundary
-            prune_group<kBF16, M, RK, SPARSE>(r, n, hash_row(mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+            prune_group<kBF16, M, RK, false>(r, n, hash_row(mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
 #pragma unroll
             for (int j = 0; j < M; ++j) {
                 out[g * M + j] = o[j];
                 keep[g * M + j] = kk[j];
             }
         }
-        if constexpr (MODE == 1) {
+        // MODE 1: the pruned channels stay in place, zeros where dropped
 #pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                u32x4_t x;
+        for (int i = 0; i < NV; ++i) {
+            u32x4_t x;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) x[w] = out[i * 8 + 2 * w] | (out[i * 8 + 2 * w + 1] << 16);
-                *(SDGP_LDS u32x4_t*)(lds_a + hp * APITCH + part * (ITEM * 2) + i * 16) = x;
-            }
-        } else {
-            uint32_t cv[8], meta = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const bool kq[4] = {keep[4 * q], keep[4 * q + 1], keep[4 * q + 2], keep[4 * q + 3]};
-                const uint32_t oq[4] = {out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]};
-                uint32_t pos;
-                compress_quad(kq, oq, cv[2 * q], cv[2 * q + 1], pos);
-                meta |= pos << (4 * q);
-            }
-            const u32x4_t x = {cv[0] | (cv[1] << 16), cv[2] | (cv[3] << 16), cv[4] | (cv[5] << 16), cv[6] | (cv[7] << 16)};
-            *(SDGP_LDS u32x4_t*)(lds_a + hp * APITCH + part * 16) = x;
-            *(SDGP_LDS uint16_t*)(lds_meta + hp * (KC / 8) + part * 2) = (uint16_t)meta;
+            for (int w = 0; w < 4; ++w) x[w] = out[i * 8 + 2 * w] | (out[i * 8 + 2 * w + 1] << 16);
+            *(SDGP_LDS u32x4_t*)(lds_a + hp * APITCH + part * (ITEM * 2) + i * 16) = x;
         }
     }
 }

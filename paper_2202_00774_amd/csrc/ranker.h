@@ -384,4 +384,83 @@ __host__ __device__ __forceinline__ void prune_compress16_random(const uint32_t 
     }
 }
 
+// Two survivors (value, position) of one aligned quad, positions ascending.
+// out[] holds the pruned values (zero where dropped), so a slot that has no
+// survivor may point at any dropped position.
+__device__ __forceinline__ void compress_quad(const bool (&k)[4], const uint32_t (&o)[4], uint32_t& v0, uint32_t& v1,
+                                              uint32_t& pos) {
+    const uint32_t p0 = k[0] ? 0u : (k[1] ? 1u : (k[2] ? 2u : 0u));
+    v0 = k[0] ? o[0] : (k[1] ? o[1] : (k[2] ? o[2] : o[0]));
+    const bool two_low = k[2] && (k[0] || k[1]);
+    const bool both01 = k[1] && k[0];
+    const uint32_t p1 = k[3] ? 3u : (two_low ? 2u : (both01 ? 1u : 3u));
+    v1 = k[3] ? o[3] : (two_low ? o[2] : (both01 ? o[1] : o[3]));
+    pos = p0 | (p1 << 2);
+}
+
+// The compressed operand of sixteen channels as a value (four dwords of kept pairs and sixteen bits of positions).
+struct Packed16 {
+    uint32_t p0, p1, p2, p3, meta;
+};
+typedef uint32_t ranker_u32x4 __attribute__((ext_vector_type(4)));
+
+// Random ranker, generic path: exact for any hashes.  Reached only when the key-based path cannot be sure (two hashes
+// of a group agreeing in 28 bits at the threshold: about four groups in a billion), so it is kept out of line --
+// inlined, its registers spilled the callers' main loops (hundreds of bytes of scratch per lane at m = 8 and 16).
+template <int M>
+__device__ __attribute__((noinline)) Packed16 prune16_random_generic(ranker_u32x4 v0, ranker_u32x4 v1, int n, uint32_t mix,
+                                                                     uint64_t e0) {
+    const ranker_u32x4 v[2] = {v0, v1};
+    uint32_t raw[16], out[16];
+    bool keep[16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
+            raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
+        }
+#pragma unroll
+    for (int g = 0; g < 16 / M; ++g) {
+        uint32_t r[M], o[M];
+        bool kk[M];
+#pragma unroll
+        for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
+        const uint64_t eg = e0 + (uint64_t)(g * M);  // a group never straddles a 2^32 boundary
+        prune_group<kBF16, M, kRandom, true>(r, n, hash_row(mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+#pragma unroll
+        for (int j = 0; j < M; ++j) out[g * M + j] = o[j], keep[g * M + j] = kk[j];
+    }
+    uint32_t packed[4], meta = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const bool kq[4] = {keep[4 * q], keep[4 * q + 1], keep[4 * q + 2], keep[4 * q + 3]};
+        const uint32_t oq[4] = {out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]};
+        uint32_t x0, x1, pos;
+        compress_quad(kq, oq, x0, x1, pos);
+        packed[q] = x0 | (x1 << 16);
+        meta |= pos << (4 * q);
+    }
+    return {packed[0], packed[1], packed[2], packed[3], meta};
+}
+
+// Sixteen consecutive bf16 channels (eight dwords), n <= 2 of m in {4, 8, 16}, any ranker -> the operand format of the
+// structured-sparse matrix instructions.  e0 = flat index of the first channel (Random only).
+template <int M, int RK>
+__device__ __forceinline__ void prune_compress16(const uint32_t (&w)[8], int n, uint32_t mix, uint64_t e0, uint32_t (&packed)[4],
+                                                 uint32_t& meta) {
+    if constexpr (RK != kRandom) {
+        prune_compress16_bf16<M, RK>(w, n, packed, meta);
+    } else {
+        // fast path; it says when it cannot be sure
+        bool exact;
+        prune_compress16_random<M>(w, n, mix, e0, packed, meta, exact);
+        if (!exact) {
+            const ranker_u32x4 v0 = {w[0], w[1], w[2], w[3]}, v1 = {w[4], w[5], w[6], w[7]};
+            const Packed16 r = prune16_random_generic<M>(v0, v1, n, mix, e0);
+            packed[0] = r.p0, packed[1] = r.p1, packed[2] = r.p2, packed[3] = r.p3, meta = r.meta;
+        }
+    }
+}
+
 }  // namespace sdgp
