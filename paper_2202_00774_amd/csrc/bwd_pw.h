@@ -72,7 +72,7 @@ struct PwLayout {
 __device__ __align__(64) const uint32_t kPwZeros[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
 template <int BN, int MODE, int M, int RK, int ROWS, int NW, bool GATHER>
-__global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
+__device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     using L = PwLayout<BN, MODE, ROWS>;
     static_assert(L::total() <= 160 * 1024, "LDS budget");
     constexpr bool SPARSE = MODE == 2;
@@ -462,6 +462,27 @@ __global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
             }
         }
     }
+}
+
+// One problem per launch.
+template <int BN, int MODE, int M, int RK, int ROWS, int NW, bool GATHER>
+__global__ void __launch_bounds__(NW * 64) bwd_pw(const PwParams p) {
+    bwd_pw_body<BN, MODE, M, RK, ROWS, NW, GATHER>(p);
+}
+
+// The parity classes of one strided filter in one launch: blockIdx.y is the class, blockIdx.x the tile of that class
+// (the grid is as wide as the largest class).  The classes are small GEMMs, often less than one round of workgroups
+// each; side by side, one class's last workgroups run beside the next one's first.
+constexpr int kPwMaxClasses = 16;
+struct PwClasses {
+    PwParams c[kPwMaxClasses];
+};
+
+template <int BN, int MODE, int M, int RK, int ROWS, int NW>
+__global__ void __launch_bounds__(NW * 64) bwd_pw_classes(const PwClasses all) {
+    const PwParams& p = all.c[blockIdx.y];
+    if ((int)blockIdx.x >= p.nblocks) return;
+    bwd_pw_body<BN, MODE, M, RK, ROWS, NW, true>(p);
 }
 
 }  // namespace sdgp

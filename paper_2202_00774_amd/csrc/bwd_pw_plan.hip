@@ -15,6 +15,14 @@ int launch_pw_masked_m4(const PwParams& p, int shape, int rk, hipStream_t stream
 int launch_pw_masked_m8(const PwParams& p, int shape, int rk, hipStream_t stream);
 int launch_pw_masked_m16(const PwParams& p, int shape, int rk, hipStream_t stream);
 int launch_pw_masked_m32(const PwParams& p, int shape, int rk, hipStream_t stream);
+int launch_pw_classes_dense(const PwClasses& all, int ncls, int shape, hipStream_t stream);
+int launch_pw_classes_sparse_m4(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
+int launch_pw_classes_sparse_m8(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
+int launch_pw_classes_sparse_m16(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
+int launch_pw_classes_masked_m4(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
+int launch_pw_classes_masked_m8(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
+int launch_pw_classes_masked_m16(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
+int launch_pw_classes_masked_m32(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
 
 namespace {
 
@@ -38,6 +46,19 @@ int launch_pw_any(const PwParams& p, int mode, int m, int shape, int rk, hipStre
     if (m == 8) return launch_pw_masked_m8(p, shape, rk, stream);
     if (m == 16) return launch_pw_masked_m16(p, shape, rk, stream);
     return launch_pw_masked_m32(p, shape, rk, stream);
+}
+
+int launch_pw_classes_any(const PwClasses& all, int ncls, int mode, int m, int shape, int rk, hipStream_t stream) {
+    if (mode == 0) return launch_pw_classes_dense(all, ncls, shape, stream);
+    if (mode == 2) {
+        if (m == 4) return launch_pw_classes_sparse_m4(all, ncls, shape, rk, stream);
+        if (m == 8) return launch_pw_classes_sparse_m8(all, ncls, shape, rk, stream);
+        return launch_pw_classes_sparse_m16(all, ncls, shape, rk, stream);
+    }
+    if (m == 4) return launch_pw_classes_masked_m4(all, ncls, shape, rk, stream);
+    if (m == 8) return launch_pw_classes_masked_m8(all, ncls, shape, rk, stream);
+    if (m == 16) return launch_pw_classes_masked_m16(all, ncls, shape, rk, stream);
+    return launch_pw_classes_masked_m32(all, ncls, shape, rk, stream);
 }
 
 }  // namespace
@@ -91,9 +112,9 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
 
 // Strided filters wider than 1x1 (the stride-2 3x3 layers of a ResNet): the input pixels split into stride x stride
 // parity classes; class (a, b) -- pixels (i*stride + a, j*stride + b) -- is a small stride-1 correlation over the
-// gradient with the taps r = a + pad (mod stride), s = b + pad (mod stride), at most four of them here.  One launch of
-// the pointwise kernel per class: a GEMM whose reduction runs over (tap, channel) and whose rows are gathered from the
-// gradient pixels (i + dp, j + dq) of each tap, zeros outside.  Each gradient element is ranked once per tap that
+// gradient with the taps r = a + pad (mod stride), s = b + pad (mod stride), at most four of them here.  Each class is
+// a GEMM of the pointwise kernel whose reduction runs over (tap, channel) and whose rows are gathered from the gradient
+// pixels (i + dp, j + dq) of each tap, zeros outside; all classes go out in one launch (blockIdx.y = class).  Each gradient element is ranked once per tap that
 // reads it (the kept set does not depend on who asks).
 // SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
 int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
@@ -128,7 +149,9 @@ int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
     base.ntiles_n = (int)((C_in + bn - 1) / bn);
 
     // all classes first: nothing is launched unless every one of them fits
-    PwParams cls[16];
+    static_assert(kPwMaxClasses >= 16, "stride up to four");
+    PwClasses all{};
+    PwParams* cls = all.c;
     int ncls = 0;
     for (int a = 0; a < stride; ++a)
         for (int b = 0; b < stride; ++b) {
@@ -153,11 +176,14 @@ int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
             q.nblocks = (int)blocks;
             cls[ncls++] = q;
         }
-    for (int i = 0; i < ncls; ++i) {
-        const int rc = launch_pw_any(cls[i], mode, m, shape, rk, stream);
-        if (rc != SDGP_OK) return rc;
-    }
-    return SDGP_OK;
+    // classes with more taps first: their workgroups run longest, and the launch should end on the short ones
+    for (int i = 1; i < ncls; ++i)
+        for (int j = i; j > 0 && cls[j].ntaps > cls[j - 1].ntaps; --j) {
+            const PwParams t = cls[j];
+            cls[j] = cls[j - 1];
+            cls[j - 1] = t;
+        }
+    return launch_pw_classes_any(all, ncls, mode, m, shape, rk, stream);
 }
 
 }  // namespace sdgp

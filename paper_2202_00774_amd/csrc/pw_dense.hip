@@ -4,4 +4,7 @@ namespace sdgp {
 int launch_pw_dense(const PwParams& p, int shape, hipStream_t stream) {
     return launch_pw_shape<0, 4, kGreedy>(p, shape, stream);
 }
+int launch_pw_classes_dense(const PwClasses& all, int ncls, int shape, hipStream_t stream) {
+    return launch_pw_classes_shape<0, 4, kGreedy>(all, ncls, shape, stream);
+}
 }  // namespace sdgp

@@ -5,4 +5,7 @@ namespace sdgp {
 int launch_pw_masked_m16(const PwParams& p, int shape, int rk, hipStream_t stream) {
     return launch_pw_rk<1, 16>(p, shape, rk, stream);
 }
+int launch_pw_classes_masked_m16(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream) {
+    return launch_pw_classes_rk<1, 16>(all, ncls, shape, rk, stream);
+}
 }  // namespace sdgp
