@@ -114,8 +114,8 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
 // parity classes; class (a, b) -- pixels (i*stride + a, j*stride + b) -- is a small stride-1 correlation over the
 // gradient with the taps r = a + pad (mod stride), s = b + pad (mod stride), at most four of them here.  Each class is
 // a GEMM of the pointwise kernel whose reduction runs over (tap, channel) and whose rows are gathered from the gradient
-// pixels (i + dp, j + dq) of each tap, zeros outside; all classes go out in one launch (blockIdx.y = class).  Each gradient element is ranked once per tap that
-// reads it (the kept set does not depend on who asks).
+// pixels (i + dp, j + dq) of each tap, zeros outside; all classes go out in one launch (blockIdx.y = class).  Each
+// gradient element is ranked once per tap that reads it (the kept set does not depend on who asks).
 // SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
 int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                       int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
