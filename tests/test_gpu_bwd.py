@@ -250,6 +250,7 @@ STRIDED_CONVS = [
     wl.ConvLayer("g_s2_4x4", 64, 32, 32, 64, 64, 4, 4, 2, 1),          # four taps in every class
     wl.ConvLayer("g_s2_3x3_valid", 64, 31, 31, 40, 32, 3, 3, 2, 0),    # no padding
     wl.ConvLayer("g_s3_3x3", 192, 30, 30, 32, 32, 3, 3, 3, 1),         # stride 3: nine classes of one tap
+    wl.ConvLayer("g_s4_5x5", 512, 33, 31, 32, 32, 5, 5, 4, 2),         # stride 4: sixteen classes of 1, 2 or 4 taps, unequal sizes
 ]
 
 
