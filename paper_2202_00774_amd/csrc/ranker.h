@@ -444,6 +444,13 @@ __device__ __attribute__((noinline)) Packed16 prune16_random_generic(ranker_u32x
     return {packed[0], packed[1], packed[2], packed[3], meta};
 }
 
+// Hash bits a key of the fast random path keeps.  A build with a shorter prefix (say 0xFF000000u) sends a few percent
+// of the groups through the exact fallback; that is how the fallback, which the full prefix reaches about four times in
+// a billion groups, is exercised on the GPU against the oracle.
+#ifndef SDGP_RANDOM_KEY_PREFIX
+#define SDGP_RANDOM_KEY_PREFIX 0xFFFFFFF0u
+#endif
+
 // Sixteen consecutive bf16 channels (eight dwords), n <= 2 of m in {4, 8, 16}, any ranker -> the operand format of the
 // structured-sparse matrix instructions.  e0 = flat index of the first channel (Random only).
 template <int M, int RK>
@@ -454,7 +461,7 @@ __device__ __forceinline__ void prune_compress16(const uint32_t (&w)[8], int n, 
     } else {
         // fast path; it says when it cannot be sure
         bool exact;
-        prune_compress16_random<M>(w, n, mix, e0, packed, meta, exact);
+        prune_compress16_random<M, SDGP_RANDOM_KEY_PREFIX>(w, n, mix, e0, packed, meta, exact);
         if (!exact) {
             const ranker_u32x4 v0 = {w[0], w[1], w[2], w[3]}, v1 = {w[4], w[5], w[6], w[7]};
             const Packed16 r = prune16_random_generic<M>(v0, v1, n, mix, e0);
