@@ -155,6 +155,56 @@ constexpr int kMmRowB = 128;    // bytes per gradient pixel in LDS: 64 channels
 constexpr int kMmMaxNt = 5;     // column tiles: up to 160 (tap, c) columns, a 7x7 filter on three channels
 constexpr int kMmMaxPairs = 8;  // (32-pixel row tile, 32-column tile) pairs per wavefront: at most 32 per workgroup
 
+// One input pixel's sum over the taps that reach it, from the table T of per-pixel, per-(tap, c) products in LDS.
+// Tap r reaches row h when h + pad - r is a multiple of the stride: r = r0 + i * stride with the gradient row falling
+// by one per step, at most NR steps (NS along the width).  Every read is issued before the first addition; a tap
+// outside the filter or the gradient reads T[0..3] and adds nothing.  Same order of additions as the plain loops.
+template <int NR, int NS>
+__device__ __forceinline__ void narrow_gather(const NarrowParams& p, const SDGP_LDSN float* lds_t, int TP, int pmin, int qmin,
+                                              int h, int w, float (&sum)[4]) {
+    // (h + pad) = pp0 * stride + r0; strides one and two without the integer division
+    const int hp = h + p.pad, wp = w + p.pad;
+    int r0, s0, pp0, qq0;
+    if (p.stride == 1) {
+        r0 = 0, s0 = 0, pp0 = hp, qq0 = wp;
+    } else if (p.stride == 2) {
+        r0 = hp & 1, s0 = wp & 1, pp0 = hp >> 1, qq0 = wp >> 1;
+    } else {
+        r0 = hp % p.stride, s0 = wp % p.stride, pp0 = hp / p.stride, qq0 = wp / p.stride;
+    }
+    int rowoff[NR], coloff[NS];
+    bool rv[NR], cv[NS];
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        const int r = r0 + i * p.stride, pp = pp0 - i;
+        rv[i] = r < p.R && pp >= 0 && pp < p.P;
+        rowoff[i] = (pp - pmin) * p.HQ * TP + r * p.S * p.C_in;
+    }
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+        const int sx = s0 + j * p.stride, qq = qq0 - j;
+        cv[j] = sx < p.S && qq >= 0 && qq < p.Q;
+        coloff[j] = (qq - qmin) * TP + sx * p.C_in;
+    }
+    float v[NR][NS][4];
+#pragma unroll
+    for (int i = 0; i < NR; ++i)
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int off = (rv[i] && cv[j]) ? rowoff[i] + coloff[j] : 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[i][j][c] = (c < p.C_in) ? lds_t[off + c] : 0.0f;
+        }
+#pragma unroll
+    for (int i = 0; i < NR; ++i)
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const bool ok = rv[i] && cv[j];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) sum[c] += ok ? v[i][j][c] : 0.0f;
+        }
+}
+
 // Matrix-core variant; p.nt = 32-column tiles of (tap, c) pairs; kMmPairs = pairs per wavefront (accumulator registers).
 template <int M, int RK, bool PRUNE, bool NLE2, int kMmPairs>
 __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
@@ -338,15 +388,24 @@ __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
     const int h = h0 + th, w = w0 + tw;
     if (tid < p.TH * p.TW && h < p.H && w < p.Wd) {
         float sum[4] = {0.f, 0.f, 0.f, 0.f};
-        const int r0 = (h + p.pad) % p.stride, s0 = (w + p.pad) % p.stride;
-        const int pp0 = (h + p.pad - r0) / p.stride, qq0 = (w + p.pad - s0) / p.stride;
-        for (int r = r0, pp = pp0; r < p.R && pp >= 0; r += p.stride, --pp) {
-            if (pp >= p.P) continue;
-            const SDGP_LDSN float* trow = lds_t + ((pp - pmin) * p.HQ + (qq0 - qmin)) * TP + (r * p.S + s0) * p.C_in;
-            for (int s = s0, qq = qq0; s < p.S && qq >= 0; s += p.stride, --qq) {
-                if (qq < p.Q)
-                    for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
-                trow += p.stride * p.C_in - TP;  // next tap of this phase, previous gradient pixel
+        const int nr = (p.R + p.stride - 1) / p.stride, ns = (p.S + p.stride - 1) / p.stride;  // taps per dimension, at most
+        if (nr <= 2 && ns <= 2) {
+            narrow_gather<2, 2>(p, lds_t, TP, pmin, qmin, h, w, sum);
+        } else if (nr <= 3 && ns <= 3) {
+            narrow_gather<3, 3>(p, lds_t, TP, pmin, qmin, h, w, sum);
+        } else if (nr <= 4 && ns <= 4) {
+            narrow_gather<4, 4>(p, lds_t, TP, pmin, qmin, h, w, sum);
+        } else {
+            const int r0 = (h + p.pad) % p.stride, s0 = (w + p.pad) % p.stride;
+            const int pp0 = (h + p.pad - r0) / p.stride, qq0 = (w + p.pad - s0) / p.stride;
+            for (int r = r0, pp = pp0; r < p.R && pp >= 0; r += p.stride, --pp) {
+                if (pp >= p.P) continue;
+                const SDGP_LDSN float* trow = lds_t + ((pp - pmin) * p.HQ + (qq0 - qmin)) * TP + (r * p.S + s0) * p.C_in;
+                for (int s = s0, qq = qq0; s < p.S && qq >= 0; s += p.stride, --qq) {
+                    if (qq < p.Q)
+                        for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
+                    trow += p.stride * p.C_in - TP;  // next tap of this phase, previous gradient pixel
+                }
             }
         }
         uint16_t* dst = p.dD + ((size_t)(b * p.H + h) * p.Wd + w) * p.C_in;
