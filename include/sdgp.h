@@ -134,8 +134,12 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
                        int m, int rk, uint64_t seed, void* workspace, size_t workspace_bytes,
                        void* hip_stream);
 
-/* Bytes of workspace sdgp_conv_bwd_data needs for these arguments (0 when the
- * call is fully fused); (size_t)-1 when the arguments are invalid. */
+/* Bytes of workspace sdgp_conv_bwd_data needs for these arguments; (size_t)-1 when
+ * the arguments are invalid.  0 for almost every layer (the call is one fused
+ * kernel); a first layer with a wide filter (C_in <= 4 and more than 32
+ * (tap, channel) pairs, e.g. 7x7 on three channels: 23 KB per 64 output channels)
+ * asks for room for a transposed copy of the filter that one small kernel builds
+ * before the fused one. */
 size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                                     int R, int S, int stride, int pad, int dt, int n, int m);
 

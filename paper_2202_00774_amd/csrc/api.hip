@@ -10,7 +10,9 @@ int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
                       hipStream_t stream);
 int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                       int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
-                      hipStream_t stream);
+                      void* workspace, hipStream_t stream);
+size_t bwd_narrow_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride,
+                            int pad, int n, int m);
 int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                   int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream);
 int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
@@ -79,10 +81,13 @@ int check_conv(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, in
 
 
 // Matrix-core kernel when the problem fits it, the shape-agnostic kernel otherwise.
+// workspace: what sdgp_conv_bwd_data_workspace asked for, or null (entry points without one).
 int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
-                 int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
+                 int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed, void* workspace,
+                 hipStream_t stream) {
     if (dt == SDGP_BF16 && C_in <= 4) {
-        const int rc = sdgp::bwd_narrow_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
+        const int rc = sdgp::bwd_narrow_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, workspace,
+                                               stream);
         if (rc <= 0) return rc;
     }
     if (dt == SDGP_BF16 && sdgp::is_aligned16(dD)) {
@@ -151,8 +156,9 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
     if (g.n_dD == 0) return SDGP_OK;
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
     const size_t need = sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return SDGP_ERR_WORKSPACE;
-    return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed,
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0))
+        return SDGP_ERR_WORKSPACE;
+    return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, need > 0 ? workspace : nullptr,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -160,6 +166,8 @@ size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_
                                     int stride, int pad, int dt, int n, int m) {
     ConvGeom g;
     if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g) != SDGP_OK) return (size_t)-1;
+    // the first-layer kernel builds a transposed image of a wide filter (the 7x7 stem) once per call
+    if (dt == SDGP_BF16 && C_in <= 4 && g.n_dD > 0) return sdgp::bwd_narrow_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m);
     return 0;
 }
 
@@ -172,7 +180,7 @@ int sdgp_linear_bwd_data(const void* dO, const void* W, void* dD, int64_t rows, 
     if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
     if (g.n_dD == 0) return SDGP_OK;
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
-    return bwd_dispatch(dO, W, dD, rows, 1, 1, C_in, C_out, 1, 1, 1, 0, dt, n, m, rk, seed,
+    return bwd_dispatch(dO, W, dD, rows, 1, 1, C_in, C_out, 1, 1, 1, 0, dt, n, m, rk, seed, nullptr,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -234,7 +242,7 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (g.n_dO == 0 || g.n_W == 0)  // nothing to rescale: the product of an empty sum, zeros
-        return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, stream);
+        return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, nullptr, stream);
     const int64_t rows = B * g.P * g.Q;
     const ChannelWorkspace w = channel_workspace(rows, C_out, g.n_W, dt, m);
     if (workspace == nullptr || workspace_bytes < w.total || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0)
@@ -246,7 +254,7 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
     if (rc != SDGP_OK) return rc;
     rc = sdgp::scale_rows_launch(W, scale, filter, C_out, (int64_t)R * S * C_in, dt, stream);
     if (rc != SDGP_OK) return rc;
-    return bwd_dispatch(dO, filter, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, stream);
+    return bwd_dispatch(dO, filter, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, nullptr, stream);
 }
 
 const char* sdgp_status_string(int status) {

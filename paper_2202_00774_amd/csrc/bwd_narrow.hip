@@ -27,6 +27,8 @@ struct NarrowParams {
     int TH, TW, tiles_h, tiles_w;
     int HP, HQ;  // gradient pixels per tile (rows, columns), upper bound
     int nt;             // 32-column tiles of (tap, c) pairs (matrix-core variant)
+    const unsigned char* wimg;  // matrix-core variant: the transposed filter slices as they sit in LDS, one image of
+    int wimg_units;             // wimg_units KB per 64 output channels (built once per call in the workspace), or null
     uint32_t hq_magic;  // floor(2^32 / HQ) + 1: x / HQ == umulhi(x, hq_magic) for the pixel counts of a tile
     int n;
     uint32_t mix;
@@ -155,6 +157,25 @@ constexpr int kMmRowB = 128;    // bytes per gradient pixel in LDS: 64 channels
 constexpr int kMmMaxNt = 5;     // column tiles: up to 160 (tap, c) columns, a 7x7 filter on three channels
 constexpr int kMmMaxPairs = 8;  // (32-pixel row tile, 32-column tile) pairs per wavefront: at most 32 per workgroup
 
+// KB of one transposed filter slice in LDS: nt * 32 columns of kAPitchN bytes, rounded up to whole copy units.
+constexpr int narrow_image_units(int nt) { return (nt * 32 * kAPitchN + 1023) / 1024; }
+
+// The filter as bwd_narrow_mm wants it in LDS, built once per call: for every slice of 64 output channels the
+// columns j = tap * C_in + c with their 64 channels contiguous (kAPitchN bytes per column), zeros in the padding, past
+// the last column and past C_out.  One workgroup per slice.
+__global__ void __launch_bounds__(256) narrow_w_image(const uint16_t* __restrict__ W, uint16_t* __restrict__ img, int C_out,
+                                                      int J, int units) {
+    const int kc0 = blockIdx.x * kNarrowKC;
+    uint16_t* dst = img + (size_t)blockIdx.x * units * 512;
+    constexpr int kPitchE = kAPitchN / 2;
+    for (int e = threadIdx.x; e < units * 512; e += 256) {
+        const int j = e / kPitchE, kk = e - j * kPitchE;
+        uint16_t v = 0;
+        if (j < J && kk < kNarrowKC && kc0 + kk < C_out) v = W[(size_t)(kc0 + kk) * J + j];
+        dst[e] = v;
+    }
+}
+
 // One input pixel's sum over the taps that reach it, from the table T of per-pixel, per-(tap, c) products in LDS.
 // Tap r reaches row h when h + pad - r is a multiple of the stride: r = r0 + i * stride with the gradient row falling
 // by one per step, at most NR steps (NS along the width).  Every read is issued before the first addition; a tap
@@ -261,8 +282,13 @@ __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
             if (k >= p.C_out) k = kc0;
             lds_copy16(p.dO + ((size_t)(b * p.P + pp) * p.Q + qq) * p.C_out + k, smem_base + (uint32_t)u * 1024u);
         }
-        // ---- filter slice [kc0, kc0 + 64) x (tap, c), transposed: column j = tap * C_in + c, channels contiguous
-        {
+        // ---- filter slice [kc0, kc0 + 64) x (tap, c), transposed: column j = tap * C_in + c, channels contiguous;
+        // copied as it is when the call built the image, else gathered element by element
+        if (p.wimg) {
+            const unsigned char* src = p.wimg + (size_t)(kc0 / kNarrowKC) * p.wimg_units * 1024;
+            for (int u = wave; u < p.wimg_units; u += 4)
+                lds_copy16(src + (size_t)u * 1024 + lane * 16, smem_base + (uint32_t)(nrt * 32 * kMmRowB) + (uint32_t)u * 1024u);
+        } else {
             constexpr int kPer = kNarrowKC * 32 / 256;  // elements per thread and column tile
             uint16_t wv[kMmMaxNt][kPer];                // every load first, then the LDS writes
 #pragma unroll
@@ -416,7 +442,7 @@ __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
 // LDS bytes of bwd_narrow_mm for a tile of npix gradient pixels, nt column tiles and J live columns.
 int narrow_mm_lds(int npix, int nt, int J) {
     const int rows = ((npix + 31) / 32) * 32;
-    const int loop = rows * kMmRowB + nt * 32 * kAPitchN;
+    const int loop = rows * kMmRowB + narrow_image_units(nt) * 1024;  // the filter slice in whole copy units
     const int t = rows * (J | 1) * 4;
     return loop > t ? loop : t;
 }
@@ -463,19 +489,18 @@ int launch_narrow_rk(const NarrowParams& p, int rk, int nt, int grid, int lds, h
 
 }  // namespace
 
-// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
-int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
-                      int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
-                      hipStream_t stream) {
-    if (C_in < 1 || C_in > 4 || (C_out % 8) != 0 || !is_aligned16(dO)) return 1;
-    const bool dense = n == m;
-    if (!dense && !(m == 4 || m == 8 || m == 16)) return 1;
+namespace {
+
+// The tiling of a problem; SDGP_OK, or a positive value when this file's kernels do not take it.  nt (p.nt) is the
+// matrix-core variant's column tiles, 0 for the vector-ALU variant; lds is the latter's LDS size.
+int narrow_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n, int m,
+                NarrowParams& p, int64_t& grid, int& lds) {
+    if (C_in < 1 || C_in > 4 || (C_out % 8) != 0) return 1;
+    if (n != m && !(m == 4 || m == 8 || m == 16)) return 1;
     const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
     if (B * P * Q >= INT32_MAX || B * H * Wd >= INT32_MAX) return 1;
-    NarrowParams p{};
-    p.dO = static_cast<const uint16_t*>(dO), p.W = static_cast<const uint16_t*>(W), p.dD = static_cast<uint16_t*>(dD);
     p.B = (int)B, p.H = (int)H, p.Wd = (int)Wd, p.P = (int)P, p.Q = (int)Q, p.C_in = (int)C_in, p.C_out = (int)C_out;
-    p.R = R, p.S = S, p.stride = stride, p.pad = pad, p.n = n, p.mix = seed_mix(seed);
+    p.R = R, p.S = S, p.stride = stride, p.pad = pad, p.n = n;
     p.TW = (int)(Wd < 16 ? Wd : 16);
     p.TH = (int)(H < 256 / p.TW ? H : 256 / p.TW);
     p.tiles_h = ((int)H + p.TH - 1) / p.TH, p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
@@ -483,16 +508,61 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
     p.HP = (p.TH - 1 + R - 1) / stride + 1, p.HQ = (p.TW - 1 + S - 1) / stride + 1;
     if (p.HQ < 2) p.HQ = 2;  // the reciprocal below needs a divisor above one
     p.hq_magic = (uint32_t)((1ull << 32) / (uint64_t)p.HQ) + 1u;
-    const int64_t grid = (int64_t)B * p.tiles_h * p.tiles_w;
+    grid = (int64_t)B * p.tiles_h * p.tiles_w;
     if (grid >= INT32_MAX) return 1;
-    if (grid == 0) return SDGP_OK;
     // the matrix-core variant when its (row tile, column tile) pairs and LDS fit; else the vector-ALU one
     const int J = R * S * (int)C_in, npix = p.HP * p.HQ;
     int nt = (J + 31) / 32;
     if (nt > kMmMaxNt || ((npix + 31) / 32) * nt > 4 * kMmMaxPairs || narrow_mm_lds(npix, nt, J) > 160 * 1024) nt = 0;
     p.nt = nt;
-    const int lds = ((npix * kAPitchN + 15) & ~15) + kNarrowKC * R * S * 16;
+    lds = ((npix * kAPitchN + 15) & ~15) + kNarrowKC * R * S * 16;
     if (nt == 0 && lds > 160 * 1024) return 1;
+    return SDGP_OK;
+}
+
+// Bytes of the filter image for a planned problem: worth building when the filter slice is more than one column tile
+// (the 7x7 stem: 160 columns; a 3x3 filter on three channels fits one tile and is gathered inside the kernel).
+size_t narrow_image_bytes(const NarrowParams& p) {
+    if (p.nt < 2) return 0;
+    const size_t slices = (size_t)((p.C_out + kNarrowKC - 1) / kNarrowKC);
+    return slices * (size_t)narrow_image_units(p.nt) * 1024u;
+}
+
+}  // namespace
+
+// Workspace bytes bwd_narrow_launch wants for these arguments (0: none, also when another kernel takes the problem).
+size_t bwd_narrow_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride,
+                            int pad, int n, int m) {
+    NarrowParams p{};
+    int64_t grid = 0;
+    int lds = 0;
+    if (narrow_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, p, grid, lds) != SDGP_OK || grid == 0) return 0;
+    return narrow_image_bytes(p);
+}
+
+// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.  workspace:
+// bwd_narrow_workspace(...) bytes, 16-byte aligned, or null (the kernel then gathers the filter itself).
+int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                      int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
+                      void* workspace, hipStream_t stream) {
+    if (!is_aligned16(dO)) return 1;
+    NarrowParams p{};
+    int64_t grid = 0;
+    int lds = 0;
+    if (narrow_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, p, grid, lds) != SDGP_OK) return 1;
+    p.dO = static_cast<const uint16_t*>(dO), p.W = static_cast<const uint16_t*>(W), p.dD = static_cast<uint16_t*>(dD);
+    p.mix = seed_mix(seed);
+    if (grid == 0) return SDGP_OK;
+    const bool dense = n == m;
+    const int nt = p.nt;
+    const size_t image = narrow_image_bytes(p);
+    if (image > 0 && workspace != nullptr && is_aligned16(workspace)) {
+        p.wimg = static_cast<const unsigned char*>(workspace);
+        p.wimg_units = narrow_image_units(nt);
+        const int slices = (p.C_out + kNarrowKC - 1) / kNarrowKC;
+        hipLaunchKernelGGL(narrow_w_image, dim3(slices), dim3(256), 0, stream, p.W, static_cast<uint16_t*>(workspace), p.C_out,
+                           R * S * p.C_in, p.wimg_units);
+    }
     if (dense && nt > 0) return launch_narrow_mm<4, kGreedy, false, true>(p, (int)grid, stream);
     if (dense) {
         auto kern = bwd_narrow<4, kGreedy, false, true>;

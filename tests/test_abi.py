@@ -110,15 +110,27 @@ def test_conv_argument_errors(lib):
     assert lib.sdgp_conv_bwd_data_workspace(2, 8, 8, 8, 16, 3, 3, 1, 1, 1, 2, 4) != bad
 
 
+def test_first_layer_workspace_query(lib):
+    # 7x7 on three channels: 160 (tap, channel) columns of 144 bytes, in whole KB, per 64 output channels
+    assert lib.sdgp_conv_bwd_data_workspace(256, 224, 224, 3, 64, 7, 7, 2, 3, 1, 2, 4) == 23 * 1024
+    assert lib.sdgp_conv_bwd_data_workspace(256, 224, 224, 3, 128, 7, 7, 2, 3, 1, 4, 4) == 2 * 23 * 1024
+    # 3x3 on three channels fits one column tile: no image; fp32 and wide layers never ask
+    assert lib.sdgp_conv_bwd_data_workspace(512, 32, 32, 3, 64, 3, 3, 1, 1, 1, 2, 4) == 0
+    assert lib.sdgp_conv_bwd_data_workspace(256, 224, 224, 3, 64, 7, 7, 2, 3, 0, 2, 4) == 0
+    assert lib.sdgp_conv_bwd_data_workspace(512, 32, 32, 64, 128, 3, 3, 1, 1, 1, 2, 4) == 0
+
+
 def test_workspace_too_small_is_rejected(lib):
     # wherever the library asks for workspace, passing none or too little is an error before any launch
-    shapes = [(512, 32, 32, 64, 128, 3, 3, 1, 1), (128, 56, 56, 256, 64, 1, 1, 1, 0), (256, 56, 56, 128, 128, 3, 3, 2, 1)]
+    shapes = [(512, 32, 32, 64, 128, 3, 3, 1, 1), (128, 56, 56, 256, 64, 1, 1, 1, 0), (256, 56, 56, 128, 128, 3, 3, 2, 1),
+              (256, 224, 224, 3, 64, 7, 7, 2, 3), (512, 32, 32, 3, 64, 3, 3, 1, 1)]   # first layers: the 7x7 one wants a filter image
     for B, H, Wd, C_in, C_out, R, S, st, pad in shapes:
         for n, m in ((2, 4), (2, 8), (4, 4)):
             need = lib.sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, st, pad, 1, n, m)
             if need:
                 assert conv(lib, B, H, Wd, C_in, C_out, R, S, st, pad, n=n, m=m) == E_WS
                 assert conv(lib, B, H, Wd, C_in, C_out, R, S, st, pad, n=n, m=m, ws=P, ws_bytes=need - 1) == E_WS
+                assert conv(lib, B, H, Wd, C_in, C_out, R, S, st, pad, n=n, m=m, ws=ctypes.c_void_p(8), ws_bytes=need) == E_WS
 
 
 # ------------------------------------------------ per-channel Rescaled Magnitude entry points

@@ -150,6 +150,7 @@ LAYERS = [
     ("c3x3_s2", 2, 16, 16, 64, 64, 3, 3, 2, 1),
     ("stem", 2, 12, 12, 3, 64, 3, 3, 1, 1),
     ("odd", 2, 7, 9, 24, 40, 3, 3, 1, 1),
+    ("stem5x5", 2, 20, 20, 2, 64, 5, 5, 1, 2),      # first-layer kernel, filter gathered inside the kernel (no filter image here)
 ]
 
 
