@@ -435,7 +435,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
             const long long row = m0 + m;
             if (row <= last_row && n0 + cc * 8 < p.C_in) {
                 const u32x4_t v = *(SDGP_LDS u32x4_t*)(smem + m * L::kOutPitch + cc * 16);
-                *reinterpret_cast<u32x4_t*>(p.dD + (size_t)row * p.C_in + n0 + cc * 8) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p.dD + (size_t)row * p.C_in + n0 + cc * 8));
             }
         }
     } else if (GATHER) {
@@ -444,7 +444,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
             const int pix = rowtab[3 * m + 2];
             if (pix >= 0 && n0 + cc * 8 < p.C_in) {
                 const u32x4_t v = *(SDGP_LDS u32x4_t*)(smem + m * L::kOutPitch + cc * 16);
-                *reinterpret_cast<u32x4_t*>(p.dD + (size_t)pix * p.C_in + n0 + cc * 8) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p.dD + (size_t)pix * p.C_in + n0 + cc * 8));
             }
         }
     } else {
@@ -458,7 +458,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
                 const int ny = lim >> 8, nx = lim & 255;
                 for (int dy = 0; dy < ny; ++dy)
                     for (int dx = 0; dx < nx; ++dx)
-                        *reinterpret_cast<u32x4_t*>(dst + (size_t)(dy * p.Wd + dx) * p.C_in) = (dy | dx) ? zero : v;
+                        __builtin_nontemporal_store((dy | dx) ? zero : v, reinterpret_cast<u32x4_t*>(dst + (size_t)(dy * p.Wd + dx) * p.C_in));
             }
         }
     }

@@ -596,7 +596,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         const int pix = rowpix[m];
         if (pix >= 0 && n0 + cc * 8 < p.C_in) {
             const u32x4_t v = *(SDGP_LDS u32x4_t*)(outb + m * L::kOutPitch + cc * 16);
-            *reinterpret_cast<u32x4_t*>(p.dD + (size_t)pix * p.C_in + n0 + cc * 8) = v;
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p.dD + (size_t)pix * p.C_in + n0 + cc * 8));
         }
     }
 #ifdef SDGP_TRACE
