@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the fused 2:4 kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what
 # the same counters read for a plain 256 MiB device copy (x2.0 and x1.0); see profiles/bwd_row_traffic.md.
-MEASURED_TRAFFIC_BYTES = {"r9_128x256_16": 114.0e6, "r9_64x128_32": 229.4e6, "prune_411MB": 822.1e6}
+MEASURED_TRAFFIC_BYTES = {"r9_128x256_16": 114.0e6, "r9_64x128_32": 228.3e6, "prune_411MB": 822.1e6}
 PAPER_CONTEXT = ("the paper reports no measured rate for this path; it estimates a 15-25 % cut of total training time "
                  "assuming 2:4 sparse tensor-core support on an A100 (abstract, Sec. IV-C)")
 
