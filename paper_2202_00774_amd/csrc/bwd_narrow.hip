@@ -30,6 +30,7 @@ struct NarrowParams {
     const unsigned char* wimg;  // matrix-core variant: the transposed filter slices as they sit in LDS, one image of
     int wimg_units;             // wimg_units KB per 64 output channels (built once per call in the workspace), or null
     uint32_t hq_magic;  // floor(2^32 / HQ) + 1: x / HQ == umulhi(x, hq_magic) for the pixel counts of a tile
+    uint32_t nt_magic;  // floor(2^16 / nt) + 1: x / nt == (x * nt_magic) >> 16 for pair numbers (x < 4096, nt <= 5)
     int n;
     uint32_t mix;
 };
@@ -260,7 +261,7 @@ __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
 #pragma unroll
     for (int i = 0; i < kMmPairs; ++i) {
         const int pr = min(wave + 4 * i, npairs - 1);
-        pair_rt[i] = pr / nt, pair_u[i] = pr - pair_rt[i] * nt;
+        pair_rt[i] = (int)(((uint32_t)pr * p.nt_magic) >> 16), pair_u[i] = pr - pair_rt[i] * nt;
         pair_a[i] = pair_rt[i] * 32 * kMmRowB, pair_b[i] = pair_u[i] * 32 * kAPitchN;
     }
     f32x16n acc[kMmPairs];
@@ -515,6 +516,7 @@ int narrow_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, i
     int nt = (J + 31) / 32;
     if (nt > kMmMaxNt || ((npix + 31) / 32) * nt > 4 * kMmMaxPairs || narrow_mm_lds(npix, nt, J) > 160 * 1024) nt = 0;
     p.nt = nt;
+    p.nt_magic = nt > 0 ? (uint32_t)(65536 / nt + 1) : 0u;
     lds = ((npix * kAPitchN + 15) & ~15) + kNarrowKC * R * S * 16;
     if (nt == 0 && lds > 160 * 1024) return 1;
     return SDGP_OK;
