@@ -44,8 +44,6 @@ struct Conv3Params {
     int nhalo, nunits;              // halo pixels, 8-pixel copy units
     int ntaps;
     int ntiles_n, nblocks;
-    int exp;                        // development aid: switches parts off (0 in normal use)
-    unsigned long long* trace;      // development aid: per-stage cycle stamps of workgroup 0 (NULL in normal use)
     TapEntry taps[kMaxTaps];
 };
 
@@ -142,12 +140,6 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
     const int cw = producer ? wave - kC3Consumers : wave;  // index inside the role
     const int wm = cw / WAVES_N, wn = cw % WAVES_N;
     const int ptid = tid - kC3Consumers * 64;   // producers: 0 .. NP*64-1
-    auto stamp = [&](int i) {
-#ifdef SDGP_TRACE
-        if (p.trace && blockIdx.x == 0 && (tid == 0 || tid == kC3Consumers * 64) && i < 128) p.trace[(tid ? 1 : 0) * 128 + i] = clock64();
-#endif
-    };
-    stamp(0);
 
     int lid = blockIdx.x;
     {
@@ -308,12 +300,6 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
         auto issue = [&](bool g_valid) {
             // stages past the end re-copy the last slab into a slot nobody reads: the copy count stays exact
             const bool w_live = wc < nchunks;
-#ifdef SDGP_TRACE
-            if (p.exp & 64) {  // W copies replaced by one cache line per wavefront
-#pragma unroll
-                for (int i = 0; i < WPW; ++i) copy_sink();
-            } else
-#endif
             copy_w(w_live ? wc : nchunks - 1, w_live ? wt : ntaps - 1, wslot);
 #pragma unroll
             for (int j = 0; j < HPW; ++j) {
@@ -326,9 +312,6 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
                 } else {
                     const int u = gt * kC3UnitsPerStep + unit;  // dense: straight into the next chunk's buffer
                     real = g_valid && gc < nchunks && gt < nb && gc + 1 < nchunks && u < nunits;
-#ifdef SDGP_TRACE
-                    if (p.exp & 32) real = false;   // halo copies replaced by cache-resident ones
-#endif
                     if (real) copy_halo_unit(u, gc + 1, smem_base + L::off_a_h(p.nhalo) + ((gc + 1) & 1) * a_buf_bytes + u * 1024, true);
                 }
                 if (!real) copy_sink();
@@ -342,9 +325,7 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
         issue(false);
         issue(false);
         wait_copies<0>();
-        stamp(1);
         __syncthreads();
-        stamp(2);
 
         for (int g = 0; g < nstages; ++g) {
             const int pc = gc, pt = gt;  // (chunk, tap) of stage g, before issue() advances them
@@ -352,13 +333,11 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
             if constexpr (SPARSE) {
                 if (pt < nb && pc + 1 < nchunks) prune_batch(pt, pc + 1, g & (kC3RawSlots - 1), upb, g);
             }
-            stamp(3 + 2 * g);
             // Only this stage's requests may still be in flight: the consumers read the fragments of stage g+1
             // before the barrier that ends stage g, so its slab (requested at stage g-2) must be complete one
             // barrier early.
             wait_copies<kPer>();
             __syncthreads();
-            stamp(4 + 2 * g);
         }
     } else {
         // =============================================================== consumers
@@ -394,9 +373,7 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
                 __syncthreads();
             }
         }
-        stamp(1);
         __syncthreads();  // end of the producers' prologue
-        stamp(2);
 
         struct Frags {
             u32x4_t a[TM];
@@ -407,9 +384,6 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
             const int tap_off = __builtin_amdgcn_readlane(my_tap_off, ti);
             SDGP_LDS unsigned char* wbuf = lds_w + slot * L::kWSlab;
             SDGP_LDS unsigned char* abuf = lds_a + (chunk & 1) * a_buf_bytes;
-#ifdef SDGP_TRACE
-            if (!(p.exp & 8))
-#endif
 #pragma unroll
             for (int t = 0; t < TM; ++t) {
                 const int hp = rowbase[t] + tap_off;
@@ -438,15 +412,6 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
                     f.b[u] = __builtin_bit_cast(bf16x16_t, all);
                 }
             } else {
-#ifdef SDGP_TRACE
-                if (p.exp & 16) return;
-                if (p.exp & 4) {
-#pragma unroll
-                    for (int u = 0; u < TN; ++u)
-                        f.b[u] = __builtin_bit_cast(bf16x8_t, *(SDGP_LDS u32x4_t*)(wbuf + (lane & 31) * 128 + (((lane >> 5) + ks * 2) ^ (lane & 7)) * 16 + u * 4096));
-                    return;
-                }
-#endif
 #pragma unroll
                 for (int u = 0; u < TN; ++u) {
                     s16x4_t q[2];
@@ -461,9 +426,6 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
             }
         };
         auto mma = [&](const Frags& f) {
-#ifdef SDGP_TRACE
-            if (p.exp & 2) return;
-#endif
             bf16x8_t a[TM];
 #pragma unroll
             for (int t = 0; t < TM; ++t) a[t] = __builtin_bit_cast(bf16x8_t, f.a[t]);
@@ -511,18 +473,12 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
                 __builtin_amdgcn_sched_barrier(0);
 #endif
             }
-            stamp(3 + 2 * s);
             __syncthreads();
-            stamp(4 + 2 * s);
             ti = nti, chunk = nchunk;
         }
     }
 
-    stamp(126);
     // ---- epilogue (consumers): fp32 -> bf16 (RNE), NHWC store
-#ifdef SDGP_TRACE
-    if (p.exp & 1) return;
-#endif
     if (!producer) {
 #pragma unroll
         for (int t = 0; t < TM; ++t) {
@@ -539,7 +495,6 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
             }
         }
     }
-    stamp(127);
 }
 
 }  // namespace sdgp

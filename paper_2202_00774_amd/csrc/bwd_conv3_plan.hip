@@ -2,7 +2,6 @@
 // channel counts fit (C_out a multiple of 64, C_in a multiple of 8), chooses the tile and launches.
 #include <algorithm>
 #include <climits>
-#include <cstdlib>
 
 #include "bwd_conv3.h"
 
@@ -37,10 +36,6 @@ int bwd_conv3_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t
     p.n = n;
     p.mix = seed_mix(seed);
     p.ntaps = ntaps;
-#ifdef SDGP_TRACE
-    if (const char* e = getenv("SDGP_EXP")) p.exp = atoi(e);
-    if (const char* t = getenv("SDGP_TRACE_PTR")) p.trace = (unsigned long long*)strtoull(t, nullptr, 0);
-#endif
     // dD[h, w] gathers dO[h + pad - r, w + pad - s]
     for (int r = 0; r < R; ++r)
         for (int s = 0; s < S; ++s) {

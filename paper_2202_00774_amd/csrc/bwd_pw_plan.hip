@@ -1,7 +1,6 @@
 // Host side of the pointwise kernel: 1x1 convolutions without padding (any stride) and linear layers whose channel
 // counts fit (C_out a multiple of 32, C_in a multiple of 8); chooses the tile shape and launches.
 #include <climits>
-#include <cstdlib>
 
 #include "bwd_pw_launch.h"
 
@@ -95,12 +94,6 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     if (C_in <= 64) shape = 2;
     else if (mode != 0 && C_in > 128) shape = 0;
     else shape = 1;
-#ifdef SDGP_TRACE
-    if (const char* e = getenv("SDGP_PW_SHAPE")) {
-        const int v = atoi(e);
-        if (v >= 0 && v < kPwNumShapes) shape = v;
-    }
-#endif
     const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
     const int64_t blocks = blocks_of(rows_per, bn);
     if (blocks < 64 || blocks >= INT_MAX) return 1;  // too small to be worth a matrix-core launch of this shape

@@ -49,8 +49,6 @@ struct RowParams {
     int halo_max;                // upper bound of the halo pixels of any tile (LDS sizing)
     int ups;                     // halo copy units per stage: a 1/R share of the halo, at most 16
     int ntiles_n, nblocks;
-    int exp;                     // development aid (builds with SDGP_TRACE only): switches parts of the kernel off
-    unsigned long long* trace;   // development aid (SDGP_TRACE only): per-workgroup cycle stamps, 32 values each
 };
 
 constexpr int kRowKC = 32;         // reduction channels per chunk
@@ -115,16 +113,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-#ifdef SDGP_TRACE
-    // stamps of wavefronts 0 and 4 (the two wavefronts of SIMD 0): [0] start, [1] prologue done, [2] main loop done,
-    // [3] accumulators staged, [4] end, [5] sum over stages of barrier -> first matrix instruction, [6] sum of the
-    // wait in front of the barrier and the barrier, [7] sum of the ranking shares
-    unsigned long long tr_bubble = 0, tr_wait = 0, tr_prune = 0;
-    auto stamp = [&](int k, unsigned long long v) {
-        if (p.trace && (wave & 3) == 0 && lane == 0) p.trace[((size_t)blockIdx.x * 2 + (wave >> 2)) * 16 + k] = v;
-    };
-    stamp(0, __builtin_readcyclecounter());
-#endif
 
     // ---- which tile: consecutive logical ids stay on one XCD (workgroups are dealt round-robin over 8 XCDs)
     int lid = blockIdx.x;
@@ -347,9 +335,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     wait_lds_copies<0>();
     __syncthreads();
 
-#ifdef SDGP_TRACE
-    stamp(1, __builtin_readcyclecounter());
-#endif
     // ---- fragments
     uint32_t b_lane[TN];  // transpose reads from the swizzled slab, one lane address per 32-column tile
 #pragma unroll
@@ -408,7 +393,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         }
     };
     auto mma_one = [&](const Frags& f, int t, int u) {
-        if (SDGP_EXP(2)) return;
         const bf16x8_t a = __builtin_bit_cast(bf16x8_t, f.a[t]);
         if constexpr (SPARSE)
             acc[t][u] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, f.b[u], acc[t][u], f.meta[t], 0, 0);
@@ -435,24 +419,19 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         const int npr = pr + 1 == R ? 0 : pr + 1;
         const int npc = row_last ? pc_next : pc;
         const bool more = x + 1 < nstages;
-#ifdef SDGP_TRACE
-        const unsigned long long tr_s0 = __builtin_readcyclecounter();
-#endif
         // first k-step: nothing of this stage was requested before the barrier except the table entries
-        if (!SDGP_EXP(8) || x == 0) {
-            read_entries(pr * TS);
-            take_entries();
+        read_entries(pr * TS);
+        take_entries();
 #pragma unroll
-            for (int t = 0; t < TM; ++t) load_a(f0, t, abuf, mbuf, 0);
+        for (int t = 0; t < TM; ++t) load_a(f0, t, abuf, mbuf, 0);
 #pragma unroll
-            for (int u = 0; u < TN; ++u) load_b(f0, u, set_off, 0);
-        }
+        for (int u = 0; u < TN; ++u) load_b(f0, u, set_off, 0);
         // share r of the next chunk's halo: one item per lane of the whole workgroup.  The two wavefronts of a SIMD
         // (w and w + 4) rank at different times -- one before the stage's first k-step, the other after it -- so
         // that one's vector work runs under the other's matrix instructions.
         auto prune_share = [&]() {
             if constexpr (PRUNES) {
-                if (c + 1 < nchunks && !SDGP_EXP(32)) {
+                if (c + 1 < nchunks) {
                     const int u0 = r * ups;
                     const int cnt = min(ups, nunits - u0);
                     if (cnt > 0)
@@ -461,14 +440,8 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 }
             }
         };
-#ifdef SDGP_TRACE
-        const unsigned long long tr_p0 = __builtin_readcyclecounter();
-#endif
         if (wave < 4) prune_share();
         __builtin_amdgcn_sched_barrier(0);
-#ifdef SDGP_TRACE
-        tr_prune += __builtin_readcyclecounter() - tr_p0;
-#endif
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             Frags& cur = (q & 1) ? f1 : f0;
@@ -498,7 +471,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                     }
                 } else if (i <= APIECES + TN) {
                     if (has_next) load_b(nxt, i - APIECES - 1, set_off + (uint32_t)ntap * L::kWSlab, nks);
-                } else if (SDGP_EXP(4)) {
                 } else if (i == APIECES + TN + 1) {
                     if (more) copy_w_set(npc, npr, (x + 1) & 1);
                 } else if (i == APIECES + TN + 2) {
@@ -520,13 +492,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 __builtin_amdgcn_sched_barrier(0);
             };
             int done = 0;
-#ifdef SDGP_TRACE
-            if (q == 0) {
-                // the first matrix instruction of the stage can issue once its fragments are here
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                tr_bubble += __builtin_readcyclecounter() - tr_s0;
-            }
-#endif
 #pragma unroll
             for (int g = 0; g < GAPS; ++g) {
                 mma_one(cur, g / TN, g % TN);
@@ -535,14 +500,8 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 for (; done < upto && done < npieces; ++done) piece(done);
             }
         }
-#ifdef SDGP_TRACE
-        const unsigned long long tr_w0 = __builtin_readcyclecounter();
-#endif
         wait_lds_copies<0>();
         __syncthreads();  // never optional: the epilogue reuses the tables' LDS as soon as a wavefront leaves the loop
-#ifdef SDGP_TRACE
-        tr_wait += __builtin_readcyclecounter() - tr_w0;
-#endif
         if (row_last) {
             r = 0, ++c, pc = pc_next;
             const uint32_t xa = abuf; abuf = abuf_other; abuf_other = xa;
@@ -563,11 +522,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         if (x < nstages) stage(fr[0], fr[1], x);
     }
 
-#ifdef SDGP_TRACE
-    stamp(2, __builtin_readcyclecounter());
-    stamp(5, tr_bubble), stamp(6, tr_wait), stamp(7, tr_prune);
-#endif
-    if (SDGP_EXP(1)) return;
     // ---- epilogue: fp32 -> bf16 (RNE) into LDS, then whole pixel rows with 16-byte stores
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -587,9 +541,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 *(SDGP_LDS uint16_t*)(outb + (m + 1) * L::kOutPitch + col * 2) = (uint16_t)(pk >> 16);
             }
     __syncthreads();
-#ifdef SDGP_TRACE
-    stamp(3, __builtin_readcyclecounter());
-#endif
 #pragma unroll 4
     for (int idx = tid; idx < ROWS * CPR; idx += 512) {
         const int m = idx / CPR, cc = idx % CPR;
@@ -599,9 +550,6 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
             __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p.dD + (size_t)pix * p.C_in + n0 + cc * 8));
         }
     }
-#ifdef SDGP_TRACE
-    stamp(4, __builtin_readcyclecounter());
-#endif
 }
 
 }  // namespace sdgp

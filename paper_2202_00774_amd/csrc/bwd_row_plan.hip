@@ -2,8 +2,6 @@
 // enough 512-row tiles to fill the chip; chooses the tile and launches.
 #include <algorithm>
 #include <climits>
-#include <cstdio>
-#include <cstdlib>
 
 #include "bwd_row.h"
 
@@ -83,10 +81,6 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
     p.w_row = ntaps * (int)C_in;
     p.n = n;
     p.mix = seed_mix(seed);
-#ifdef SDGP_TRACE
-    if (const char* e = getenv("SDGP_EXP")) p.exp = atoi(e);
-    if (const char* t = getenv("SDGP_TRACE_PTR")) p.trace = (unsigned long long*)strtoull(t, nullptr, 0);
-#endif
 
     // 512-row tiles when they fill the chip, else 256-row tiles (twice the workgroups, half the matrix work per stage);
     // 128-column tiles unless they leave a quarter of the CUs without a workgroup: then 64-column tiles, twice as many
@@ -103,20 +97,6 @@ int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H
         const int64_t n256 = plan_tiles(p256, 256, mode, bn, B, H, Wd, R, S, P, Q);
         if (n512 >= 192 || (n512 >= 128 && n256 < 128) || n256 == 0) rows = 512, chosen = p512, blocks = n512;
         else rows = 256, chosen = p256, blocks = n256;
-#ifdef SDGP_TRACE
-        if (const char* e = getenv("SDGP_ROW_SHAPE")) {  // "<rows>x<bn>"
-            int fr = 0, fb = 0;
-            if (sscanf(e, "%dx%d", &fr, &fb) == 2 && (fr == 512 || fr == 256) && (fb == 128 || fb == 64) && fb <= bn) {
-                if (fb != bn) {
-                    bn = fb;
-                    continue;
-                }
-                if (fr == 512 && n512 > 0) rows = 512, chosen = p512, blocks = n512;
-                if (fr == 256 && n256 > 0) rows = 256, chosen = p256, blocks = n256;
-                break;
-            }
-        }
-#endif
         if (bn == 128 && blocks < 192) {
             bn = 64;
             continue;

@@ -38,10 +38,5 @@ __device__ __forceinline__ void prune16_compressed(const u32x4_t (&v)[2], int n,
     prune_compress16<M, RK>(w, n, mix, e0, packed, meta);
 }
 
-#ifdef SDGP_TRACE
-#define SDGP_EXP(bit) (p.exp & (bit))
-#else
-#define SDGP_EXP(bit) false
-#endif
 
 }  // namespace sdgp
