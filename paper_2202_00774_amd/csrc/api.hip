@@ -85,6 +85,9 @@ int check_conv(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, in
 int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                  int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed, void* workspace,
                  hipStream_t stream) {
+    // no output channels: every element of dD is an empty sum.  The shape-agnostic kernel writes the zeros; the
+    // matrix-core kernels assume at least one reduction chunk.
+    if (C_out == 0) return sdgp::bwd_simple_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, stream);
     if (dt == SDGP_BF16 && C_in <= 4) {
         const int rc = sdgp::bwd_narrow_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, workspace,
                                                stream);

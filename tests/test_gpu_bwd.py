@@ -189,12 +189,14 @@ def test_many_tile_fused_equals_prune_then_dense():
 
 @pytest.mark.parametrize("index", range(6))
 def test_resnet9_batch512_sampled(index):
-    """Every ResNet-9 layer at batch 512: the fused 2:4 kernels and the dense kernel against the oracle on 4096 sampled
+    """Every ResNet-9 layer at batch 512, in the launches bench.py times: the fused 2:4 kernels of the three rankers,
+    2:8 and 2:16 Magnitude (the sparsity sweep on these shapes) and the dense kernel against the oracle on 4096 sampled
     output pixels (plus the corners of the first and last image); the oracle prunes the whole gradient."""
     layer = wl.resnet9_layers(512)[index]
     dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=2000 + index, dtype=oracle.BF16)
     pixels = sample_pixels(layer, 4096, 100 + index)
-    for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (2, 4, oracle.RANDOM), (4, 4, oracle.GREEDY)):
+    for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (2, 4, oracle.RANDOM), (2, 8, oracle.GREEDY),
+                         (2, 16, oracle.GREEDY), (4, 4, oracle.GREEDY)):
         check_conv(layer, dO, W, n, m, ranker, 0, oracle.BF16, pixels=pixels)
 
 

@@ -151,6 +151,10 @@ LAYERS = [
     ("stem", 2, 12, 12, 3, 64, 3, 3, 1, 1),
     ("odd", 2, 7, 9, 24, 40, 3, 3, 1, 1),
     ("stem5x5", 2, 20, 20, 2, 64, 5, 5, 1, 2),      # first-layer kernel, filter gathered inside the kernel (no filter image here)
+    # a wide first-layer filter (five column tiles of (tap, channel) pairs): sdgp_conv_bwd_data would build a transposed
+    # image of it in its workspace; this entry point hands the first-layer kernel no workspace, so the kernel gathers
+    # the filter itself
+    ("stem7x7s2", 2, 30, 30, 3, 64, 7, 7, 2, 3),
 ]
 
 
@@ -193,6 +197,19 @@ def test_fused_linear_matches_oracle(dtype):
     ref, absum = oracle.linear_bwd_data(pruned, W)
     got = wl.to_f64(to_host(sdgp.sdgp_linear_bwd_data_channel_rescaled(to_gpu(dO), to_gpu(W), n, m)))
     assert rel_error(got, ref, absum) <= (1e-2 if dtype == oracle.BF16 else 1e-5)
+
+
+def test_no_output_channels_gives_zeros():
+    """C_out = 0: an empty sum for every element of dL/dD."""
+    B, H, Wd, C_in = 2, 6, 5, 8
+    dO = torch.empty((B, H, Wd, 0), dtype=torch.bfloat16, device="cuda")
+    W = torch.empty((0, 3, 3, C_in), dtype=torch.bfloat16, device="cuda")
+    out = torch.full((B, H, Wd, C_in), 7.0, dtype=torch.bfloat16, device="cuda")
+    sdgp.sdgp_conv_bwd_data_channel_rescaled(dO, W, H, Wd, 1, 1, 2, 4, out=out)
+    assert torch.all(out == 0)
+    out.fill_(7.0)
+    sdgp.sdgp_conv_bwd_data(dO, W, H, Wd, 1, 1, 2, 4, sdgp.GREEDY, out=out)
+    assert torch.all(out == 0)
 
 
 def test_fused_equals_its_three_steps():

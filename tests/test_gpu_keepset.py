@@ -1,0 +1,136 @@
+"""The kept set and the kept values of the FUSED kernels, bit for bit (Sec. III-B; Alg. 1).
+
+Inside the fused backward-data kernels the pruned gradient exists only in LDS, so a product with a general filter
+shows it only through sums of hundreds of terms.  Here the filter is one-hot -- every output channel k of the
+gradient feeds exactly one (tap, input channel) with weight 1 -- and, where more than one tap is used, the gradient is
+nonzero only on a lattice of pixels whose footprints do not overlap.  Every element of dL/dD is then a single term
+x * 1 (or nothing), so it must EQUAL the oracle's pruned value: a wrong survivor, a wrong tie decision, a wrong
+position code or a wrong rescaled value changes bits of the output.
+
+Values are finite and normal (signed zeros included; a kept -0 comes out as a zero of either sign, which compares
+equal): half the rows Laplace with 30 % zeros, half drawn from a small alphabet so that equal magnitudes meet in
+every position of a group.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_00774_amd as sdgp
+from paper_2202_00774_amd import workloads as wl
+from util import to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+RANKERS = (oracle.RANDOM, oracle.GREEDY, oracle.GREEDY_ADJUSTED)
+ONE = np.uint16(0x3F80)
+# +-0, the smallest normal and its neighbour, +-1, 1.5, +-2, +-2^97: repeats of a magnitude with both signs
+ALPHABET = np.array([0x0000, 0x8000, 0x0080, 0x8080, 0x0081, 0x3F80, 0xBF80, 0x3FC0, 0x4000, 0xC000, 0x7000, 0xF000],
+                    np.uint16)
+
+
+def one_hot_filter(layer, spread):
+    """W [C_out, R, S, C_in] with a single 1 per output channel.  spread=False: channel k -> (centre tap, k)
+    (needs C_in == C_out); spread=True: channel k -> (tap k mod R*S, input channel k div R*S)."""
+    W = np.zeros(layer.W_shape, np.uint16)
+    T = layer.R * layer.S
+    for k in range(layer.C_out):
+        if spread:
+            tap, c = k % T, k // T
+        else:
+            tap, c = (layer.R // 2) * layer.S + layer.S // 2, k
+        assert c < layer.C_in
+        W[k, tap // layer.S, tap % layer.S, c] = ONE
+    return W
+
+
+def gradient(layer, seed, lattice):
+    """Half Laplace rows, half alphabet rows; with lattice > 1 only pixels (p, q) = (1, 1) mod lattice are nonzero."""
+    shape = layer.dO_shape
+    rng = np.random.Generator(np.random.PCG64(seed))
+    dO = wl.laplace_with_zeros(shape, 1e-3, 0.3, seed, wl.BF16)
+    alpha = rng.choice(ALPHABET, size=shape)
+    pick = rng.random(size=shape[:3]) < 0.5
+    dO[pick] = alpha[pick]
+    if lattice > 1:
+        mask = np.zeros(shape[:3], bool)
+        mask[:, 1 % shape[1]::lattice, 1 % shape[2]::lattice] = True
+        dO[~mask] = 0
+    return dO
+
+
+def sample(layer, count, seed):
+    total = layer.B * layer.H * layer.Wd
+    if total <= count:
+        return np.arange(total, dtype=np.int64)
+    hw = layer.H * layer.Wd
+    fixed = np.array([0, layer.Wd - 1, hw - layer.Wd, hw - 1, total - hw, total - 1, total - layer.Wd], np.int64)
+    return np.unique(np.concatenate([fixed, np.random.default_rng(seed).integers(0, total, count)]))
+
+
+def check_exact(layer, spread, settings, npix=12000):
+    lattice = 1
+    if spread:
+        lattice = max(-(-layer.R // layer.stride), -(-layer.S // layer.stride))  # footprints must not overlap
+    dO = gradient(layer, 4242 + layer.C_out + layer.H, lattice)
+    W = one_hot_filter(layer, spread)
+    pixels = sample(layer, npix, 17)
+    d, w = to_gpu(dO), to_gpu(W)
+    for n, m, ranker in settings:
+        pruned = oracle.prune(dO, n, m, ranker, seed=29)[0]
+        ref, ab = oracle.conv_bwd_data(pruned, W, layer.H, layer.Wd, layer.stride, layer.pad, pixels=pixels)
+        # single-term sums: the reference is exactly a stored value
+        assert np.array_equal(ref, wl.to_f64(wl.f32_to_bf16_bits(ref.astype(np.float32))))
+        out = sdgp.sdgp_conv_bwd_data(d, w, layer.H, layer.Wd, layer.stride, layer.pad, n, m, ranker, 29)
+        torch.cuda.synchronize()
+        got = wl.to_f64(to_host(out.reshape(-1, layer.C_in)[torch.from_numpy(pixels).to(out.device)]))
+        bad = np.argwhere(got != ref)
+        assert bad.size == 0, (layer.name, spread, n, m, ranker, len(bad), bad[:4].tolist(),
+                               [(got[tuple(i)], ref[tuple(i)]) for i in bad[:4]])
+        assert np.count_nonzero(ref) > 0
+
+
+def nm_settings(ms=(4, 8, 16)):
+    return [(2, m, r) for m in ms for r in RANKERS] + [(1, 4, oracle.GREEDY), (1, 8, oracle.RANDOM)]
+
+
+# (layer, spread): which kernel the dispatcher picks for it is noted per case
+CASES = [
+    # row-per-stage kernel: 512-row tiles with 64 and with 128 columns, 256-row tiles
+    (wl.ConvLayer("row512_n64", 400, 16, 16, 64, 64, 3, 3, 1, 1), False),
+    (wl.ConvLayer("row512_n128", 400, 16, 16, 128, 128, 3, 3, 1, 1), False),
+    (wl.ConvLayer("row512_n128_spread", 400, 16, 16, 128, 128, 3, 3, 1, 1), True),
+    (wl.ConvLayer("row256_n64", 200, 16, 16, 64, 64, 3, 3, 1, 1), False),
+    (wl.ConvLayer("row512_8x8_n128", 1608, 8, 8, 128, 128, 3, 3, 1, 1), True),
+    # pointwise kernel: 256 x 64 tiles, all of C_in (160 of 256 columns) per workgroup
+    (wl.ConvLayer("pw_n64", 64, 23, 23, 64, 64, 1, 1, 1, 0), False),
+    (wl.ConvLayer("pw_n160", 64, 23, 23, 160, 160, 1, 1, 1, 0), False),
+    (wl.ConvLayer("pw_s2_n64", 64, 31, 29, 64, 64, 1, 1, 2, 0), False),
+    # pointwise kernel gathering rows per tap: stride-2 3x3 (classes of 1, 2, 2, 4 taps) and 4x4
+    (wl.ConvLayer("gather_s2_3x3", 64, 30, 28, 64, 64, 3, 3, 2, 1), True),
+    (wl.ConvLayer("gather_s2_4x4", 64, 32, 32, 64, 64, 4, 4, 2, 1), True),
+    # few tiles: the producer/consumer kernel
+    (wl.ConvLayer("conv3_n64", 4, 16, 16, 64, 64, 3, 3, 1, 1), False),
+    (wl.ConvLayer("conv3_n64_spread", 4, 16, 16, 64, 64, 3, 3, 1, 1), True),
+    (wl.ConvLayer("conv3_5x5", 3, 12, 12, 64, 64, 5, 5, 1, 2), True),
+    # channel count not a multiple of 32: the parity-class kernel; stride 2 with few tiles
+    (wl.ConvLayer("tiled_n48", 4, 16, 16, 48, 48, 3, 3, 1, 1), False),
+    (wl.ConvLayer("tiled_n48_spread", 4, 16, 16, 48, 48, 3, 3, 1, 1), True),
+    (wl.ConvLayer("tiled_s2", 2, 14, 14, 32, 32, 3, 3, 2, 1), True),
+    # first-layer kernel (C_in <= 4): 3x3 on four channels, the 7x7 stride-2 stem on three
+    (wl.ConvLayer("narrow_3x3", 2, 19, 21, 4, 32, 3, 3, 1, 1), True),
+    (wl.ConvLayer("narrow_7x7s2", 2, 30, 30, 3, 64, 7, 7, 2, 3), True),
+]
+
+
+@pytest.mark.parametrize("layer,spread", CASES, ids=lambda v: v.name if hasattr(v, "name") else "")
+def test_fused_pruned_values_equal_the_oracle(layer, spread):
+    ms = tuple(m for m in (4, 8, 16) if layer.C_out % m == 0)
+    check_exact(layer, spread, nm_settings(ms))
+
+
+def test_linear_identity_equals_the_oracle():
+    """dD = prune(dO) @ I for a linear layer: the pointwise kernel on rows of one pixel."""
+    rows, C = 40001, 96
+    layer = wl.ConvLayer("linear_n96", rows, 1, 1, C, C, 1, 1, 1, 0)
+    check_exact(layer, False, nm_settings(), npix=rows)

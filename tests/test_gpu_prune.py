@@ -77,11 +77,39 @@ def test_prune_paper_example_on_gpu():
     assert p.cpu().tolist() == [[0.0, 7.0, -3.0, 0.0]] and i.cpu().tolist() == [[1, 2]] and v.cpu().tolist() == [[7.0, -3.0]]
 
 
-def test_prune_random_seed_words_and_high_index_bits():
-    """Both words of the seed matter, and the result follows the flat element index."""
+def test_prune_random_both_seed_words():
+    """Both words of the seed matter."""
     dO = wl.laplace_with_zeros((16, 64), 1.0, 0.0, seed=1, dtype=oracle.BF16)
     for seed in (0, 1, 2 ** 32, 2 ** 63 + 5, 2 ** 64 - 1):
         check(dO, 2, 4, oracle.RANDOM, seed)
+
+
+@pytest.mark.parametrize("n,m", [(2, 4), (2, 16)])
+def test_prune_random_beyond_2_to_32_elements(n, m):
+    """A tensor of 2^32 + 8192 bf16 elements: the high word of the flat element index enters the hash.  The rows around
+    the 2^32 boundary and the last rows are compared with kept sets computed here from the oracle's hash of (seed, flat
+    index): the n largest (key, -position) of every group; kept values are copies, dropped positions +0."""
+    C = 64
+    rows = (2 ** 32 + 8192) // C
+    seed = 2 ** 33 + 12345
+    d = torch.zeros((rows, C), dtype=torch.bfloat16, device="cuda")
+    first = 2 ** 32 // C - 32                       # 32 rows below the boundary ... the end: 160 rows
+    tail = wl.laplace_with_zeros((rows - first, C), 1.0, 0.0, seed=3, dtype=oracle.BF16)
+    d[first:] = to_gpu(tail)
+    p, _, _ = sdgp.sdgp_prune(d, n, m, sdgp.RANDOM, seed)
+    got = to_host(p[first:])
+    head = to_host(p[:64])
+    del p, d
+    want = np.zeros_like(tail)
+    for r in range(tail.shape[0]):
+        for g in range(C // m):
+            e0 = (first + r) * C + g * m
+            keys = [oracle.hash32(seed, e0 + j) for j in range(m)]
+            order = sorted(range(m), key=lambda j: (-keys[j], j))[:n]
+            for j in order:
+                want[r, g * m + j] = tail[r, g * m + j]
+    assert np.array_equal(got, want)
+    assert not head.any()
 
 
 @pytest.mark.parametrize("ranker", RANKERS)
