@@ -144,6 +144,26 @@ size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_
                                     int R, int S, int stride, int pad, int dt, int n, int m);
 
 /*
+ * sdgp_conv_bwd_data_noalloc -- sdgp_conv_bwd_data for callers that cannot allocate device memory and therefore
+ * cannot bring a workspace: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and error behaviour as sdgp_conv_bwd_data, minus the workspace: where that call
+ * needs scratch memory (the transposed filter of a wide first layer), this one takes it from an array of
+ * SDGP_NOALLOC_SCRATCH_BYTES that is part of the library's device image (each GPU the library runs on holds its own
+ * copy until the process ends).  The call allocates and frees nothing.
+ *
+ *   - A problem whose sdgp_conv_bwd_data_workspace(...) exceeds SDGP_NOALLOC_SCRATCH_BYTES (a 7x7 first layer with
+ *     more than 704 output channels) returns SDGP_ERR_WORKSPACE and launches nothing; SDGP_ERR_HIP when the runtime
+ *     cannot report the array's address.
+ *   - All calls on one GPU share that GPU's array, and it keeps the last call's contents (every call rewrites the
+ *     part it reads, nothing has to start at zero).  Calls that overlap in time on one GPU -- different streams,
+ *     or different host threads -- race on it: order them on one stream.
+ */
+#define SDGP_NOALLOC_SCRATCH_BYTES (256 * 1024)
+int sdgp_conv_bwd_data_noalloc(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd,
+                               int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dt,
+                               int n, int m, int rk, uint64_t seed, void* hip_stream);
+
+/*
  * Rescaled Magnitude with one factor per channel.
  *
  * Sec. III-B defines Rescaled Magnitude on the group that P receives (what

@@ -21,6 +21,7 @@ _lock = threading.Lock()
 _lib = None
 
 EXPORTS = ("sdgp_prune", "sdgp_linear_bwd_data", "sdgp_conv_bwd_data", "sdgp_conv_bwd_data_workspace",
+           "sdgp_conv_bwd_data_noalloc",
            "sdgp_channel_scales_workspace", "sdgp_channel_scales", "sdgp_prune_channel_rescaled", "sdgp_scale_filter",
            "sdgp_conv_bwd_data_channel_rescaled_workspace", "sdgp_conv_bwd_data_channel_rescaled",
            "sdgp_status_string", "sdgp_version")
@@ -52,6 +53,9 @@ def load():
             lib.sdgp_conv_bwd_data.restype = i32
             lib.sdgp_conv_bwd_data.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32,
                                                i32, u64, vp, sz, vp]
+            lib.sdgp_conv_bwd_data_noalloc.restype = i32
+            lib.sdgp_conv_bwd_data_noalloc.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32,
+                                                       i32, i32, u64, vp]
             lib.sdgp_conv_bwd_data_workspace.restype = sz
             lib.sdgp_conv_bwd_data_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32]
             lib.sdgp_channel_scales_workspace.restype = sz
@@ -176,6 +180,25 @@ def sdgp_conv_bwd_data(dO: torch.Tensor, W: torch.Tensor, H: int, Wd: int, strid
                                    ranker, seed & (2**64 - 1), _ptr(workspace), wbytes, _stream(dO))
     if rc != 0:
         raise SdgpError(rc, "sdgp_conv_bwd_data")
+    return out
+
+
+def sdgp_conv_bwd_data_noalloc(dO: torch.Tensor, W: torch.Tensor, H: int, Wd: int, stride: int, pad: int, n: int, m: int,
+                               ranker: int, seed: int, out: torch.Tensor) -> torch.Tensor:
+    """sdgp_conv_bwd_data into the caller's ``out`` without a workspace: scratch comes from the library's own array."""
+    _dev(dO, "dO"), _dev(W, "W"), _dev(out, "out")
+    if dO.dim() != 4 or W.dim() != 4 or W.shape[0] != dO.shape[3] or W.dtype != dO.dtype:
+        raise ValueError("expected dO [B,P,Q,C_out] and W [C_out,R,S,C_in] of one dtype")
+    B, P, Q, C_out = dO.shape
+    _, R, S, C_in = W.shape
+    if (H + 2 * pad - R) // stride + 1 != P or (Wd + 2 * pad - S) // stride + 1 != Q:
+        raise ValueError("dO's spatial size does not match H, Wd, stride, pad")
+    if tuple(out.shape) != (B, H, Wd, C_in) or out.dtype != dO.dtype:
+        raise ValueError("out must be [B,H,Wd,C_in] of dO's dtype")
+    rc = load().sdgp_conv_bwd_data_noalloc(_ptr(dO), _ptr(W), _ptr(out), B, H, Wd, C_in, C_out, R, S, stride, pad,
+                                           _dtype_code(dO), n, m, ranker, seed & (2**64 - 1), _stream(dO))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_conv_bwd_data_noalloc")
     return out
 
 

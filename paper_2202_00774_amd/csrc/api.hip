@@ -1,5 +1,7 @@
 // extern "C" boundary of the SDGP library: argument validation and dispatch.
 // Every check happens before the first launch, so a failing call has no effect.
+#include <atomic>
+
 #include "common.h"
 
 namespace sdgp {
@@ -34,9 +36,32 @@ int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int d
 int scale_rows_launch(const void* W, const float* scale, void* out, int64_t C_out, int64_t inner, int dt, hipStream_t stream);
 }  // namespace sdgp
 
+// Scratch memory of sdgp_conv_bwd_data_noalloc: lives in the library's device image, one copy per GPU, for the life
+// of the process.  Host code never uses this name as an address: it asks the runtime where the array sits on the
+// current device (scratch_on_current_device) and hands that pointer to the kernels.
+static __device__ __align__(256) unsigned char scratch[SDGP_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int64_t kMaxElements = (int64_t)1 << 40;
+
+// Device address of `scratch` on the current device, looked up once per device; null when the runtime refuses.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+void* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // every thread finds the same address
+    }
+    return ptr;
+}
 
 bool valid_dtype(int dt) { return dt == SDGP_F32 || dt == SDGP_BF16; }
 bool valid_ranker(int rk) { return rk == SDGP_RANDOM || rk == SDGP_GREEDY || rk == SDGP_GREEDY_ADJUSTED; }
@@ -162,6 +187,26 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
     if (need > 0 && (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0))
         return SDGP_ERR_WORKSPACE;
     return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, need > 0 ? workspace : nullptr,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int sdgp_conv_bwd_data_noalloc(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                               int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk,
+                               uint64_t seed, void* hip_stream) {
+    ConvGeom g;
+    const int rc = check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g);
+    if (rc != SDGP_OK) return rc;
+    if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
+    if (g.n_dD == 0) return SDGP_OK;
+    if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
+    const size_t need = sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m);
+    if (need > (size_t)SDGP_NOALLOC_SCRATCH_BYTES) return SDGP_ERR_WORKSPACE;  // more scratch than the library holds
+    void* ws = nullptr;
+    if (need > 0) {
+        ws = scratch_on_current_device();
+        if (ws == nullptr) return SDGP_ERR_HIP;
+    }
+    return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, ws,
                         static_cast<hipStream_t>(hip_stream));
 }
 

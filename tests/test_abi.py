@@ -133,6 +133,25 @@ def test_workspace_too_small_is_rejected(lib):
                 assert conv(lib, B, H, Wd, C_in, C_out, R, S, st, pad, n=n, m=m, ws=ctypes.c_void_p(8), ws_bytes=need) == E_WS
 
 
+def test_noalloc_argument_errors(lib):
+    """The entry point without a workspace: the checks of sdgp_conv_bwd_data, and a clear refusal when the problem
+    wants more scratch than the library's own array holds (nothing is launched on these paths)."""
+    def call(B=2, H=8, Wd=8, C_in=8, C_out=16, R=3, S=3, stride=1, pad=1, dt=1, n=2, m=4, rk=1, dO=P, W=P, dD=P):
+        return lib.sdgp_conv_bwd_data_noalloc(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, 0, None)
+    assert call(dt=-1) == E_DTYPE
+    assert call(rk=5) == E_RANKER
+    assert call(n=0) == E_NM
+    assert call(C_out=10) == E_SHAPE
+    assert call(dO=None) == E_NULL
+    assert call(dD=None) == E_NULL
+    assert call(B=0) == OK
+    # a 7x7 first layer on three channels wants 23 KB per 64 output channels: 704 channels fit the 256 KB array, 768 do not
+    limit = 256 * 1024
+    assert lib.sdgp_conv_bwd_data_workspace(2, 64, 64, 3, 704, 7, 7, 2, 3, 1, 2, 4) <= limit
+    assert lib.sdgp_conv_bwd_data_workspace(2, 64, 64, 3, 768, 7, 7, 2, 3, 1, 2, 4) > limit
+    assert call(B=2, H=64, Wd=64, C_in=3, C_out=768, R=7, S=7, stride=2, pad=3) == E_WS
+
+
 # ------------------------------------------------ per-channel Rescaled Magnitude entry points
 
 BAD = ctypes.c_size_t(-1).value

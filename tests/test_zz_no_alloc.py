@@ -1,0 +1,55 @@
+"""sdgp_conv_bwd_data_noalloc against sdgp_conv_bwd_data: same bits, no workspace from the caller.
+
+Two calls in a row on one GPU share the library's scratch array; the second one is smaller, so the array still holds
+what the first one left beyond the second one's part.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2202_00774_amd as sdgp
+from paper_2202_00774_amd import workloads as wl
+from util import rel_error, to_gpu, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def run_pair(layer, n, m, ranker, seed):
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=60 + layer.C_out, dtype=oracle.BF16)
+    d, w = to_gpu(dO), to_gpu(W)
+    want = sdgp.sdgp_conv_bwd_data(d, w, layer.H, layer.Wd, layer.stride, layer.pad, n, m, ranker, seed)
+    out = torch.full(layer.dD_shape, 3.0, dtype=torch.bfloat16, device="cuda")
+    sdgp.sdgp_conv_bwd_data_noalloc(d, w, layer.H, layer.Wd, layer.stride, layer.pad, n, m, ranker, seed, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), want.view(torch.int16)), (layer.name, n, m, ranker)
+    # and against the oracle, to the product's tolerance
+    pruned = oracle.prune(dO, n, m, ranker, seed=seed)[0]
+    ref, ab = oracle.conv_bwd_data(pruned, W, layer.H, layer.Wd, layer.stride, layer.pad)
+    assert rel_error(wl.to_f64(to_host(out)), ref, ab) <= 1e-2
+
+
+def test_noalloc_matches_the_workspace_entry_point_twice_in_a_row():
+    big = wl.ConvLayer("stem_k192", 2, 40, 36, 3, 192, 7, 7, 2, 3)     # 3 x 23 KB of the scratch array
+    small = wl.ConvLayer("stem_k64", 1, 22, 30, 3, 64, 7, 7, 2, 3)     # 23 KB: the rest keeps the first call's bytes
+    assert sdgp.conv_bwd_data_workspace(2, 40, 36, 3, 192, 7, 7, 2, 3, sdgp.BF16, 2, 4) == 3 * 23 * 1024
+    for layer in (big, small):
+        run_pair(layer, 2, 4, sdgp.GREEDY_ADJUSTED, 5)
+    for layer in (big, small):
+        run_pair(layer, 2, 8, sdgp.RANDOM, 6)
+    run_pair(small, 4, 4, sdgp.GREEDY, 0)
+
+
+def test_noalloc_without_scratch_and_refusal():
+    # a layer that needs no scratch at all goes straight through
+    layer = wl.ConvLayer("c3x3", 3, 12, 10, 16, 32, 3, 3, 1, 1)
+    run_pair(layer, 2, 4, sdgp.GREEDY, 1)
+    # more scratch than the array holds: refused, the output is untouched
+    wide = wl.ConvLayer("stem_k768", 1, 16, 16, 3, 768, 7, 7, 2, 3)
+    d = torch.zeros(wide.dO_shape, dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros(wide.W_shape, dtype=torch.bfloat16, device="cuda")
+    out = torch.full(wide.dD_shape, 3.0, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sdgp.SdgpError) as e:
+        sdgp.sdgp_conv_bwd_data_noalloc(d, w, wide.H, wide.Wd, 2, 3, 2, 4, sdgp.GREEDY, 0, out)
+    assert e.value.status == -6
+    assert torch.all(out == 3.0)
