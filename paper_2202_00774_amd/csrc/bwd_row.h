@@ -47,6 +47,7 @@ struct RowParams {
     int TB, TH, TW;              // tile: TB images x TH x TW pixels (<= the kernel's ROWS)
     int tiles_h, tiles_w;
     int halo_max;                // upper bound of the halo pixels of any tile (LDS sizing)
+    int npad;                    // positions of the zero-padded halo grid of a tile: TB * (TH + R - 1) * (TW + 2)
     int ups;                     // halo copy units per stage: a 1/R share of the halo, at most 16
     int ntiles_n, nblocks;
 };
@@ -63,24 +64,31 @@ struct RowLayout {
     static constexpr int kWSlab = kRowKC * kWRow;
     static constexpr int kWUnits = kWSlab / 1024;
     static constexpr int kWSet = kRowTaps * kWSlab;            // the slabs of one filter row
-    static constexpr int kAPitch = kSparse ? 32 : 64;
+    static constexpr int kAPitch = 64;                         // dense and zero-filled halo: 32 channels per pixel
     static constexpr int kRawSlot = 16 * 1024;
     static constexpr int kOutPitch = BN * 2 + 16;
     __host__ __device__ static int pad16(int halo) { return (halo + 15) & ~15; }
     __host__ __device__ static int pixels(int halo) { return pad16(halo) + 16; }  // + one all-zero pixel
     __host__ __device__ static int zero_pixel(int halo) { return pad16(halo); }
+    // Compressed halo (kSparse): a zero-padded grid of `npad` positions, in planes -- per buffer two planes of kept
+    // values (16 bytes per position: the eight survivors of sixteen channels) and two planes of their 2-bit positions
+    // (2 bytes per position), one plane per half of the 32-channel chunk.  Plane sizes are 128 modulo 256 bytes, so
+    // the two planes a wavefront touches in one access fall into different halves of the banks.
+    __host__ __device__ static int plane_a(int npad) { return ((npad * 16 + 255) & ~255) + 128; }
+    __host__ __device__ static int plane_m(int npad) { return ((npad * 2 + 255) & ~255) + 128; }
     __host__ __device__ static int off_rowpix() { return 0; }
     __host__ __device__ static int off_out() { return ROWS * 4; }
     __host__ __device__ static int off_w() { return off_out(); }
     __host__ __device__ static int off_atab() { return off_w() + 2 * kWSet; }
-    __host__ __device__ static int off_haloaddr() { return off_atab() + kRowMaxRows * kRowTaps * ROWS * 4; }
-    __host__ __device__ static int off_raw(int halo) { return off_haloaddr() + pixels(halo) * 8; }
+    __host__ __device__ static int off_haloaddr() { return off_atab() + (kSparse ? 0 : kRowMaxRows * kRowTaps * ROWS * 4); }
+    __host__ __device__ static int off_halopos(int halo) { return off_haloaddr() + pixels(halo) * 8; }
+    __host__ __device__ static int off_raw(int halo) { return off_halopos(halo) + (kSparse ? pixels(halo) * 4 : 0); }
     __host__ __device__ static int off_a(int halo) { return off_raw(halo) + (kPrunes ? 2 * kRawSlot : 0); }
-    __host__ __device__ static int a_bytes(int halo) { return pixels(halo) * kAPitch; }
-    __host__ __device__ static int off_meta(int halo) { return off_a(halo) + 2 * a_bytes(halo); }
-    __host__ __device__ static int meta_bytes(int halo) { return kSparse ? pixels(halo) * 4 : 0; }
-    __host__ __device__ static int total(int halo) {
-        const int loop = off_meta(halo) + 2 * meta_bytes(halo);
+    __host__ __device__ static int a_bytes(int halo, int npad) { return kSparse ? 2 * plane_a(npad) : pixels(halo) * kAPitch; }
+    __host__ __device__ static int off_meta(int halo, int npad) { return off_a(halo) + 2 * a_bytes(halo, npad); }
+    __host__ __device__ static int meta_bytes(int npad) { return kSparse ? 2 * plane_m(npad) : 0; }
+    __host__ __device__ static int total(int halo, int npad) {
+        const int loop = off_meta(halo, npad) + 2 * meta_bytes(npad);
         const int out = off_out() + ROWS * kOutPitch;
         return loop > out ? loop : out;
     }
@@ -147,10 +155,17 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     typedef unsigned long long u64_t;
     SDGP_LDS u64_t* haloaddr = (SDGP_LDS u64_t*)(smem + L::off_haloaddr());
     SDGP_LDS uint32_t* atab = (SDGP_LDS uint32_t*)(smem + L::off_atab());
-    const uint32_t off_a = (uint32_t)L::off_a(p.halo_max), a_buf_bytes = (uint32_t)L::a_bytes(p.halo_max);
-    const uint32_t off_meta = (uint32_t)L::off_meta(p.halo_max), meta_buf_bytes = (uint32_t)L::meta_bytes(p.halo_max);
+    const uint32_t off_a = (uint32_t)L::off_a(p.halo_max), a_buf_bytes = (uint32_t)L::a_bytes(p.halo_max, p.npad);
+    const uint32_t off_meta = (uint32_t)L::off_meta(p.halo_max, p.npad), meta_buf_bytes = (uint32_t)L::meta_bytes(p.npad);
     const uint32_t off_raw = (uint32_t)L::off_raw(p.halo_max);
     const uint32_t zero_pix = (uint32_t)L::zero_pixel(p.halo_max);
+    // compressed halo: the zero-padded grid of the positions the tile's taps reach, image borders included
+    // (tap (r, s) of tile pixel (hl, wl) reads grid position (hl + R - 1 - r, wl + 2 - s)); positions outside the
+    // gradient stay zero, so a tap is a constant offset from a row's base position and needs no table
+    const int GH = p.TH + R - 1, GW = p.TW + TS - 1;
+    const int g_p0 = hh0 + p.pad - (R - 1), g_q0 = ww0 + p.pad - (TS - 1);  // gradient pixel of grid position (0, 0)
+    const uint32_t plane_a = (uint32_t)L::plane_a(p.npad), plane_m = (uint32_t)L::plane_m(p.npad);
+    SDGP_LDS uint32_t* halopos = (SDGP_LDS uint32_t*)(smem + L::off_halopos(p.halo_max));
     const uint16_t* const gdO = p.dO;
     const unsigned char* const gWb = reinterpret_cast<const unsigned char*>(p.W);
 
@@ -165,7 +180,9 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         if (hp < nhalo) {
             const int tb = hp / halo_hw, rem = hp % halo_hw;
             const int b = min(b0 + tb, p.B - 1);  // images past the batch: valid memory, rows never stored
-            gp = ((size_t)b * p.P + (py0 + rem / HTW)) * p.Q + (qx0 + rem % HTW);
+            const int py = py0 + rem / HTW, qx = qx0 + rem % HTW;
+            gp = ((size_t)b * p.P + py) * p.Q + qx;
+            if constexpr (SPARSE) halopos[hp] = (uint32_t)((tb * GH + (py - g_p0)) * GW + (qx - g_q0));
         }
         haloaddr[hp] = (u64_t)(uintptr_t)(gdO + gp * p.C_out);
     }
@@ -184,19 +201,27 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
             }
         }
         rowpix[m] = pix;
-        for (int r = 0; r < R; ++r)
-            for (int sx = 0; sx < TS; ++sx) {
-                const int pp = h + p.pad - r, qq = w + p.pad - sx;
-                const bool inside = live && pp >= 0 && pp < p.P && qq >= 0 && qq < p.Q;
-                const uint32_t hp = inside ? (uint32_t)(rowbase + (p.pad - r) * HTW + (p.pad - sx)) : zero_pix;
-                atab[(r * TS + sx) * ROWS + m] = SPARSE ? hp * 32u : hp * 64u + (((hp >> 2) & 3u) << 4);
-            }
+        if constexpr (!SPARSE) {
+            for (int r = 0; r < R; ++r)
+                for (int sx = 0; sx < TS; ++sx) {
+                    const int pp = h + p.pad - r, qq = w + p.pad - sx;
+                    const bool inside = live && pp >= 0 && pp < p.P && qq >= 0 && qq < p.Q;
+                    const uint32_t hp = inside ? (uint32_t)(rowbase + (p.pad - r) * HTW + (p.pad - sx)) : zero_pix;
+                    atab[(r * TS + sx) * ROWS + m] = hp * 64u + (((hp >> 2) & 3u) << 4);
+                }
+        }
       }
-      if (tid < 64) {
-        // the zero pixel of both halo buffers; compressed format: values 0 and positions (0, 1) in every quad
-        const uint32_t buf = tid >> 5, i = tid & 31;
-        if (i < L::kAPitch / 4) *(SDGP_LDS uint32_t*)(smem + off_a + buf * a_buf_bytes + zero_pix * L::kAPitch + i * 4) = 0u;
-        if (SPARSE && i == 31) *(SDGP_LDS uint32_t*)(smem + off_meta + buf * meta_buf_bytes + zero_pix * 4) = 0x44444444u;
+      if constexpr (!SPARSE) {
+        if (tid < 32) {
+            // the zero pixel of both halo buffers
+            const uint32_t buf = tid >> 4, i = tid & 15;
+            *(SDGP_LDS uint32_t*)(smem + off_a + buf * a_buf_bytes + zero_pix * L::kAPitch + i * 4) = 0u;
+        }
+      } else {
+        // both compressed buffers start as zeros: values 0 (and positions 0) wherever the ranking never writes
+        const u32x4_t z = {0u, 0u, 0u, 0u};
+        const uint32_t bytes = 2u * a_buf_bytes + 2u * meta_buf_bytes;  // the value planes and the position planes are adjacent
+        for (uint32_t o = (uint32_t)tid * 16u; o < bytes; o += 512u * 16u) *(SDGP_LDS u32x4_t*)(smem + off_a + o) = z;
       }
     };
 
@@ -292,8 +317,9 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 uint32_t packed[4], meta;
                 prune16_compressed<M, RK>(v, p.n, p.mix, e0, packed, meta);
                 const u32x4_t x = {packed[0], packed[1], packed[2], packed[3]};
-                *(SDGP_LDS u32x4_t*)(smem + abuf + hp * 32 + part * 16) = x;
-                *(SDGP_LDS uint16_t*)(smem + mbuf + hp * 4 + part * 2) = (uint16_t)meta;
+                const uint32_t pos = halopos[hp];
+                *(SDGP_LDS u32x4_t*)(smem + abuf + (uint32_t)part * plane_a + pos * 16u) = x;
+                *(SDGP_LDS uint16_t*)(smem + mbuf + (uint32_t)part * plane_m + pos * 2u) = (uint16_t)meta;
             }
         }
     };
@@ -362,11 +388,36 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         for (int t = 0; t < TM; ++t) a_ent[t] = a_ent_n[t];
     };
     const uint32_t a_k0 = half << 4;
-    const uint32_t m_k0 = half * 2u;
-    auto load_a = [&](Frags& f, int t, uint32_t abuf, uint32_t mbuf, int ks) {
+    // compressed halo: per row tile the lane's byte offsets into the value and position planes of its half of the
+    // chunk, at the grid position of the row's LAST tap of filter row 0 (tap s of filter row r sits (TS - 1 - s)
+    // positions after it and r grid rows before); a_stage / m_stage add the buffer and the filter row once per stage
+    uint32_t lane_a[TM], lane_m[TM], a_stage[TM], m_stage[TM];
+    if constexpr (SPARSE) {
+#pragma unroll
+        for (int t = 0; t < TM; ++t) {
+            const int m = wm * WM + t * 32 + (lane & 31);
+            int pos = (R - 1) * GW;  // rows without an output pixel read image 0's first grid positions: valid memory
+            if (m < tile_rows) {
+                const int tb = m / tile_hw, rem = m % tile_hw;
+                const int hl = rem / p.TW, wl = rem % p.TW;
+                if (b0 + tb < p.B && hh0 + hl < p.H && ww0 + wl < p.Wd) pos = (tb * GH + hl + R - 1) * GW + wl;
+            }
+            lane_a[t] = half * plane_a + (uint32_t)pos * 16u;
+            lane_m[t] = half * plane_m + (uint32_t)pos * 2u;
+        }
+    }
+    auto set_stage = [&](uint32_t abuf, uint32_t mbuf, int frow) {
         if constexpr (SPARSE) {
-            f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] | a_k0) + abuf));
-            f.meta[t] = *(SDGP_LDS uint16_t*)(smem + (((a_ent[t] >> 3) | m_k0) + mbuf));
+            const uint32_t back = (uint32_t)(frow * GW);
+#pragma unroll
+            for (int t = 0; t < TM; ++t) a_stage[t] = lane_a[t] + (abuf - back * 16u), m_stage[t] = lane_m[t] + (mbuf - back * 2u);
+        }
+    };
+    // tap: position in the filter row (compressed halo); ks: k-step inside the chunk (table-driven halo)
+    auto load_a = [&](Frags& f, int t, uint32_t abuf, int tap, int ks) {
+        if constexpr (SPARSE) {
+            f.a[t] = *(SDGP_LDS u32x4_t*)(smem + a_stage[t] + (TS - 1 - tap) * 16);
+            f.meta[t] = *(SDGP_LDS uint16_t*)(smem + m_stage[t] + (TS - 1 - tap) * 2);
         } else {
             f.a[t] = *(SDGP_LDS u32x4_t*)(smem + ((a_ent[t] ^ (a_k0 | (uint32_t)(ks * 32))) + abuf));
         }
@@ -420,10 +471,14 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
         const int npc = row_last ? pc_next : pc;
         const bool more = x + 1 < nstages;
         // first k-step: nothing of this stage was requested before the barrier except the table entries
-        read_entries(pr * TS);
-        take_entries();
+        if constexpr (SPARSE) {
+            set_stage(abuf, mbuf, pr);
+        } else {
+            read_entries(pr * TS);
+            take_entries();
+        }
 #pragma unroll
-        for (int t = 0; t < TM; ++t) load_a(f0, t, abuf, mbuf, 0);
+        for (int t = 0; t < TM; ++t) load_a(f0, t, abuf, 0, 0);
 #pragma unroll
         for (int u = 0; u < TN; ++u) load_b(f0, u, set_off, 0);
         // share r of the next chunk's halo: one item per lane of the whole workgroup.  The two wavefronts of a SIMD
@@ -460,14 +515,18 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
             const int npieces = 1 + APIECES + TN + (q == 0 ? 3 : 0);
             auto piece = [&](int i) {
                 if (i == 0) {
-                    if (entries_now) read_entries(pr * TS + tap + 1);
-                    if (NKS == 1 && new_tap) read_entries(pr * TS + ntap);
+                    if constexpr (!SPARSE) {
+                        if (entries_now) read_entries(pr * TS + tap + 1);
+                        if (NKS == 1 && new_tap) read_entries(pr * TS + ntap);
+                    }
                 } else if (i <= APIECES) {
                     if (has_next) {
-                        if (i == 1 && new_tap) take_entries();
+                        if constexpr (!SPARSE) {
+                            if (i == 1 && new_tap) take_entries();
+                        }
                         const int t0 = 2 * (i - 1);
-                        load_a(nxt, t0, abuf, mbuf, nks);
-                        if (t0 + 1 < TM) load_a(nxt, t0 + 1, abuf, mbuf, nks);
+                        load_a(nxt, t0, abuf, ntap, nks);
+                        if (t0 + 1 < TM) load_a(nxt, t0 + 1, abuf, ntap, nks);
                     }
                 } else if (i <= APIECES + TN) {
                     if (has_next) load_b(nxt, i - APIECES - 1, set_off + (uint32_t)ntap * L::kWSlab, nks);

@@ -8,7 +8,7 @@ namespace sdgp {
 template <int BN, int MODE, int M, int RK, int ROWS>
 int launch_row_one(const RowParams& p, hipStream_t stream) {
     using L = RowLayout<BN, MODE, ROWS>;
-    const int lds = L::total(p.halo_max);
+    const int lds = L::total(p.halo_max, p.npad);
     if (lds > 160 * 1024) return SDGP_ERR_SHAPE;
     auto kern = bwd_row<BN, MODE, M, RK, ROWS>;
     static const hipError_t attr =

@@ -15,7 +15,7 @@ int launch_row_masked_m4(const RowParams& p, int bn, int rows, int rk, hipStream
 int launch_row_masked_m8(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
 int launch_row_masked_m16(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
 int launch_row_masked_m32(const RowParams& p, int bn, int rows, int rk, hipStream_t stream);
-int row_lds_bytes(int mode, int bn, int rows, int halo);
+int row_lds_bytes(int mode, int bn, int rows, int halo, int npad);
 
 namespace {
 
@@ -24,7 +24,7 @@ namespace {
 int64_t plan_tiles(RowParams& p, int rows, int mode, int bn, int64_t B, int64_t H, int64_t Wd, int R, int S, int64_t P, int64_t Q) {
     const int ntaps = R * S;
     double best = 1e300;
-    int bTB = 0, bTH = 0, bTW = 0, bhalo = 0;
+    int bTB = 0, bTH = 0, bTW = 0, bhalo = 0, bnpad = 0;
     for (int TH = 1; TH <= std::min((int)H, rows); ++TH) {
         for (int TW = 1; TW <= std::min((int)Wd, rows / TH); ++TW) {
             const int tb_max = std::max(1, std::min((int)B, rows / (TH * TW)));
@@ -33,10 +33,11 @@ int64_t plan_tiles(RowParams& p, int rows, int mode, int bn, int64_t B, int64_t 
                 const int halo = TB * (int)std::min<int64_t>(TH + R - 1, P) * (int)std::min<int64_t>(TW + S - 1, Q);
                 const int units = (halo + 15) / 16;
                 if (units > 16 * R) continue;
-                if (row_lds_bytes(mode, bn, rows, halo) > 160 * 1024) continue;
+                const int npad = TB * (TH + R - 1) * (TW + S - 1);  // the same window with the image borders
+                if (row_lds_bytes(mode, bn, rows, halo, npad) > 160 * 1024) continue;
                 const double tiles = (double)((B + TB - 1) / TB) * ((H + TH - 1) / TH) * ((Wd + TW - 1) / TW);
                 const double cost = tiles * (rows * (double)ntaps + 2.0 * halo + 64.0);
-                if (cost < best || (cost == best && TW > bTW)) best = cost, bTB = TB, bTH = TH, bTW = TW, bhalo = halo;
+                if (cost < best || (cost == best && TW > bTW)) best = cost, bTB = TB, bTH = TH, bTW = TW, bhalo = halo, bnpad = npad;
             }
         }
     }
@@ -45,6 +46,7 @@ int64_t plan_tiles(RowParams& p, int rows, int mode, int bn, int64_t B, int64_t 
     p.tiles_h = ((int)H + p.TH - 1) / p.TH;
     p.tiles_w = ((int)Wd + p.TW - 1) / p.TW;
     p.halo_max = bhalo;
+    p.npad = bnpad;
     p.ups = (((bhalo + 15) / 16) + R - 1) / R;
     return (int64_t)((B + p.TB - 1) / p.TB) * p.tiles_h * p.tiles_w * p.ntiles_n;
 }

@@ -38,5 +38,4 @@ __device__ __forceinline__ void prune16_compressed(const u32x4_t (&v)[2], int n,
     prune_compress16<M, RK>(w, n, mix, e0, packed, meta);
 }
 
-
 }  // namespace sdgp
