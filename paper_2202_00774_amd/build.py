@@ -60,5 +60,16 @@ def build(force: bool = False, jobs: int = 8) -> str:
     return LIB
 
 
+def build_test_helpers() -> str:
+    """tests/native/libmatrix_layout_probe.so: the single-instruction kernels the lane-layout GPU test runs."""
+    src = os.path.join(ROOT, "tests", "native", "matrix_layout_probe.hip")
+    out = os.path.join(ROOT, "tests", "native", "libmatrix_layout_probe.so")
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-O2", "-std=c++17", "-fPIC", "-shared", "-Xclang", "-target-feature",
+                    "-Xclang", "-packed-fp32-ops", src, "-o", out + ".tmp"], check=True, capture_output=True)
+    os.replace(out + ".tmp", out)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))
+    print(build_test_helpers())
