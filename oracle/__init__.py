@@ -62,6 +62,11 @@ def _load():
             lib.sdgp_ref_conv_bwd_data_at.restype = i32
             lib.sdgp_ref_conv_bwd_data_at.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32,
                                                       i32, i32, vp, i64, vp, vp]
+            lib.sdgp_ref_conv_fwd.restype = i32
+            lib.sdgp_ref_conv_fwd.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, i64, vp, vp]
+            lib.sdgp_ref_conv_bwd_weight.restype = i32
+            lib.sdgp_ref_conv_bwd_weight.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, i64,
+                                                     vp, vp]
             lib.sdgp_ref_threads.restype = i32
             lib.sdgp_ref_threads.argtypes = []
             _lib = lib
@@ -205,3 +210,58 @@ def conv_bwd_data(dOp: np.ndarray, W: np.ndarray, H: int, Wd: int, stride: int, 
     if rc != 0:
         raise ValueError("sdgp_ref_conv_bwd_data rejected its arguments")
     return dD, ab
+
+
+def conv_fwd(D: np.ndarray, W: np.ndarray, stride: int, pad: int, dtype: int | None = None,
+             pixels: np.ndarray | None = None):
+    """Forward convolution of D [B,H,Wd,C_in] with W [C_out,R,S,C_in] (Sec. II-A, Fig. 1).
+
+    Returns ``(O, absum)`` as fp64 [B,P,Q,C_out]; with ``pixels`` (flat ``(b*P+p)*Q+q`` indices) only those output
+    pixels, as [len(pixels), C_out].
+    """
+    if dtype is None:
+        dtype = F32 if D.dtype == np.float32 else BF16
+    D, W = _check(D, dtype, "D"), _check(W, dtype, "W")
+    B, H, Wd, C_in = D.shape
+    C_out, R, S, C2 = W.shape
+    if C2 != C_in:
+        raise ValueError("W must be [C_out, R, S, C_in]")
+    P, Q = conv_out_size(H, R, stride, pad), conv_out_size(Wd, S, stride, pad)
+    if pixels is None:
+        shape, px, cnt = (B, P, Q, C_out), None, 0
+    else:
+        px = np.ascontiguousarray(pixels, dtype=np.int64)
+        shape, cnt = (px.size, C_out), px.size
+    O, ab = np.empty(shape, np.float64), np.empty(shape, np.float64)
+    rc = _load().sdgp_ref_conv_fwd(_ptr(D), _ptr(W), B, H, Wd, C_in, C_out, R, S, stride, pad, dtype, _ptr(px), cnt,
+                                   _ptr(O), _ptr(ab))
+    if rc != 0:
+        raise ValueError("sdgp_ref_conv_fwd rejected its arguments")
+    return O, ab
+
+
+def conv_bwd_weight(D: np.ndarray, dO: np.ndarray, R: int, S: int, stride: int, pad: int, dtype: int | None = None,
+                    entries: np.ndarray | None = None):
+    """Weight gradient from D [B,H,Wd,C_in] and the UNPRUNED dO [B,P,Q,C_out] (Sec. II-A, Fig. 1; Sec. III-A).
+
+    Returns ``(dW, absum)`` as fp64 [C_out,R,S,C_in]; with ``entries`` (flat ``((k*R+r)*S+s)*C_in+c`` indices) only
+    those filter elements, as [len(entries)].
+    """
+    if dtype is None:
+        dtype = F32 if D.dtype == np.float32 else BF16
+    D, dO = _check(D, dtype, "D"), _check(dO, dtype, "dO")
+    B, H, Wd, C_in = D.shape
+    B2, P, Q, C_out = dO.shape
+    if B2 != B or P != conv_out_size(H, R, stride, pad) or Q != conv_out_size(Wd, S, stride, pad):
+        raise ValueError("dO does not match D, R, S, stride, pad")
+    if entries is None:
+        shape, en, cnt = (C_out, R, S, C_in), None, 0
+    else:
+        en = np.ascontiguousarray(entries, dtype=np.int64)
+        shape, cnt = (en.size,), en.size
+    dW, ab = np.empty(shape, np.float64), np.empty(shape, np.float64)
+    rc = _load().sdgp_ref_conv_bwd_weight(_ptr(D), _ptr(dO), B, H, Wd, C_in, C_out, R, S, stride, pad, dtype, _ptr(en),
+                                          cnt, _ptr(dW), _ptr(ab))
+    if rc != 0:
+        raise ValueError("sdgp_ref_conv_bwd_weight rejected its arguments")
+    return dW, ab

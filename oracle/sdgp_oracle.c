@@ -15,7 +15,10 @@
  *     one factor per channel;
  *   - the backward-data product that consumes the pruned tensor (Fig. 1, Fig. 2,
  *     Fig. 3): a matrix product for a linear layer, the transposed correlation
- *     for a convolution layer.
+ *     for a convolution layer;
+ *   - the two other products of a layer's training step (Sec. II-A, Fig. 1): the
+ *     forward convolution and the weight gradient, which takes the unpruned
+ *     dL/dO (Sec. III-A).
  *
  * Arithmetic.  Ranking is integer work on bit patterns and is exact.  The
  * rescale of Rescaled Magnitude is done in IEEE fp32 in a fixed order because
@@ -388,6 +391,111 @@ int sdgp_ref_conv_bwd_data_at(const void* dOp, const void* W, int64_t B, int64_t
         int64_t w = pix % Wd, h = (pix / Wd) % H, b = pix / (Wd * H);
         conv_pixel(dOp, W, b, h, w, P, Q, C_in, C_out, R, S, stride, pad, dtype, dD + t * C_in,
                    absum ? absum + t * C_in : NULL);
+    }
+    return 0;
+}
+
+/* ---------------------------------------- forward and weight-gradient products */
+
+/*
+ * One output pixel of the forward convolution (Sec. II-A, Fig. 1 right, with the
+ * filter footprint written out instead of im2col):
+ *   O[b,p,q,k] = sum_{r,s,c} D[b, p*stride + r - pad, q*stride + s - pad, c] * W[k,r,s,c]
+ * Taps that fall outside the image contribute nothing (zero padding).  Same
+ * reading as for the backward product: correlation, dilation 1, one group.
+ */
+static void fwd_pixel(const void* D, const void* W, int64_t b, int64_t p, int64_t q, int64_t H, int64_t Wd,
+                      int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dtype,
+                      double* out, double* mag) {
+    for (int64_t k = 0; k < C_out; ++k) {
+        double acc = 0.0, am = 0.0;
+        for (int r = 0; r < R; ++r) {
+            int64_t h = p * stride + r - pad;
+            if (h < 0 || h >= H) continue;
+            for (int s = 0; s < S; ++s) {
+                int64_t w = q * stride + s - pad;
+                if (w < 0 || w >= Wd) continue;
+                for (int64_t c = 0; c < C_in; ++c) {
+                    double a = load_as_double(D, ((b * H + h) * Wd + w) * C_in + c, dtype);
+                    double v = load_as_double(W, ((k * R + r) * S + s) * C_in + c, dtype);
+                    acc += a * v;
+                    am += (a < 0 ? -a : a) * (v < 0 ? -v : v);
+                }
+            }
+        }
+        out[k] = acc;
+        if (mag) mag[k] = am;
+    }
+}
+
+/*
+ * Forward pass of a convolution layer: D [B,H,Wd,C_in], W [C_out,R,S,C_in] ->
+ * O and absum [B,P,Q,C_out] in fp64.  With pixels != NULL only the output
+ * pixels pixels[t] = (b*P + p)*Q + q are computed, as [count, C_out].
+ */
+int sdgp_ref_conv_fwd(const void* D, const void* W, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                      int64_t C_out, int R, int S, int stride, int pad, int dtype, const int64_t* pixels,
+                      int64_t count, double* O, double* absum) {
+    if (B < 0 || H < 0 || Wd < 0 || C_in < 0 || C_out < 0 || R < 1 || S < 1 || stride < 1 || pad < 0)
+        return -1;
+    if (H + 2 * pad < R || Wd + 2 * pad < S) return -1;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    const int64_t total = pixels ? count : B * P * Q;
+    if (pixels)
+        for (int64_t t = 0; t < count; ++t)
+            if (pixels[t] < 0 || pixels[t] >= B * P * Q) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < total; ++t) {
+        int64_t pix = pixels ? pixels[t] : t;
+        int64_t q = pix % Q, p = (pix / Q) % P, b = pix / (Q * P);
+        fwd_pixel(D, W, b, p, q, H, Wd, C_in, C_out, R, S, stride, pad, dtype, O + t * C_out,
+                  absum ? absum + t * C_out : NULL);
+    }
+    return 0;
+}
+
+/*
+ * Weight gradient of the same layer (Sec. II-A, Fig. 1 right: the second product of
+ * the backward pass).  Differentiating the forward sum with respect to W gives
+ *   dW[k,r,s,c] = sum_{b,p,q} dO[b,p,q,k] * D[b, p*stride + r - pad, q*stride + s - pad, c]
+ * over the output pixels whose tap (r,s) lies inside the image.  dO is the
+ * UNPRUNED output gradient: Sec. III-A keeps dO for this product and prunes a
+ * copy for the data gradient.  dW and absum are [C_out,R,S,C_in] in fp64; the sum
+ * runs over b, p, q ascending.  With entries != NULL only the filter elements
+ * entries[t] = ((k*R + r)*S + s)*C_in + c are computed, as [count].
+ */
+int sdgp_ref_conv_bwd_weight(const void* D, const void* dO, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                             int64_t C_out, int R, int S, int stride, int pad, int dtype,
+                             const int64_t* entries, int64_t count, double* dW, double* absum) {
+    if (B < 0 || H < 0 || Wd < 0 || C_in < 0 || C_out < 0 || R < 1 || S < 1 || stride < 1 || pad < 0)
+        return -1;
+    if (H + 2 * pad < R || Wd + 2 * pad < S) return -1;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    const int64_t nW = C_out * R * S * C_in;
+    const int64_t total = entries ? count : nW;
+    if (entries)
+        for (int64_t t = 0; t < count; ++t)
+            if (entries[t] < 0 || entries[t] >= nW) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < total; ++t) {
+        int64_t e = entries ? entries[t] : t;
+        int64_t c = e % C_in, s = (e / C_in) % S, r = (e / (C_in * S)) % R, k = e / (C_in * S * R);
+        double acc = 0.0, am = 0.0;
+        for (int64_t b = 0; b < B; ++b)
+            for (int64_t p = 0; p < P; ++p) {
+                int64_t h = p * stride + r - pad;
+                if (h < 0 || h >= H) continue;
+                for (int64_t q = 0; q < Q; ++q) {
+                    int64_t w = q * stride + s - pad;
+                    if (w < 0 || w >= Wd) continue;
+                    double g = load_as_double(dO, ((b * P + p) * Q + q) * C_out + k, dtype);
+                    double a = load_as_double(D, ((b * H + h) * Wd + w) * C_in + c, dtype);
+                    acc += g * a;
+                    am += (g < 0 ? -g : g) * (a < 0 ? -a : a);
+                }
+            }
+        dW[t] = acc;
+        if (absum) absum[t] = am;
     }
     return 0;
 }
