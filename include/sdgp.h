@@ -217,6 +217,39 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
                                         int stride, int pad, int dt, int n, int m, void* workspace,
                                         size_t workspace_bytes, void* hip_stream);
 
+/*
+ * The two other products of a layer's training step (Sec. II-A, Fig. 1; Sec. IV-C, Fig. 9 times all three).
+ * Neither prunes anything: SDGP touches only the data gradient, and Sec. III-A keeps the unpruned dL/dO for the
+ * weight gradient.  They exist so that a whole step of a layer can run, and be timed, on this library's kernels.
+ *
+ * sdgp_conv_fwd          O[b,p,q,k] = sum_{r,s,c} D[b, p*stride + r - pad, q*stride + s - pad, c] * W[k,r,s,c]
+ *                        D [B,H,Wd,C_in], W [C_out,R,S,C_in], O [B,P,Q,C_out], all `dt`; fp32 accumulation, RNE
+ *                        on output; taps outside the image contribute nothing.  With stride 1 and R == S the
+ *                        dense matrix-core kernels of the backward-data path compute it from a mirrored,
+ *                        transposed copy of W that the call builds in the workspace; other layers take a
+ *                        plain kernel.  O 16-byte aligned for the matrix-core path.
+ * sdgp_conv_bwd_weight   dW[k,r,s,c] = sum_{b,p,q} dO[b,p,q,k] * D[b, p*stride + r - pad, q*stride + s - pad, c]
+ *                        D and dO `dt`, dO UNPRUNED; dW [C_out,R,S,C_in] is written in fp32 whatever `dt` is.
+ *                        bf16, stride 1, 3x3, C_in and C_out multiples of 64: matrix-core kernel whose workgroups
+ *                        split the pixels and leave fp32 partial filters in the workspace, added in a fixed
+ *                        order by a second kernel (the result is the same from call to call); other layers
+ *                        take a plain reduction kernel.  D and dO 16-byte aligned for the matrix-core path.
+ *
+ * workspace: sdgp_conv_fwd_workspace(...) / sdgp_conv_bwd_weight_workspace(...) bytes (0 for layers that need none),
+ * 16-byte aligned, contents undefined afterwards; the queries return (size_t)-1 for invalid arguments.  Geometry
+ * rules and error behaviour are those of sdgp_conv_bwd_data (without n, m, ranker, seed).
+ */
+size_t sdgp_conv_fwd_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
+                               int stride, int pad, int dt);
+int sdgp_conv_fwd(const void* D, const void* W, void* O, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                  int64_t C_out, int R, int S, int stride, int pad, int dt, void* workspace,
+                  size_t workspace_bytes, void* hip_stream);
+size_t sdgp_conv_bwd_weight_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R,
+                                      int S, int stride, int pad, int dt);
+int sdgp_conv_bwd_weight(const void* D, const void* dO, float* dW, int64_t B, int64_t H, int64_t Wd,
+                         int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dt,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* sdgp_status_string(int status);
 

@@ -24,6 +24,7 @@ EXPORTS = ("sdgp_prune", "sdgp_linear_bwd_data", "sdgp_conv_bwd_data", "sdgp_con
            "sdgp_conv_bwd_data_noalloc",
            "sdgp_channel_scales_workspace", "sdgp_channel_scales", "sdgp_prune_channel_rescaled", "sdgp_scale_filter",
            "sdgp_conv_bwd_data_channel_rescaled_workspace", "sdgp_conv_bwd_data_channel_rescaled",
+           "sdgp_conv_fwd_workspace", "sdgp_conv_fwd", "sdgp_conv_bwd_weight_workspace", "sdgp_conv_bwd_weight",
            "sdgp_status_string", "sdgp_version")
 
 
@@ -72,6 +73,15 @@ def load():
             lib.sdgp_conv_bwd_data_channel_rescaled.restype = i32
             lib.sdgp_conv_bwd_data_channel_rescaled.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32,
                                                                i32, i32, i32, vp, sz, vp]
+            geom = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i32]
+            lib.sdgp_conv_fwd_workspace.restype = sz
+            lib.sdgp_conv_fwd_workspace.argtypes = geom
+            lib.sdgp_conv_fwd.restype = i32
+            lib.sdgp_conv_fwd.argtypes = [vp, vp, vp] + geom + [vp, sz, vp]
+            lib.sdgp_conv_bwd_weight_workspace.restype = sz
+            lib.sdgp_conv_bwd_weight_workspace.argtypes = geom
+            lib.sdgp_conv_bwd_weight.restype = i32
+            lib.sdgp_conv_bwd_weight.argtypes = [vp, vp, vp] + geom + [vp, sz, vp]
             lib.sdgp_status_string.restype = ctypes.c_char_p
             lib.sdgp_status_string.argtypes = [i32]
             lib.sdgp_version.restype = i32
@@ -298,3 +308,54 @@ def sdgp_linear_bwd_data_channel_rescaled(dO: torch.Tensor, W: torch.Tensor, n: 
     rows, C_out = dO.shape
     out = sdgp_conv_bwd_data_channel_rescaled(dO.view(rows, 1, 1, C_out), W.view(C_out, 1, 1, W.shape[1]), 1, 1, 1, 0, n, m)
     return out.view(rows, W.shape[1])
+
+
+# ---------------------------------------------- the two other products of a layer's step (nothing is pruned)
+
+def sdgp_conv_fwd(D: torch.Tensor, W: torch.Tensor, stride: int, pad: int, out: torch.Tensor | None = None,
+                  workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """O [B,P,Q,C_out] from D [B,H,Wd,C_in] (NHWC) and W [C_out,R,S,C_in]."""
+    _dev(D, "D"), _dev(W, "W")
+    if D.dim() != 4 or W.dim() != 4 or W.shape[3] != D.shape[3] or W.dtype != D.dtype:
+        raise ValueError("expected D [B,H,Wd,C_in] and W [C_out,R,S,C_in] of one dtype")
+    B, H, Wd, C_in = D.shape
+    C_out, R, S, _ = W.shape
+    P, Q = (H + 2 * pad - R) // stride + 1, (Wd + 2 * pad - S) // stride + 1
+    if out is None:
+        out = torch.empty((B, max(P, 0), max(Q, 0), C_out), dtype=D.dtype, device=D.device)
+    _dev(out, "out")
+    dt = _dtype_code(D)
+    lib = load()
+    need = int(lib.sdgp_conv_fwd_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt))
+    workspace, wbytes = _workspace(need, workspace, D.device, "sdgp_conv_fwd_workspace")
+    rc = lib.sdgp_conv_fwd(_ptr(D), _ptr(W), _ptr(out), B, H, Wd, C_in, C_out, R, S, stride, pad, dt, _ptr(workspace), wbytes,
+                           _stream(D))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_conv_fwd")
+    return out
+
+
+def sdgp_conv_bwd_weight(D: torch.Tensor, dO: torch.Tensor, R: int, S: int, stride: int, pad: int,
+                         out: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """dW [C_out,R,S,C_in] in float32 from D [B,H,Wd,C_in] and the unpruned dO [B,P,Q,C_out]."""
+    _dev(D, "D"), _dev(dO, "dO")
+    if D.dim() != 4 or dO.dim() != 4 or dO.shape[0] != D.shape[0] or dO.dtype != D.dtype:
+        raise ValueError("expected D [B,H,Wd,C_in] and dO [B,P,Q,C_out] of one dtype")
+    B, H, Wd, C_in = D.shape
+    _, P, Q, C_out = dO.shape
+    if (H + 2 * pad - R) // stride + 1 != P or (Wd + 2 * pad - S) // stride + 1 != Q:
+        raise ValueError("dO's spatial size does not match D, R, S, stride, pad")
+    if out is None:
+        out = torch.empty((C_out, R, S, C_in), dtype=torch.float32, device=D.device)
+    _dev(out, "out")
+    if out.dtype != torch.float32 or tuple(out.shape) != (C_out, R, S, C_in):
+        raise ValueError("out must be float32 [C_out,R,S,C_in]")
+    dt = _dtype_code(D)
+    lib = load()
+    need = int(lib.sdgp_conv_bwd_weight_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt))
+    workspace, wbytes = _workspace(need, workspace, D.device, "sdgp_conv_bwd_weight_workspace")
+    rc = lib.sdgp_conv_bwd_weight(_ptr(D), _ptr(dO), _ptr(out), B, H, Wd, C_in, C_out, R, S, stride, pad, dt,
+                                  _ptr(workspace), wbytes, _stream(D))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_conv_bwd_weight")
+    return out

@@ -34,6 +34,12 @@ int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n
 int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, const float* scale,
                                   void* pruned, hipStream_t stream);
 int scale_rows_launch(const void* W, const float* scale, void* out, int64_t C_out, int64_t inner, int dt, hipStream_t stream);
+int mirror_transpose_filter_launch(const void* W, void* V, int64_t C_out, int64_t C_in, int R, int S, int dt, hipStream_t stream);
+int fwd_simple_launch(const void* D, const void* W, void* O, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                      int R, int S, int stride, int pad, int dt, hipStream_t stream);
+size_t wgrad_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dt);
+int wgrad_launch(const void* D, const void* dO, float* dW, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                 int R, int S, int stride, int pad, int dt, void* workspace, hipStream_t stream);
 }  // namespace sdgp
 
 // Scratch memory of sdgp_conv_bwd_data_noalloc: lives in the library's device image, one copy per GPU, for the life
@@ -303,6 +309,63 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
     rc = sdgp::scale_rows_launch(W, scale, filter, C_out, (int64_t)R * S * C_in, dt, stream);
     if (rc != SDGP_OK) return rc;
     return bwd_dispatch(dO, filter, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, nullptr, stream);
+}
+
+// The forward sum is a backward-data sum of the mirrored, transposed filter when stride is 1 and the filter square;
+// the matrix-core kernels take it when the transposed problem's channel counts suit them (its reduction runs over C_in).
+static bool fwd_as_bwd(int64_t C_in, int64_t C_out, int R, int S, int stride) {
+    return stride == 1 && R == S && C_out > 4 && C_in > 0 && C_in % 32 == 0;
+}
+
+size_t sdgp_conv_fwd_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride,
+                               int pad, int dt) {
+    ConvGeom g;
+    if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, 1, 1, &g) != SDGP_OK) return (size_t)-1;
+    if (g.n_dO == 0 || !fwd_as_bwd(C_in, C_out, R, S, stride)) return 0;
+    return align256((size_t)g.n_W * (dt == SDGP_BF16 ? 2u : 4u));
+}
+
+int sdgp_conv_fwd(const void* D, const void* W, void* O, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                  int R, int S, int stride, int pad, int dt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ConvGeom g;
+    const int rc = check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, 1, 1, &g);
+    if (rc != SDGP_OK) return rc;
+    if (g.n_dO == 0) return SDGP_OK;  // O has no element
+    if (O == nullptr || (g.n_dD > 0 && D == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const size_t need = sdgp_conv_fwd_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt);
+    if (need == 0) return sdgp::fwd_simple_launch(D, W, O, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, stream);
+    if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0)
+        return SDGP_ERR_WORKSPACE;
+    const int rc2 = sdgp::mirror_transpose_filter_launch(W, workspace, C_out, C_in, R, S, dt, stream);
+    if (rc2 != SDGP_OK) return rc2;
+    // backward-data problem with the channel axes exchanged: "gradient" D [B,H,Wd,C_in], "input" O [B,P,Q,C_out]
+    return bwd_dispatch(D, workspace, O, B, g.P, g.Q, C_out, C_in, R, S, 1, R - 1 - pad, dt, 1, 1, SDGP_GREEDY, 0, nullptr, stream);
+}
+
+size_t sdgp_conv_bwd_weight_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
+                                      int stride, int pad, int dt) {
+    ConvGeom g;
+    if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, 1, 1, &g) != SDGP_OK) return (size_t)-1;
+    if (g.n_W == 0) return 0;
+    return sdgp::wgrad_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt);
+}
+
+int sdgp_conv_bwd_weight(const void* D, const void* dO, float* dW, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                         int64_t C_out, int R, int S, int stride, int pad, int dt, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+    ConvGeom g;
+    const int rc = check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, 1, 1, &g);
+    if (rc != SDGP_OK) return rc;
+    if (g.n_W == 0) return SDGP_OK;
+    if (dW == nullptr || (g.n_dD > 0 && D == nullptr) || (g.n_dO > 0 && dO == nullptr)) return SDGP_ERR_NULL;
+    const size_t need = sdgp::wgrad_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt);
+    const bool aligned = sdgp::is_aligned16(D) && sdgp::is_aligned16(dO);  // unaligned tensors take the plain kernel
+    if (need > 0 && aligned &&
+        (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0))
+        return SDGP_ERR_WORKSPACE;
+    return sdgp::wgrad_launch(D, dO, dW, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, (need > 0 && aligned) ? workspace : nullptr,
+                              static_cast<hipStream_t>(hip_stream));
 }
 
 const char* sdgp_status_string(int status) {
