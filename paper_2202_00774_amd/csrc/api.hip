@@ -35,6 +35,8 @@ int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int d
                                   void* pruned, hipStream_t stream);
 int scale_rows_launch(const void* W, const float* scale, void* out, int64_t C_out, int64_t inner, int dt, hipStream_t stream);
 int mirror_transpose_filter_launch(const void* W, void* V, int64_t C_out, int64_t C_in, int R, int S, int dt, hipStream_t stream);
+int fwd_narrow_launch(const void* D, const void* W, void* O, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                      int R, int S, int stride, int pad, int dt, hipStream_t stream);
 int fwd_simple_launch(const void* D, const void* W, void* O, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                       int R, int S, int stride, int pad, int dt, hipStream_t stream);
 size_t wgrad_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dt);
@@ -334,7 +336,11 @@ int sdgp_conv_fwd(const void* D, const void* W, void* O, int64_t B, int64_t H, i
     if (O == nullptr || (g.n_dD > 0 && D == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const size_t need = sdgp_conv_fwd_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt);
-    if (need == 0) return sdgp::fwd_simple_launch(D, W, O, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, stream);
+    if (need == 0) {
+        const int rcn = sdgp::fwd_narrow_launch(D, W, O, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, stream);
+        if (rcn <= 0) return rcn;
+        return sdgp::fwd_simple_launch(D, W, O, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, stream);
+    }
     if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0)
         return SDGP_ERR_WORKSPACE;
     const int rc2 = sdgp::mirror_transpose_filter_launch(W, workspace, C_out, C_in, R, S, dt, stream);

@@ -328,6 +328,92 @@ __global__ void __launch_bounds__(kThreads) wgrad_small(SimpleArgs a, float* par
 
 bool small_filter(int64_t nW, int64_t npix) { return nW > 0 && nW <= kSmallElems && npix >= 4 * kSmallGroups; }
 
+// Layers with few input channels (a first layer, R*S*C_in of 27 or 147) and 64 or 128 output channels.  A workgroup
+// walks over segments of up to 64 pixels of one gradient row, with the segment's gradient values (fp32 [pixel][k]) and
+// the R image rows it touches in LDS.  Thread (k = tid % 64, g = tid / 64) owns filter elements (k, t) and (k + 64, t)
+// for t = g, g + 4, ... of the R*S*C_in patch positions: per pixel one gradient read per output channel and one
+// patch read per position (the same address in every lane of a wavefront), one FMA each.
+constexpr int kNarrowPix = 64;
+constexpr int kNarrowMaxT = 148;                  // 7 x 7 x 3 and below
+constexpr int kNarrowGroups = 1024;
+
+struct NarrowArgs {
+    const uint16_t* D;
+    const uint16_t* dO;
+    float* partial;                   // [gridDim.x][C_out * T]
+    int64_t B, segments;
+    int H, Wd, P, Q, C_in, C_out, R, S, stride, pad;
+    int T, SC, rowlen, qsegs;
+    uint32_t cin_magic;               // ceil(2^16 / C_in): x / C_in == (x * magic) >> 16 for the x of a staged row
+};
+
+template <int KB, int kNarrowSlots>   // C_out / 64; patch positions per thread: 4 * kNarrowSlots >= R*S*C_in
+__global__ void __launch_bounds__(kThreads) wgrad_narrow(NarrowArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float* const gl = lds;                                  // [64 pixels][64 * KB]
+    float* const halo = lds + kNarrowPix * 64 * KB;         // [R][rowlen]
+    const int tid = threadIdx.x, k = tid & 63, g = tid >> 6;
+    int off[kNarrowSlots];                                  // where patch position t = g + 4 i sits for pixel 0
+    float acc[KB][kNarrowSlots];
+#pragma unroll
+    for (int i = 0; i < kNarrowSlots; ++i) {
+        const int t = g + 4 * i, tt = t < a.T ? t : 0;
+        off[i] = (tt / a.SC) * a.rowlen + tt % a.SC;
+#pragma unroll
+        for (int u = 0; u < KB; ++u) acc[u][i] = 0.0f;
+    }
+    for (int64_t seg = blockIdx.x; seg < a.segments; seg += gridDim.x) {
+        const int q0 = (int)(seg % a.qsegs) * kNarrowPix;
+        const int p = (int)((seg / a.qsegs) % a.P);
+        const int64_t b = seg / ((int64_t)a.qsegs * a.P);
+        const int npx = a.Q - q0 < kNarrowPix ? a.Q - q0 : kNarrowPix;
+        __syncthreads();
+        for (int e = tid; e < kNarrowPix * 64 * KB; e += kThreads) {
+            const int px = e / (64 * KB), kk = e % (64 * KB);
+            gl[e] = px < npx ? bf16_to_float(a.dO[((b * a.P + p) * (int64_t)a.Q + q0 + px) * a.C_out + kk]) : 0.0f;
+        }
+        for (int r = 0; r < a.R; ++r) {
+            const int h = p * a.stride + r - a.pad;
+            const uint16_t* const src = a.D + ((b * a.H + h) * (int64_t)a.Wd + q0 * a.stride - a.pad) * a.C_in;
+            for (int x = tid; x < a.rowlen; x += kThreads) {
+                const int w = q0 * a.stride - a.pad + (int)(((uint32_t)x * a.cin_magic) >> 16);
+                halo[r * a.rowlen + x] = (h >= 0 && h < a.H && w >= 0 && w < a.Wd) ? bf16_to_float(src[x]) : 0.0f;
+            }
+        }
+        __syncthreads();
+        for (int px = 0; px < npx; ++px) {
+            float gv[KB];
+#pragma unroll
+            for (int u = 0; u < KB; ++u) gv[u] = gl[px * 64 * KB + u * 64 + k];
+            const float* const patch = halo + px * a.stride * a.C_in;
+#pragma unroll
+            for (int i = 0; i < kNarrowSlots; ++i) {   // a slot past the patch's end repeats position 0 and is not stored
+                const float xv = patch[off[i]];
+#pragma unroll
+                for (int u = 0; u < KB; ++u) acc[u][i] = fmaf(gv[u], xv, acc[u][i]);
+            }
+        }
+    }
+    float* const out = a.partial + (int64_t)blockIdx.x * a.C_out * a.T;
+#pragma unroll
+    for (int i = 0; i < kNarrowSlots; ++i) {
+        const int t = g + 4 * i;
+        if (t < a.T) {
+#pragma unroll
+            for (int u = 0; u < KB; ++u) out[(int64_t)(k + 64 * u) * a.T + t] = acc[u][i];
+        }
+    }
+}
+
+bool narrow_layer(int64_t C_in, int64_t C_out, int R, int S, int stride, int dt, int64_t H, int64_t Wd) {
+    const int64_t T = (int64_t)R * S * C_in;
+    if (dt != SDGP_BF16 || T > kNarrowMaxT || (C_out != 64 && C_out != 128) || C_in >= 32) return false;
+    if (H > (1 << 24) || Wd > (1 << 24)) return false;
+    const int64_t rowlen = ((kNarrowPix - 1) * stride + S) * C_in;
+    const size_t lds = ((size_t)kNarrowPix * C_out + (size_t)R * rowlen) * sizeof(float);
+    return lds <= 150 * 1024 && rowlen <= 2048;
+}
+
 struct Plan {
     bool mfma;
     int TM, TR, NI, TP, TP16, tiles_per_image, hrows, hw, cblocks, kblocks, nsplit, lds;
@@ -379,6 +465,7 @@ size_t wgrad_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C
     const int64_t nW = C_out * R * S * C_in;
     if (pl.mfma) return (size_t)pl.nsplit * (size_t)nW * sizeof(float);
     const int64_t npix = B * ((H + 2 * pad - R) / stride + 1) * ((Wd + 2 * pad - S) / stride + 1);
+    if (npix > 0 && narrow_layer(C_in, C_out, R, S, stride, dt, H, Wd)) return (size_t)kNarrowGroups * (size_t)nW * sizeof(float);
     if (small_filter(nW, npix)) return (size_t)kSmallGroups * (size_t)nW * sizeof(float);
     return 0;
 }
@@ -414,6 +501,28 @@ int wgrad_launch(const void* D, const void* dO, float* dW, int64_t B, int64_t H,
     }
     if (nW > 0x7FFFFFFF) return SDGP_ERR_SHAPE;
     SimpleArgs a{D, dO, dW, B, H, Wd, P, Q, C_in, C_out, R, S, stride, pad};
+    if (workspace != nullptr && !pl.mfma && B * P * Q > 0 && narrow_layer(C_in, C_out, R, S, stride, dt, H, Wd)) {
+        NarrowArgs n{};
+        n.D = (const uint16_t*)D, n.dO = (const uint16_t*)dO, n.partial = (float*)workspace, n.B = B;
+        n.H = (int)H, n.Wd = (int)Wd, n.P = (int)P, n.Q = (int)Q, n.C_in = (int)C_in, n.C_out = (int)C_out;
+        n.R = R, n.S = S, n.stride = stride, n.pad = pad;
+        n.T = R * S * (int)C_in, n.SC = S * (int)C_in;
+        n.rowlen = ((kNarrowPix - 1) * stride + S) * (int)C_in;
+        n.qsegs = (int)((Q + kNarrowPix - 1) / kNarrowPix);
+        n.segments = B * P * n.qsegs;
+        n.cin_magic = (65536u + (uint32_t)C_in - 1) / (uint32_t)C_in;
+        const size_t lds = ((size_t)kNarrowPix * C_out + (size_t)R * n.rowlen) * sizeof(float);
+        // every workgroup writes its partial filter, so the grid is fixed: the reduction reads kNarrowGroups of them
+        const bool few = n.T <= 28;
+        void (*kernel)(NarrowArgs) = C_out == 64 ? (few ? wgrad_narrow<1, 7> : wgrad_narrow<1, 37>)
+                                                 : (few ? wgrad_narrow<2, 7> : wgrad_narrow<2, 37>);
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return SDGP_ERR_HIP;
+        kernel<<<kNarrowGroups, kThreads, lds, stream>>>(n);
+        if (hipGetLastError() != hipSuccess) return SDGP_ERR_HIP;
+        wgrad_reduce<<<(unsigned)((nW + 63) / 64), kThreads, 0, stream>>>((const float*)workspace, dW, nW, kNarrowGroups);
+        return launch_status();
+    }
     if (workspace != nullptr && !pl.mfma && small_filter(nW, B * P * Q)) {
         if (dt == SDGP_BF16) wgrad_small<SDGP_BF16><<<kSmallGroups, kThreads, 0, stream>>>(a, (float*)workspace, nW);
         else wgrad_small<SDGP_F32><<<kSmallGroups, kThreads, 0, stream>>>(a, (float*)workspace, nW);

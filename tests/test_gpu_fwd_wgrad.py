@@ -75,6 +75,9 @@ PLAIN_LAYERS = [
     wl.ConvLayer("pw_1x1_s2", 2, 9, 10, 24, 40, 1, 1, 2, 0),
     wl.ConvLayer("stem_7x7", 2, 30, 30, 3, 64, 7, 7, 2, 3),
     wl.ConvLayer("first_3x3", 3, 16, 16, 3, 64, 3, 3, 1, 1),
+    wl.ConvLayer("first_wide_rows", 2, 12, 70, 3, 128, 3, 3, 1, 1),      # two segments per row, the second ragged
+    wl.ConvLayer("first_many", 300, 9, 9, 4, 64, 3, 3, 1, 1),            # more segments than workgroups
+    wl.ConvLayer("stem_7x7_wide", 1, 40, 150, 3, 64, 7, 7, 2, 3),
     wl.ConvLayer("odd_5x5", 2, 11, 12, 20, 36, 5, 5, 1, 2),
     wl.ConvLayer("rect_2x3", 2, 8, 9, 16, 32, 2, 3, 1, 1),
 ]
@@ -110,7 +113,7 @@ def test_weight_gradient_reads_every_gradient_element():
     assert np.all(out[:, 1, 1, :] != 0)
 
 
-@pytest.mark.parametrize("i", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("i", [0, 1, 2, 3, 4, 5])
 def test_resnet9_batch512_sampled(i):
     """The launches bench.py times: forward at sampled output pixels, weight gradient at sampled filter elements."""
     L = wl.resnet9_layers(512)[i]
