@@ -286,6 +286,32 @@ def main():
         table.append(row)
     result["resnet50_bottleneck_batch128"] = table
 
+    # ---- the compacted-gradient path (K' = (n/m) C_out kept values per pixel, W rows gathered by index, fp32 FMAs) against
+    # the fused path (structured-sparse instruction up to m = 16, masked dense instruction at m = 32) and the dense
+    # kernel: two HBM-bound pointwise layers and one compute-bound 3x3 layer, Magnitude ranker (Sec. IV-C: ratios 4, 8, 16)
+    rows = []
+    picks = [(b50[0], b50_stats[0]), (b50[2], b50_stats[2]), (r9[3], r9_stats[3])]
+    for (L, dO, W, out) in resident([p[0] for p in picks], [p[1] for p in picks]):
+        row = {"layer": L.name, "dense_us": round(time_call(lambda: call(L, dO, W, out, 4, 4, sdgp.GREEDY)) * 1e3, 1)}
+        for n_, m_ in ((2, 4), (2, 8), (2, 16), (4, 32), (2, 32)):
+            need = int(lib.sdgp_conv_bwd_data_compact_workspace(L.B, L.H, L.Wd, L.C_in, L.C_out, L.R, L.S, L.stride, L.pad,
+                                                                sdgp.BF16, n_, m_))
+            ws_c = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+            t_f = time_call(lambda: call(L, dO, W, out, n_, m_, sdgp.GREEDY), reps=5)
+            t_c = time_call(lambda: sdgp.sdgp_conv_bwd_data_compact(dO, W, L.H, L.Wd, L.stride, L.pad, n_, m_, sdgp.GREEDY, 0,
+                                                                    out=out, workspace=ws_c), reps=3, warm=1)
+            row["%d:%d_fused_us" % (n_, m_)] = round(t_f * 1e3, 1)
+            row["%d:%d_compact_us" % (n_, m_)] = round(t_c * 1e3, 1)
+            del ws_c
+        rows.append(row)
+    wins = [(r["layer"], k[:-11]) for r in rows for k in r if k.endswith("_compact_us") and r[k] < r[k[:-11] + "_fused_us"]]
+    result["compact_vs_fused"] = {
+        "layers": rows, "compact_faster_at": wins,
+        "note": "compact = prune pass to (values, positions) + one AXPY per kept value on the vector ALUs; fused = the "
+                "matrix-core path of sdgp_conv_bwd_data; compact_faster_at lists the (layer, n:m) where the compacted path "
+                "wins -- the measured crossover of the sparsity grid",
+    }
+
     # ------------------------------------------------------------------ prune pass: tensors beyond the last-level cache
     import ctypes
     nelem = 256 * 112 * 112 * 64

@@ -218,6 +218,25 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
                                         size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Backward-data product from the compacted gradient (the K' = (n/m) * C_out form of Sec. III-A and of the ratio-4 and
+ * ratio-8 estimates of Sec. IV-C): the prune pass writes the kept values and their positions into the workspace, then
+ * every kept value adds its multiple of the matching row of W to its output pixels (one AXPY per kept value per tap,
+ * fp32 FMAs on the vector ALUs; the rows differ from pixel to pixel, so this is not a matrix product).  Same result as
+ * sdgp_conv_bwd_data up to summation order; its work falls with n/m, so it is the faster path only at high sparsity.
+ *
+ * bf16 only (SDGP_ERR_DTYPE otherwise); C_in a multiple of 8 and W, dD 16-byte aligned (SDGP_ERR_SHAPE otherwise, and
+ * for a filter so large that m of its rows exceed 150 KB of LDS).  workspace:
+ * sdgp_conv_bwd_data_compact_workspace(...) bytes, 16-byte aligned, contents undefined afterwards; the query returns
+ * (size_t)-1 for arguments the call would refuse.  Everything else as sdgp_conv_bwd_data.
+ */
+size_t sdgp_conv_bwd_data_compact_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R,
+                                            int S, int stride, int pad, int dt, int n, int m);
+int sdgp_conv_bwd_data_compact(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd,
+                               int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dt, int n,
+                               int m, int rk, uint64_t seed, void* workspace, size_t workspace_bytes,
+                               void* hip_stream);
+
+/*
  * The two other products of a layer's training step (Sec. II-A, Fig. 1; Sec. IV-C, Fig. 9 times all three).
  * Neither prunes anything: SDGP touches only the data gradient, and Sec. III-A keeps the unpruned dL/dO for the
  * weight gradient.  They exist so that a whole step of a layer can run, and be timed, on this library's kernels.

@@ -24,6 +24,7 @@ EXPORTS = ("sdgp_prune", "sdgp_linear_bwd_data", "sdgp_conv_bwd_data", "sdgp_con
            "sdgp_conv_bwd_data_noalloc",
            "sdgp_channel_scales_workspace", "sdgp_channel_scales", "sdgp_prune_channel_rescaled", "sdgp_scale_filter",
            "sdgp_conv_bwd_data_channel_rescaled_workspace", "sdgp_conv_bwd_data_channel_rescaled",
+           "sdgp_conv_bwd_data_compact_workspace", "sdgp_conv_bwd_data_compact",
            "sdgp_conv_fwd_workspace", "sdgp_conv_fwd", "sdgp_conv_bwd_weight_workspace", "sdgp_conv_bwd_weight",
            "sdgp_status_string", "sdgp_version")
 
@@ -73,6 +74,11 @@ def load():
             lib.sdgp_conv_bwd_data_channel_rescaled.restype = i32
             lib.sdgp_conv_bwd_data_channel_rescaled.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32,
                                                                i32, i32, i32, vp, sz, vp]
+            lib.sdgp_conv_bwd_data_compact_workspace.restype = sz
+            lib.sdgp_conv_bwd_data_compact_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32]
+            lib.sdgp_conv_bwd_data_compact.restype = i32
+            lib.sdgp_conv_bwd_data_compact.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32,
+                                                       i32, u64, vp, sz, vp]
             geom = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i32]
             lib.sdgp_conv_fwd_workspace.restype = sz
             lib.sdgp_conv_fwd_workspace.argtypes = geom
@@ -308,6 +314,31 @@ def sdgp_linear_bwd_data_channel_rescaled(dO: torch.Tensor, W: torch.Tensor, n: 
     rows, C_out = dO.shape
     out = sdgp_conv_bwd_data_channel_rescaled(dO.view(rows, 1, 1, C_out), W.view(C_out, 1, 1, W.shape[1]), 1, 1, 1, 0, n, m)
     return out.view(rows, W.shape[1])
+
+
+def sdgp_conv_bwd_data_compact(dO: torch.Tensor, W: torch.Tensor, H: int, Wd: int, stride: int, pad: int, n: int, m: int,
+                               ranker: int, seed: int = 0, out: torch.Tensor | None = None,
+                               workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """sdgp_conv_bwd_data through the compacted gradient: prune pass to (values, positions), then one AXPY per kept value."""
+    _dev(dO, "dO"), _dev(W, "W")
+    if dO.dim() != 4 or W.dim() != 4 or W.shape[0] != dO.shape[3] or W.dtype != dO.dtype:
+        raise ValueError("expected dO [B,P,Q,C_out] and W [C_out,R,S,C_in] of one dtype")
+    B, P, Q, C_out = dO.shape
+    _, R, S, C_in = W.shape
+    if (H + 2 * pad - R) // stride + 1 != P or (Wd + 2 * pad - S) // stride + 1 != Q:
+        raise ValueError("dO's spatial size does not match H, Wd, stride, pad")
+    if out is None:
+        out = torch.empty((B, H, Wd, C_in), dtype=dO.dtype, device=dO.device)
+    _dev(out, "out")
+    dt = _dtype_code(dO)
+    lib = load()
+    need = int(lib.sdgp_conv_bwd_data_compact_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m))
+    workspace, wbytes = _workspace(need, workspace, dO.device, "sdgp_conv_bwd_data_compact_workspace")
+    rc = lib.sdgp_conv_bwd_data_compact(_ptr(dO), _ptr(W), _ptr(out), B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m,
+                                        ranker, seed & (2**64 - 1), _ptr(workspace), wbytes, _stream(dO))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_conv_bwd_data_compact")
+    return out
 
 
 # ---------------------------------------------- the two other products of a layer's step (nothing is pruned)

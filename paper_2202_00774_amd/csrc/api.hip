@@ -34,6 +34,8 @@ int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n
 int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, const float* scale,
                                   void* pruned, hipStream_t stream);
 int scale_rows_launch(const void* W, const float* scale, void* out, int64_t C_out, int64_t inner, int dt, hipStream_t stream);
+int kprime_launch(const void* vals, const uint8_t* idx, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                  int64_t C_out, int R, int S, int stride, int pad, int n, int m, hipStream_t stream);
 int mirror_transpose_filter_launch(const void* W, void* V, int64_t C_out, int64_t C_in, int R, int S, int dt, hipStream_t stream);
 int fwd_narrow_launch(const void* D, const void* W, void* O, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                       int R, int S, int stride, int pad, int dt, hipStream_t stream);
@@ -311,6 +313,43 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
     rc = sdgp::scale_rows_launch(W, scale, filter, C_out, (int64_t)R * S * C_in, dt, stream);
     if (rc != SDGP_OK) return rc;
     return bwd_dispatch(dO, filter, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, nullptr, stream);
+}
+
+size_t sdgp_conv_bwd_data_compact_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
+                                            int stride, int pad, int dt, int n, int m) {
+    ConvGeom g;
+    if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g) != SDGP_OK || dt != SDGP_BF16) return (size_t)-1;
+    if (g.n_dD == 0) return 0;
+    if (C_in % 8 != 0 || (int64_t)m * R * S * (C_in <= 64 ? 128 : C_in <= 128 ? 256 : C_in <= 256 ? 512 : 1024) > 150 * 1024)
+        return (size_t)-1;
+    const size_t kept = (size_t)(g.n_dO / m * n);
+    return align256(kept * 2) + align256(kept);   // values | positions
+}
+
+int sdgp_conv_bwd_data_compact(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                               int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    ConvGeom g;
+    const int rc = check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g);
+    if (rc != SDGP_OK) return rc;
+    if (dt != SDGP_BF16) return SDGP_ERR_DTYPE;
+    if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
+    if (g.n_dD == 0) return SDGP_OK;
+    if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
+    const size_t need = sdgp_conv_bwd_data_compact_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m);
+    if (need == (size_t)-1 || !sdgp::is_aligned16(dD) || !sdgp::is_aligned16(W)) return SDGP_ERR_SHAPE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (g.n_dO == 0 || g.n_W == 0)  // empty sums: zeros, written by the shape-agnostic kernel
+        return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, nullptr, stream);
+    if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0)
+        return SDGP_ERR_WORKSPACE;
+    const size_t kept = (size_t)(g.n_dO / m * n);
+    void* vals = workspace;
+    uint8_t* idx = static_cast<uint8_t*>(workspace) + align256(kept * 2);
+    const int rcp = sdgp::prune_launch(dO, g.n_dO, dt, n, m, rk, seed, nullptr, vals, idx, stream);
+    if (rcp != SDGP_OK) return rcp;
+    const int rck = sdgp::kprime_launch(vals, idx, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, stream);
+    return rck > 0 ? SDGP_ERR_SHAPE : rck;
 }
 
 // The forward sum is a backward-data sum of the mirrored, transposed filter when stride is 1 and the filter square;
