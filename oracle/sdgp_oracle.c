@@ -74,19 +74,23 @@ float sdgp_ref_bf16_to_float(uint16_t h) { return bf16_to_float(h); }
  * Counter hash for the Random ranker.  Reading: the paper only says that m-n
  * elements are pruned at random (Sec. III-B); to make the result a pure function
  * of (seed, element) the key of element e is H(seed, e) below, all arithmetic
- * modulo 2^32.  Constants: floor(2^32/phi) and the fractional parts of
- * sqrt(2), sqrt(3), sqrt(7), sqrt(11) scaled by 2^32.
+ * modulo 2^32.  One mixed word is made per aligned quad of flat element indices
+ * (e >> 2); its four elements take the four byte rotations of that word, so the
+ * order of their keys is the order of four different bytes of one well mixed
+ * word.  Constants: floor(2^32/phi) and the fractional parts of sqrt(2), sqrt(3),
+ * sqrt(7), sqrt(11) scaled by 2^32.
  */
 uint32_t sdgp_ref_hash(uint64_t seed, uint64_t e) {
     uint32_t x = (uint32_t)e, y = (uint32_t)(e >> 32);
     uint32_t s0 = (uint32_t)seed, s1 = (uint32_t)(seed >> 32);
-    uint32_t v = 0xA54FF53Au ^ x ^ (s0 * 0x9E3779B9u) ^ (y * 0xBB67AE85u) ^ (s1 * 0x510E527Fu);
+    uint32_t v = 0xA54FF53Au ^ (x >> 2) ^ (s0 * 0x9E3779B9u) ^ (y * 0xBB67AE85u) ^ (s1 * 0x510E527Fu);
     v ^= v >> 16;
     v *= 0x6A09E667u;
     v ^= v >> 15;
     v *= 0xBB67AE85u;
     v ^= v >> 16;
-    return v;
+    unsigned rot = 8u * (x & 3u);
+    return rot ? (v << rot) | (v >> (32u - rot)) : v;
 }
 
 /* ------------------------------------------------------------ one group */

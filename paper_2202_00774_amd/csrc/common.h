@@ -41,10 +41,13 @@ __host__ __device__ __forceinline__ uint32_t float2_to_bf16x2(float lo, float hi
 // Key of flat element e under `seed` for the random pruning function
 // (Sec. III-B, "Random"; the paper names no generator, this is the library's
 // definition).  With x = low and y = high word of e, s0/s1 the words of seed:
-//   v = 0xA54FF53A ^ x ^ s0*0x9E3779B9 ^ y*0xBB67AE85 ^ s1*0x510E527F
+//   v = 0xA54FF53A ^ (x >> 2) ^ s0*0x9E3779B9 ^ y*0xBB67AE85 ^ s1*0x510E527F
 //   v ^= v>>16; v *= 0x6A09E667; v ^= v>>15; v *= 0xBB67AE85; v ^= v>>16
-// The seed terms are folded on the host (seed_mix), the y term once per group
-// (hash_row), leaving two multiplies per element.
+//   key = v rotated left by 8 * (x & 3) bits
+// One mixed word serves an aligned quad of elements (hash_quad), each element
+// taking one of its four byte rotations: two multiplies per quad instead of per
+// element.  The seed terms are folded on the host (seed_mix), the y term once
+// per group (hash_row).
 
 __host__ __device__ inline uint32_t seed_mix(uint64_t seed) {
     return 0xA54FF53Au ^ ((uint32_t)seed * 0x9E3779B9u) ^ ((uint32_t)(seed >> 32) * 0x510E527Fu);
@@ -52,14 +55,24 @@ __host__ __device__ inline uint32_t seed_mix(uint64_t seed) {
 
 __host__ __device__ __forceinline__ uint32_t hash_row(uint32_t mix, uint32_t e_hi) { return mix ^ (e_hi * 0xBB67AE85u); }
 
-__host__ __device__ __forceinline__ uint32_t hash_elem(uint32_t row, uint32_t e_lo) {
-    uint32_t v = row ^ e_lo;
+// The mixed word of the quad that holds element e_lo.
+__host__ __device__ __forceinline__ uint32_t hash_quad(uint32_t row, uint32_t e_lo) {
+    uint32_t v = row ^ (e_lo >> 2);
     v ^= v >> 16;
     v *= 0x6A09E667u;
     v ^= v >> 15;
     v *= 0xBB67AE85u;
     v ^= v >> 16;
     return v;
+}
+
+// Key of element i (0..3) of a quad from the quad's mixed word.
+__host__ __device__ __forceinline__ uint32_t hash_lane(uint32_t quad_word, uint32_t i) {
+    return __builtin_rotateleft32(quad_word, 8u * (i & 3u));
+}
+
+__host__ __device__ __forceinline__ uint32_t hash_elem(uint32_t row, uint32_t e_lo) {
+    return hash_lane(hash_quad(row, e_lo), e_lo);
 }
 
 // ------------------------------------------------------------ host helpers

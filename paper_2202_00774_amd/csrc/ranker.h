@@ -135,7 +135,15 @@ __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uin
                                             bool (&keep)[M], uint32_t (&out)[M]) {
     constexpr uint32_t kMagMask = (DT == kBF16) ? 0x7FFFu : 0x7FFFFFFFu;
     uint32_t key[M];
-    if constexpr (RK == kRandom) {
+    if constexpr (RK == kRandom && M % 4 == 0) {
+        // a group starts at a multiple of M, so its quads are the hash's quads: one mixed word each
+#pragma unroll
+        for (int q = 0; q < M / 4; ++q) {
+            const uint32_t hq = hash_quad(hrow, e_lo + 4u * (uint32_t)q);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) key[4 * q + i] = hash_lane(hq, (uint32_t)i);
+        }
+    } else if constexpr (RK == kRandom) {
 #pragma unroll
         for (int j = 0; j < M; ++j) key[j] = hash_elem(hrow, e_lo + (uint32_t)j);
     } else {
@@ -332,10 +340,11 @@ __host__ __device__ __forceinline__ void prune_compress16_random(const uint32_t 
         const uint32_t hrow = hash_row(mix, (uint32_t)(eg >> 32));
         const uint32_t e_lo = (uint32_t)eg + (uint32_t)((4 * q) % M);      // the quad's first element
         const uint32_t c0 = (uint32_t)(15 - (4 * q) % M);
-        const uint32_t k0 = (hash_elem(hrow, e_lo) & kPrefix) | c0;
-        const uint32_t k1 = (hash_elem(hrow, e_lo + 1u) & kPrefix) | (c0 - 1u);
-        const uint32_t k2 = (hash_elem(hrow, e_lo + 2u) & kPrefix) | (c0 - 2u);
-        const uint32_t k3 = (hash_elem(hrow, e_lo + 3u) & kPrefix) | (c0 - 3u);
+        const uint32_t hq = hash_quad(hrow, e_lo);                         // e_lo is a multiple of 4: one word per quad
+        const uint32_t k0 = (hq & kPrefix) | c0;
+        const uint32_t k1 = (hash_lane(hq, 1u) & kPrefix) | (c0 - 1u);
+        const uint32_t k2 = (hash_lane(hq, 2u) & kPrefix) | (c0 - 2u);
+        const uint32_t k3 = (hash_lane(hq, 3u) & kPrefix) | (c0 - 3u);
         const uint32_t hi = sdgp_umax(k0, k1), lo = sdgp_umin(k0, k1);
         const uint32_t hi2 = sdgp_umax(k2, k3), lo2 = sdgp_umin(k2, k3);
         const uint32_t x = sdgp_umin(hi, hi2), y = sdgp_umax(lo, lo2), z = sdgp_umin(lo, lo2);

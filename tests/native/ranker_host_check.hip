@@ -108,9 +108,10 @@ static int run_mag(int iters, unsigned seed) {
 }
 static uint32_t H(uint64_t seed, uint64_t e) {  // the definition, written out
     uint32_t x = (uint32_t)e, y = (uint32_t)(e >> 32), s0 = (uint32_t)seed, s1 = (uint32_t)(seed >> 32);
-    uint32_t v = 0xA54FF53Au ^ x ^ (s0 * 0x9E3779B9u) ^ (y * 0xBB67AE85u) ^ (s1 * 0x510E527Fu);
+    uint32_t v = 0xA54FF53Au ^ (x >> 2) ^ (s0 * 0x9E3779B9u) ^ (y * 0xBB67AE85u) ^ (s1 * 0x510E527Fu);
     v ^= v >> 16; v *= 0x6A09E667u; v ^= v >> 15; v *= 0xBB67AE85u; v ^= v >> 16;
-    return v;
+    const unsigned rot = 8u * (x & 3u);   // one mixed word per aligned quad, one byte rotation per element
+    return rot ? (v << rot) | (v >> (32u - rot)) : v;
 }
 template <int M, uint32_t PFX>
 static int run_rand(int iters, unsigned sd, bool narrow_hash) {
