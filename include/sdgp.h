@@ -137,9 +137,10 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
 /* Bytes of workspace sdgp_conv_bwd_data needs for these arguments; (size_t)-1 when
  * the arguments are invalid.  0 for almost every layer (the call is one fused
  * kernel); a first layer with a wide filter (C_in <= 4 and more than 32
- * (tap, channel) pairs, e.g. 7x7 on three channels: 23 KB per 64 output channels)
- * asks for room for a transposed copy of the filter that one small kernel builds
- * before the fused one. */
+ * (tap, channel) pairs) asks for room for a re-indexed copy of the filter that one
+ * small kernel builds before the fused one: 20 KB per 32 output channels for a 7x7
+ * stride-2 filter with padding 3 on an image of even size, 23 KB per 64 output
+ * channels for other 7x7 layers on three channels. */
 size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                                     int R, int S, int stride, int pad, int dt, int n, int m);
 
@@ -151,8 +152,8 @@ size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_
  * SDGP_NOALLOC_SCRATCH_BYTES that is part of the library's device image (each GPU the library runs on holds its own
  * copy until the process ends).  The call allocates and frees nothing.
  *
- *   - A problem whose sdgp_conv_bwd_data_workspace(...) exceeds SDGP_NOALLOC_SCRATCH_BYTES (a 7x7 first layer with
- *     more than 704 output channels) returns SDGP_ERR_WORKSPACE and launches nothing; SDGP_ERR_HIP when the runtime
+ *   - A problem whose sdgp_conv_bwd_data_workspace(...) exceeds SDGP_NOALLOC_SCRATCH_BYTES (the 7x7 stride-2 first layer
+ *     of an ImageNet network with more than 384 output channels) returns SDGP_ERR_WORKSPACE and launches nothing; SDGP_ERR_HIP when the runtime
  *     cannot report the array's address.
  *   - All calls on one GPU share that GPU's array, and it keeps the last call's contents (every call rewrites the
  *     part it reads, nothing has to start at zero).  Calls that overlap in time on one GPU -- different streams,

@@ -227,6 +227,107 @@ __device__ __forceinline__ void narrow_gather(const NarrowParams& p, const SDGP_
         }
 }
 
+// Sixteen consecutive channels of one gradient pixel, pruned (Sec. III-B) and written back dense with zeros.
+// v[0], v[1]: the two 16-byte halves; e0: flat index of the first element (for the random ranker's hash).
+template <int M, int RK, bool NLE2>
+__device__ __forceinline__ void prune16_dense(u32x4n (&v)[2], int n, uint32_t mix, uint64_t e0) {
+    if constexpr (NLE2 && RK != kRandom) {
+        // magnitude rankers, n <= 2: rank on packed keys, then spread the two kept values of every quad back to
+        // their positions
+        const uint32_t w[8] = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
+        uint32_t packed[4], meta;
+        prune_compress16_bf16<M, RK>(w, n, packed, meta);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t i0 = (meta >> (4 * q)) & 3u, i1 = (meta >> (4 * q + 2)) & 3u;
+            const uint64_t x = ((uint64_t)(packed[q] & 0xFFFFu) << (16 * i0)) | ((uint64_t)(packed[q] >> 16) << (16 * i1));
+            v[q >> 1][2 * (q & 1)] = (uint32_t)x;
+            v[q >> 1][2 * (q & 1) + 1] = (uint32_t)(x >> 32);
+        }
+    } else {
+        uint32_t raw[16], out[16];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
+                raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
+            }
+#pragma unroll
+        for (int g = 0; g < 16 / M; ++g) {
+            uint32_t r[M], o[M];
+            bool kk[M];
+#pragma unroll
+            for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
+            const uint64_t eg = e0 + (uint64_t)(g * M);
+            prune_group<kBF16, M, RK, NLE2>(r, n, hash_row(mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+#pragma unroll
+            for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) v[i][x] = out[i * 8 + 2 * x] | (out[i * 8 + 2 * x + 1] << 16);
+    }
+}
+
+// One 16-channel item of the gradient tile in LDS, in place: positions that are not gradient (outside the image, past
+// C_out) are cleared, the rest pruned and stored dense with zeros.
+template <int M, int RK, bool PRUNE, bool NLE2>
+__device__ __forceinline__ void narrow_item_in_place(const NarrowParams& p, int b, int pmin, int qmin, int kc0, int it,
+                                                     SDGP_LDSN unsigned char* lds_a) {
+    const int hp = it >> 2, part = it & 3;
+    const int hrow = (int)__umulhi((uint32_t)hp, p.hq_magic);
+    const int pp = pmin + hrow, qq = qmin + (hp - hrow * p.HQ);
+    const int k = kc0 + part * 16;
+    const int sw = (hp >> 1) & 7;
+    SDGP_LDSN u32x4n* g0 = (SDGP_LDSN u32x4n*)(lds_a + hp * kMmRowB + (((2 * part) ^ sw) << 4));
+    SDGP_LDSN u32x4n* g1 = (SDGP_LDSN u32x4n*)(lds_a + hp * kMmRowB + (((2 * part + 1) ^ sw) << 4));
+    const u32x4n zero = {0u, 0u, 0u, 0u};
+    if (!(pp < p.P && qq < p.Q) || k >= p.C_out) {
+        *g0 = zero;
+        *g1 = zero;
+    } else if (PRUNE || k + 8 >= p.C_out) {
+        u32x4n v[2] = {*g0, k + 8 < p.C_out ? *g1 : zero};
+        if constexpr (PRUNE) {
+            const size_t gp = (size_t)(b * p.P + pp) * p.Q + qq;
+            prune16_dense<M, RK, NLE2>(v, p.n, p.mix, (uint64_t)gp * (uint64_t)p.C_out + (uint64_t)k);
+        }
+        *g0 = v[0];
+        *g1 = v[1];
+    }
+}
+
+// The input pixel (h, w) of image b: sums, from the table T in LDS, the entry of each tap that reaches it -- tap r
+// reaches row h when h + pad - r is a multiple of the stride, so r starts at (h + pad) mod stride and steps by the
+// stride while the gradient row falls -- and stores the pixel.
+__device__ __forceinline__ void narrow_sum_and_store(const NarrowParams& p, const SDGP_LDSN float* lds_t, int TP, int pmin,
+                                                     int qmin, int b, int h, int w) {
+    float sum[4] = {0.f, 0.f, 0.f, 0.f};
+    const int nr = (p.R + p.stride - 1) / p.stride, ns = (p.S + p.stride - 1) / p.stride;  // taps per dimension, at most
+    if (nr <= 2 && ns <= 2) {
+        narrow_gather<2, 2>(p, lds_t, TP, pmin, qmin, h, w, sum);
+    } else if (nr <= 3 && ns <= 3) {
+        narrow_gather<3, 3>(p, lds_t, TP, pmin, qmin, h, w, sum);
+    } else if (nr <= 4 && ns <= 4) {
+        narrow_gather<4, 4>(p, lds_t, TP, pmin, qmin, h, w, sum);
+    } else {
+        const int r0 = (h + p.pad) % p.stride, s0 = (w + p.pad) % p.stride;
+        const int pp0 = (h + p.pad - r0) / p.stride, qq0 = (w + p.pad - s0) / p.stride;
+        for (int r = r0, pp = pp0; r < p.R && pp >= 0; r += p.stride, --pp) {
+            if (pp >= p.P) continue;
+            const SDGP_LDSN float* trow = lds_t + ((pp - pmin) * p.HQ + (qq0 - qmin)) * TP + (r * p.S + s0) * p.C_in;
+            for (int s = s0, qq = qq0; s < p.S && qq >= 0; s += p.stride, --qq) {
+                if (qq < p.Q)
+                    for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
+                trow += p.stride * p.C_in - TP;  // next tap of this phase, previous gradient pixel
+            }
+        }
+    }
+    uint16_t* dst = p.dD + ((size_t)(b * p.H + h) * p.Wd + w) * p.C_in;
+    for (int c = 0; c < p.C_in; ++c) dst[c] = (uint16_t)float_to_bf16(sum[c]);
+}
+
 // Matrix-core variant; p.nt = 32-column tiles of (tap, c) pairs; kMmPairs = pairs per wavefront (accumulator registers).
 template <int M, int RK, bool PRUNE, bool NLE2, int kMmPairs>
 __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
@@ -318,64 +419,8 @@ __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
         // tile whose gradient pixels and channels all exist
         const bool all_there = pmin + p.HP <= p.P && qmin + p.HQ <= p.Q && kc0 + kNarrowKC <= p.C_out;
         if (PRUNE || !all_there) {
-            for (int it = tid; it < npix * (kNarrowKC / 16); it += 256) {
-                const int hp = it >> 2, part = it & 3;
-                const int hrow = (int)__umulhi((uint32_t)hp, p.hq_magic);
-                const int pp = pmin + hrow, qq = qmin + (hp - hrow * p.HQ);
-                const int k = kc0 + part * 16;
-                const int sw = (hp >> 1) & 7;
-                SDGP_LDSN u32x4n* g0 = (SDGP_LDSN u32x4n*)(lds_a + hp * kMmRowB + (((2 * part) ^ sw) << 4));
-                SDGP_LDSN u32x4n* g1 = (SDGP_LDSN u32x4n*)(lds_a + hp * kMmRowB + (((2 * part + 1) ^ sw) << 4));
-                const u32x4n zero = {0u, 0u, 0u, 0u};
-                if (!(pp < p.P && qq < p.Q) || k >= p.C_out) {
-                    *g0 = zero;
-                    *g1 = zero;
-                } else if (PRUNE || k + 8 >= p.C_out) {
-                    u32x4n v[2] = {*g0, k + 8 < p.C_out ? *g1 : zero};
-                    if constexpr (PRUNE && NLE2 && RK != kRandom) {
-                        // magnitude rankers, n <= 2: rank on packed keys, then spread the two kept values of every
-                        // quad back to their positions
-                        const uint32_t w[8] = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
-                        uint32_t packed[4], meta;
-                        prune_compress16_bf16<M, RK>(w, p.n, packed, meta);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const uint32_t i0 = (meta >> (4 * q)) & 3u, i1 = (meta >> (4 * q + 2)) & 3u;
-                            const uint64_t x = ((uint64_t)(packed[q] & 0xFFFFu) << (16 * i0)) | ((uint64_t)(packed[q] >> 16) << (16 * i1));
-                            v[q >> 1][2 * (q & 1)] = (uint32_t)x;
-                            v[q >> 1][2 * (q & 1) + 1] = (uint32_t)(x >> 32);
-                        }
-                    } else if constexpr (PRUNE) {
-                        uint32_t raw[16], out[16];
-#pragma unroll
-                        for (int i = 0; i < 2; ++i)
-#pragma unroll
-                            for (int x = 0; x < 4; ++x) {
-                                raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
-                                raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
-                            }
-                        const size_t gp = (size_t)(b * p.P + pp) * p.Q + qq;
-                        const uint64_t e0 = (uint64_t)gp * (uint64_t)p.C_out + (uint64_t)k;
-#pragma unroll
-                        for (int g = 0; g < 16 / M; ++g) {
-                            uint32_t r[M], o[M];
-                            bool kk[M];
-#pragma unroll
-                            for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
-                            const uint64_t eg = e0 + (uint64_t)(g * M);
-                            prune_group<kBF16, M, RK, NLE2>(r, p.n, hash_row(p.mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
-#pragma unroll
-                            for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
-                        }
-#pragma unroll
-                        for (int i = 0; i < 2; ++i)
-#pragma unroll
-                            for (int x = 0; x < 4; ++x) v[i][x] = out[i * 8 + 2 * x] | (out[i * 8 + 2 * x + 1] << 16);
-                    }
-                    *g0 = v[0];
-                    *g1 = v[1];
-                }
-            }
+            for (int it = tid; it < npix * (kNarrowKC / 16); it += 256)
+                narrow_item_in_place<M, RK, PRUNE, NLE2>(p, b, pmin, qmin, kc0, it, lds_a);
         }
         __syncthreads();
 
@@ -413,31 +458,207 @@ __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
     // multiple of the stride, so r starts at (h + pad) mod stride and steps by the stride while the gradient row falls
     const int th = tid / p.TW, tw = tid % p.TW;
     const int h = h0 + th, w = w0 + tw;
-    if (tid < p.TH * p.TW && h < p.H && w < p.Wd) {
-        float sum[4] = {0.f, 0.f, 0.f, 0.f};
-        const int nr = (p.R + p.stride - 1) / p.stride, ns = (p.S + p.stride - 1) / p.stride;  // taps per dimension, at most
-        if (nr <= 2 && ns <= 2) {
-            narrow_gather<2, 2>(p, lds_t, TP, pmin, qmin, h, w, sum);
-        } else if (nr <= 3 && ns <= 3) {
-            narrow_gather<3, 3>(p, lds_t, TP, pmin, qmin, h, w, sum);
-        } else if (nr <= 4 && ns <= 4) {
-            narrow_gather<4, 4>(p, lds_t, TP, pmin, qmin, h, w, sum);
-        } else {
-            const int r0 = (h + p.pad) % p.stride, s0 = (w + p.pad) % p.stride;
-            const int pp0 = (h + p.pad - r0) / p.stride, qq0 = (w + p.pad - s0) / p.stride;
-            for (int r = r0, pp = pp0; r < p.R && pp >= 0; r += p.stride, --pp) {
-                if (pp >= p.P) continue;
-                const SDGP_LDSN float* trow = lds_t + ((pp - pmin) * p.HQ + (qq0 - qmin)) * TP + (r * p.S + s0) * p.C_in;
-                for (int s = s0, qq = qq0; s < p.S && qq >= 0; s += p.stride, --qq) {
-                    if (qq < p.Q)
-                        for (int c = 0; c < p.C_in; ++c) sum[c] += trow[c];
-                    trow += p.stride * p.C_in - TP;  // next tap of this phase, previous gradient pixel
+    if (tid < p.TH * p.TW && h < p.H && w < p.Wd) narrow_sum_and_store(p, lds_t, TP, pmin, qmin, b, h, w);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// 7x7, stride 2, padding 3 on C_in <= 4 (the first layer of an ImageNet ResNet), even image sizes.
+//
+// An input pixel (2i + a, 2j + b) is reached by the taps r = a + 3 - 2 dp, s = b + 3 - 2 dq of the gradient pixels
+// (i + dp, j + dq), dp, dq in [-1, 2].  So the four pixels of a 2 x 2 block and their channels (padded to four) are the
+// 16 columns n = (a, b, c) of ONE small product over a 4 x 4 window of gradient pixels,
+//   out[(i, j)][n] = sum_{dp, dq} sum_k dO[i + dp, j + dq][k] * V[(dp, dq)][k][n],
+// with V the filter re-indexed (zeros where r or s falls outside the filter): rows = gradient-grid positions,
+// reduction = 16 window positions x C_out, on v_mfma_f32_16x16x32_bf16 with the result left in registers -- no table
+// of per-tap products in LDS, no per-pixel gather.  A lane ends up with the channels of one input pixel.
+//   * workgroup = 4 wavefronts, tile = 8 x 64 gradient-grid positions (16 x 128 input pixels); wavefront (rq, gp) owns
+//     grid rows 4 rq .. 4 rq + 3 and columns 32 gp .. 32 gp + 31: 4 x 2 accumulators of four registers;
+//   * the reduction runs in chunks of 32 channels: the 11 x 67 gradient pixels the tile's windows reach (64 bytes each,
+//     80-byte pitch: sixteen consecutive pixels read conflict-free, and every fragment address is a per-lane base plus
+//     a constant) and V's chunk (16 window positions x 16 columns, built once per call in the workspace) arrive by
+//     direct-to-LDS copies; slots of pixels outside the gradient are cleared once and skipped by the copies; pruning, when asked
+//     for, is done in place;
+//   * a gradient fragment (16 pixels x 32 channels) is read once per (tile row, dq) and feeds up to four matrix
+//     instructions (the output rows whose window holds that gradient row); V's 16 fragments sit in registers.
+constexpr int kFWin = 4;                                  // window positions per dimension
+constexpr int kFKC = 32;                                  // channels per chunk
+constexpr int kFRows = 8, kFCols = 64;                    // tile, in gradient-grid positions
+constexpr int kFHaloRows = kFRows + kFWin - 1, kFHaloCols = kFCols + kFWin - 1;
+constexpr int kFPix = kFHaloRows * kFHaloCols;            // 737 gradient pixels
+constexpr int kFPitch = 80;                               // bytes per pixel in LDS: 64 of data, 16 of padding
+constexpr int kFAUnits = (kFPix * kFPitch + 1023) / 1024; // 1 KB copy units
+constexpr int kFABytes = kFAUnits * 1024;
+constexpr int kFWRows = kFWin * kFWin * 16;               // rows of V's chunk: (window position, column)
+constexpr int kFWUnits = kFWRows * kFPitch / 1024;        // 20
+constexpr int kFThreads = 256;
+static_assert(kFWRows * kFPitch % 1024 == 0, "V's chunk is whole copy units");
+
+struct FirstParams {
+    const uint16_t* dO;
+    const unsigned char* vimg;   // [C_out / 32][kFWRows][kFPitch bytes]
+    uint16_t* dD;
+    int B, P, Q, C_in, C_out;
+    int tiles_i, tiles_j;
+    int n;
+    uint32_t mix;
+};
+
+// V's image for one chunk of 32 output channels: row (window position t = (dp+1)*4 + (dq+1), column n = a*8 + b*4 + c),
+// 32 channels contiguous, kFPitch bytes per row.  One workgroup per chunk.
+__global__ void __launch_bounds__(256) first_v_image(const uint16_t* __restrict__ W, uint16_t* __restrict__ img, int C_in) {
+    const int kc = blockIdx.x;
+    uint16_t* dst = img + (size_t)kc * kFWRows * (kFPitch / 2);
+    for (int e = threadIdx.x; e < kFWRows * (kFPitch / 2); e += 256) {
+        const int row = e / (kFPitch / 2), kk = e % (kFPitch / 2);
+        const int t = row >> 4, nn = row & 15;
+        const int dp = (t >> 2) - 1, dq = (t & 3) - 1, a = nn >> 3, b = (nn >> 2) & 1, c = nn & 3;
+        const int r = a + 3 - 2 * dp, s2 = b + 3 - 2 * dq;
+        uint16_t v = 0;
+        if (kk < kFKC && c < C_in && r >= 0 && r < 7 && s2 >= 0 && s2 < 7)
+            v = W[(((size_t)(kc * kFKC + kk) * 7 + r) * 7 + s2) * C_in + c];
+        dst[e] = v;
+    }
+}
+
+typedef float f32x4f __attribute__((ext_vector_type(4)));
+
+template <int M, int RK, bool PRUNE, bool NLE2>
+__global__ void __launch_bounds__(kFThreads, 2) bwd_first2(const FirstParams p) {
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    SDGP_LDSN unsigned char* smem = (SDGP_LDSN unsigned char*)smem_generic;
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rq = wave >> 1, gp = wave & 1;
+    const int tile = blockIdx.x;
+    const int tj = tile % p.tiles_j, ti = (tile / p.tiles_j) % p.tiles_i, b = tile / (p.tiles_j * p.tiles_i);
+    const int i0 = ti * kFRows, j0 = tj * kFCols;
+    const int px = lane & 15, oct = lane >> 4;
+
+    f32x4f acc[4][2];
+#pragma unroll
+    for (int ri = 0; ri < 4; ++ri)
+#pragma unroll
+        for (int g = 0; g < 2; ++g) acc[ri][g] = f32x4f{0.f, 0.f, 0.f, 0.f};
+
+    // this lane's bases: V fragments (row = window position * 16 + column px), gradient fragments (tile row 4 rq,
+    // column 32 gp + px, window column 0)
+    SDGP_LDSN unsigned char* const vbase = smem + kFABytes + px * kFPitch + oct * 16;
+    SDGP_LDSN unsigned char* const abase = smem + ((4 * rq) * kFHaloCols + 32 * gp + px) * kFPitch + oct * 16;
+
+    // Where this lane's 16-byte slots of the gradient tile come from: a byte offset inside image b (the same for every
+    // chunk, which only moves the base by 64 bytes), or "nothing" -- padding slots, slots past the tile, pixels outside
+    // the gradient.  The latter are cleared once; the copies skip them.
+    constexpr int kUnitsPerWave = (kFAUnits + 3) / 4;
+    constexpr uint32_t kNothing = 0xFFFFFFFFu;
+    uint32_t voff[kUnitsPerWave];
+#pragma unroll
+    for (int x = 0; x < kUnitsPerWave; ++x) {
+        const int u = wave + 4 * x;
+        const int slot = u * 64 + lane;                                  // 16-byte slot of the tile
+        const int pix = (int)(((uint32_t)slot * 13108u) >> 16);          // slot / 5
+        const int part = slot - 5 * pix;                                 // 0..3 data, 4 padding
+        const int hr = (int)(((uint32_t)pix * 979u) >> 16);              // pix / 67
+        const int gi = i0 - 1 + hr, gj = j0 - 1 + (pix - hr * kFHaloCols);
+        const bool ok = u < kFAUnits && part < 4 && pix < kFPix && gi >= 0 && gi < p.P && gj >= 0 && gj < p.Q;
+        voff[x] = ok ? (uint32_t)((gi * p.Q + gj) * p.C_out + part * 8) * 2u : kNothing;
+        if (!ok && u < kFAUnits) *(SDGP_LDSN u32x4n*)(smem + slot * 16) = u32x4n{0u, 0u, 0u, 0u};
+    }
+    const unsigned char* const image = reinterpret_cast<const unsigned char*>(p.dO + (size_t)b * p.P * p.Q * p.C_out);
+
+    const int nchunks = p.C_out / kFKC;
+    for (int kc = 0; kc < nchunks; ++kc) {
+        if (kc > 0) __syncthreads();   // the previous chunk's fragments are read
+#pragma unroll
+        for (int x = 0; x < kUnitsPerWave; ++x) {
+            const int u = wave + 4 * x;
+            if (voff[x] != kNothing) lds_copy16(image + (size_t)kc * (kFKC * 2), voff[x], smem_base + (uint32_t)u * 1024u);
+        }
+        for (int u = wave; u < kFWUnits; u += 4)
+            lds_copy16(p.vimg + ((size_t)kc * kFWUnits + u) * 1024 + lane * 16, smem_base + (uint32_t)(kFABytes + u * 1024));
+        wait_lds_copies<0>();
+        __syncthreads();
+        if constexpr (PRUNE) {
+            for (int it = tid; it < kFPix * 2; it += kFThreads) {
+                const int hp = it >> 1, half = it & 1;
+                const int hr = (int)(((uint32_t)hp * 979u) >> 16);
+                const int gi = i0 - 1 + hr, gj = j0 - 1 + (hp - hr * kFHaloCols);
+                if (gi >= 0 && gi < p.P && gj >= 0 && gj < p.Q) {
+                    SDGP_LDSN u32x4n* g0 = (SDGP_LDSN u32x4n*)(smem + hp * kFPitch + half * 32);
+                    u32x4n v[2] = {g0[0], g0[1]};
+                    const size_t gpix = (size_t)(b * p.P + gi) * p.Q + gj;
+                    prune16_dense<M, RK, NLE2>(v, p.n, p.mix, (uint64_t)gpix * (uint64_t)p.C_out + (uint64_t)(kc * kFKC + half * 16));
+                    g0[0] = v[0];
+                    g0[1] = v[1];
+                }
+            }
+            __syncthreads();
+        }
+        bf16x8n vf[kFWin * kFWin];
+#pragma unroll
+        for (int t = 0; t < kFWin * kFWin; ++t) vf[t] = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(vbase + t * 16 * kFPitch));
+#pragma unroll
+        for (int rr = 0; rr < 4 + kFWin - 1; ++rr) {       // gradient rows of this wavefront's four output rows
+#pragma unroll
+            for (int dqi = 0; dqi < kFWin; ++dqi) {
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    const bf16x8n gf = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(abase + (rr * kFHaloCols + 16 * g + dqi) * kFPitch));
+#pragma unroll
+                    for (int ri = 0; ri < 4; ++ri) {
+                        const int dpi = rr - ri;             // window row of gradient row rr for output row ri
+                        if (dpi >= 0 && dpi < kFWin)
+                            acc[ri][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dpi * kFWin + dqi], gf, acc[ri][g], 0, 0, 0);
+                    }
                 }
             }
         }
-        uint16_t* dst = p.dD + ((size_t)(b * p.H + h) * p.Wd + w) * p.C_in;
-        for (int c = 0; c < p.C_in; ++c) dst[c] = (uint16_t)float_to_bf16(sum[c]);
     }
+    // result register c of lane (px, oct = 2 a + b): channel c of input pixel (2 i + a, 2 j + b)
+    const int a = oct >> 1, bb = oct & 1;
+#pragma unroll
+    for (int ri = 0; ri < 4; ++ri)
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            const int i = i0 + 4 * rq + ri, j = j0 + 32 * gp + 16 * g + px;
+            if (i < p.P && j < p.Q) {
+                uint16_t* dst = p.dD + ((size_t)(b * 2 * p.P + 2 * i + a) * (2 * p.Q) + 2 * j + bb) * p.C_in;
+                const uint32_t c01 = float2_to_bf16x2(acc[ri][g][0], acc[ri][g][1]), c23 = float2_to_bf16x2(acc[ri][g][2], acc[ri][g][3]);
+                dst[0] = (uint16_t)c01;
+                if (p.C_in > 1) dst[1] = (uint16_t)(c01 >> 16);
+                if (p.C_in > 2) dst[2] = (uint16_t)c23;
+                if (p.C_in > 3) dst[3] = (uint16_t)(c23 >> 16);
+            }
+        }
+}
+
+// Whether bwd_first2 takes the problem (everything but the workspace).
+bool first2_fits(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n, int m) {
+    if (R != 7 || S != 7 || stride != 2 || pad != 3 || C_in < 1 || C_in > 4 || C_out < kFKC || C_out % kFKC != 0) return false;
+    if ((H & 1) || (Wd & 1) || H < 2 || Wd < 2) return false;
+    if (n != m && !(m == 4 || m == 8 || m == 16)) return false;
+    const int64_t P = H / 2, Q = Wd / 2;   // (H + 6 - 7) / 2 + 1 for even H
+    const int64_t tiles = B * ((P + kFRows - 1) / kFRows) * ((Q + kFCols - 1) / kFCols);
+    return tiles > 0 && tiles < INT32_MAX && B * H * Wd < INT32_MAX && P * Q * C_out < ((int64_t)1 << 30);
+}
+
+size_t first2_image_bytes(int64_t C_out) { return (size_t)(C_out / kFKC) * kFWRows * kFPitch; }
+
+template <int M, int RK, bool PRUNE, bool NLE2>
+int launch_first2(const FirstParams& p, hipStream_t stream) {
+    auto kern = bwd_first2<M, RK, PRUNE, NLE2>;
+    constexpr int lds = kFABytes + kFWRows * kFPitch;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return SDGP_ERR_HIP;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(p.B * p.tiles_i * p.tiles_j)), dim3(kFThreads), lds, stream, p);
+    return launch_status();
+}
+
+template <int M, bool NLE2>
+int launch_first2_rk(const FirstParams& p, int rk, hipStream_t stream) {
+    if (rk == kRandom) return launch_first2<M, kRandom, true, NLE2>(p, stream);
+    if (rk == kGreedy) return launch_first2<M, kGreedy, true, NLE2>(p, stream);
+    return launch_first2<M, kAdjusted, true, NLE2>(p, stream);
 }
 
 // LDS bytes of bwd_narrow_mm for a tile of npix gradient pixels, nt column tiles and J live columns.
@@ -539,7 +760,9 @@ size_t bwd_narrow_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int6
     int64_t grid = 0;
     int lds = 0;
     if (narrow_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, p, grid, lds) != SDGP_OK || grid == 0) return 0;
-    return narrow_image_bytes(p);
+    const size_t image = narrow_image_bytes(p);
+    if (first2_fits(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m) && first2_image_bytes(C_out) > image) return first2_image_bytes(C_out);
+    return image;
 }
 
 // SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.  workspace:
@@ -548,6 +771,20 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
                       int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                       void* workspace, hipStream_t stream) {
     if (!is_aligned16(dO)) return 1;
+    if (workspace != nullptr && is_aligned16(workspace) && B * H * Wd > 0 && first2_fits(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m)) {
+        FirstParams f{};
+        f.dO = static_cast<const uint16_t*>(dO), f.vimg = static_cast<const unsigned char*>(workspace), f.dD = static_cast<uint16_t*>(dD);
+        f.B = (int)B, f.P = (int)(H / 2), f.Q = (int)(Wd / 2), f.C_in = (int)C_in, f.C_out = (int)C_out;
+        f.tiles_i = (f.P + kFRows - 1) / kFRows, f.tiles_j = (f.Q + kFCols - 1) / kFCols;
+        f.n = n, f.mix = seed_mix(seed);
+        hipLaunchKernelGGL(first_v_image, dim3((unsigned)(C_out / kFKC)), dim3(256), 0, stream, static_cast<const uint16_t*>(W),
+                           static_cast<uint16_t*>(workspace), (int)C_in);
+        if (n == m) return launch_first2<4, kGreedy, false, true>(f, stream);
+        const bool le2 = n <= 2;
+        if (m == 4) return le2 ? launch_first2_rk<4, true>(f, rk, stream) : launch_first2_rk<4, false>(f, rk, stream);
+        if (m == 8) return le2 ? launch_first2_rk<8, true>(f, rk, stream) : launch_first2_rk<8, false>(f, rk, stream);
+        return le2 ? launch_first2_rk<16, true>(f, rk, stream) : launch_first2_rk<16, false>(f, rk, stream);
+    }
     NarrowParams p{};
     int64_t grid = 0;
     int lds = 0;

@@ -37,6 +37,17 @@ __global__ void __launch_bounds__(64) k_smfmac(const short* a, const uint32_t* i
     for (int r = 0; r < 16; ++r) d[l * 16 + r] = acc[r];
 }
 
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(64) k_mfma16(const short* a, const short* b, float* d) {
+    const int l = threadIdx.x;
+    s16x8_t ra, rb;
+    for (int e = 0; e < 8; ++e) ra[e] = a[l * 8 + e], rb[e] = b[l * 8 + e];
+    f32x4_t acc = {};
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ra), __builtin_bit_cast(bf16x8_t, rb), acc, 0, 0, 0);
+    for (int r = 0; r < 4; ++r) d[l * 4 + r] = acc[r];
+}
+
 struct LaneAddr {
     uint32_t byte[64];
 };
@@ -59,6 +70,11 @@ extern "C" {
 
 int layout_mfma_32x32x16_bf16(const void* a, const void* b, void* d, void* stream) {
     k_mfma<<<1, 64, 0, (hipStream_t)stream>>>((const short*)a, (const short*)b, (float*)d);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int layout_mfma_16x16x32_bf16(const void* a, const void* b, void* d, void* stream) {
+    k_mfma16<<<1, 64, 0, (hipStream_t)stream>>>((const short*)a, (const short*)b, (float*)d);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

@@ -111,9 +111,13 @@ def test_conv_argument_errors(lib):
 
 
 def test_first_layer_workspace_query(lib):
-    # 7x7 on three channels: 160 (tap, channel) columns of 144 bytes, in whole KB, per 64 output channels
-    assert lib.sdgp_conv_bwd_data_workspace(256, 224, 224, 3, 64, 7, 7, 2, 3, 1, 2, 4) == 23 * 1024
-    assert lib.sdgp_conv_bwd_data_workspace(256, 224, 224, 3, 128, 7, 7, 2, 3, 1, 4, 4) == 2 * 23 * 1024
+    # 7x7 stride 2 pad 3 on an even image: 16 window positions x 16 columns of 80 bytes per 32 output channels
+    assert lib.sdgp_conv_bwd_data_workspace(256, 224, 224, 3, 64, 7, 7, 2, 3, 1, 2, 4) == 2 * 20 * 1024
+    assert lib.sdgp_conv_bwd_data_workspace(256, 224, 224, 3, 128, 7, 7, 2, 3, 1, 4, 4) == 4 * 20 * 1024
+    # other 7x7 layers on three channels (here: an odd image): 160 (tap, channel) columns of 144 bytes, in whole KB,
+    # per 64 output channels
+    assert lib.sdgp_conv_bwd_data_workspace(4, 223, 223, 3, 64, 7, 7, 2, 3, 1, 2, 4) == 23 * 1024
+    assert lib.sdgp_conv_bwd_data_workspace(4, 223, 223, 3, 128, 7, 7, 2, 3, 1, 4, 4) == 2 * 23 * 1024
     # 3x3 on three channels fits one column tile: no image; fp32 and wide layers never ask
     assert lib.sdgp_conv_bwd_data_workspace(512, 32, 32, 3, 64, 3, 3, 1, 1, 1, 2, 4) == 0
     assert lib.sdgp_conv_bwd_data_workspace(256, 224, 224, 3, 64, 7, 7, 2, 3, 0, 2, 4) == 0
@@ -145,9 +149,9 @@ def test_noalloc_argument_errors(lib):
     assert call(dO=None) == E_NULL
     assert call(dD=None) == E_NULL
     assert call(B=0) == OK
-    # a 7x7 first layer on three channels wants 23 KB per 64 output channels: 704 channels fit the 256 KB array, 768 do not
+    # the 7x7 stride-2 first layer wants 20 KB per 32 output channels: 384 channels fit the 256 KB array, 768 do not
     limit = 256 * 1024
-    assert lib.sdgp_conv_bwd_data_workspace(2, 64, 64, 3, 704, 7, 7, 2, 3, 1, 2, 4) <= limit
+    assert lib.sdgp_conv_bwd_data_workspace(2, 64, 64, 3, 384, 7, 7, 2, 3, 1, 2, 4) <= limit
     assert lib.sdgp_conv_bwd_data_workspace(2, 64, 64, 3, 768, 7, 7, 2, 3, 1, 2, 4) > limit
     assert call(B=2, H=64, Wd=64, C_in=3, C_out=768, R=7, S=7, stride=2, pad=3) == E_WS
 

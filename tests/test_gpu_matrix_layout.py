@@ -5,6 +5,8 @@ in the fp32 sums); the result registers must be the matrix product, read back th
 
   mfma 32x32x16 bf16:    A lane l: row l%32, k = 8*(l/32) + e (e < 8); B lane l: column l%32, same k;
                          D lane l, register r: column l%32, row 8*(r/4) + 4*(l/32) + r%4.
+  mfma 16x16x32 bf16:    A lane l: row l%16, k = 8*(l/16) + e (e < 8); B lane l: column l%16, same k;
+                         D lane l, register r: column l%16, row 4*(l/16) + r.
   smfmac 32x32x32 bf16:  A lane l: row l%32, 8 kept values of dense k = 16*(l/32) .. +15; value e belongs to quad e/2
                          and sits at position (idx >> 2e) & 3 of it; B lane l: column l%32, element eb:
                          k = 16*(eb/8) + 8*(l/32) + eb%8; D as above.
@@ -29,7 +31,7 @@ LIB = os.path.join(os.path.dirname(os.path.abspath(__file__)), "native", "libmat
 def probe():
     assert os.path.exists(LIB), "tests/native/libmatrix_layout_probe.so is not built: run python -m paper_2202_00774_amd.build"
     lib = ctypes.CDLL(LIB)
-    for name in ("layout_mfma_32x32x16_bf16", "layout_smfmac_32x32x32_bf16", "layout_ds_read_tr16_b64"):
+    for name in ("layout_mfma_32x32x16_bf16", "layout_mfma_16x16x32_bf16", "layout_smfmac_32x32x32_bf16", "layout_ds_read_tr16_b64"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -70,6 +72,28 @@ def test_mfma_32x32x16_operand_layout(probe):
     assert probe.layout_mfma_32x32x16_bf16(ptr(ta), ptr(tb), ptr(d), stream()) == 0
     torch.cuda.synchronize()
     assert np.array_equal(result_matrix(d.cpu().numpy()), A @ B)
+
+
+def test_mfma_16x16x32_operand_layout(probe):
+    rng = np.random.default_rng(11)
+    A = rng.integers(-8, 9, (16, 32)).astype(np.float32)
+    B = rng.integers(-8, 9, (32, 16)).astype(np.float32)
+    a = np.empty((64, 8), np.float32)
+    b = np.empty((64, 8), np.float32)
+    for l in range(64):
+        for e in range(8):
+            a[l, e] = A[l % 16, 8 * (l // 16) + e]
+            b[l, e] = B[8 * (l // 16) + e, l % 16]
+    d = torch.zeros((64, 4), dtype=torch.float32, device="cuda")
+    ta, tb = to_gpu(bf16(a)), to_gpu(bf16(b))
+    assert probe.layout_mfma_16x16x32_bf16(ptr(ta), ptr(tb), ptr(d), stream()) == 0
+    torch.cuda.synchronize()
+    got = d.cpu().numpy()
+    D = np.empty((16, 16), np.float32)
+    for l in range(64):
+        for r in range(4):
+            D[4 * (l // 16) + r, l % 16] = got[l, r]
+    assert np.array_equal(D, A @ B)
 
 
 @pytest.mark.parametrize("seed", [2, 3])

@@ -30,14 +30,20 @@ def run_pair(layer, n, m, ranker, seed):
 
 
 def test_noalloc_matches_the_workspace_entry_point_twice_in_a_row():
-    big = wl.ConvLayer("stem_k192", 2, 40, 36, 3, 192, 7, 7, 2, 3)     # 3 x 23 KB of the scratch array
-    small = wl.ConvLayer("stem_k64", 1, 22, 30, 3, 64, 7, 7, 2, 3)     # 23 KB: the rest keeps the first call's bytes
-    assert sdgp.conv_bwd_data_workspace(2, 40, 36, 3, 192, 7, 7, 2, 3, sdgp.BF16, 2, 4) == 3 * 23 * 1024
+    big = wl.ConvLayer("stem_k192", 2, 40, 36, 3, 192, 7, 7, 2, 3)     # 6 x 20 KB of the scratch array
+    small = wl.ConvLayer("stem_k64", 1, 22, 30, 3, 64, 7, 7, 2, 3)     # 40 KB: the rest keeps the first call's bytes
+    assert sdgp.conv_bwd_data_workspace(2, 40, 36, 3, 192, 7, 7, 2, 3, sdgp.BF16, 2, 4) == 6 * 20 * 1024
     for layer in (big, small):
         run_pair(layer, 2, 4, sdgp.GREEDY_ADJUSTED, 5)
     for layer in (big, small):
         run_pair(layer, 2, 8, sdgp.RANDOM, 6)
     run_pair(small, 4, 4, sdgp.GREEDY, 0)
+    # a 7x7 first layer the stride-2 kernel does not take (odd image): the older kernel's image, 3 x 23 KB, then 23 KB
+    odd_big = wl.ConvLayer("stem_odd_k192", 2, 39, 35, 3, 192, 7, 7, 2, 3)
+    odd_small = wl.ConvLayer("stem_odd_k64", 1, 21, 29, 3, 64, 7, 7, 2, 3)
+    assert sdgp.conv_bwd_data_workspace(2, 39, 35, 3, 192, 7, 7, 2, 3, sdgp.BF16, 2, 4) == 3 * 23 * 1024
+    for layer in (odd_big, odd_small):
+        run_pair(layer, 2, 4, sdgp.GREEDY, 7)
 
 
 def test_noalloc_without_scratch_and_refusal():
