@@ -77,7 +77,9 @@ float sdgp_ref_bf16_to_float(uint16_t h) { return bf16_to_float(h); }
  * modulo 2^32.  One mixed word is made per aligned quad of flat element indices
  * (e >> 2); its four elements take the four byte rotations of that word, so the
  * order of their keys is the order of four different bytes of one well mixed
- * word.  Constants: floor(2^32/phi) and the fractional parts of sqrt(2), sqrt(3),
+ * word.  The low four bits of a key are cleared: a key is 28 bits wide, and keys
+ * that agree in them tie (the lower position then wins, like any tie), which
+ * leaves a kernel room to carry a position code below the key.  Constants: floor(2^32/phi) and the fractional parts of sqrt(2), sqrt(3),
  * sqrt(7), sqrt(11) scaled by 2^32.
  */
 uint32_t sdgp_ref_hash(uint64_t seed, uint64_t e) {
@@ -90,7 +92,8 @@ uint32_t sdgp_ref_hash(uint64_t seed, uint64_t e) {
     v *= 0xBB67AE85u;
     v ^= v >> 16;
     unsigned rot = 8u * (x & 3u);
-    return rot ? (v << rot) | (v >> (32u - rot)) : v;
+    v = rot ? (v << rot) | (v >> (32u - rot)) : v;
+    return v & 0xFFFFFFF0u;
 }
 
 /* ------------------------------------------------------------ one group */

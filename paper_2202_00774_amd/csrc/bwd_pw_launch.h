@@ -33,7 +33,7 @@ int launch_pw_classes_one(const PwClasses& all, int ncls, hipStream_t stream) {
 struct PwShape {
     int bn, rows, waves;
 };
-constexpr PwShape kPwShapes[] = {{256, 128, 4}, {128, 128, 4}, {64, 256, 4}};
+constexpr PwShape kPwShapes[] = {{256, 128, 4}, {128, 128, 4}, {64, 256, 4}, {64, 128, 4}};
 constexpr int kPwNumShapes = sizeof(kPwShapes) / sizeof(kPwShapes[0]);
 
 template <int MODE, int M, int RK>
@@ -45,6 +45,7 @@ int launch_pw_shape(const PwParams& p, int shape, hipStream_t stream) {
         SDGP_PW_CASE(0)
         SDGP_PW_CASE(1)
         SDGP_PW_CASE(2)
+        SDGP_PW_CASE(3)
 #undef SDGP_PW_CASE
         default: return SDGP_ERR_SHAPE;
     }
@@ -58,6 +59,7 @@ int launch_pw_classes_shape(const PwClasses& all, int ncls, int shape, hipStream
         SDGP_PW_CASE(0)
         SDGP_PW_CASE(1)
         SDGP_PW_CASE(2)
+        SDGP_PW_CASE(3)
 #undef SDGP_PW_CASE
         default: return SDGP_ERR_SHAPE;
     }

@@ -91,7 +91,7 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     // the gradient rows in its L2).
     auto blocks_of = [&](int rows_per, int bn) { return ((rows + rows_per - 1) / rows_per) * ((C_in + bn - 1) / bn); };
     int shape;
-    if (C_in <= 64) shape = 2;
+    if (C_in <= 64) shape = (mode != 0) ? 3 : 2;
     else if (mode != 0 && C_in > 128) shape = 0;
     else shape = 1;
     const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
@@ -135,7 +135,7 @@ int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
     base.rows_dO = B * P * Q, base.gather = 1, base.w_taps = R * S;
 
     int shape;
-    if (C_in <= 64) shape = 2;
+    if (C_in <= 64) shape = (mode != 0) ? 3 : 2;
     else if (mode != 0 && C_in > 128) shape = 0;
     else shape = 1;
     const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;

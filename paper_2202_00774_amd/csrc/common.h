@@ -43,10 +43,11 @@ __host__ __device__ __forceinline__ uint32_t float2_to_bf16x2(float lo, float hi
 // definition).  With x = low and y = high word of e, s0/s1 the words of seed:
 //   v = 0xA54FF53A ^ (x >> 2) ^ s0*0x9E3779B9 ^ y*0xBB67AE85 ^ s1*0x510E527F
 //   v ^= v>>16; v *= 0x6A09E667; v ^= v>>15; v *= 0xBB67AE85; v ^= v>>16
-//   key = v rotated left by 8 * (x & 3) bits
+//   key = (v rotated left by 8 * (x & 3) bits) with the low four bits cleared
 // One mixed word serves an aligned quad of elements (hash_quad), each element
 // taking one of its four byte rotations: two multiplies per quad instead of per
-// element.  The seed terms are folded on the host (seed_mix), the y term once
+// element.  A key is 28 bits wide (equal keys tie, the lower position wins): the kernels put a 4-bit position code
+// below it and rank single 32-bit words.  The seed terms are folded on the host (seed_mix), the y term once
 // per group (hash_row).
 
 __host__ __device__ inline uint32_t seed_mix(uint64_t seed) {
@@ -68,7 +69,7 @@ __host__ __device__ __forceinline__ uint32_t hash_quad(uint32_t row, uint32_t e_
 
 // Key of element i (0..3) of a quad from the quad's mixed word.
 __host__ __device__ __forceinline__ uint32_t hash_lane(uint32_t quad_word, uint32_t i) {
-    return __builtin_rotateleft32(quad_word, 8u * (i & 3u));
+    return __builtin_rotateleft32(quad_word, 8u * (i & 3u)) & 0xFFFFFFF0u;
 }
 
 __host__ __device__ __forceinline__ uint32_t hash_elem(uint32_t row, uint32_t e_lo) {

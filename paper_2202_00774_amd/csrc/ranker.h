@@ -321,19 +321,16 @@ __host__ __device__ __forceinline__ void prune_compress16_bf16(const uint32_t (&
 }
 
 // Random with n <= 2 on sixteen consecutive bf16 channels, into the same operand format as prune_compress16_bf16.
-// Key of an element: the upper 28 bits of its hash with (15 - position in group) below them, so keys are distinct and
-// ordered like (hash, -position) unless two hashes agree in their upper 28 bits.  The kept set is {key >= n-th
-// largest}; it can differ from the exact one only if the n-th and the (n+1)-th largest keys of a group share those 28
-// bits (their low hash bits, not their positions, would decide): then `exact` comes back false and the caller takes
-// the generic path.  The values are fetched by position afterwards (they are not part of the key).  kPrefix (the
-// hash bits a key keeps; the low four bits are the position code's) is a parameter so that a test can shorten it and
-// exercise the `exact` flag.
-template <int M, uint32_t kPrefix = 0xFFFFFFF0u>
+// Key of an element: its 28-bit hash key with (15 - position in group) in the four bits below it, so the words are
+// distinct and ordered exactly like (key, lower position first): the kept set is {word >= n-th largest of the group}.
+// The two largest words of a quad contain every survivor of that quad.  The values are fetched by position afterwards
+// (they are not part of the key).
+template <int M>
 __host__ __device__ __forceinline__ void prune_compress16_random(const uint32_t (&w)[8], int n, uint32_t mix, uint64_t e0,
-                                                                 uint32_t (&packed)[4], uint32_t& meta, bool& exact) {
+                                                                 uint32_t (&packed)[4], uint32_t& meta) {
     static_assert(M == 4 || M == 8 || M == 16, "group sizes that tile sixteen channels");
     const bool two = n >= 2;
-    uint32_t f[4], s[4], t[4];  // largest, second and third largest key of each quad
+    uint32_t f[4], s[4];  // largest and second largest word of each quad
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const uint64_t eg = e0 + (uint64_t)((4 * q) / M * M);              // first element of the quad's group
@@ -341,44 +338,35 @@ __host__ __device__ __forceinline__ void prune_compress16_random(const uint32_t 
         const uint32_t e_lo = (uint32_t)eg + (uint32_t)((4 * q) % M);      // the quad's first element
         const uint32_t c0 = (uint32_t)(15 - (4 * q) % M);
         const uint32_t hq = hash_quad(hrow, e_lo);                         // e_lo is a multiple of 4: one word per quad
-        const uint32_t k0 = (hq & kPrefix) | c0;
-        const uint32_t k1 = (hash_lane(hq, 1u) & kPrefix) | (c0 - 1u);
-        const uint32_t k2 = (hash_lane(hq, 2u) & kPrefix) | (c0 - 2u);
-        const uint32_t k3 = (hash_lane(hq, 3u) & kPrefix) | (c0 - 3u);
+        const uint32_t k0 = hash_lane(hq, 0u) | c0;
+        const uint32_t k1 = hash_lane(hq, 1u) | (c0 - 1u);
+        const uint32_t k2 = hash_lane(hq, 2u) | (c0 - 2u);
+        const uint32_t k3 = hash_lane(hq, 3u) | (c0 - 3u);
         const uint32_t hi = sdgp_umax(k0, k1), lo = sdgp_umin(k0, k1);
         const uint32_t hi2 = sdgp_umax(k2, k3), lo2 = sdgp_umin(k2, k3);
-        const uint32_t x = sdgp_umin(hi, hi2), y = sdgp_umax(lo, lo2), z = sdgp_umin(lo, lo2);
         f[q] = sdgp_umax(hi, hi2);
-        s[q] = sdgp_umax(x, y);
-        t[q] = sdgp_umax(sdgp_umin(x, y), z);
+        s[q] = sdgp_umax(sdgp_umin(hi, hi2), sdgp_umax(lo, lo2));
     }
-    exact = true;
     uint32_t thr[4];  // the group's threshold, per quad
 #pragma unroll
     for (int g = 0; g < 16 / M; ++g) {
         constexpr int QG = M / 4;
-        // the three largest keys of the group: every candidate is among its quads' three largest
-        uint32_t v1 = f[g * QG], v2 = s[g * QG], v3 = t[g * QG];
+        // the two largest words of the group: every candidate is among its quads' two largest
+        uint32_t v1 = f[g * QG], v2 = s[g * QG];
 #pragma unroll
         for (int i = 1; i < QG; ++i) {
-            const uint32_t cand[3] = {f[g * QG + i], s[g * QG + i], t[g * QG + i]};
-#pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                const uint32_t k = cand[c];
-                const uint32_t n3 = sdgp_umax(sdgp_umin(v2, k), v3);  // new third: median of (v2, v3, k) as v2 >= v3
-                const uint32_t n2 = sdgp_umax(sdgp_umin(v1, k), v2);
-                v1 = sdgp_umax(v1, k), v2 = n2, v3 = n3;
-            }
+            const uint32_t cf = f[g * QG + i], cs = s[g * QG + i];   // cf > cs
+            v2 = sdgp_umax(sdgp_umax(sdgp_umin(v1, cf), v2), sdgp_umin(sdgp_umax(v1, cf), cs));
+            v1 = sdgp_umax(v1, cf);
         }
-        const uint32_t th = two ? v2 : v1, below = two ? v3 : v2;
-        exact = exact && ((th & kPrefix) != (below & kPrefix));
+        const uint32_t th = two ? v2 : v1;
 #pragma unroll
         for (int i = 0; i < QG; ++i) thr[g * QG + i] = th;
     }
     meta = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        // the quad's survivors are among its two largest keys; a slot without one keeps a (dropped) position, value +0
+        // the quad's survivors are among its two largest words; a slot without one keeps a (dropped) position, value +0
         const bool keep_f = f[q] >= thr[q], keep_s = s[q] >= thr[q];
         const uint32_t pf = (15u - (f[q] & 15u)) & 3u, ps = (15u - (s[q] & 15u)) & 3u;  // position in the quad
         const uint32_t d01 = w[2 * q], d23 = w[2 * q + 1];
@@ -407,59 +395,6 @@ __device__ __forceinline__ void compress_quad(const bool (&k)[4], const uint32_t
     pos = p0 | (p1 << 2);
 }
 
-// The compressed operand of sixteen channels as a value (four dwords of kept pairs and sixteen bits of positions).
-struct Packed16 {
-    uint32_t p0, p1, p2, p3, meta;
-};
-typedef uint32_t ranker_u32x4 __attribute__((ext_vector_type(4)));
-
-// Random ranker, generic path: exact for any hashes.  Reached only when the key-based path cannot be sure (two hashes
-// of a group agreeing in 28 bits at the threshold: about four groups in a billion), so it is kept out of line --
-// inlined, its registers spilled the callers' main loops (hundreds of bytes of scratch per lane at m = 8 and 16).
-template <int M>
-__device__ __attribute__((noinline)) Packed16 prune16_random_generic(ranker_u32x4 v0, ranker_u32x4 v1, int n, uint32_t mix,
-                                                                     uint64_t e0) {
-    const ranker_u32x4 v[2] = {v0, v1};
-    uint32_t raw[16], out[16];
-    bool keep[16];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
-            raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
-        }
-#pragma unroll
-    for (int g = 0; g < 16 / M; ++g) {
-        uint32_t r[M], o[M];
-        bool kk[M];
-#pragma unroll
-        for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
-        const uint64_t eg = e0 + (uint64_t)(g * M);  // a group never straddles a 2^32 boundary
-        prune_group<kBF16, M, kRandom, true>(r, n, hash_row(mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
-#pragma unroll
-        for (int j = 0; j < M; ++j) out[g * M + j] = o[j], keep[g * M + j] = kk[j];
-    }
-    uint32_t packed[4], meta = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const bool kq[4] = {keep[4 * q], keep[4 * q + 1], keep[4 * q + 2], keep[4 * q + 3]};
-        const uint32_t oq[4] = {out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]};
-        uint32_t x0, x1, pos;
-        compress_quad(kq, oq, x0, x1, pos);
-        packed[q] = x0 | (x1 << 16);
-        meta |= pos << (4 * q);
-    }
-    return {packed[0], packed[1], packed[2], packed[3], meta};
-}
-
-// Hash bits a key of the fast random path keeps.  A build with a shorter prefix (say 0xFF000000u) sends a few percent
-// of the groups through the exact fallback; that is how the fallback, which the full prefix reaches about four times in
-// a billion groups, is exercised on the GPU against the oracle.
-#ifndef SDGP_RANDOM_KEY_PREFIX
-#define SDGP_RANDOM_KEY_PREFIX 0xFFFFFFF0u
-#endif
-
 // Sixteen consecutive bf16 channels (eight dwords), n <= 2 of m in {4, 8, 16}, any ranker -> the operand format of the
 // structured-sparse matrix instructions.  e0 = flat index of the first channel (Random only).
 template <int M, int RK>
@@ -468,14 +403,7 @@ __device__ __forceinline__ void prune_compress16(const uint32_t (&w)[8], int n, 
     if constexpr (RK != kRandom) {
         prune_compress16_bf16<M, RK>(w, n, packed, meta);
     } else {
-        // fast path; it says when it cannot be sure
-        bool exact;
-        prune_compress16_random<M, SDGP_RANDOM_KEY_PREFIX>(w, n, mix, e0, packed, meta, exact);
-        if (!exact) {
-            const ranker_u32x4 v0 = {w[0], w[1], w[2], w[3]}, v1 = {w[4], w[5], w[6], w[7]};
-            const Packed16 r = prune16_random_generic<M>(v0, v1, n, mix, e0);
-            packed[0] = r.p0, packed[1] = r.p1, packed[2] = r.p2, packed[3] = r.p3, meta = r.meta;
-        }
+        prune_compress16_random<M>(w, n, mix, e0, packed, meta);
     }
 }
 

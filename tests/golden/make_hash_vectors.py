@@ -15,7 +15,7 @@ def hash32(seed, e):
     v = (v * 0xBB67AE85) & M
     v ^= v >> 16
     rot = 8 * (x & 3)
-    return ((v << rot) | (v >> (32 - rot))) & M
+    return ((v << rot) | (v >> (32 - rot))) & M & 0xFFFFFFF0   # a key is 28 bits wide: the low four are cleared
 
 
 CASES = [(0, e) for e in range(16)] + [(1, e) for e in range(8)] + [

@@ -41,7 +41,7 @@ def py_hash(seed, e):
     v = (v * 0xBB67AE85) & M
     v ^= v >> 16
     rot = 8 * (x & 3)           # one mixed word per aligned quad of elements, one byte rotation of it per element
-    return ((v << rot) | (v >> (32 - rot))) & M
+    return ((v << rot) | (v >> (32 - rot))) & M & 0xFFFFFFF0   # a key is 28 bits wide: the low four are cleared
 
 
 def brute_force_keep(keys, n):
@@ -241,8 +241,8 @@ def test_hash_matches_stored_vectors_and_python_integers():
 
 
 def test_random_first_groups_from_stored_vectors():
-    """With seed 0 the stored hash values (0x20179656 and its three byte rotations for elements 0-3, 0x69A5D3E6 and its
-    rotations for 4-7) make row 0 keep {2,3} in group 0 and {2,3} in group 1 at 2:4, {6,7} at 2:8."""
+    """With seed 0 the stored hash values (the byte rotations of 0x20179656 for elements 0-3 and of 0x69A5D3E6 for 4-7, low four
+    bits cleared) make row 0 keep {2,3} in group 0 and {2,3} in group 1 at 2:4, {6,7} at 2:8."""
     dO = np.arange(16, dtype=np.float32)[None]
     _, _, idx = oracle.prune(dO, 2, 4, oracle.RANDOM, seed=0)
     assert idx[0, :4].tolist() == [2, 3, 2, 3]

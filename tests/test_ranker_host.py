@@ -19,6 +19,3 @@ def test_key_based_rankers_match_plain_selection(tmp_path):
     run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, run.stdout[-2000:]
     assert "total mismatches 0" in run.stdout
-    # the shortened prefixes must have made the random ranker decline some groups, or the flag is not exercised
-    declined = [int(line.split("mismatches,")[1].split("inexact")[0]) for line in run.stdout.splitlines() if "prefix ff" in line and "fffffff0" not in line]
-    assert declined and all(d > 100 for d in declined), run.stdout
