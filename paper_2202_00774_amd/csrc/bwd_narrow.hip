@@ -1,8 +1,9 @@
 // Backward-data for layers with very few input channels (C_in <= 4: the first convolution of a network); the layer
 // is bound by reading dL/dO once.  A workgroup owns a TH x TW tile of input pixels of one image and brings every
 // gradient pixel its taps can reach into LDS once, pruning each m-group with the register ranker on the way
-// (Sec. III-B; stored dense with zeros).  Two kernels (Fig. 3 left, any filter size, stride and padding; bf16 storage,
-// fp32 accumulation):
+// (Sec. III-B; stored dense with zeros).  Three kernels (Fig. 3 left; bf16 storage, fp32 accumulation):
+//   * bwd_first2 (further down), for 7x7 stride-2 padding-3 filters on even images: a 2 x 2 block of input pixels and
+//     their channels are the 16 columns of one small product over a 4 x 4 window of gradient pixels.
 //   * bwd_narrow_mm, when the tile's (row tile, column tile) pairs and LDS fit (up to 7x7 filters on RGB): with so few columns per tap the product is turned around.  The matrix
 //     cores compute T[gradient pixel][tap, c] = sum_k prune(dL/dO)[pixel][k] W[k][tap][c] -- a plain GEMM with
 //     taps x C_in columns (27 for a 3x3 filter on RGB, padded to 32) -- into LDS, and every thread then sums, for

@@ -2,8 +2,8 @@
 // feed the structured-sparse matrix instruction against plain per-group selections written out here.
 //   * prune_compress16_bf16 (Magnitude, Rescaled Magnitude; Sec. III-B) against a rank count by (|x|, -position) and
 //     the rescale in fp32;
-//   * prune_compress16_random against a rank count by (H(seed, e), -position) with H written out from its definition;
-//     shortened hash prefixes make its "not sure" flag fire often, and every result it vouches for must be right.
+//   * prune_compress16_random against a rank count by (H(seed, e), -position) with H written out from its definition
+//     (28-bit keys: the kernel's word "key | position code" must order exactly like the pair).
 // Prints one line per configuration and returns the number of mismatches.  Test infrastructure, not product code.
 #include <hip/hip_runtime.h>
 #include <cstdio>
