@@ -16,9 +16,13 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
 size_t bwd_narrow_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride,
                             int pad, int n, int m);
 int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
-                  int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream);
+                  int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, void* workspace, size_t workspace_bytes,
+                  hipStream_t stream);
 int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
-                      int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream);
+                      int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, void* workspace, size_t workspace_bytes,
+                      hipStream_t stream);
+size_t bwd_pw_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n,
+                        int m);
 int bwd_row_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                    int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                    hipStream_t stream);
@@ -116,10 +120,11 @@ int check_conv(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, in
 
 
 // Matrix-core kernel when the problem fits it, the shape-agnostic kernel otherwise.
-// workspace: what sdgp_conv_bwd_data_workspace asked for, or null (entry points without one).
+// workspace: what sdgp_conv_bwd_data_workspace asked for, or null (entry points without one); the first-layer kernel
+// needs all of its share, the pointwise kernels use theirs when workspace_bytes covers it and run fused otherwise.
 int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                  int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed, void* workspace,
-                 hipStream_t stream) {
+                 size_t workspace_bytes, hipStream_t stream) {
     // no output channels: every element of dD is an empty sum.  The shape-agnostic kernel writes the zeros; the
     // matrix-core kernels assume at least one reduction chunk.
     if (C_out == 0) return sdgp::bwd_simple_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, stream);
@@ -129,11 +134,11 @@ int bwd_dispatch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, 
         if (rc <= 0) return rc;
     }
     if (dt == SDGP_BF16 && sdgp::is_aligned16(dD)) {
-        int rc = sdgp::bwd_pw_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
+        int rc = sdgp::bwd_pw_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, workspace, workspace_bytes, stream);
         if (rc <= 0) return rc;
         rc = sdgp::bwd_row_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
         if (rc <= 0) return rc;
-        rc = sdgp::bwd_gather_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
+        rc = sdgp::bwd_gather_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, workspace, workspace_bytes, stream);
         if (rc <= 0) return rc;
         rc = sdgp::bwd_conv3_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, seed, stream);
         if (rc <= 0) return rc;
@@ -164,6 +169,13 @@ ChannelWorkspace channel_workspace(int64_t rows, int64_t C_out, int64_t n_W, int
     w.off_filter = w.off_scale + align256((size_t)C_out * sizeof(float));
     w.total = w.off_filter + align256((size_t)n_W * (dt == SDGP_BF16 ? 2u : 4u));
     return w;
+}
+
+// the first-layer kernel builds a re-indexed image of a wide filter (the 7x7 stem) once per call
+size_t first_layer_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad,
+                             int dt, int n, int m, const ConvGeom& g) {
+    if (dt == SDGP_BF16 && C_in <= 4 && g.n_dD > 0) return sdgp::bwd_narrow_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m);
+    return 0;
 }
 
 }  // namespace
@@ -197,7 +209,7 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
     if (need > 0 && (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0))
         return SDGP_ERR_WORKSPACE;
     return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, need > 0 ? workspace : nullptr,
-                        static_cast<hipStream_t>(hip_stream));
+                        need > 0 ? workspace_bytes : 0, static_cast<hipStream_t>(hip_stream));
 }
 
 int sdgp_conv_bwd_data_noalloc(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
@@ -209,23 +221,28 @@ int sdgp_conv_bwd_data_noalloc(const void* dO, const void* W, void* dD, int64_t 
     if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
     if (g.n_dD == 0) return SDGP_OK;
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
+    // what the call cannot do without (a first layer's filter image); a pass that ranks the gradient ahead of the
+    // product is only an option, taken when its arrays fit the scratch
+    const size_t must = first_layer_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, g);
+    if (must > (size_t)SDGP_NOALLOC_SCRATCH_BYTES) return SDGP_ERR_WORKSPACE;  // more scratch than the library holds
     const size_t need = sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m);
-    if (need > (size_t)SDGP_NOALLOC_SCRATCH_BYTES) return SDGP_ERR_WORKSPACE;  // more scratch than the library holds
     void* ws = nullptr;
-    if (need > 0) {
+    if (need > 0 && need <= (size_t)SDGP_NOALLOC_SCRATCH_BYTES) {
         ws = scratch_on_current_device();
         if (ws == nullptr) return SDGP_ERR_HIP;
     }
     return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, ws,
-                        static_cast<hipStream_t>(hip_stream));
+                        ws != nullptr ? (size_t)SDGP_NOALLOC_SCRATCH_BYTES : 0, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
                                     int stride, int pad, int dt, int n, int m) {
     ConvGeom g;
     if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g) != SDGP_OK) return (size_t)-1;
-    // the first-layer kernel builds a transposed image of a wide filter (the 7x7 stem) once per call
-    if (dt == SDGP_BF16 && C_in <= 4 && g.n_dD > 0) return sdgp::bwd_narrow_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m);
+    const size_t first = first_layer_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, g);
+    if (first > 0) return first;
+    // 1x1 layers many column tiles wide and strided filters: room for the gradient ranked and compressed once
+    if (dt == SDGP_BF16 && C_in > 4 && g.n_dD > 0 && g.n_dO > 0) return sdgp::bwd_pw_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m);
     return 0;
 }
 
@@ -238,7 +255,7 @@ int sdgp_linear_bwd_data(const void* dO, const void* W, void* dD, int64_t rows, 
     if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
     if (g.n_dD == 0) return SDGP_OK;
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
-    return bwd_dispatch(dO, W, dD, rows, 1, 1, C_in, C_out, 1, 1, 1, 0, dt, n, m, rk, seed, nullptr,
+    return bwd_dispatch(dO, W, dD, rows, 1, 1, C_in, C_out, 1, 1, 1, 0, dt, n, m, rk, seed, nullptr, 0,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -300,7 +317,7 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (g.n_dO == 0 || g.n_W == 0)  // nothing to rescale: the product of an empty sum, zeros
-        return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, nullptr, stream);
+        return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, nullptr, 0, stream);
     const int64_t rows = B * g.P * g.Q;
     const ChannelWorkspace w = channel_workspace(rows, C_out, g.n_W, dt, m);
     if (workspace == nullptr || workspace_bytes < w.total || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0)
@@ -312,7 +329,7 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
     if (rc != SDGP_OK) return rc;
     rc = sdgp::scale_rows_launch(W, scale, filter, C_out, (int64_t)R * S * C_in, dt, stream);
     if (rc != SDGP_OK) return rc;
-    return bwd_dispatch(dO, filter, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, nullptr, stream);
+    return bwd_dispatch(dO, filter, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, SDGP_GREEDY, 0, nullptr, 0, stream);
 }
 
 size_t sdgp_conv_bwd_data_compact_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
@@ -340,7 +357,7 @@ int sdgp_conv_bwd_data_compact(const void* dO, const void* W, void* dD, int64_t 
     if (need == (size_t)-1 || !sdgp::is_aligned16(dD) || !sdgp::is_aligned16(W)) return SDGP_ERR_SHAPE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (g.n_dO == 0 || g.n_W == 0)  // empty sums: zeros, written by the shape-agnostic kernel
-        return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, nullptr, stream);
+        return bwd_dispatch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, nullptr, 0, stream);
     if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0)
         return SDGP_ERR_WORKSPACE;
     const size_t kept = (size_t)(g.n_dO / m * n);
@@ -385,7 +402,7 @@ int sdgp_conv_fwd(const void* D, const void* W, void* O, int64_t B, int64_t H, i
     const int rc2 = sdgp::mirror_transpose_filter_launch(W, workspace, C_out, C_in, R, S, dt, stream);
     if (rc2 != SDGP_OK) return rc2;
     // backward-data problem with the channel axes exchanged: "gradient" D [B,H,Wd,C_in], "input" O [B,P,Q,C_out]
-    return bwd_dispatch(D, workspace, O, B, g.P, g.Q, C_out, C_in, R, S, 1, R - 1 - pad, dt, 1, 1, SDGP_GREEDY, 0, nullptr, stream);
+    return bwd_dispatch(D, workspace, O, B, g.P, g.Q, C_out, C_in, R, S, 1, R - 1 - pad, dt, 1, 1, SDGP_GREEDY, 0, nullptr, 0, stream);
 }
 
 size_t sdgp_conv_bwd_weight_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,

@@ -505,14 +505,14 @@ struct FirstParams {
 };
 
 // V's image for one chunk of 32 output channels: row (window position t = (dp+1)*4 + (dq+1), column n = a*8 + b*4 + c),
-// 32 channels contiguous, kFPitch bytes per row.  One workgroup per chunk.
+// 32 channels contiguous, kFPitch bytes per row.  One workgroup per (chunk, window position).
 __global__ void __launch_bounds__(256) first_v_image(const uint16_t* __restrict__ W, uint16_t* __restrict__ img, int C_in) {
-    const int kc = blockIdx.x;
-    uint16_t* dst = img + (size_t)kc * kFWRows * (kFPitch / 2);
-    for (int e = threadIdx.x; e < kFWRows * (kFPitch / 2); e += 256) {
-        const int row = e / (kFPitch / 2), kk = e % (kFPitch / 2);
-        const int t = row >> 4, nn = row & 15;
-        const int dp = (t >> 2) - 1, dq = (t & 3) - 1, a = nn >> 3, b = (nn >> 2) & 1, c = nn & 3;
+    const int kc = blockIdx.x >> 4, t = blockIdx.x & 15;
+    uint16_t* dst = img + ((size_t)kc * kFWRows + t * 16) * (kFPitch / 2);
+    const int dp = (t >> 2) - 1, dq = (t & 3) - 1;
+    for (int e = threadIdx.x; e < 16 * (kFPitch / 2); e += 256) {
+        const int nn = e / (kFPitch / 2), kk = e % (kFPitch / 2);
+        const int a = nn >> 3, b = (nn >> 2) & 1, c = nn & 3;
         const int r = a + 3 - 2 * dp, s2 = b + 3 - 2 * dq;
         uint16_t v = 0;
         if (kk < kFKC && c < C_in && r >= 0 && r < 7 && s2 >= 0 && s2 < 7)
@@ -778,7 +778,7 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
         f.B = (int)B, f.P = (int)(H / 2), f.Q = (int)(Wd / 2), f.C_in = (int)C_in, f.C_out = (int)C_out;
         f.tiles_i = (f.P + kFRows - 1) / kFRows, f.tiles_j = (f.Q + kFCols - 1) / kFCols;
         f.n = n, f.mix = seed_mix(seed);
-        hipLaunchKernelGGL(first_v_image, dim3((unsigned)(C_out / kFKC)), dim3(256), 0, stream, static_cast<const uint16_t*>(W),
+        hipLaunchKernelGGL(first_v_image, dim3((unsigned)(C_out / kFKC * 16)), dim3(256), 0, stream, static_cast<const uint16_t*>(W),
                            static_cast<uint16_t*>(workspace), (int)C_in);
         if (n == m) return launch_first2<4, kGreedy, false, true>(f, stream);
         const bool le2 = n <= 2;

@@ -9,6 +9,11 @@
 //   * pruning (Sec. III-B): the raw rows of chunk s+2 stream in while chunk s+1 is ranked / pruned / compressed (two
 //     values + two 2-bit positions per aligned quad, the operand of v_smfmac_f32_32x32x32_bf16; every n <= 2 pattern
 //     fits it) and chunk s is multiplied;
+//   * MODE 3 takes the gradient already ranked and compressed (a pass of its own wrote, per row and 64 channels, the 32
+//     kept values and their positions: csrc/compress.hip): nothing is ranked here, the reduction runs in chunks of 64
+//     channels on the structured-sparse instruction, and the copies bring values and positions straight into the
+//     layout the fragments are read from.  For layers where the fused kernel would rank a gradient element many
+//     times over (one workgroup per column tile and per tap ranks its rows itself);
 //   * wavefronts of one kind, register tiles of up to 128 x 64, two workgroups to a CU; fragments as in bwd_row.h (swizzled 16-byte
 //     reads for the gradient, transpose reads for W in its native layout);
 //   * the result leaves through LDS as whole rows with 16-byte stores; with a stride, a gradient pixel's row goes to
@@ -38,21 +43,26 @@ struct PwParams {
     int n;
     uint32_t mix;
     int ntiles_n, nblocks;
+    // MODE 3: dO points at the compressed values ([rows_dO][C_out / 2] bf16) and meta at the positions
+    // ([C_out / 64][rows_dO] x 8 bytes: four 16-bit words of 2-bit positions per row and 64 channels)
+    const unsigned char* meta;
 };
 
-constexpr int kPwKC = 32;  // reduction channels per chunk
+constexpr int kPwKC = 32;  // reduction channels per chunk (64 when the operand arrives compressed)
 
 template <int BN, int MODE, int ROWS>
 struct PwLayout {
-    static constexpr bool kSparse = MODE == 2;
-    static constexpr bool kPrunes = MODE != 0;  // raw rows are staged and ranked (MODE 1 stores them dense, zero-filled)
+    static constexpr bool kPre = MODE == 3;     // the gradient arrives ranked and compressed
+    static constexpr bool kSparse = MODE == 2 || MODE == 3;
+    static constexpr bool kPrunes = MODE == 1 || MODE == 2;  // raw rows are staged and ranked (MODE 1 stores them dense, zero-filled)
+    static constexpr int kKC = kPre ? 64 : kPwKC;
     static constexpr int kWRow = BN * 2;
-    static constexpr int kWSlab = kPwKC * kWRow;
+    static constexpr int kWSlab = kKC * kWRow;
     static constexpr int kWUnits = kWSlab / 1024;
     static constexpr int kAUnits = ROWS / 16;                  // 1 KB copy units (16 rows x 64 B) of a gradient chunk
-    static constexpr int kABytes = ROWS * (kSparse ? 32 : 64);  // one gradient buffer as the matrix instructions read it
+    static constexpr int kABytes = ROWS * (kSparse && !kPre ? 32 : 64);  // one gradient buffer as the matrix instructions read it
     static constexpr int kRawBytes = ROWS * 64;
-    static constexpr int kMetaBytes = kSparse ? ROWS * 4 : 0;
+    static constexpr int kMetaBytes = kPre ? ROWS * 8 : kSparse ? ROWS * 4 : 0;
     static constexpr int kOutPitch = BN * 2 + 16;
     // buffer sets in the request ring: the dense kernel requests kSets - 1 chunks ahead.  Two: with three or four
     // sets the 128 x 128 dense tile drops from four workgroups per CU to two and runs 20-30 % slower -- more
@@ -75,9 +85,10 @@ template <int BN, int MODE, int M, int RK, int ROWS, int NW, bool GATHER>
 __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     using L = PwLayout<BN, MODE, ROWS>;
     static_assert(L::total() <= 160 * 1024, "LDS budget");
-    constexpr bool SPARSE = MODE == 2;
-    constexpr bool PRUNES = MODE != 0;
-    constexpr int KC = kPwKC;
+    constexpr bool SPARSE = L::kSparse;
+    constexpr bool PRUNES = L::kPrunes;
+    constexpr bool PRE = L::kPre;
+    constexpr int KC = L::kKC;
     constexpr int WAVES_N = BN / 64;
     constexpr int WAVES_M = NW / WAVES_N;
     constexpr int NT = NW * 64;
@@ -118,7 +129,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     auto tap_of = [&](int st) { return GATHER ? (st >= nchunks) + (st >= 2 * nchunks) + (st >= 3 * nchunks) : 0; };
     const unsigned char* const gdO = reinterpret_cast<const unsigned char*>(p.dO);
     const unsigned char* const gWb = reinterpret_cast<const unsigned char*>(p.W);
-    const uint32_t rowB = (uint32_t)p.C_out * 2u;      // bytes per gradient row
+    const uint32_t rowB = PRE ? (uint32_t)p.C_out : (uint32_t)p.C_out * 2u;  // bytes per gradient row (half of them when compressed)
     const uint32_t wrowB = (uint32_t)p.C_in * 2u * (uint32_t)p.w_taps;  // bytes per W row (all taps of one output channel)
 
     // ---- copies.  Gradient: unit u = rows 16u .. 16u+15 of the tile, 64 bytes each; LDS position (lane & 3) of row
@@ -130,7 +141,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         if constexpr (!GATHER) {
             long long row = m0 + u * 16 + (lane >> 2);
             if (row > last_row) row = last_row;
-            lds_copy16(gdO + ((size_t)row * rowB + (size_t)st * (KC * 2) + c16_a), dst);
+            lds_copy16(gdO + ((size_t)row * rowB + (size_t)st * 64u + c16_a), dst);
         } else {
             const int t = tap_of(st), chunk = st - t * nchunks;
             const int rl = u * 16 + (lane >> 2);
@@ -139,7 +150,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
             const bool ok = base >= 0 && i >= 0 && i < p.P && j >= 0 && j < p.Q;
             long long src = (long long)base + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
             src = src < 0 ? 0 : (src > last_pix ? last_pix : src);  // (a valid tap is inside anyway)
-            const unsigned char* a = ok ? gdO + ((size_t)src * rowB + (size_t)chunk * (KC * 2) + c16_a)
+            const unsigned char* a = ok ? gdO + ((size_t)src * rowB + (size_t)chunk * 64u + c16_a)
                                         : reinterpret_cast<const unsigned char*>(kPwZeros) + c16_a;
             lds_copy16(a, dst);
         }
@@ -154,10 +165,32 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         const int wtap = GATHER ? p.tap_w[t] : 0;
         lds_copy16(gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(wtap * p.C_in + col) * 2u), dst);
     };
+    // MODE 3: the positions of 32 rows (8 bytes each, one 4-byte word per lane) of reduction step `st`
+    auto copy_meta_unit = [&](int u, int st, uint32_t dst) {
+        const int rl = u * 32 + (lane >> 1);
+        const uint32_t word = (uint32_t)(lane & 1) * 4u;
+        if constexpr (!GATHER) {
+            long long row = m0 + rl;
+            if (row > last_row) row = last_row;
+            lds_copy4(p.meta + (((size_t)st * (size_t)p.rows_dO + (size_t)row) * 8u + word), dst);
+        } else {
+            const int t = tap_of(st), chunk = st - t * nchunks;
+            const int base = rowtab[3 * rl], ij = rowtab[3 * rl + 1];
+            const int i = (ij & 0xFFFF) + p.tap_dp[t], j = (ij >> 16) + p.tap_dq[t];
+            const bool ok = base >= 0 && i >= 0 && i < p.P && j >= 0 && j < p.Q;
+            long long src = (long long)base + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
+            src = src < 0 ? 0 : (src > last_pix ? last_pix : src);
+            const unsigned char* a = ok ? p.meta + (((size_t)chunk * (size_t)p.rows_dO + (size_t)src) * 8u + word)
+                                        : reinterpret_cast<const unsigned char*>(kPwZeros) + word;
+            lds_copy4(a, dst);
+        }
+    };
     // everything chunk `chunk` needs, into buffer set `set` (pruning: the gradient goes to raw slot `set`)
     auto copy_chunk = [&](int chunk, int set, bool with_w) {
         const uint32_t a_dst = smem_base + (PRUNES ? L::off_raw() + set * L::kRawBytes : L::off_a() + set * L::kABytes);
         for (int i = wave; i < AU; i += NW) copy_a_unit(i, chunk, a_dst + (uint32_t)i * 1024u);
+        if constexpr (PRE)
+            for (int i = wave; i < ROWS / 32; i += NW) copy_meta_unit(i, chunk, smem_base + L::off_meta() + set * L::kMetaBytes + (uint32_t)i * 256u);
         if (with_w)
             for (int i = wave; i < WU; i += NW) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
     };
@@ -212,7 +245,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
                 }
             }
         }
-        if constexpr (SPARSE) {
+        if constexpr (SPARSE && PRUNES) {
 #pragma unroll 1
             for (int item = tid; item < ROWS * 2; item += NT) {
                 const int row = item >> 1, part = item & 1;
@@ -298,8 +331,8 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
 #pragma unroll
     for (int t = 0; t < TM; ++t) {
         const uint32_t row = (uint32_t)(wm * WM + t * 32 + (lane & 31));
-        a_lane[t] = SPARSE ? row * 32u + half * 16u : row * 64u + (((half ^ (row >> 2)) & 3u) << 4);
-        m_lane[t] = row * 4u + half * 2u;
+        a_lane[t] = SPARSE && !PRE ? row * 32u + half * 16u : row * 64u + (((half ^ (row >> 2)) & 3u) << 4);
+        m_lane[t] = PRE ? row * 8u + half * 2u : row * 4u + half * 2u;
     }
     struct Frags {
         u32x4_t a[TM];
@@ -309,7 +342,10 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     auto load_frags = [&](Frags& f, int set, int ks) {
 #pragma unroll
         for (int t = 0; t < TM; ++t) {
-            if constexpr (SPARSE) {
+            if constexpr (PRE) {
+                f.a[t] = *(SDGP_LDS u32x4_t*)(smem + L::off_a() + set * L::kABytes + (a_lane[t] ^ (uint32_t)(ks * 32)));
+                f.meta[t] = *(SDGP_LDS uint16_t*)(smem + L::off_meta() + set * L::kMetaBytes + m_lane[t] + ks * 4);
+            } else if constexpr (SPARSE) {
                 f.a[t] = *(SDGP_LDS u32x4_t*)(smem + L::off_a() + set * L::kABytes + a_lane[t]);
                 f.meta[t] = *(SDGP_LDS uint16_t*)(smem + L::off_meta() + set * L::kMetaBytes + m_lane[t]);
             } else {
@@ -323,7 +359,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
                 s16x4_t q[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + ((i >> 1) * 16 + (i & 1) * 4) * L::kWRow));
+                    q[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SDGP_LDS s16x4_t*)(wb + (ks * 32 + (i >> 1) * 16 + (i & 1) * 4) * L::kWRow));
                 typedef short s16x16_t __attribute__((ext_vector_type(16)));
                 const s16x16_t all = {q[0][0], q[0][1], q[0][2], q[0][3], q[1][0], q[1][1], q[1][2], q[1][3],
                                       q[2][0], q[2][1], q[2][2], q[2][3], q[3][0], q[3][1], q[3][2], q[3][3]};

@@ -22,6 +22,12 @@ int launch_pw_classes_masked_m4(const PwClasses& all, int ncls, int shape, int r
 int launch_pw_classes_masked_m8(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
 int launch_pw_classes_masked_m16(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
 int launch_pw_classes_masked_m32(const PwClasses& all, int ncls, int shape, int rk, hipStream_t stream);
+int launch_pw_pre(const PwParams& p, int shape, hipStream_t stream);
+int launch_pw_classes_pre(const PwClasses& all, int ncls, int shape, hipStream_t stream);
+size_t compress_meta_offset(int64_t rows, int64_t C_out);
+size_t compress_bytes(int64_t rows, int64_t C_out);
+int compress_launch(const void* dO, int64_t rows, int64_t C_out, int n, int m, int rk, uint64_t seed, void* workspace,
+                    hipStream_t stream);
 
 namespace {
 
@@ -60,47 +66,104 @@ int launch_pw_classes_any(const PwClasses& all, int ncls, int mode, int m, int s
     return launch_pw_classes_masked_m32(all, ncls, shape, rk, stream);
 }
 
-}  // namespace
+// Tile shape of the fused and dense kernels.  Workgroups of four wavefronts, two or more to a CU, so that one's loads
+// and stores overlap the other's arithmetic.  Pruning: all of C_in (up to 256 columns) in one workgroup, so every
+// gradient row is ranked once per 256 columns; dense: 128 x 128 tiles measured fastest (column tiles of one row tile
+// run side by side on one XCD and find the gradient rows in its L2).
+int pw_shape(int mode, int64_t C_in) {
+    if (C_in <= 64) return (mode != 0) ? 3 : 2;
+    if (mode != 0 && C_in > 128) return 0;
+    return 1;
+}
+// Tile shape when the gradient arrives compressed (nothing is ranked in the kernel): the dense kernel's.
+int pw_pre_shape(int64_t C_in) { return C_in <= 64 ? 2 : 1; }
 
-// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
-int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
-                  int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
+// Whether a pass that ranks and compresses the gradient first (csrc/compress.hip) pays: the fused kernel would rank
+// every gradient element `times` times, the pass reads it once and writes half of it, and the product that follows
+// runs 1.15-1.3 times as fast as the dense one.  Measured on the layers of ResNet-50 at batch 256: from two times on
+// with the random ranker (the hash makes ranking dearer), from four on with the magnitude rankers.
+bool pre_pays(int mode, int64_t C_out, int64_t rows_dO, int times, int rk) {
+    const int least = rk == kRandom ? 2 : 4;
+    return mode == 2 && (C_out % 64) == 0 && times >= least && rows_dO * (C_out / 16) < ((int64_t)1 << 31);
+}
+
+struct PwPlan {
+    PwParams p;
+    int mode, shape;
+    bool pre;       // rank and compress first, then MODE 3 (needs the workspace)
+    size_t bytes;   // workspace of the pre path
+};
+
+// 0 and the plan, or 1 when the pointwise kernel does not take the problem.
+int pw_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n, int m,
+            int rk, PwPlan& out) {
     const int mode = pw_mode(n, m);
     if (mode < 0) return 1;
     if (R != 1 || S != 1 || stride < 1 || stride > 255 || pad != 0 || (C_out % kPwKC) != 0 || (C_in % 8) != 0) return 1;
     if (mode != 0 && (C_out % m) != 0) return 1;
-    if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
     const int64_t P = (H - 1) / stride + 1, Q = (Wd - 1) / stride + 1;  // gradient image
     const int64_t rows = B * P * Q;
     if (stride > 1 && (B * H * Wd >= INT_MAX || H < 1 || Wd < 1)) return 1;
     if (rows < 1 || C_out < kPwKC || C_in < 8 || C_out >= (1 << 24) || C_in >= (1 << 24)) return 1;
 
     PwParams p{};
-    p.dO = static_cast<const uint16_t*>(dO);
-    p.W = static_cast<const uint16_t*>(W);
-    p.dD = static_cast<uint16_t*>(dD);
     p.rows = rows, p.C_out = (int)C_out, p.C_in = (int)C_in;
     p.n = n;
     p.stride = stride, p.P = (int)P, p.Q = (int)Q, p.H = (int)H, p.Wd = (int)Wd;
     p.rows_dO = rows, p.gather = 0, p.ntaps = 1, p.w_taps = 1;
-    p.mix = seed_mix(seed);
 
-    // tile shape.  Workgroups of four wavefronts, two to a CU, so that one's loads and stores overlap the other's
-    // arithmetic.  Pruning: all of C_in (up to 256 columns) in one workgroup, so every gradient row is ranked once;
-    // dense: 128 x 128 tiles measured fastest (column tiles of one row tile run side by side on one XCD and find
-    // the gradient rows in its L2).
-    auto blocks_of = [&](int rows_per, int bn) { return ((rows + rows_per - 1) / rows_per) * ((C_in + bn - 1) / bn); };
-    int shape;
-    if (C_in <= 64) shape = (mode != 0) ? 3 : 2;
-    else if (mode != 0 && C_in > 128) shape = 0;
-    else shape = 1;
+    int shape = pw_shape(mode, C_in);
+    const int fused_tiles_n = (int)((C_in + kPwShapes[shape].bn - 1) / kPwShapes[shape].bn);
+    out.pre = pre_pays(mode, C_out, rows, fused_tiles_n, rk);
+    if (out.pre) shape = pw_pre_shape(C_in);
     const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
-    const int64_t blocks = blocks_of(rows_per, bn);
+    const int64_t blocks = ((rows + rows_per - 1) / rows_per) * ((C_in + bn - 1) / bn);
     if (blocks < 64 || blocks >= INT_MAX) return 1;  // too small to be worth a matrix-core launch of this shape
     p.ntiles_n = (int)((C_in + bn - 1) / bn);
     p.nblocks = (int)blocks;
+    out.p = p, out.mode = mode, out.shape = shape;
+    out.bytes = out.pre ? compress_bytes(rows, C_out) : 0;
+    return 0;
+}
 
-    return launch_pw_any(p, mode, m, shape, rk, stream);
+}  // namespace
+
+// Workspace bytes with which bwd_pw_launch / bwd_gather_launch rank the gradient once, in a pass of their own (0: the
+// fused kernel is used, or neither takes the problem).
+size_t bwd_pw_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n,
+                        int m);
+
+// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.  With a
+// workspace of at least bwd_pw_workspace(...) bytes the gradient is ranked once, in a pass of its own, where that
+// pays; with less the fused kernel runs.
+int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                  int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, void* workspace, size_t workspace_bytes,
+                  hipStream_t stream) {
+    if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
+    PwPlan plan{};
+    if (pw_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, plan) != 0) return 1;
+    if (plan.pre && (workspace == nullptr || workspace_bytes < plan.bytes || !is_aligned16(workspace))) {
+        // no room for the compressed gradient: the fused kernel
+        const int shape = pw_shape(plan.mode, C_in);
+        const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
+        const int64_t blocks = ((plan.p.rows + rows_per - 1) / rows_per) * ((C_in + bn - 1) / bn);
+        if (blocks < 64 || blocks >= INT_MAX) return 1;
+        plan.p.ntiles_n = (int)((C_in + bn - 1) / bn), plan.p.nblocks = (int)blocks;
+        plan.shape = shape, plan.pre = false;
+    }
+    PwParams& p = plan.p;
+    p.W = static_cast<const uint16_t*>(W);
+    p.dD = static_cast<uint16_t*>(dD);
+    p.mix = seed_mix(seed);
+    if (plan.pre) {
+        const int rc = compress_launch(dO, p.rows_dO, C_out, n, m, rk, seed, workspace, stream);
+        if (rc != SDGP_OK) return rc;
+        p.dO = static_cast<const uint16_t*>(workspace);
+        p.meta = static_cast<const unsigned char*>(workspace) + compress_meta_offset(p.rows_dO, C_out);
+        return launch_pw_pre(p, plan.shape, stream);
+    }
+    p.dO = static_cast<const uint16_t*>(dO);
+    return launch_pw_any(p, plan.mode, m, plan.shape, rk, stream);
 }
 
 // Strided filters wider than 1x1 (the stride-2 3x3 layers of a ResNet): the input pixels split into stride x stride
@@ -109,15 +172,23 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
 // a GEMM of the pointwise kernel whose reduction runs over (tap, channel) and whose rows are gathered from the gradient
 // pixels (i + dp, j + dq) of each tap, zeros outside; all classes go out in one launch (blockIdx.y = class).  Each
 // gradient element is ranked once per tap that reads it (the kept set does not depend on who asks).
-// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.
-int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
-                      int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, hipStream_t stream) {
+namespace {
+
+struct GatherPlan {
+    PwClasses all;
+    int ncls, mode, shape;
+    bool pre;
+    size_t bytes;
+};
+
+// 0 and the plan for the shape the fused kernels use (pre == false) or the compressed-operand kernel uses, or 1.
+int gather_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n, int m,
+                bool want_pre, GatherPlan& out) {
     const int mode = pw_mode(n, m);
     if (mode < 0) return 1;
     if (stride < 2 || stride > 4 || R < stride || S < stride || R > 2 * stride || S > 2 * stride || pad < 0) return 1;
     if (C_out < kPwKC || (C_out % kPwKC) != 0 || C_in < 8 || (C_in % 8) != 0) return 1;
     if (mode != 0 && (C_out % m) != 0) return 1;
-    if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
     if (H + 2 * pad < R || Wd + 2 * pad < S || H < stride || Wd < stride) return 1;
     const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
     if (B < 1 || P < 1 || Q < 1 || P >= 65536 || Q >= 32768 || H >= 65536 || Wd >= 32768 || B * (P + 8) * (Q + 8) >= (1 << 30) || B * H * Wd >= INT_MAX ||
@@ -125,26 +196,20 @@ int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
         return 1;
 
     PwParams base{};
-    base.dO = static_cast<const uint16_t*>(dO);
-    base.W = static_cast<const uint16_t*>(W);
-    base.dD = static_cast<uint16_t*>(dD);
     base.C_out = (int)C_out, base.C_in = (int)C_in;
     base.n = n;
-    base.mix = seed_mix(seed);
     base.stride = stride, base.P = (int)P, base.Q = (int)Q, base.H = (int)H, base.Wd = (int)Wd;
     base.rows_dO = B * P * Q, base.gather = 1, base.w_taps = R * S;
 
-    int shape;
-    if (C_in <= 64) shape = (mode != 0) ? 3 : 2;
-    else if (mode != 0 && C_in > 128) shape = 0;
-    else shape = 1;
+    // every tap of every class ranks the rows it reads: R * S times per gradient element and column tile
+    out.pre = want_pre && pre_pays(mode, C_out, base.rows_dO, R * S, kRandom);
+    const int shape = out.pre ? pw_pre_shape(C_in) : pw_shape(mode, C_in);
     const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
     base.ntiles_n = (int)((C_in + bn - 1) / bn);
 
     // all classes first: nothing is launched unless every one of them fits
     static_assert(kPwMaxClasses >= 16, "stride up to four");
-    PwClasses all{};
-    PwParams* cls = all.c;
+    PwParams* cls = out.all.c;
     int ncls = 0;
     for (int a = 0; a < stride; ++a)
         for (int b = 0; b < stride; ++b) {
@@ -176,7 +241,52 @@ int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
             cls[j] = cls[j - 1];
             cls[j - 1] = t;
         }
-    return launch_pw_classes_any(all, ncls, mode, m, shape, rk, stream);
+    out.ncls = ncls, out.mode = mode, out.shape = shape;
+    out.bytes = out.pre ? compress_bytes(base.rows_dO, C_out) : 0;
+    return 0;
+}
+
+}  // namespace
+
+// SDGP_OK after launching, a positive value when the problem does not fit, or a negative sdgp_status.  Workspace as
+// for bwd_pw_launch.
+int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
+                      int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, void* workspace, size_t workspace_bytes,
+                      hipStream_t stream) {
+    if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
+    GatherPlan plan{};
+    bool planned = false;
+    if (workspace != nullptr && is_aligned16(workspace)) {
+        planned = gather_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, true, plan) == 0 && (!plan.pre || workspace_bytes >= plan.bytes);
+    }
+    if (!planned && gather_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, false, plan) != 0) return 1;
+    const int64_t rows_dO = plan.all.c[0].rows_dO;
+    const void* grad = dO;
+    const unsigned char* meta = nullptr;
+    if (plan.pre) {
+        const int rc = compress_launch(dO, rows_dO, C_out, n, m, rk, seed, workspace, stream);
+        if (rc != SDGP_OK) return rc;
+        grad = workspace;
+        meta = static_cast<const unsigned char*>(workspace) + compress_meta_offset(rows_dO, C_out);
+    }
+    for (int i = 0; i < plan.ncls; ++i) {
+        PwParams& q = plan.all.c[i];
+        q.dO = static_cast<const uint16_t*>(grad), q.meta = meta;
+        q.W = static_cast<const uint16_t*>(W), q.dD = static_cast<uint16_t*>(dD);
+        q.mix = seed_mix(seed);
+    }
+    if (plan.pre) return launch_pw_classes_pre(plan.all, plan.ncls, plan.shape, stream);
+    return launch_pw_classes_any(plan.all, plan.ncls, plan.mode, m, plan.shape, rk, stream);
+}
+
+size_t bwd_pw_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n,
+                        int m) {
+    PwPlan one{};
+    // (the ranker that takes the pass soonest: the size is enough for any)
+    if (pw_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, kRandom, one) == 0) return one.bytes;
+    GatherPlan many{};
+    if (gather_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, true, many) == 0) return many.bytes;
+    return 0;
 }
 
 }  // namespace sdgp

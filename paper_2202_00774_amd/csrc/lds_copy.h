@@ -13,6 +13,11 @@ __device__ __forceinline__ void lds_copy16(const void* gptr, uint32_t lds_base) 
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);  // wave-uniform by construction
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
 }
+// Four bytes per lane: lane l's word lands at lds_base + 4 l.
+__device__ __forceinline__ void lds_copy4(const void* gptr, uint32_t lds_base) {
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(base), "v"(gptr) : "memory");
+}
 // Same, address = wave-uniform base + 32-bit byte offset per lane.
 __device__ __forceinline__ void lds_copy16(const void* sbase, uint32_t voff, uint32_t lds_base) {
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);

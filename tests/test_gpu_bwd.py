@@ -185,6 +185,78 @@ def test_many_tile_fused_equals_prune_then_dense():
         assert diff <= 2e-2 * scale, (n, m, ranker, diff, scale)
 
 
+# ------------------------------------------------- 3x3 first layers (C_in <= 4): ragged tiles, one to four channels,
+# several passes of 64 output channels, few and many tiles
+
+FIRST_3X3 = [
+    wl.ConvLayer("f3_rgb_32", 5, 32, 32, 3, 64, 3, 3, 1, 1),             # CIFAR shape
+    wl.ConvLayer("f3_ragged", 2, 20, 36, 4, 128, 3, 3, 1, 1),            # ragged tiles both ways, two passes of 64 channels
+    wl.ConvLayer("f3_gray_tiny", 3, 2, 2, 1, 64, 3, 3, 1, 1),            # one block per image
+    wl.ConvLayer("f3_two_ch_wide", 1, 6, 70, 2, 192, 3, 3, 1, 1),        # three column tiles, the last ragged
+]
+FIRST_3X3_MANY = [
+    wl.ConvLayer("f3_rgb_32_many", 300, 32, 32, 3, 64, 3, 3, 1, 1),      # many tiles
+    wl.ConvLayer("f3_ragged_many", 90, 40, 44, 4, 128, 3, 3, 1, 1),      # 3 x 2 tiles per image, ragged both ways
+]
+
+
+@pytest.mark.parametrize("layer", FIRST_3X3, ids=lambda l: l.name)
+@pytest.mark.parametrize("ranker", RANKERS)
+def test_first_3x3_matches_oracle(layer, ranker):
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=91, dtype=oracle.BF16)
+    for n, m in ((2, 4), (4, 4), (1, 4), (3, 4), (2, 8), (2, 16), (4, 16)):
+        check_conv(layer, dO, W, n, m, ranker, 17, oracle.BF16)
+
+
+@pytest.mark.parametrize("layer", FIRST_3X3_MANY, ids=lambda l: l.name)
+def test_first_3x3_many_tiles_sampled(layer):
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=92, dtype=oracle.BF16)
+    pixels = sample_pixels(layer, 3000, 9)
+    for n, m, ranker in ((4, 4, oracle.GREEDY), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (2, 4, oracle.RANDOM),
+                         (2, 8, oracle.RANDOM), (4, 8, oracle.GREEDY), (2, 16, oracle.GREEDY_ADJUSTED)):
+        check_conv(layer, dO, W, n, m, ranker, 23, oracle.BF16, pixels=pixels)
+
+
+# ------------------------------------------------- gradient ranked and compressed ahead of the product
+# 1x1 layers several column tiles wide and strided filters with C_out a multiple of 64 and n <= 2: a pass of its own
+# writes kept values and positions to the workspace, and the product reads them (no ranking in the matrix kernel).
+
+PRE_COMPRESSED = [
+    wl.ConvLayer("pre_1x1_wide", 3, 13, 13, 2048, 128, 1, 1, 1, 0),      # ragged last row tile, 16 column tiles
+    wl.ConvLayer("pre_1x1_s2", 5, 27, 27, 1024, 192, 1, 1, 2, 0),        # stride 2: three chunks of 64 channels
+    wl.ConvLayer("pre_3x3s2", 44, 40, 40, 64, 128, 3, 3, 2, 1),          # four parity classes, one to four taps
+    wl.ConvLayer("pre_4x4s2", 44, 40, 40, 72, 64, 4, 4, 2, 1),           # four taps in every class, ragged column tile
+]
+
+
+@pytest.mark.parametrize("layer", PRE_COMPRESSED, ids=lambda l: l.name)
+def test_pre_compressed_gradient_matches_oracle(layer):
+    assert sdgp.conv_bwd_data_workspace(layer.B, layer.H, layer.Wd, layer.C_in, layer.C_out, layer.R, layer.S, layer.stride,
+                                        layer.pad, sdgp.BF16, 2, 4) > 0
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=61, dtype=oracle.BF16)
+    pixels = sample_pixels(layer, 1500, 13)
+    for n, m, ranker in ((2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (2, 4, oracle.RANDOM), (1, 4, oracle.RANDOM),
+                         (2, 8, oracle.GREEDY_ADJUSTED), (1, 8, oracle.GREEDY), (2, 16, oracle.RANDOM), (2, 16, oracle.GREEDY),
+                         (4, 4, oracle.GREEDY), (3, 4, oracle.GREEDY)):      # the last two: dense and masked kernels, no pass
+        check_conv(layer, dO, W, n, m, ranker, 29, oracle.BF16, pixels=pixels)
+
+
+def test_pre_compressed_equals_fused():
+    """With and without room for the compressed gradient the same kept values are multiplied (the entry point without
+    a workspace runs the fused kernel when the arrays do not fit its scratch)."""
+    layer = wl.ConvLayer("pre_1x1_big", 13, 13, 13, 2048, 128, 1, 1, 1, 0)    # 290 KB of arrays: more than the scratch
+    assert sdgp.conv_bwd_data_workspace(13, 13, 13, 2048, 128, 1, 1, 1, 0, sdgp.BF16, 2, 4) > 256 * 1024
+    dO, W = wl.layer_inputs(layer, 1e-3, 0.3, seed=62, dtype=oracle.BF16)
+    d, w = to_gpu(dO), to_gpu(W)
+    for n, m, ranker in ((2, 4, sdgp.RANDOM), (2, 8, sdgp.GREEDY_ADJUSTED)):
+        a = sdgp.sdgp_conv_bwd_data(d, w, layer.H, layer.Wd, 1, 0, n, m, ranker, 5)
+        b = torch.empty_like(a)
+        sdgp.sdgp_conv_bwd_data_noalloc(d, w, layer.H, layer.Wd, 1, 0, n, m, ranker, 5, out=b)
+        torch.cuda.synchronize()
+        diff = (a.float() - b.float()).abs().max().item()
+        assert diff <= 2e-2 * a.float().abs().max().item()
+
+
 # ------------------------------------------------- full-size workload (the shapes and launches bench.py times)
 
 @pytest.mark.parametrize("index", range(6))
