@@ -67,6 +67,9 @@ def _load():
             lib.sdgp_ref_conv_bwd_weight.restype = i32
             lib.sdgp_ref_conv_bwd_weight.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, i64,
                                                      vp, vp]
+            lib.sdgp_ref_conv_bwd_data_grouped.restype = i32
+            lib.sdgp_ref_conv_bwd_data_grouped.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i64, i32, vp, i64,
+                                                           vp, vp]
             lib.sdgp_ref_threads.restype = i32
             lib.sdgp_ref_threads.argtypes = []
             _lib = lib
@@ -209,6 +212,38 @@ def conv_bwd_data(dOp: np.ndarray, W: np.ndarray, H: int, Wd: int, stride: int, 
                                            dtype, _ptr(pixels), pixels.size, _ptr(dD), _ptr(ab))
     if rc != 0:
         raise ValueError("sdgp_ref_conv_bwd_data rejected its arguments")
+    return dD, ab
+
+
+def conv_bwd_data_grouped(dOp: np.ndarray, W: np.ndarray, H: int, Wd: int, stride: int, pad: int, groups: int,
+                          dtype: int | None = None, pixels: np.ndarray | None = None):
+    """Backward-data of a grouped convolution (the RegNetX layers of Sec. IV) for the already pruned dOp
+    [B,P,Q,C_out] and W [C_out,R,S,C_in/groups].
+
+    Returns ``(dD, absum)`` as fp64 [B,H,Wd,C_in]; with ``pixels`` (flat ``(b*H+h)*Wd+w`` indices) only those input
+    pixels, as [len(pixels), C_in].
+    """
+    if dtype is None:
+        dtype = F32 if dOp.dtype == np.float32 else BF16
+    dOp, W = _check(dOp, dtype, "dOp"), _check(W, dtype, "W")
+    B, P, Q, C_out = dOp.shape
+    K, R, S, cig = W.shape
+    if K != C_out:
+        raise ValueError("W must be [C_out, R, S, C_in/groups]")
+    if P != conv_out_size(H, R, stride, pad) or Q != conv_out_size(Wd, S, stride, pad):
+        raise ValueError("dOp spatial size does not match H, Wd, stride, pad")
+    C_in = cig * groups
+    lib = _load()
+    if pixels is None:
+        shape, pp, count = (B, H, Wd, C_in), None, 0
+    else:
+        pixels = np.ascontiguousarray(pixels, dtype=np.int64)
+        shape, pp, count = (pixels.size, C_in), _ptr(pixels), pixels.size
+    dD, ab = np.empty(shape, np.float64), np.empty(shape, np.float64)
+    rc = lib.sdgp_ref_conv_bwd_data_grouped(_ptr(dOp), _ptr(W), B, H, Wd, C_in, C_out, R, S, stride, pad, groups, dtype,
+                                            pp, count, _ptr(dD), _ptr(ab))
+    if rc != 0:
+        raise ValueError("sdgp_ref_conv_bwd_data_grouped rejected its arguments")
     return dD, ab
 
 

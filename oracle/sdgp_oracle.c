@@ -402,6 +402,55 @@ int sdgp_ref_conv_bwd_data_at(const void* dOp, const void* W, int64_t B, int64_t
     return 0;
 }
 
+/*
+ * Grouped convolution (the RegNetX layers of Sec. IV): the channels are split into `groups` independent convolutions.
+ * Output channel k belongs to group g = k / (C_out/groups) and sees only the input channels
+ * [g*C_in/groups, (g+1)*C_in/groups); W is [C_out, R, S, C_in/groups].  Differentiating
+ *   O[b,p,q,k] = sum_{r,s} sum_{c' < C_in/groups} D[b, p*stride+r-pad, q*stride+s-pad, g*C_in/groups + c'] * W[k,r,s,c']
+ * with respect to D: input channel c of group g = c / (C_in/groups) collects the output channels of its group only,
+ *   dD[b,h,w,c] = sum_{r,s} sum_{k in group g} dOp[b,p,q,k] * W[k,r,s, c - g*C_in/groups].
+ * dOp is the pruned tensor (pruned along all of C_out as one row: Alg. 1 does not know about groups).  With
+ * pixels != NULL only the input pixels pixels[t] = (b*H + h)*Wd + w are computed, as [count, C_in].
+ */
+int sdgp_ref_conv_bwd_data_grouped(const void* dOp, const void* W, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                                   int64_t C_out, int R, int S, int stride, int pad, int64_t groups, int dtype,
+                                   const int64_t* pixels, int64_t count, double* dD, double* absum) {
+    if (B < 0 || H < 0 || Wd < 0 || C_in < 0 || C_out < 0 || R < 1 || S < 1 || stride < 1 || pad < 0) return -1;
+    if (groups < 1 || C_in % groups != 0 || C_out % groups != 0) return -1;
+    if (H + 2 * pad < R || Wd + 2 * pad < S) return -1;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    const int64_t cig = C_in / groups, cog = C_out / groups;
+    const int64_t npix = pixels ? count : B * H * Wd;
+    for (int64_t t = 0; pixels && t < count; ++t)
+        if (pixels[t] < 0 || pixels[t] >= B * H * Wd) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < npix; ++t) {
+        const int64_t pix = pixels ? pixels[t] : t;
+        const int64_t w = pix % Wd, h = (pix / Wd) % H, b = pix / (Wd * H);
+        for (int64_t c = 0; c < C_in; ++c) {
+            const int64_t g = c / cig, cl = c - g * cig;
+            double acc = 0.0, am = 0.0;
+            for (int r = 0; r < R; ++r) {
+                const int64_t hp = h + pad - r;
+                if (hp < 0 || hp % stride != 0 || hp / stride >= P) continue;
+                for (int s = 0; s < S; ++s) {
+                    const int64_t wq = w + pad - s;
+                    if (wq < 0 || wq % stride != 0 || wq / stride >= Q) continue;
+                    for (int64_t k = g * cog; k < (g + 1) * cog; ++k) {
+                        double a = load_as_double(dOp, ((b * P + hp / stride) * Q + wq / stride) * C_out + k, dtype);
+                        double v = load_as_double(W, ((k * R + r) * S + s) * cig + cl, dtype);
+                        acc += a * v;
+                        am += (a < 0 ? -a : a) * (v < 0 ? -v : v);
+                    }
+                }
+            }
+            dD[t * C_in + c] = acc;
+            if (absum) absum[t * C_in + c] = am;
+        }
+    }
+    return 0;
+}
+
 /* ---------------------------------------- forward and weight-gradient products */
 
 /*
