@@ -135,12 +135,18 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
                        void* hip_stream);
 
 /* Bytes of workspace sdgp_conv_bwd_data needs for these arguments; (size_t)-1 when
- * the arguments are invalid.  0 for almost every layer (the call is one fused
- * kernel); a first layer with a wide filter (C_in <= 4 and more than 32
- * (tap, channel) pairs) asks for room for a re-indexed copy of the filter that one
- * small kernel builds before the fused one: 20 KB per 32 output channels for a 7x7
- * stride-2 filter with padding 3 on an image of even size, 23 KB per 64 output
- * channels for other 7x7 layers on three channels. */
+ * the arguments are invalid.  0 for most layers (the call is one fused kernel).
+ *   - A first layer with a wide filter (C_in <= 4 and more than 32 (tap, channel)
+ *     pairs) asks for room for a re-indexed copy of the filter that one small kernel
+ *     builds before the fused one: 20 KB per 32 output channels for a 7x7 stride-2
+ *     filter with padding 3 on an image of even size, 23 KB per 64 output channels
+ *     for other 7x7 layers on three channels.
+ *   - bf16 layers with n <= 2, m in {4, 8, 16} and C_out a multiple of 64 in which the
+ *     fused kernel would rank a gradient element several times -- 1x1 filters with
+ *     more than 256 input channels, strided filters up to 2*stride taps wide -- ask
+ *     for room for the gradient ranked and compressed once (Sec. III-B: kept values
+ *     and positions; 9/16 of the gradient's bytes), written by a pass of its own
+ *     ahead of the product. */
 size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                                     int R, int S, int stride, int pad, int dt, int n, int m);
 
@@ -148,13 +154,15 @@ size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_
  * sdgp_conv_bwd_data_noalloc -- sdgp_conv_bwd_data for callers that cannot allocate device memory and therefore
  * cannot bring a workspace: code running under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, results and error behaviour as sdgp_conv_bwd_data, minus the workspace: where that call
- * needs scratch memory (the transposed filter of a wide first layer), this one takes it from an array of
+ * needs scratch memory (the re-indexed filter of a wide first layer), this one takes it from an array of
  * SDGP_NOALLOC_SCRATCH_BYTES that is part of the library's device image (each GPU the library runs on holds its own
  * copy until the process ends).  The call allocates and frees nothing.
  *
- *   - A problem whose sdgp_conv_bwd_data_workspace(...) exceeds SDGP_NOALLOC_SCRATCH_BYTES (the 7x7 stride-2 first layer
- *     of an ImageNet network with more than 384 output channels) returns SDGP_ERR_WORKSPACE and launches nothing; SDGP_ERR_HIP when the runtime
- *     cannot report the array's address.
+ *   - A first layer whose filter image exceeds SDGP_NOALLOC_SCRATCH_BYTES (the 7x7 stride-2 first layer of an
+ *     ImageNet network with more than 384 output channels) returns SDGP_ERR_WORKSPACE and launches nothing;
+ *     SDGP_ERR_HIP when the runtime cannot report the array's address.  Where the workspace of sdgp_conv_bwd_data
+ *     only holds the gradient ranked ahead of the product, a problem whose arrays do not fit the scratch runs the
+ *     fused kernel instead (same kept values, same result up to summation order).
  *   - All calls on one GPU share that GPU's array, and it keeps the last call's contents (every call rewrites the
  *     part it reads, nothing has to start at zero).  Calls that overlap in time on one GPU -- different streams,
  *     or different host threads -- race on it: order them on one stream.
@@ -217,6 +225,26 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
                                         int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
                                         int stride, int pad, int dt, int n, int m, void* workspace,
                                         size_t workspace_bytes, void* hip_stream);
+
+/*
+ * sdgp_conv_bwd_data_grouped -- sdgp_conv_bwd_data for a grouped convolution (Sec. IV: RegNetX's 3x3 layers).
+ * The channels split into `groups` independent convolutions: output channel k belongs to group
+ * g = k / (C_out/groups) and saw the input channels [g*C_in/groups, (g+1)*C_in/groups) only, so
+ *   W   [C_out, R, S, C_in/groups]
+ *   dD[b,h,w,c] = sum over taps (r,s) and the output channels k of c's group of
+ *                 prune(dO)[b,p,q,k] * W[k,r,s, c - g*C_in/groups].
+ * dO is pruned along all of C_out as one row (Alg. 1 knows nothing of groups); C_out/groups must be a multiple of m
+ * so that no m-group straddles two convolution groups (SDGP_ERR_SHAPE otherwise, and when groups does not divide
+ * C_in and C_out).  groups == 1 is sdgp_conv_bwd_data.  For groups > 1 and n < m the gradient is pruned once into
+ * the workspace (sdgp_conv_bwd_data_grouped_workspace(...) bytes: the size of dO) and a plain kernel (one thread
+ * per dD element, fp32 accumulation) multiplies: correct for every shape and dtype, not a matrix-core kernel.
+ */
+size_t sdgp_conv_bwd_data_grouped_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R,
+                                            int S, int stride, int pad, int64_t groups, int dt, int n, int m);
+int sdgp_conv_bwd_data_grouped(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd,
+                               int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int64_t groups,
+                               int dt, int n, int m, int rk, uint64_t seed, void* workspace,
+                               size_t workspace_bytes, void* hip_stream);
 
 /*
  * Backward-data product from the compacted gradient (the K' = (n/m) * C_out form of Sec. III-A and of the ratio-4 and

@@ -25,6 +25,7 @@ EXPORTS = ("sdgp_prune", "sdgp_linear_bwd_data", "sdgp_conv_bwd_data", "sdgp_con
            "sdgp_channel_scales_workspace", "sdgp_channel_scales", "sdgp_prune_channel_rescaled", "sdgp_scale_filter",
            "sdgp_conv_bwd_data_channel_rescaled_workspace", "sdgp_conv_bwd_data_channel_rescaled",
            "sdgp_conv_bwd_data_compact_workspace", "sdgp_conv_bwd_data_compact",
+           "sdgp_conv_bwd_data_grouped_workspace", "sdgp_conv_bwd_data_grouped",
            "sdgp_conv_fwd_workspace", "sdgp_conv_fwd", "sdgp_conv_bwd_weight_workspace", "sdgp_conv_bwd_weight",
            "sdgp_status_string", "sdgp_version")
 
@@ -76,6 +77,11 @@ def load():
                                                                i32, i32, i32, vp, sz, vp]
             lib.sdgp_conv_bwd_data_compact_workspace.restype = sz
             lib.sdgp_conv_bwd_data_compact_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32]
+            lib.sdgp_conv_bwd_data_grouped_workspace.restype = sz
+            lib.sdgp_conv_bwd_data_grouped_workspace.argtypes = [i64, i64, i64, i64, i64, i32, i32, i32, i32, i64, i32, i32, i32]
+            lib.sdgp_conv_bwd_data_grouped.restype = i32
+            lib.sdgp_conv_bwd_data_grouped.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i64, i32, i32,
+                                                       i32, i32, u64, vp, sz, vp]
             lib.sdgp_conv_bwd_data_compact.restype = i32
             lib.sdgp_conv_bwd_data_compact.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, i32, i32,
                                                        i32, u64, vp, sz, vp]
@@ -338,6 +344,32 @@ def sdgp_conv_bwd_data_compact(dO: torch.Tensor, W: torch.Tensor, H: int, Wd: in
                                         ranker, seed & (2**64 - 1), _ptr(workspace), wbytes, _stream(dO))
     if rc != 0:
         raise SdgpError(rc, "sdgp_conv_bwd_data_compact")
+    return out
+
+
+def sdgp_conv_bwd_data_grouped(dO: torch.Tensor, W: torch.Tensor, H: int, Wd: int, stride: int, pad: int, groups: int,
+                               n: int, m: int, ranker: int, seed: int = 0, out: torch.Tensor | None = None,
+                               workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """sdgp_conv_bwd_data for a grouped convolution: dO [B,P,Q,C_out], W [C_out,R,S,C_in/groups] -> dD [B,H,Wd,C_in]."""
+    _dev(dO, "dO"), _dev(W, "W")
+    if dO.dim() != 4 or W.dim() != 4 or W.shape[0] != dO.shape[3] or W.dtype != dO.dtype:
+        raise ValueError("expected dO [B,P,Q,C_out] and W [C_out,R,S,C_in/groups] of one dtype")
+    B, P, Q, C_out = dO.shape
+    _, R, S, cig = W.shape
+    C_in = cig * groups
+    if (H + 2 * pad - R) // stride + 1 != P or (Wd + 2 * pad - S) // stride + 1 != Q:
+        raise ValueError("dO's spatial size does not match H, Wd, stride, pad")
+    if out is None:
+        out = torch.empty((B, H, Wd, C_in), dtype=dO.dtype, device=dO.device)
+    _dev(out, "out")
+    dt = _dtype_code(dO)
+    lib = load()
+    need = int(lib.sdgp_conv_bwd_data_grouped_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, groups, dt, n, m))
+    workspace, wbytes = _workspace(need, workspace, dO.device, "sdgp_conv_bwd_data_grouped_workspace")
+    rc = lib.sdgp_conv_bwd_data_grouped(_ptr(dO), _ptr(W), _ptr(out), B, H, Wd, C_in, C_out, R, S, stride, pad, groups, dt,
+                                        n, m, ranker, seed & (2**64 - 1), _ptr(workspace), wbytes, _stream(dO))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_conv_bwd_data_grouped")
     return out
 
 

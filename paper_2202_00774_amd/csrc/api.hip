@@ -10,6 +10,9 @@ int prune_launch(const void* dO, int64_t total, int dt, int n, int m, int rk, ui
 int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                       int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed,
                       hipStream_t stream);
+int bwd_simple_grouped_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                              int64_t C_out, int R, int S, int stride, int pad, int64_t groups, int dt, int n, int m, int rk,
+                              uint64_t seed, hipStream_t stream);
 int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                       int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                       void* workspace, hipStream_t stream);
@@ -244,6 +247,52 @@ size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_
     // 1x1 layers many column tiles wide and strided filters: room for the gradient ranked and compressed once
     if (dt == SDGP_BF16 && C_in > 4 && g.n_dD > 0 && g.n_dO > 0) return sdgp::bwd_pw_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m);
     return 0;
+}
+
+// The checks of a grouped problem beyond check_conv's.
+static int check_groups(int64_t C_in, int64_t C_out, int64_t groups, int m) {
+    if (groups < 1 || (C_in % groups) != 0 || (C_out % groups) != 0) return SDGP_ERR_SHAPE;
+    if (groups > 1 && ((C_out / groups) % m) != 0) return SDGP_ERR_SHAPE;   // an m-group would straddle two convolution groups
+    return SDGP_OK;
+}
+
+size_t sdgp_conv_bwd_data_grouped_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S,
+                                            int stride, int pad, int64_t groups, int dt, int n, int m) {
+    ConvGeom g;
+    if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g) != SDGP_OK) return (size_t)-1;
+    if (check_groups(C_in, C_out, groups, m) != SDGP_OK) return (size_t)-1;
+    if (groups == 1) return sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m);
+    if (n == m || g.n_dD == 0) return 0;
+    return (size_t)g.n_dO * (dt == SDGP_BF16 ? 2u : 4u);   // the pruned gradient
+}
+
+int sdgp_conv_bwd_data_grouped(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                               int64_t C_out, int R, int S, int stride, int pad, int64_t groups, int dt, int n, int m,
+                               int rk, uint64_t seed, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (groups == 1)
+        return sdgp_conv_bwd_data(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, rk, seed, workspace,
+                                  workspace_bytes, hip_stream);
+    ConvGeom g;
+    int rc = check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g);
+    if (rc != SDGP_OK) return rc;
+    if (!valid_ranker(rk)) return SDGP_ERR_RANKER;
+    rc = check_groups(C_in, C_out, groups, m);
+    if (rc != SDGP_OK) return rc;
+    if (g.n_dD == 0) return SDGP_OK;
+    if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const void* grad = dO;
+    if (n != m && g.n_dO > 0) {
+        // Alg. 1 once over the whole gradient, then the dense sum reads the pruned copy
+        const size_t need = (size_t)g.n_dO * (dt == SDGP_BF16 ? 2u : 4u);
+        if (workspace == nullptr || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15u) != 0)
+            return SDGP_ERR_WORKSPACE;
+        rc = sdgp::prune_launch(dO, g.n_dO, dt, n, m, rk, seed, workspace, nullptr, nullptr, stream);
+        if (rc != SDGP_OK) return rc;
+        grad = workspace;
+    }
+    return sdgp::bwd_simple_grouped_launch(grad, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, groups, dt, m, m, SDGP_GREEDY, 0,
+                                           stream);
 }
 
 int sdgp_linear_bwd_data(const void* dO, const void* W, void* dD, int64_t rows, int64_t C_out, int64_t C_in, int dt,

@@ -23,6 +23,7 @@ struct SimpleArgs {
     int R, S, stride, pad;
     int n, m, rk;
     uint32_t mix;
+    int64_t cig, cog;   // channels per convolution group (all of them when there is one group)
 };
 
 template <int DT>
@@ -85,6 +86,7 @@ __global__ void __launch_bounds__(kBlock) bwd_simple(SimpleArgs a) {
     const int64_t pix = t / a.C_in;
     const int64_t w = pix % a.Wd, h = (pix / a.Wd) % a.H, b = pix / (a.Wd * a.H);
 
+    const int64_t g = c / a.cig, cl = c - g * a.cig;   // the convolution group of this input channel
     float acc = 0.0f;
     for (int r = 0; r < a.R; ++r) {
         const int64_t hp = h + a.pad - r;
@@ -97,7 +99,7 @@ __global__ void __launch_bounds__(kBlock) bwd_simple(SimpleArgs a) {
             const int64_t q = wq / a.stride;
             if (q >= a.Q) continue;
             const uint64_t row0 = (uint64_t)((b * a.P + p) * a.Q + q) * (uint64_t)a.C_out;
-            for (int64_t k0 = 0; k0 < a.C_out; k0 += a.m) {
+            for (int64_t k0 = g * a.cog; k0 < (g + 1) * a.cog; k0 += a.m) {
                 float val[32];
                 if (a.n == a.m) {
                     for (int j = 0; j < a.m; ++j) val[j] = raw_to_float<DT>(load_raw<DT>(a.dO, (int64_t)row0 + k0 + j));
@@ -105,7 +107,7 @@ __global__ void __launch_bounds__(kBlock) bwd_simple(SimpleArgs a) {
                     pruned_group<DT>(a.dO, row0 + (uint64_t)k0, a.n, a.m, a.rk, a.mix, val);
                 }
                 for (int j = 0; j < a.m; ++j) {
-                    const float wv = raw_to_float<DT>(load_raw<DT>(a.W, (((k0 + j) * a.R + r) * a.S + s) * a.C_in + c));
+                    const float wv = raw_to_float<DT>(load_raw<DT>(a.W, (((k0 + j) * a.R + r) * a.S + s) * a.cig + cl));
                     acc = fmaf(val[j], wv, acc);
                 }
             }
@@ -117,19 +119,29 @@ __global__ void __launch_bounds__(kBlock) bwd_simple(SimpleArgs a) {
 
 }  // namespace
 
-int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
-                      int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed,
-                      hipStream_t stream) {
+// groups > 1: W is [C_out, R, S, C_in / groups] and input channel c sums over the output channels of its group only
+// (C_in and C_out multiples of groups, C_out / groups a multiple of m: the callers check).
+int bwd_simple_grouped_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                              int64_t C_out, int R, int S, int stride, int pad, int64_t groups, int dt, int n, int m, int rk,
+                              uint64_t seed, hipStream_t stream) {
     SimpleArgs a;
+    a.cig = C_in / groups, a.cog = C_out / groups;
     a.dO = dO, a.W = W, a.dD = dD;
     a.B = B, a.H = H, a.Wd = Wd, a.C_in = C_in, a.C_out = C_out;
     a.P = (H + 2 * pad - R) / stride + 1, a.Q = (Wd + 2 * pad - S) / stride + 1;
     a.R = R, a.S = S, a.stride = stride, a.pad = pad, a.n = n, a.m = m, a.rk = rk, a.mix = seed_mix(seed);
     const int64_t total = B * H * Wd * C_in;
+    if (total == 0) return SDGP_OK;
     const dim3 grid((unsigned)((total + kBlock - 1) / kBlock)), block(kBlock);
     if (dt == kBF16) hipLaunchKernelGGL(bwd_simple<kBF16>, grid, block, 0, stream, a);
     else hipLaunchKernelGGL(bwd_simple<kF32>, grid, block, 0, stream, a);
     return launch_status();
+}
+
+int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
+                      int64_t C_out, int R, int S, int stride, int pad, int dt, int n, int m, int rk, uint64_t seed,
+                      hipStream_t stream) {
+    return bwd_simple_grouped_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, 1, dt, n, m, rk, seed, stream);
 }
 
 }  // namespace sdgp

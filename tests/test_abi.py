@@ -227,3 +227,23 @@ def test_conv_channel_rescaled_argument_errors(lib):
     assert conv_cr(ws=ctypes.c_void_p(24)) == E_WS                # not 16-byte aligned
     assert conv_cr(B=0) == OK
     assert lib.sdgp_conv_bwd_data_channel_rescaled_workspace(2, 8, 8, 8, 10, 3, 3, 1, 1, 1, 2, 4) == BAD
+
+
+def test_grouped_argument_errors(lib):
+    def call(groups, C_in=32, C_out=64, n=2, m=4, dt=1, rk=1, dO=P, W=P, dD=P, ws=None, ws_bytes=0):
+        return lib.sdgp_conv_bwd_data_grouped(dO, W, dD, 2, 8, 8, C_in, C_out, 3, 3, 1, 1, groups, dt, n, m, rk, 0, ws, ws_bytes, None)
+
+    def need(groups, C_in=32, C_out=64, n=2, m=4, dt=1):
+        return lib.sdgp_conv_bwd_data_grouped_workspace(2, 8, 8, C_in, C_out, 3, 3, 1, 1, groups, dt, n, m)
+
+    bad = ctypes.c_size_t(-1).value
+    assert call(0) == E_SHAPE and call(3) == E_SHAPE and call(-2) == E_SHAPE      # 32 % 3 != 0
+    assert call(32, m=4) == E_SHAPE                                               # two output channels per group
+    assert need(0) == bad and need(3) == bad and need(32) == bad
+    assert need(4) == 2 * 8 * 8 * 64 * 2 and need(4, dt=0) == 2 * 8 * 8 * 64 * 4    # the pruned gradient
+    assert need(4, n=4) == 0                                                      # dense: nothing to prune
+    assert need(1) == lib.sdgp_conv_bwd_data_workspace(2, 8, 8, 32, 64, 3, 3, 1, 1, 1, 2, 4)
+    assert call(4) == E_WS and call(4, ws=P, ws_bytes=need(4) - 1) == E_WS
+    assert call(4, ws=P, ws_bytes=need(4), dO=None) == E_NULL
+    assert call(4, rk=7, ws=P, ws_bytes=need(4)) == E_RANKER
+    assert call(4, dt=5) == E_DTYPE and call(4, n=5) == E_NM
