@@ -5,7 +5,7 @@ Workload of the headline (the largest named configuration that fits one GPU): th
 ResNet-50 at batch 256 and 224 x 224 -- its 53 convolutions and the 2048 -> 1000 classifier, NHWC bf16, every layer's
 dL/dO Laplace distributed with a layer-dependent scale 10^-U(3,5) and 20-50 % exact zeros, He-normal weights, 2:4
 pruning with the random ranker seeded by the layer index (Sec. IV; Alg. 1).  One "step" is one pass of the hot path
-over that batch: 54 fused calls (rank + prune + backward-data product), last layer first.  All inputs are drawn on the
+over that batch: 54 calls (rank + prune + backward-data product), last layer first.  All inputs are drawn on the
 host by the seeded generators the parity tests use and are resident in HBM before the timed region.
 
 Prints ONE JSON line.  `value` is the effective rate: the FLOPs of the unpruned products divided by the time the
@@ -317,6 +317,28 @@ def main():
         "note": "compact = prune pass to (values, positions) + one AXPY per kept value on the vector ALUs; fused = the "
                 "matrix-core path of sdgp_conv_bwd_data; compact_faster_at lists the (layer, n:m) where the compacted path "
                 "wins -- the measured crossover of the sparsity grid",
+    }
+
+    # ---- ranking ahead of the product (one pass writes kept values + positions, the product reads them and ranks
+    # nothing) against the fused kernel (the entry point without a workspace runs it: these arrays do not fit its
+    # scratch) and the dense kernel, on the ResNet-50 layers where the library takes the pass: strided 3x3 filters
+    # and 1x1 filters onto many input channels
+    rows = []
+    for name in ("l2b0_3x3", "l3b0_3x3", "l4b0_3x3", "l2b1_1x1a", "l3b1_1x1a", "l4b1_1x1a", "l4b0_1x1b"):
+        L, dO, W, out = next(d for d in data50 if d[0].name == name)
+        row = {"layer": name, "dense_us": round(time_call(lambda: call(L, dO, W, out, 4, 4, sdgp.GREEDY), reps=5) * 1e3, 1)}
+        for rname, rk in (("random", sdgp.RANDOM), ("greedy", sdgp.GREEDY)):
+            t_a = time_call(lambda: call(L, dO, W, out, 2, 4, rk), reps=5)
+            t_f = time_call(lambda: sdgp.sdgp_conv_bwd_data_noalloc(dO, W, L.H, L.Wd, L.stride, L.pad, 2, 4, rk, 0, out=out), reps=5)
+            row["2:4_%s_fused_us" % rname] = round(t_f * 1e3, 1)
+            row["2:4_%s_ranked_ahead_us" % rname] = round(t_a * 1e3, 1)
+        row["speedup_vs_dense_random"] = round(row["dense_us"] / row["2:4_random_ranked_ahead_us"], 3)
+        rows.append(row)
+    result["ranked_ahead_vs_fused"] = {
+        "layers": rows,
+        "note": "ranked_ahead = what sdgp_conv_bwd_data runs on these layers given its workspace (for the Magnitude ranker "
+                "only where the fused kernel would rank four times or more: otherwise both columns are the fused kernel); "
+                "the product kernel alone runs 1.15-1.3x as fast as the dense one (profiles/ranked_ahead_kernel_stats.md)",
     }
 
     # ------------------------------------------------------------------ prune pass: tensors beyond the last-level cache

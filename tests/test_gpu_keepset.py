@@ -134,3 +134,19 @@ def test_linear_identity_equals_the_oracle():
     rows, C = 40001, 96
     layer = wl.ConvLayer("linear_n96", rows, 1, 1, C, C, 1, 1, 1, 0)
     check_exact(layer, False, nm_settings(), npix=rows)
+
+
+# The gradient ranked and compressed by a pass of its own, then multiplied without ranking (1x1 layers with several
+# column tiles; the strided cases above take the same route): kept values and positions go through global memory.
+RANKED_AHEAD = [
+    (wl.ConvLayer("ahead_pw_n512", 16, 23, 23, 512, 512, 1, 1, 1, 0), 3000,
+     [(2, 4, oracle.RANDOM), (2, 8, oracle.RANDOM), (2, 16, oracle.RANDOM), (1, 4, oracle.RANDOM), (2, 4, oracle.GREEDY_ADJUSTED)]),
+    (wl.ConvLayer("ahead_pw_n1024", 8, 16, 16, 1024, 1024, 1, 1, 1, 0), 1000,
+     [(2, 4, oracle.GREEDY), (2, 8, oracle.GREEDY_ADJUSTED), (2, 16, oracle.GREEDY), (2, 4, oracle.RANDOM)]),
+]
+
+
+@pytest.mark.parametrize("layer,npix,settings", RANKED_AHEAD, ids=lambda v: v.name if hasattr(v, "name") else "")
+def test_ranked_ahead_pruned_values_equal_the_oracle(layer, npix, settings):
+    assert sdgp.conv_bwd_data_workspace(layer.B, layer.H, layer.Wd, layer.C_in, layer.C_out, 1, 1, 1, 0, sdgp.BF16, 2, 4) > 0
+    check_exact(layer, False, settings, npix=npix)
