@@ -236,6 +236,28 @@ def main():
         "note": "sums of per-layer launch times (HIP events), random ranker seeded with the layer index; ideal = sum over "
                 "layers of max(bytes / HBM peak, dense FLOPs / bf16 MFMA peak); per_shape names the first layer of a shape",
     }
+    # ---- ranking ahead of the product (one pass writes kept values + positions, the product reads them and ranks
+    # nothing) against the fused kernel (the entry point without a workspace runs it: these arrays do not fit its
+    # scratch) and the dense kernel, on the ResNet-50 layers where the library takes the pass: strided 3x3 filters
+    # and 1x1 filters onto many input channels
+    rows = []
+    for name in ("l2b0_3x3", "l3b0_3x3", "l4b0_3x3", "l2b1_1x1a", "l3b1_1x1a", "l4b1_1x1a", "l4b0_1x1b"):
+        L, dO, W, out = next(d for d in data50 if d[0].name == name)
+        row = {"layer": name, "dense_us": round(time_call(lambda: call(L, dO, W, out, 4, 4, sdgp.GREEDY), reps=5) * 1e3, 1)}
+        for rname, rk in (("random", sdgp.RANDOM), ("greedy", sdgp.GREEDY)):
+            t_a = time_call(lambda: call(L, dO, W, out, 2, 4, rk), reps=5)
+            t_f = time_call(lambda: sdgp.sdgp_conv_bwd_data_noalloc(dO, W, L.H, L.Wd, L.stride, L.pad, 2, 4, rk, 0, out=out), reps=5)
+            row["2:4_%s_fused_us" % rname] = round(t_f * 1e3, 1)
+            row["2:4_%s_ranked_ahead_us" % rname] = round(t_a * 1e3, 1)
+        row["speedup_vs_dense_random"] = round(row["dense_us"] / row["2:4_random_ranked_ahead_us"], 3)
+        rows.append(row)
+    result["ranked_ahead_vs_fused"] = {
+        "layers": rows,
+        "note": "ranked_ahead = what sdgp_conv_bwd_data runs on these layers given its workspace (for the Magnitude ranker "
+                "only where the fused kernel would rank four times or more: otherwise both columns are the fused kernel); "
+                "the product kernel alone runs 1.15-1.3x as fast as the dense one (profiles/ranked_ahead_kernel_stats.md)",
+    }
+
     del data50, shapes
 
     # ------------------------------------------------------------------ ResNet-9 sweep, batch 512, the three rankers
@@ -317,28 +339,6 @@ def main():
         "note": "compact = prune pass to (values, positions) + one AXPY per kept value on the vector ALUs; fused = the "
                 "matrix-core path of sdgp_conv_bwd_data; compact_faster_at lists the (layer, n:m) where the compacted path "
                 "wins -- the measured crossover of the sparsity grid",
-    }
-
-    # ---- ranking ahead of the product (one pass writes kept values + positions, the product reads them and ranks
-    # nothing) against the fused kernel (the entry point without a workspace runs it: these arrays do not fit its
-    # scratch) and the dense kernel, on the ResNet-50 layers where the library takes the pass: strided 3x3 filters
-    # and 1x1 filters onto many input channels
-    rows = []
-    for name in ("l2b0_3x3", "l3b0_3x3", "l4b0_3x3", "l2b1_1x1a", "l3b1_1x1a", "l4b1_1x1a", "l4b0_1x1b"):
-        L, dO, W, out = next(d for d in data50 if d[0].name == name)
-        row = {"layer": name, "dense_us": round(time_call(lambda: call(L, dO, W, out, 4, 4, sdgp.GREEDY), reps=5) * 1e3, 1)}
-        for rname, rk in (("random", sdgp.RANDOM), ("greedy", sdgp.GREEDY)):
-            t_a = time_call(lambda: call(L, dO, W, out, 2, 4, rk), reps=5)
-            t_f = time_call(lambda: sdgp.sdgp_conv_bwd_data_noalloc(dO, W, L.H, L.Wd, L.stride, L.pad, 2, 4, rk, 0, out=out), reps=5)
-            row["2:4_%s_fused_us" % rname] = round(t_f * 1e3, 1)
-            row["2:4_%s_ranked_ahead_us" % rname] = round(t_a * 1e3, 1)
-        row["speedup_vs_dense_random"] = round(row["dense_us"] / row["2:4_random_ranked_ahead_us"], 3)
-        rows.append(row)
-    result["ranked_ahead_vs_fused"] = {
-        "layers": rows,
-        "note": "ranked_ahead = what sdgp_conv_bwd_data runs on these layers given its workspace (for the Magnitude ranker "
-                "only where the fused kernel would rank four times or more: otherwise both columns are the fused kernel); "
-                "the product kernel alone runs 1.15-1.3x as fast as the dense one (profiles/ranked_ahead_kernel_stats.md)",
     }
 
     # ------------------------------------------------------------------ prune pass: tensors beyond the last-level cache

@@ -272,6 +272,22 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
                 SDGP_LDS unsigned char* src = smem + raw + j * 1024 + px * 64;
                 SDGP_LDS unsigned char* dst = smem + abuf + hp * 64;
                 const int sw = (px >> 2) & 1, sw2 = (hp >> 2) & 3;
+                if constexpr (RK != kRandom && (M == 16 || M == 32)) {
+                    // one group per item, magnitude keys: the packed 16-bit ranker (ranker.h), no unpacking
+                    uint32_t wv[IC / 2], ov[IC / 2];
+#pragma unroll
+                    for (int g = 0; g < IC / 8; ++g) {
+                        const u32x4_t v = *(SDGP_LDS u32x4_t*)(src + (((part * 2 + g) ^ sw) * 16));
+                        wv[4 * g] = v[0], wv[4 * g + 1] = v[1], wv[4 * g + 2] = v[2], wv[4 * g + 3] = v[3];
+                    }
+                    prune_packed<M, RK>(wv, p.n, ov);
+#pragma unroll
+                    for (int g = 0; g < IC / 8; ++g) {
+                        const u32x4_t x = {ov[4 * g], ov[4 * g + 1], ov[4 * g + 2], ov[4 * g + 3]};
+                        *(SDGP_LDS u32x4_t*)(dst + (((part * 2 + g) ^ sw2) << 4)) = x;
+                    }
+                    return;
+                }
                 uint32_t rawv[IC], out[IC];
 #pragma unroll
                 for (int g = 0; g < IC / 8; ++g) {

@@ -95,6 +95,22 @@ prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, v
         continue;
     }
 
+    if constexpr (DT == kBF16 && (M == 16 || M == 32) && !NLE2 && RK != kRandom && MASKED && !COMPACT) {
+        // one group of 16 or 32 bf16 channels, any n, Magnitude keys: packed 16-bit sorting network and 0/1 arithmetic
+        // (ranker.h) instead of the pairwise rank count
+        uint32_t w[M / 2], o[M / 2];
+#pragma unroll
+        for (int i = 0; i < VECS; ++i) w[4 * i] = v[i].x, w[4 * i + 1] = v[i].y, w[4 * i + 2] = v[i].z, w[4 * i + 3] = v[i].w;
+        prune_packed<M, RK>(w, n, o);
+        u32x4* dst = reinterpret_cast<u32x4*>(pruned_) + item * VECS;
+#pragma unroll
+        for (int i = 0; i < VECS; ++i) {
+            const u32x4 pk = {o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]};
+            __builtin_nontemporal_store(pk, dst + i);
+        }
+        continue;
+    }
+
     uint32_t raw[ITEM];
 #pragma unroll
     for (int i = 0; i < VECS; ++i) {
@@ -200,6 +216,74 @@ prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, v
     }  // items of this thread
 }
 
+// ----------------------------------------------- 16- and 32-channel groups of bf16, dense-shaped output
+//
+// One lane per group means 32 or 64 bytes per lane, and a wavefront's 16-byte loads and stores then touch every
+// second or fourth 16 bytes of the span it covers: measured at 3 TB/s for 64 bytes per lane even when the ranking is a
+// handful of instructions (2:32).  Here a wavefront moves its 2 or 4 KB with whole-line accesses (lane i takes vector
+// i of each 1 KB part) and the vectors change lanes through LDS on the way in and on the way out; slot c of a
+// wavefront's region holds vector c ^ ((c >> 4) & (V - 1)), V vectors per group, which keeps both the row-wise and
+// the group-wise accesses free of bank conflicts.
+template <int M, int RK, bool NLE2>
+__global__ void __launch_bounds__(kBlock)
+prune_items_wide(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, void* __restrict__ pruned_) {
+    static_assert(M == 16 || M == 32, "two or four vectors per group");
+    constexpr int V = M / 8;
+    __shared__ u32x4 stage[kBlock * V];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t item = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t vec0 = ((int64_t)blockIdx.x * kBlock + wave * 64) * V;   // first vector of this wavefront's 64 groups
+    const int64_t nvec = nitems * V;
+    u32x4* region = stage + wave * (64 * V);
+    const u32x4* src = reinterpret_cast<const u32x4*>(dO_);
+    u32x4 in[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        const int c = k * 64 + lane;
+        in[k] = u32x4{0u, 0u, 0u, 0u};
+        if (vec0 + c < nvec) in[k] = __builtin_nontemporal_load(src + vec0 + c);
+    }
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        const int c = k * 64 + lane;
+        region[c ^ ((c >> 4) & (V - 1))] = in[k];
+    }
+    __syncthreads();
+    uint32_t w[M / 2];
+#pragma unroll
+    for (int p = 0; p < V; ++p) {
+        const int c = V * lane + p;
+        const u32x4 v = region[c ^ ((c >> 4) & (V - 1))];
+        w[4 * p] = v.x, w[4 * p + 1] = v.y, w[4 * p + 2] = v.z, w[4 * p + 3] = v.w;
+    }
+    uint32_t o[M / 2];
+    if constexpr (!NLE2 && RK != kRandom) {
+        prune_packed<M, RK>(w, n, o);
+    } else {
+        uint32_t r[M], out[M];
+        bool keep[M];
+#pragma unroll
+        for (int i = 0; i < M / 2; ++i) r[2 * i] = w[i] & 0xFFFFu, r[2 * i + 1] = w[i] >> 16;
+        const uint64_t e0 = (uint64_t)item * M;   // (a group past the end is ranked on zeros and never stored)
+        prune_group<kBF16, M, RK, NLE2, false>(r, n, hash_row(mix, (uint32_t)(e0 >> 32)), (uint32_t)e0, keep, out);
+#pragma unroll
+        for (int i = 0; i < M / 2; ++i) o[i] = out[2 * i] | (out[2 * i + 1] << 16);
+    }
+    __syncthreads();   // every lane has read its group
+#pragma unroll
+    for (int p = 0; p < V; ++p) {
+        const int c = V * lane + p;
+        region[c ^ ((c >> 4) & (V - 1))] = u32x4{o[4 * p], o[4 * p + 1], o[4 * p + 2], o[4 * p + 3]};
+    }
+    __syncthreads();
+    u32x4* dst = reinterpret_cast<u32x4*>(pruned_);
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        const int c = k * 64 + lane;
+        if (vec0 + c < nvec) __builtin_nontemporal_store(region[c ^ ((c >> 4) & (V - 1))], dst + vec0 + c);
+    }
+}
+
 // ------------------------------------------------------------- group kernel
 
 template <int DT>
@@ -276,6 +360,13 @@ template <int DT, int M, int RK, bool NLE2>
 void launch_items_out(const PruneArgs& a, int64_t nitems) {
     const int64_t per_block = (int64_t)kBlock * items_per_thread(M, RK);
     const dim3 grid((unsigned)((nitems + per_block - 1) / per_block)), block(kBlock);
+    if constexpr (DT == kBF16 && (M == 16 || M == 32)) {
+        if (a.pruned && !a.vals) {   // one group per thread
+            const dim3 wide((unsigned)((nitems + kBlock - 1) / kBlock));
+            hipLaunchKernelGGL((prune_items_wide<M, RK, NLE2>), wide, block, 0, a.stream, a.dO, nitems, a.n, a.mix, a.pruned);
+            return;
+        }
+    }
     if (a.pruned && a.vals)
         hipLaunchKernelGGL((prune_items<DT, M, RK, NLE2, true, true>), grid, block, 0, a.stream, a.dO, nitems, a.n, a.mix,
                            a.pruned, a.vals, a.idx);

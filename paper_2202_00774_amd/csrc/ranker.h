@@ -153,11 +153,11 @@ __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uin
 
     if constexpr (M == 1) {
         keep[0] = true;
-    } else if constexpr (RK != kRandom && DT == kBF16) {
-        // 15-bit magnitudes: fold the position in to make the keys distinct,
-        // a lower position giving the larger key.
+    } else if constexpr ((RK != kRandom && DT == kBF16) || (RK == kRandom && M <= 16)) {
+        // 15-bit magnitudes, and hash keys (28 bits wide, their low four bits clear) of groups up to 16: fold the
+        // position in to make the keys distinct, a lower position giving the larger key.
 #pragma unroll
-        for (int j = 0; j < M; ++j) key[j] = (key[j] << 5) | (uint32_t)(31 - j);
+        for (int j = 0; j < M; ++j) key[j] = RK == kRandom ? (key[j] | (uint32_t)(15 - j)) : ((key[j] << 5) | (uint32_t)(31 - j));
         if constexpr (NLE2) select_top2_distinct<M>(key, n, keep);
         else if constexpr (SORT && M >= 8 && (M & (M - 1)) == 0) select_by_sort<M>(key, n, keep);
         else select_by_rank<M>(key, n, keep);
@@ -212,6 +212,188 @@ __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uin
 // quad contain every survivor of that quad; the group's threshold is the n-th largest key over its quads.
 // Rotated right by nine bits a key reads [code | sign | magnitude | mark]: unsigned order is now position order
 // and the bf16 value sits byte-aligned in bits 8..23.
+// ---- Magnitude / Rescaled Magnitude on a group of 16 or 32 bf16 channels, any n, on packed 16-bit arithmetic.
+// A dword carries two magnitudes and the packed instructions (max, min, saturating subtract) treat both at once:
+//   1. the magnitudes are sorted by a bitonic network whose slot s is half s / (M/2) of dword s % (M/2) -- a stage
+//      pairs whole dwords (one packed max and one packed min for two compare-exchanges) except the one stage whose
+//      partner is the other half of the same dword; the network only needs the values, not where they came from;
+//   2. the threshold T is the n-th largest magnitude; an element is kept when its magnitude exceeds T, or equals T
+//      and fewer than n - #(greater) equal elements precede it (the lower position wins: Sec. III-B reading), all of it
+//      as 0/1 arithmetic on halves: [a > T] = min(a -sat T, 1), [a == T] = 1 -sat (a xor T), a running count of
+//      equals in position order.
+// About 20 instructions per element at M = 32 where the pairwise rank count takes about 46.
+typedef uint16_t sdgp_u16x2 __attribute__((ext_vector_type(2)));
+__host__ __device__ __forceinline__ uint32_t sdgp_max_u32(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__host__ __device__ __forceinline__ uint32_t sdgp_min_u32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__host__ __device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(sdgp_u16x2, a), __builtin_bit_cast(sdgp_u16x2, b)));
+}
+__host__ __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(sdgp_u16x2, a), __builtin_bit_cast(sdgp_u16x2, b)));
+}
+__host__ __device__ __forceinline__ uint32_t pk_sub_sat(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(__builtin_bit_cast(sdgp_u16x2, a), __builtin_bit_cast(sdgp_u16x2, b)));
+}
+__host__ __device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, (sdgp_u16x2)(__builtin_bit_cast(sdgp_u16x2, a) + __builtin_bit_cast(sdgp_u16x2, b)));
+}
+__host__ __device__ __forceinline__ uint32_t pk_neg(uint32_t a) {   // 0 -> 0, 1 -> 0xFFFF per half
+    return __builtin_bit_cast(uint32_t, (sdgp_u16x2)(-__builtin_bit_cast(sdgp_u16x2, a)));
+}
+
+__host__ __device__ __forceinline__ uint32_t pk_mul(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, (sdgp_u16x2)(__builtin_bit_cast(sdgp_u16x2, a) * __builtin_bit_cast(sdgp_u16x2, b)));
+}
+// c + low half of a + high half of a
+__host__ __device__ __forceinline__ uint32_t pk_sum_into(uint32_t a, uint32_t c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_sad_u16(a, 0u, c);
+#else
+    return c + (a & 0xFFFFu) + (a >> 16);
+#endif
+}
+
+// The n-th largest of M 15-bit magnitudes, two per dword (any assignment of values to halves).
+//   n <= M/2: both halves of the dwords are sorted at once (two descending runs of M/2), the M/2 largest of the union
+//             are max(low run[r], high run[M/2-1-r]) -- a bitonic sequence -- and one merge orders them;
+//   n >  M/2: the whole network (the one stage whose partner is the other half of the same dword costs four
+//             instructions per dword).
+template <int M>
+__host__ __device__ __forceinline__ uint32_t nth_largest_packed(const uint32_t (&mag)[M / 2], int n) {
+    constexpr int R = M / 2;
+    uint32_t s[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) s[i] = mag[i];
+    // slot t = half t / R of s[t % R]; runs of length k, descending where (slot & k) == 0.  With `both_down` every
+    // run of length R is descending in both halves (two independent sorts of R values).
+    auto stage = [&](int k, int j, bool both_down) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int l = r ^ j;
+            if (l > r) {
+                const uint32_t hi = pk_max(s[r], s[l]), lo = pk_min(s[r], s[l]);
+                const bool desc_low = (r & k) == 0, desc_high = both_down ? desc_low : ((r + R) & k) == 0;
+                const uint32_t first_low = desc_low ? hi : lo, first_high = desc_high ? hi : lo;
+                const uint32_t second_low = desc_low ? lo : hi, second_high = desc_high ? lo : hi;
+                s[r] = desc_low == desc_high ? first_low : ((first_low & 0xFFFFu) | (first_high & 0xFFFF0000u));
+                s[l] = desc_low == desc_high ? second_low : ((second_low & 0xFFFFu) | (second_high & 0xFFFF0000u));
+            }
+        }
+    };
+    uint32_t thr;
+    if (n <= R) {
+#pragma unroll
+        for (int k = 2; k <= R; k <<= 1)
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1) stage(k, j, true);
+        uint32_t top[R];   // the R largest, one per dword (low half; the high half is zero)
+#pragma unroll
+        for (int r = 0; r < R; ++r) top[r] = sdgp_max_u32(s[r] & 0xFFFFu, s[R - 1 - r] >> 16);
+#pragma unroll
+        for (int j = R >> 1; j > 0; j >>= 1) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int l = r ^ j;
+                if (l > r) {
+                    const uint32_t hi = sdgp_max_u32(top[r], top[l]), lo = sdgp_min_u32(top[r], top[l]);
+                    top[r] = hi, top[l] = lo;
+                }
+            }
+        }
+        thr = top[0];
+#pragma unroll
+        for (int r = 1; r < R; ++r) thr = (n - 1 == r) ? top[r] : thr;
+    } else {
+#pragma unroll
+        for (int k = 2; k <= M; k <<= 1) {
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                if (j == R) {
+                    // partner = the other half of the same dword; both slots lie in a descending run (k == M)
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const uint32_t a = s[r], b = (a << 16) | (a >> 16);
+                        s[r] = (pk_max(a, b) & 0xFFFFu) | (pk_min(a, b) & 0xFFFF0000u);
+                    }
+                } else {
+                    stage(k, j, false);
+                }
+            }
+        }
+        thr = s[0];
+#pragma unroll
+        for (int r = 1; r < R; ++r) thr = ((n - 1) % R == r) ? s[r] : thr;
+        thr = thr >> 16;   // slots R .. M-1 are the high halves
+    }
+    return thr;
+}
+
+// w: M bf16 channels, channel 2i in the low half of w[i].  keep[i]: 1 in the halves of the kept channels, else 0.
+template <int M>
+__host__ __device__ __forceinline__ void keep_flags_packed(const uint32_t (&w)[M / 2], int n, uint32_t (&keep)[M / 2]) {
+    static_assert(M == 16 || M == 32, "two or four 16-byte vectors");
+    constexpr int R = M / 2;
+    constexpr uint32_t kOne = 0x00010001u;
+    uint32_t mag[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) mag[i] = w[i] & 0x7FFF7FFFu;
+    uint32_t thr = nth_largest_packed<M>(mag, n);   // (n is uniform over the wavefront: one branch)
+    thr |= thr << 16;
+
+    uint32_t gt[R], eq[R], greater = 0;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        gt[i] = pk_min(pk_sub_sat(mag[i], thr), kOne);
+        eq[i] = pk_sub_sat(kOne, mag[i] ^ thr);
+        greater = pk_sum_into(gt[i], greater);
+    }
+    uint32_t quota = (uint32_t)n - greater;   // equals still to be kept: at least one
+    quota |= quota << 16;
+    uint32_t before = 0;                      // equals at lower positions
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const uint32_t seen = pk_add(before | (before << 16), eq[i] << 16);      // the high half also follows the low one
+        const uint32_t room = pk_min(pk_sub_sat(quota, seen), kOne);            // [seen < quota]
+        keep[i] = gt[i] | (eq[i] & room);
+        before = pk_sum_into(eq[i], before);
+    }
+}
+
+// The same as masks: 0xFFFF in the halves of the kept channels.
+template <int M>
+__host__ __device__ __forceinline__ void keep_mask_packed(const uint32_t (&w)[M / 2], int n, uint32_t (&mask)[M / 2]) {
+    uint32_t keep[M / 2];
+    keep_flags_packed<M>(w, n, keep);
+#pragma unroll
+    for (int i = 0; i < M / 2; ++i) mask[i] = pk_neg(keep[i]);
+}
+
+// Alg. 1 on one group of M = 16 or 32 bf16 channels (two per dword), Magnitude or Rescaled Magnitude, any n: the
+// pruned group in the same packing (+0 where dropped).  Bit-identical to prune_group.
+template <int M, int RK>
+__host__ __device__ __forceinline__ void prune_packed(const uint32_t (&w)[M / 2], int n, uint32_t (&o)[M / 2]) {
+    static_assert(RK == kGreedy || RK == kAdjusted, "magnitude keys");
+    uint32_t flag[M / 2];
+    keep_flags_packed<M>(w, n, flag);
+    if constexpr (RK == kAdjusted) {
+        float total = 0.0f, kept = 0.0f, x[M];
+#pragma unroll
+        for (int j = 0; j < M; ++j) {
+            x[j] = bits_to_float((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
+            const float a = bits_to_float(float_to_bits(x[j]) & 0x7FFFFFFFu);
+            total = __fadd_rn(total, a);
+            kept = ((flag[j >> 1] >> (16 * (j & 1))) & 1u) ? __fadd_rn(kept, a) : kept;
+        }
+        const float scale = (kept == 0.0f) ? 1.0f : __fdiv_rn(total, kept);
+#pragma unroll
+        for (int i = 0; i < M / 2; ++i)
+            o[i] = pk_mul(float2_to_bf16x2(__fmul_rn(x[2 * i], scale), __fmul_rn(x[2 * i + 1], scale)), flag[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < M / 2; ++i) o[i] = pk_mul(w[i], flag[i]);
+    }
+}
+
 __host__ __device__ __forceinline__ uint32_t sdgp_umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 __host__ __device__ __forceinline__ uint32_t sdgp_umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __host__ __device__ __forceinline__ uint32_t sdgp_rotl(uint32_t x, int s) { return (x << s) | (x >> (32 - s)); }

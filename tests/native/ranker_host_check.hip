@@ -4,6 +4,7 @@
 //     the rescale in fp32;
 //   * prune_compress16_random against a rank count by (H(seed, e), -position) with H written out from its definition
 //     (28-bit keys: the kernel's word "key | position code" must order exactly like the pair).
+//   * keep_mask_packed (Magnitude on 16 or 32 channels, any n, packed 16-bit arithmetic) against the same rank count.
 // Prints one line per configuration and returns the number of mismatches.  Test infrastructure, not product code.
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -160,11 +161,57 @@ static int run_rand(int iters, unsigned sd) {
     printf("M=%d random: %d mismatches of %d\n", M, bad, 2 * iters);
     return bad;
 }
+// keep_mask_packed against a rank count by (magnitude, lower position first), any n
+template <int M>
+static int run_packed(int iters, unsigned seed) {
+    int bad = 0;
+    srand(seed);
+    for (int it = 0; it < iters; ++it) {
+        uint16_t x[M];
+        const int kind = it % 6;
+        for (int i = 0; i < M; ++i) {
+            const uint32_t r = (uint32_t)rand();
+            switch (kind) {
+                case 0: x[i] = (uint16_t)r; break;                                                  // anything incl. NaN/inf
+                case 1: x[i] = (uint16_t)((r & 0x8000) | 0x3F80 | (r & 3)); break;                  // many ties
+                case 2: x[i] = (r & 3) ? (uint16_t)(r & 0x8000) : (uint16_t)(0x3C00 + (r >> 8) % 512); break;  // mostly +-0
+                case 3: x[i] = (uint16_t)((r & 0x8000) | 0x3F80); break;                            // all equal magnitude
+                case 4: x[i] = (uint16_t)((r & 0x8000) | (0x7F00 + (r >> 4) % 256)); break;        // huge / inf / nan
+                default: x[i] = (uint16_t)((r & 0x8000) | ((r >> 3) % 4)); break;                  // tiny alphabet
+            }
+        }
+        uint32_t w[M / 2], mask[M / 2];
+        for (int i = 0; i < M / 2; ++i) w[i] = x[2 * i] | ((uint32_t)x[2 * i + 1] << 16);
+        for (int n = 1; n <= M; n += (n < 4 ? 1 : (n < 16 ? 3 : 5))) {
+            keep_mask_packed<M>(w, n, mask);
+            bool ok = true;
+            for (int j = 0; j < M; ++j) {
+                int rank = 0;
+                for (int i = 0; i < M; ++i) {
+                    const uint32_t ki = x[i] & 0x7FFF, kj = x[j] & 0x7FFF;
+                    if (ki > kj || (ki == kj && i < j)) ++rank;
+                }
+                const uint32_t got = (mask[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                if (got != (rank < n ? 0xFFFFu : 0u)) ok = false;
+            }
+            if (!ok && bad++ < 5) {
+                printf("MISMATCH packed M=%d n=%d kind=%d\n in :", M, n, kind);
+                for (int i = 0; i < M; ++i) printf(" %04x", x[i]);
+                printf("\n got:");
+                for (int i = 0; i < M; ++i) printf(" %d", (int)((mask[i >> 1] >> (16 * (i & 1))) & 1));
+                printf("\n");
+            }
+        }
+    }
+    printf("M=%d packed keep mask: %d mismatches\n", M, bad);
+    return bad;
+}
 int main() {
     int bad = 0;
     bad += run_mag<4, kGreedy>(100000, 1); bad += run_mag<8, kGreedy>(100000, 2); bad += run_mag<16, kGreedy>(100000, 3);
     bad += run_mag<4, kAdjusted>(100000, 4); bad += run_mag<8, kAdjusted>(100000, 5); bad += run_mag<16, kAdjusted>(100000, 6);
     bad += run_rand<4>(200000, 1); bad += run_rand<8>(200000, 2); bad += run_rand<16>(200000, 3);
+    bad += run_packed<16>(100000, 7); bad += run_packed<32>(60000, 8);
     printf("total mismatches %d\n", bad);
     return bad != 0;
 }
