@@ -255,7 +255,7 @@ def main():
         "layers": rows,
         "note": "ranked_ahead = what sdgp_conv_bwd_data runs on these layers given its workspace (for the Magnitude ranker "
                 "only where the fused kernel would rank four times or more: otherwise both columns are the fused kernel); "
-                "the product kernel alone runs 1.15-1.3x as fast as the dense one (profiles/ranked_ahead_kernel_stats.md)",
+                "the product kernel alone runs 1.15-1.4x as fast as the dense one (profiles/ranked_ahead_kernel_stats.md)",
     }
 
     del data50, shapes
