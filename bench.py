@@ -341,6 +341,29 @@ def main():
                 "wins -- the measured crossover of the sparsity grid",
     }
 
+    # ---- grouped 3x3 layers of RegNetX-400MF (Sec. IV; group width 16, widths 32/64/160/384, batch 256): the stride-2
+    # layer that opens each stage and the stride-1 layer of its other blocks
+    rows = []
+    for C, H, stride in ((32, 112, 2), (64, 56, 2), (64, 28, 1), (160, 28, 2), (160, 14, 1), (384, 14, 2), (384, 7, 1)):
+        P = (H + 2 - 3) // stride + 1
+        gd = (torch.randn((args.batch, P, P, C), device=dev) * 1e-3).to(torch.bfloat16)
+        gw = (torch.randn((C, 3, 3, 16), device=dev) * 0.05).to(torch.bfloat16)
+        go = torch.empty((args.batch, H, H, C), dtype=torch.bfloat16, device=dev)
+        need = int(lib.sdgp_conv_bwd_data_grouped_workspace(args.batch, H, H, C, C, 3, 3, stride, 1, C // 16, sdgp.BF16, 2, 4))
+        gws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        row = {"channels": C, "input": H, "stride": stride, "groups": C // 16,
+               "hbm_floor_us": round((gd.numel() + go.numel()) * 2 / (HBM_PEAK_GBS * 1e9) * 1e6, 1)}
+        for name, n_, rk in (("dense", 4, sdgp.GREEDY), ("2:4_random", 2, sdgp.RANDOM), ("2:4_greedy-adjusted", 2, sdgp.GREEDY_ADJUSTED)):
+            row[name + "_us"] = round(time_call(lambda: sdgp.sdgp_conv_bwd_data_grouped(gd, gw, H, H, stride, 1, C // 16, n_, 4, rk, 0,
+                                                                                        out=go, workspace=gws)) * 1e3, 1)
+        rows.append(row)
+        del gd, gw, go, gws
+    result["regnetx400mf_grouped_3x3"] = {
+        "layers": rows,
+        "note": "sdgp_conv_bwd_data_grouped: a small kernel that re-indexes the filter, then one fused kernel "
+                "(v_mfma_f32_16x16x32_bf16, a group's 16 input channels as the rows); times include both launches",
+    }
+
     # ------------------------------------------------------------------ prune pass: tensors beyond the last-level cache
     import ctypes
     nelem = 256 * 112 * 112 * 64

@@ -235,9 +235,14 @@ int sdgp_conv_bwd_data_channel_rescaled(const void* dO, const void* W, void* dD,
  *                 prune(dO)[b,p,q,k] * W[k,r,s, c - g*C_in/groups].
  * dO is pruned along all of C_out as one row (Alg. 1 knows nothing of groups); C_out/groups must be a multiple of m
  * so that no m-group straddles two convolution groups (SDGP_ERR_SHAPE otherwise, and when groups does not divide
- * C_in and C_out).  groups == 1 is sdgp_conv_bwd_data.  For groups > 1 and n < m the gradient is pruned once into
- * the workspace (sdgp_conv_bwd_data_grouped_workspace(...) bytes: the size of dO) and a plain kernel (one thread
- * per dD element, fp32 accumulation) multiplies: correct for every shape and dtype, not a matrix-core kernel.
+ * C_in and C_out).  groups == 1 is sdgp_conv_bwd_data.  For groups > 1:
+ *   - bf16, 16 channels per group on both sides, 3x3, stride 1, padding 1 (RegNetX-400MF's layers), dO 16-byte and
+ *     dD 8-byte aligned: one fused matrix-core kernel; the workspace holds the re-indexed filter (5 KB per group).
+ *   - anything else: with n < m the gradient is pruned once into the workspace (the size of dO) and a plain kernel
+ *     (one thread per dD element, fp32 accumulation) multiplies: correct for every shape and dtype, slow.
+ * sdgp_conv_bwd_data_grouped_workspace(...) returns the bytes of the case the shape selects ((size_t)-1 for arguments
+ * the call would refuse); a call of the first kind whose pointers are not aligned as stated falls to the second and
+ * then needs the second's workspace (SDGP_ERR_WORKSPACE otherwise).
  */
 size_t sdgp_conv_bwd_data_grouped_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R,
                                             int S, int stride, int pad, int64_t groups, int dt, int n, int m);

@@ -22,27 +22,29 @@ from . import binding
 
 class _Conv2dFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x, weight, stride, padding, n, m, ranker, seed, per_channel):
+    def forward(ctx, x, weight, stride, padding, n, m, ranker, seed, per_channel, groups):
         ctx.save_for_backward(x, weight)
-        ctx.cfg = (int(stride), int(padding), int(n), int(m), int(ranker), int(seed), bool(per_channel))
-        return F.conv2d(x, weight, None, stride, padding)
+        ctx.cfg = (int(stride), int(padding), int(n), int(m), int(ranker), int(seed), bool(per_channel), int(groups))
+        return F.conv2d(x, weight, None, stride, padding, 1, int(groups))
 
     @staticmethod
     def backward(ctx, gy):
         x, weight = ctx.saved_tensors
-        stride, padding, n, m, ranker, seed, per_channel = ctx.cfg
+        stride, padding, n, m, ranker, seed, per_channel, groups = ctx.cfg
         gx = gw = None
         if ctx.needs_input_grad[1]:
-            gw = torch.nn.grad.conv2d_weight(x, weight.shape, gy, stride, padding)  # dense dL/dO
+            gw = torch.nn.grad.conv2d_weight(x, weight.shape, gy, stride, padding, 1, groups)  # dense dL/dO
         if ctx.needs_input_grad[0]:
             dO = gy.permute(0, 2, 3, 1).contiguous()          # [B, P, Q, C_out]; a view when gy is channels_last
             Wk = weight.permute(0, 2, 3, 1).contiguous()      # [C_out, R, S, C_in]
-            if per_channel:
+            if groups > 1:
+                dD = binding.sdgp_conv_bwd_data_grouped(dO, Wk, x.shape[2], x.shape[3], stride, padding, groups, n, m, ranker, seed)
+            elif per_channel:
                 dD = binding.sdgp_conv_bwd_data_channel_rescaled(dO, Wk, x.shape[2], x.shape[3], stride, padding, n, m)
             else:
                 dD = binding.sdgp_conv_bwd_data(dO, Wk, x.shape[2], x.shape[3], stride, padding, n, m, ranker, seed)
             gx = dD.permute(0, 3, 1, 2)                       # NCHW view of NHWC memory (channels_last)
-        return gx, gw, None, None, None, None, None, None, None
+        return gx, gw, None, None, None, None, None, None, None, None
 
 
 class _LinearFn(torch.autograd.Function):
@@ -69,9 +71,12 @@ class _LinearFn(torch.autograd.Function):
 
 
 def sdgp_conv2d(x: torch.Tensor, weight: torch.Tensor, stride: int = 1, padding: int = 0, n: int = 2, m: int = 4,
-                ranker: int = binding.GREEDY, seed: int = 0, per_channel: bool = False) -> torch.Tensor:
-    """conv2d (no bias, dilation 1, one group; x [B,C,H,W], weight [K,C,R,S]) whose input gradient is SDGP-pruned."""
-    return _Conv2dFn.apply(x, weight, stride, padding, n, m, ranker, seed, per_channel)
+                ranker: int = binding.GREEDY, seed: int = 0, per_channel: bool = False, groups: int = 1) -> torch.Tensor:
+    """conv2d (no bias, dilation 1; x [B,C,H,W], weight [K,C/groups,R,S]) whose input gradient is SDGP-pruned.
+    With groups > 1 (K/groups a multiple of m) the per-channel reading of the rescale is not available."""
+    if groups > 1 and per_channel:
+        raise ValueError("per_channel is not available for grouped convolutions")
+    return _Conv2dFn.apply(x, weight, stride, padding, n, m, ranker, seed, per_channel, groups)
 
 
 def sdgp_linear(x: torch.Tensor, weight: torch.Tensor, n: int = 2, m: int = 4, ranker: int = binding.GREEDY,

@@ -13,6 +13,11 @@ int bwd_simple_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
 int bwd_simple_grouped_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                               int64_t C_out, int R, int S, int stride, int pad, int64_t groups, int dt, int n, int m, int rk,
                               uint64_t seed, hipStream_t stream);
+size_t bwd_grouped_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad,
+                             int64_t groups, int dt, int n, int m);
+int bwd_grouped_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R,
+                       int S, int stride, int pad, int64_t groups, int dt, int n, int m, int rk, uint64_t seed, void* workspace,
+                       hipStream_t stream);
 int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                       int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                       void* workspace, hipStream_t stream);
@@ -262,7 +267,11 @@ size_t sdgp_conv_bwd_data_grouped_workspace(int64_t B, int64_t H, int64_t Wd, in
     if (check_conv(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m, &g) != SDGP_OK) return (size_t)-1;
     if (check_groups(C_in, C_out, groups, m) != SDGP_OK) return (size_t)-1;
     if (groups == 1) return sdgp_conv_bwd_data_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, dt, n, m);
-    if (n == m || g.n_dD == 0) return 0;
+    if (g.n_dD == 0) return 0;
+    // 16 channels per group, 3x3, stride 1: the matrix-core kernel wants the filter re-indexed
+    const size_t image = sdgp::bwd_grouped_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, groups, dt, n, m);
+    if (image > 0) return image;
+    if (n == m) return 0;
     return (size_t)g.n_dO * (dt == SDGP_BF16 ? 2u : 4u);   // the pruned gradient
 }
 
@@ -281,6 +290,11 @@ int sdgp_conv_bwd_data_grouped(const void* dO, const void* W, void* dD, int64_t 
     if (g.n_dD == 0) return SDGP_OK;
     if (dD == nullptr || (g.n_dO > 0 && dO == nullptr) || (g.n_W > 0 && W == nullptr)) return SDGP_ERR_NULL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const size_t image = sdgp::bwd_grouped_workspace(B, H, Wd, C_in, C_out, R, S, stride, pad, groups, dt, n, m);
+    if (image > 0 && workspace != nullptr && workspace_bytes >= image) {
+        rc = sdgp::bwd_grouped_launch(dO, W, dD, B, H, Wd, C_in, C_out, R, S, stride, pad, groups, dt, n, m, rk, seed, workspace, stream);
+        if (rc <= 0) return rc;   // (a positive value: pointers not aligned for it -- the plain kernel below)
+    }
     const void* grad = dO;
     if (n != m && g.n_dO > 0) {
         // Alg. 1 once over the whole gradient, then the dense sum reads the pruned copy

@@ -85,3 +85,23 @@ def test_per_channel_rescale_through_autograd():
     pruned = oracle.prune_channel_rescaled(bits(gl.reshape(-1, 64)), 2, 4)[0]
     ref, ab = oracle.linear_bwd_data(pruned, bits(wl_))
     assert rel_error(wl.to_f64(bits(xl.grad.reshape(-1, 24))), ref, ab) <= 1e-2
+
+
+@pytest.mark.parametrize("groups,stride", [(4, 1), (2, 2)])
+def test_grouped_conv2d_gradients(groups, stride):
+    """A grouped layer (RegNetX style): input gradient against the grouped oracle, weight gradient PyTorch's."""
+    torch.manual_seed(6)
+    B, C, K, H = 4, 32, 64, 12
+    x = torch.randn(B, C, H, H, device="cuda", dtype=torch.bfloat16).contiguous(memory_format=torch.channels_last).requires_grad_()
+    w = (torch.randn(K, C // groups, 3, 3, device="cuda", dtype=torch.bfloat16) * 0.2).requires_grad_()
+    y = sa.sdgp_conv2d(x, w, stride, 1, 2, 4, sdgp.GREEDY_ADJUSTED, seed=0, groups=groups)
+    gy = (torch.randn_like(y) * 1e-2).contiguous(memory_format=torch.channels_last)
+    y.backward(gy)
+    xr, wr = x.detach().clone().requires_grad_(), w.detach().clone().requires_grad_()
+    torch.nn.functional.conv2d(xr, wr, None, stride, 1, 1, groups).backward(gy)
+    assert torch.allclose(w.grad.float(), wr.grad.float(), rtol=2e-2, atol=2e-2 * wr.grad.float().abs().max().item())
+    pruned = oracle.prune(bits(gy.permute(0, 2, 3, 1)), 2, 4, oracle.GREEDY_ADJUSTED)[0]
+    ref, ab = oracle.conv_bwd_data_grouped(pruned, bits(w.permute(0, 2, 3, 1)), H, H, stride, 1, groups)
+    assert rel_error(wl.to_f64(bits(x.grad.permute(0, 2, 3, 1))), ref, ab) <= 1e-2
+    with pytest.raises(ValueError):
+        sa.sdgp_conv2d(x, w, stride, 1, 2, 4, groups=groups, per_channel=True)

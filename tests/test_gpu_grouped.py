@@ -15,8 +15,11 @@ pytestmark = pytest.mark.gpu
 
 # B, H, Wd, C_in, C_out, R, S, stride, pad, groups
 GEOMS = [
-    (3, 14, 14, 48, 48, 3, 3, 1, 1, 3),        # group width 16 as in RegNetX-400MF
-    (2, 15, 13, 64, 64, 3, 3, 2, 1, 4),        # the stride-2 block of a stage
+    (3, 14, 14, 48, 48, 3, 3, 1, 1, 3),        # group width 16 as in RegNetX-400MF: the matrix-core kernel (bf16)
+    (2, 20, 37, 160, 160, 3, 3, 1, 1, 10),     # the same kernel: ragged tiles both ways, a slab of two groups
+    (5, 7, 7, 64, 64, 3, 3, 1, 1, 4),          # images smaller than a tile
+    (2, 15, 13, 64, 64, 3, 3, 2, 1, 4),        # the stride-2 block of a stage: four parity classes, odd image sizes
+    (3, 28, 70, 160, 160, 3, 3, 2, 1, 10),     # stride 2, even sizes, two column tiles, a slab of two groups
     (2, 9, 9, 32, 64, 1, 1, 1, 0, 2),
     (2, 8, 8, 16, 16, 3, 3, 1, 1, 4),          # four channels per group: one 2:4 group each
     (1, 12, 10, 24, 48, 5, 3, 1, 1, 3),
@@ -67,3 +70,43 @@ def test_groups_that_split_an_m_group_are_refused():
         sdgp.sdgp_conv_bwd_data_grouped(dO, W, 4, 4, 1, 1, 4, 2, 4, sdgp.GREEDY)     # two output channels per group, m = 4
     with pytest.raises(sdgp.SdgpError):
         sdgp.sdgp_conv_bwd_data_grouped(dO, W, 4, 4, 1, 1, 3, 4, 4, sdgp.GREEDY)     # 8 % 3 != 0
+
+
+def test_group_width_16_keeps_exactly_the_oracle_values():
+    """The matrix-core kernel for 16-channel groups prunes in LDS: with a one-hot filter (output channel k feeds input
+    channel k through the centre tap) dD must equal the oracle's pruned gradient bit for bit."""
+    B, H, Wd, C, groups = 3, 19, 33, 96, 6
+    dO = wl.laplace_with_zeros((B, H, Wd, C), 1e-3, 0.3, 77, wl.BF16)
+    W = np.zeros((C, 3, 3, 16), np.uint16)
+    for k in range(C):
+        W[k, 1, 1, k % 16] = 0x3F80
+    d, w = to_gpu(dO), to_gpu(W)
+    for n, m, ranker in ((2, 4, oracle.RANDOM), (2, 4, oracle.GREEDY), (2, 4, oracle.GREEDY_ADJUSTED), (1, 4, oracle.GREEDY),
+                         (2, 8, oracle.RANDOM), (2, 8, oracle.GREEDY_ADJUSTED), (2, 16, oracle.GREEDY), (2, 16, oracle.RANDOM),
+                         (4, 8, oracle.GREEDY), (4, 16, oracle.GREEDY_ADJUSTED), (3, 4, oracle.RANDOM), (16, 16, oracle.GREEDY)):
+        want = oracle.prune(dO, n, m, ranker, seed=9)[0]
+        got = to_host(sdgp.sdgp_conv_bwd_data_grouped(d, w, H, Wd, 1, 1, groups, n, m, ranker, 9))
+        torch.cuda.synchronize()
+        a, b = wl.to_f64(got), wl.to_f64(want)          # (a kept -0 may come out as +0: compare values)
+        assert np.array_equal(a, b), (n, m, ranker, int(np.count_nonzero(a != b)))
+
+
+def test_group_width_16_stride_2_keeps_exactly_the_oracle_values():
+    """The same through the stride-2 form of the kernel: the centre tap of output pixel (p, q) read input pixel
+    (2p, 2q), so dD there equals the pruned gradient and every other input pixel receives nothing."""
+    B, H, Wd, C, groups = 2, 21, 38, 64, 4
+    P, Q = (H - 1) // 2 + 1, (Wd - 1) // 2 + 1
+    dO = wl.laplace_with_zeros((B, P, Q, C), 1e-3, 0.3, 78, wl.BF16)
+    W = np.zeros((C, 3, 3, 16), np.uint16)
+    for k in range(C):
+        W[k, 1, 1, k % 16] = 0x3F80
+    d, w = to_gpu(dO), to_gpu(W)
+    for n, m, ranker in ((2, 4, oracle.RANDOM), (2, 4, oracle.GREEDY_ADJUSTED), (2, 8, oracle.GREEDY), (2, 16, oracle.RANDOM),
+                         (4, 16, oracle.GREEDY), (4, 4, oracle.GREEDY)):
+        want = wl.to_f64(oracle.prune(dO, n, m, ranker, seed=3)[0])
+        got = wl.to_f64(to_host(sdgp.sdgp_conv_bwd_data_grouped(d, w, H, Wd, 2, 1, groups, n, m, ranker, 3)))
+        torch.cuda.synchronize()
+        assert np.array_equal(got[:, ::2, ::2, :], want), (n, m, ranker)
+        rest = got.copy()
+        rest[:, ::2, ::2, :] = 0
+        assert not rest.any()
