@@ -1,7 +1,9 @@
 // Backward-data for layers with very few input channels (C_in <= 4: the first convolution of a network); the layer
 // is bound by reading dL/dO once.  A workgroup owns a TH x TW tile of input pixels of one image and brings every
 // gradient pixel its taps can reach into LDS once, pruning each m-group with the register ranker on the way
-// (Sec. III-B; stored dense with zeros).  Three kernels (Fig. 3 left; bf16 storage, fp32 accumulation):
+// (Sec. III-B; stored dense with zeros).  Four kernels (Fig. 3 left; bf16 storage, fp32 accumulation):
+//   * bwd_first_stream (further down), for 3x3 stride-1 padding-1 filters with 64 output channels on even images: the
+//     16-column product below, one wavefront streaming a strip of the image through a ring of gradient rows.
 //   * bwd_first2 (further down), for 7x7 stride-2 padding-3 filters on even images: a 2 x 2 block of input pixels and
 //     their channels are the 16 columns of one small product over a 4 x 4 window of gradient pixels.
 //   * bwd_narrow_mm, when the tile's (row tile, column tile) pairs and LDS fit (up to 7x7 filters on RGB): with so few columns per tap the product is turned around.  The matrix
@@ -618,6 +620,238 @@ int launch_first2_rk(const FirstParams& p, int rk, hipStream_t stream) {
     return launch_first2<M, kAdjusted, true, NLE2>(p, stream);
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// 3x3, stride 1, padding 1 on C_in <= 4 with 64 output channels (the first layer of a CIFAR-style network), even image
+// sizes: the stem kernel's 16-column product, streamed.  Input pixel (2i + a, 2j + b) is reached by tap
+// (a + 1 - du, b + 1 - dv) of gradient pixel (2i + du, 2j + dv), du, dv in [-1, 2]: a 4 x 4 window on the gradient,
+// 16 columns (a, b, c), rows = 16 consecutive blocks j of one block row i.  The layer is bound by reading the
+// gradient once, and a tile kernel keeps the memory system idle whenever its workgroups compute in step; so here
+// every WAVEFRONT streams on its own: it owns a strip of 16 blocks (32 input columns) and a range of block rows of
+// one image, keeps eight gradient rows in a ring in LDS (4352 bytes each: both 32-channel halves, even and odd
+// columns apart so that the 16 lanes of a fragment read neighbours, 16-byte parts permuted by bits 2..3 of the
+// record number), computes block row i from rows 2i-1 .. 2i+2 while the rows of the next three block rows are in
+// flight, and never meets a barrier after the filter is in place.  The copies are counted: every block row issues
+// the same ten instructions (rows or columns outside the image copy from a block of zeros), so "all but the youngest
+// 20" is exactly "the rows of this block row have landed".
+//   * the filter's fragments are built in the kernel: W is copied transposed into LDS ([tap, c][k], 144-byte pitch)
+//     and a fragment is one 16-byte read (or zeros where the tap falls outside the filter);
+//   * pruning: a block row prunes the two rows that are new to it, in place, before reading fragments: every
+//     gradient row is ranked once per wavefront that streams it (rows shared by two row ranges twice).
+constexpr int kSRowBytes = 4352;                          // 68 records of 64 bytes: [half][column parity][17]
+constexpr int kSRing = 8;                                 // gradient rows per wavefront
+constexpr int kSRingBytes = kSRing * kSRowBytes;
+constexpr int kSCopiesPerRow = 5;                         // 272 sixteen-byte slots: four full instructions and 16 lanes
+constexpr int kSWPitch = 144;                             // bytes per (tap, c) row of the transposed filter
+constexpr int kSLds = 4 * kSRingBytes + 36 * kSWPitch;
+
+__device__ __align__(64) const uint32_t kStreamZeros[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+struct StreamParams {
+    const uint16_t* dO;
+    const uint16_t* W;
+    uint16_t* dD;
+    int B, H, Wd, C_in;
+    int strips, splits, steps_per_split;   // column strips per image, row ranges per strip, block rows per range
+    int tasks;                             // B * strips * splits
+    int n;
+    uint32_t mix;
+};
+
+template <int M, int RK, bool PRUNE, bool NLE2>
+__global__ void __launch_bounds__(256, 1) bwd_first_stream(const StreamParams p) {
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    SDGP_LDSN unsigned char* smem = (SDGP_LDSN unsigned char*)smem_generic;
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int px = lane & 15, oct = lane >> 4;
+    const int task = blockIdx.x * 4 + wave;
+    const bool active = task < p.tasks;                       // (an idle wavefront still helps with the filter)
+    const int split = task % p.splits, strip = (task / p.splits) % p.strips, b = task / (p.splits * p.strips);
+    const int nblockrows = p.H >> 1;
+    const int i_begin = split * p.steps_per_split;
+    const int i_end = active ? min(i_begin + p.steps_per_split, nblockrows) : i_begin;
+    const int j0 = strip * 16;                                // first block of the strip
+    const int q0 = 2 * j0 - 1;                                // gradient column of record column 0
+    const uint32_t ring = smem_base + (uint32_t)wave * kSRingBytes;
+    SDGP_LDSN unsigned char* const ringp = smem + wave * kSRingBytes;
+
+    // ---- where this lane's slots of a row come from: byte offset inside the gradient row, or "zeros"
+    uint32_t src_off[kSCopiesPerRow];
+    bool src_ok[kSCopiesPerRow];
+#pragma unroll
+    for (int k = 0; k < kSCopiesPerRow; ++k) {
+        const int slot = k * 64 + lane;                       // 16-byte slot of the row (272 of them)
+        const int rec = slot >> 2;
+        const int part = (slot & 3) ^ ((rec >> 2) & 3);       // which eight channels of the half sit here
+        const int half = rec >= 34 ? 1 : 0, rem = rec - 34 * half;
+        const int plane = rem >= 17 ? 1 : 0, idx = rem - 17 * plane;
+        const int q = q0 + 2 * idx + plane;
+        src_ok[k] = slot < 272 && q >= 0 && q < p.Wd;
+        src_off[k] = (uint32_t)(q * 64 + half * 32 + part * 8) * 2u;
+    }
+    const unsigned char* const image = reinterpret_cast<const unsigned char*>(p.dO) + (size_t)b * p.H * p.Wd * 128u;
+    const unsigned char* const zeros = reinterpret_cast<const unsigned char*>(kStreamZeros);
+    const size_t row_bytes = (size_t)p.Wd * 128u;
+    // the two (or four) gradient rows that are new to block row i: gradient row r goes to ring slot (r + 1) & 7
+    auto issue_row = [&](int r) {
+        const bool row_ok = r >= 0 && r < p.H;
+        const unsigned char* base = image + (size_t)(row_ok ? r : 0) * row_bytes;
+        const uint32_t dst = ring + (uint32_t)((r + 1) & 7) * kSRowBytes;
+#pragma unroll
+        for (int k = 0; k < kSCopiesPerRow; ++k) {
+            const unsigned char* src = (row_ok && src_ok[k]) ? base + src_off[k] : zeros;
+            if (k < 4 || lane < 16) lds_copy16(src, dst + (uint32_t)k * 1024u);
+        }
+    };
+    auto issue_step = [&](int i, bool first) {
+        if (first) issue_row(2 * i - 1), issue_row(2 * i);
+        issue_row(2 * i + 1), issue_row(2 * i + 2);
+    };
+    if (active) {
+        issue_step(i_begin, true);
+        if (i_begin + 1 < i_end) issue_step(i_begin + 1, false);
+        if (i_begin + 2 < i_end) issue_step(i_begin + 2, false);
+    }
+
+    // ---- the filter, transposed: row (tap, c), 64 output channels contiguous
+    SDGP_LDSN unsigned char* const wt = smem + 4 * kSRingBytes;
+    const int wcols = 9 * p.C_in;
+    for (int e = tid; e < 64 * wcols; e += 256) {
+        const int k = e / wcols, rsc = e - k * wcols;
+        *(SDGP_LDSN uint16_t*)(wt + rsc * kSWPitch + k * 2) = p.W[e];
+    }
+    __syncthreads();
+    if (!active) return;
+    bf16x8n vf[2][16];
+    {
+        const int a = px >> 3, bb = (px >> 2) & 1, c = px & 3;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int r = a + 1 - ((t >> 2) - 1), s2 = bb + 1 - ((t & 3) - 1);
+            const bool ok = r >= 0 && r < 3 && s2 >= 0 && s2 < 3 && c < p.C_in;
+            const int row = ok ? (r * 3 + s2) * p.C_in + c : 0;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                u32x4n v = *(SDGP_LDSN u32x4n*)(wt + row * kSWPitch + half * 64 + oct * 16);
+                if (!ok) v = u32x4n{0u, 0u, 0u, 0u};
+                vf[half][t] = __builtin_bit_cast(bf16x8n, v);
+            }
+        }
+    }
+    // this lane's fragment of (half, window column dv): record (half, parity of dv, px + dv / 2), part oct
+    uint32_t frag_off[2][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int dv = 0; dv < 4; ++dv) {
+            const int rec = (half * 2 + (dv & 1)) * 17 + (dv >> 1) + px;
+            frag_off[half][dv] = (uint32_t)(rec * 64 + ((oct ^ ((rec >> 2) & 3)) << 4));
+        }
+
+    const int a = oct >> 1, bb = oct & 1;
+    for (int i = i_begin; i < i_end; ++i) {
+        // the rows of block rows i + 1 and i + 2 (ten copies each) may still be in flight.  (The stores of earlier block
+        // rows are in the same counter; not counting them only makes the wait stricter.)
+        const int ahead = i_end - 1 - i;
+        if (ahead >= 2) wait_lds_copies<20>();
+        else if (ahead == 1) wait_lds_copies<10>();
+        else wait_lds_copies<0>();
+        // (the copies, and below the in-place pruning, hand data from lane to lane through LDS inside one wavefront:
+        // the hardware keeps a wavefront's LDS operations in order, the fences keep the compiler from reordering them)
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if constexpr (PRUNE) {
+            // the rows new to this block row: up to 34 pixels (the strip's 32 and a neighbour each side where the image
+            // goes on) x 4 items of 16 channels.  Every lane ranks an item in every round (straight-line code lets the
+            // compiler interleave the rounds); lanes past the last item redo it and do not store.
+            const int r_first = i == i_begin ? 2 * i - 1 : 2 * i + 1;
+            const int col_first = q0 < 0 ? 1 : 0;
+            const int ncols = min(34, p.Wd - q0) - col_first;          // record columns that are gradient pixels
+            const int nitems = 4 * ncols;
+            for (int r = r_first; r <= 2 * i + 2; ++r) {
+                if (r < 0 || r >= p.H) continue;
+                SDGP_LDSN unsigned char* const rowp = ringp + ((r + 1) & 7) * kSRowBytes;
+                const size_t gpix0 = ((size_t)b * p.H + r) * p.Wd + q0;
+                for (int it0 = 0; it0 < nitems; it0 += 128) {
+                    SDGP_LDSN u32x4n* g0[2];
+                    SDGP_LDSN u32x4n* g1[2];
+                    u32x4n v[2][2];
+                    bool live[2];
+#pragma unroll
+                    for (int x = 0; x < 2; ++x) {
+                        const int it = it0 + x * 64 + lane;
+                        live[x] = it < nitems;
+                        const int itc = live[x] ? it : nitems - 1;
+                        const int col = (itc >> 2) + col_first, half = (itc >> 1) & 1, sixteen = itc & 1;
+                        const int rec = (half * 2 + (col & 1)) * 17 + (col >> 1);
+                        const int sw = (rec >> 2) & 3;
+                        g0[x] = (SDGP_LDSN u32x4n*)(rowp + rec * 64 + (((2 * sixteen) ^ sw) << 4));
+                        g1[x] = (SDGP_LDSN u32x4n*)(rowp + rec * 64 + (((2 * sixteen + 1) ^ sw) << 4));
+                        v[x][0] = *g0[x], v[x][1] = *g1[x];
+                        prune16_dense<M, RK, NLE2>(v[x], p.n, p.mix, (uint64_t)(gpix0 + col) * 64u + (uint64_t)(half * 32 + sixteen * 16));
+                    }
+#pragma unroll
+                    for (int x = 0; x < 2; ++x)
+                        if (live[x]) *g0[x] = v[x][0], *g1[x] = v[x][1];
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        f32x4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int du = 0; du < 4; ++du) {
+            SDGP_LDSN unsigned char* const rowp = ringp + ((2 * i + du) & 7) * kSRowBytes;   // gradient row 2i - 1 + du
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+#pragma unroll
+                for (int dv = 0; dv < 4; ++dv) {
+                    const bf16x8n gf = __builtin_bit_cast(bf16x8n, *(SDGP_LDSN u32x4n*)(rowp + frag_off[half][dv]));
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[half][du * 4 + dv], gf, acc, 0, 0, 0);
+                }
+        }
+        // result register c of lane (px, oct = 2 a + b): channel c of input pixel (2 i + a, 2 (j0 + px) + b)
+        const int h = 2 * i + a, w = 2 * (j0 + px) + bb;
+        if (w < p.Wd) {
+            uint16_t* dst = p.dD + (((size_t)b * p.H + h) * p.Wd + w) * p.C_in;
+            const uint32_t c01 = float2_to_bf16x2(acc[0], acc[1]), c23 = float2_to_bf16x2(acc[2], acc[3]);
+            dst[0] = (uint16_t)c01;
+            if (p.C_in > 1) dst[1] = (uint16_t)(c01 >> 16);
+            if (p.C_in > 2) dst[2] = (uint16_t)c23;
+            if (p.C_in > 3) dst[3] = (uint16_t)(c23 >> 16);
+        }
+        // rows 2i - 1 and 2i are done with: their ring slots take the rows of block row i + 3
+        if (i + 3 < i_end) {
+            __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this block row's fragment reads have returned
+            issue_step(i + 3, false);
+        }
+    }
+}
+
+bool stream_fits(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n, int m) {
+    if (R != 3 || S != 3 || stride != 1 || pad != 1 || C_in < 1 || C_in > 4 || C_out != 64) return false;
+    if ((H & 1) || (Wd & 1) || H < 2 || Wd < 2 || B < 1) return false;
+    if (n != m && !(m == 4 || m == 8 || m == 16)) return false;
+    return B * ((Wd + 31) / 32) * (H / 2) < (1 << 28) && B * H * Wd < INT32_MAX;
+}
+
+template <int M, int RK, bool PRUNE, bool NLE2>
+int launch_stream(const StreamParams& p, hipStream_t stream) {
+    auto kern = bwd_first_stream<M, RK, PRUNE, NLE2>;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kSLds);
+    if (attr != hipSuccess) return SDGP_ERR_HIP;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((p.tasks + 3) / 4)), dim3(256), kSLds, stream, p);
+    return launch_status();
+}
+
+template <int M, bool NLE2>
+int launch_stream_rk(const StreamParams& p, int rk, hipStream_t stream) {
+    if (rk == kRandom) return launch_stream<M, kRandom, true, NLE2>(p, stream);
+    if (rk == kGreedy) return launch_stream<M, kGreedy, true, NLE2>(p, stream);
+    return launch_stream<M, kAdjusted, true, NLE2>(p, stream);
+}
+
 // LDS bytes of bwd_narrow_mm for a tile of npix gradient pixels, nt column tiles and J live columns.
 int narrow_mm_lds(int npix, int nt, int J) {
     const int rows = ((npix + 31) / 32) * 32;
@@ -728,6 +962,26 @@ int bwd_narrow_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
                       int64_t C_out, int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed,
                       void* workspace, hipStream_t stream) {
     if (!is_aligned16(dO)) return 1;
+    if (stream_fits(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m)) {
+        StreamParams f{};
+        f.dO = static_cast<const uint16_t*>(dO), f.W = static_cast<const uint16_t*>(W), f.dD = static_cast<uint16_t*>(dD);
+        f.B = (int)B, f.H = (int)H, f.Wd = (int)Wd, f.C_in = (int)C_in;
+        f.strips = (int)((Wd + 31) / 32);
+        // one wavefront per (image, strip, range of block rows): about 1024 of them (four per CU) when the batch allows,
+        // ranges of at least four block rows
+        const int64_t units = B * f.strips, rows = H / 2;
+        int64_t splits = units >= 1024 ? 1 : (1024 + units - 1) / units;
+        if (splits > rows / 4) splits = rows / 4 > 0 ? rows / 4 : 1;
+        f.steps_per_split = (int)((rows + splits - 1) / splits);
+        f.splits = (int)((rows + f.steps_per_split - 1) / f.steps_per_split);
+        f.tasks = (int)(units * f.splits);
+        f.n = n, f.mix = seed_mix(seed);
+        if (n == m) return launch_stream<4, kGreedy, false, true>(f, stream);
+        const bool le2 = n <= 2;
+        if (m == 4) return le2 ? launch_stream_rk<4, true>(f, rk, stream) : launch_stream_rk<4, false>(f, rk, stream);
+        if (m == 8) return le2 ? launch_stream_rk<8, true>(f, rk, stream) : launch_stream_rk<8, false>(f, rk, stream);
+        return le2 ? launch_stream_rk<16, true>(f, rk, stream) : launch_stream_rk<16, false>(f, rk, stream);
+    }
     if (workspace != nullptr && is_aligned16(workspace) && B * H * Wd > 0 && first2_fits(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m)) {
         FirstParams f{};
         f.dO = static_cast<const uint16_t*>(dO), f.vimg = static_cast<const unsigned char*>(workspace), f.dD = static_cast<uint16_t*>(dD);

@@ -193,10 +193,15 @@ FIRST_3X3 = [
     wl.ConvLayer("f3_ragged", 2, 20, 36, 4, 128, 3, 3, 1, 1),            # ragged tiles both ways, two passes of 64 channels
     wl.ConvLayer("f3_gray_tiny", 3, 2, 2, 1, 64, 3, 3, 1, 1),            # one block per image
     wl.ConvLayer("f3_two_ch_wide", 1, 6, 70, 2, 192, 3, 3, 1, 1),        # three column tiles, the last ragged
+    # 64 output channels on even images: the streaming kernel (a wavefront per strip of 32 columns and range of rows)
+    wl.ConvLayer("f3_stream_strips", 2, 20, 36, 4, 64, 3, 3, 1, 1),      # two strips, the second four columns wide
+    wl.ConvLayer("f3_stream_wide", 1, 6, 70, 2, 64, 3, 3, 1, 1),         # three strips, three block rows
+    wl.ConvLayer("f3_stream_tall", 1, 64, 8, 3, 64, 3, 3, 1, 1),         # one strip, row ranges of four block rows
 ]
 FIRST_3X3_MANY = [
     wl.ConvLayer("f3_rgb_32_many", 300, 32, 32, 3, 64, 3, 3, 1, 1),      # many tiles
     wl.ConvLayer("f3_ragged_many", 90, 40, 44, 4, 128, 3, 3, 1, 1),      # 3 x 2 tiles per image, ragged both ways
+    wl.ConvLayer("f3_stream_many", 700, 24, 44, 3, 64, 3, 3, 1, 1),      # more wavefront tasks than the chip holds at once
 ]
 
 

@@ -150,3 +150,24 @@ RANKED_AHEAD = [
 def test_ranked_ahead_pruned_values_equal_the_oracle(layer, npix, settings):
     assert sdgp.conv_bwd_data_workspace(layer.B, layer.H, layer.Wd, layer.C_in, layer.C_out, 1, 1, 1, 0, sdgp.BF16, 2, 4) > 0
     check_exact(layer, False, settings, npix=npix)
+
+
+def test_streaming_first_layer_pruned_values_equal_the_oracle():
+    """The streaming 3x3 first-layer kernel (64 output channels, four input channels): output channels 0..35 feed
+    (tap k mod 9, input channel k div 9) with weight 1, channels 36..63 carry zeros in the gradient, and only pixels
+    (1, 1) mod 3 are nonzero -- every dD element is one kept value or nothing."""
+    layer = wl.ConvLayer("stream_3x3", 3, 20, 36, 4, 64, 3, 3, 1, 1)
+    dO = gradient(layer, 911, 3)
+    dO[..., 36:] = 0
+    W = np.zeros(layer.W_shape, np.uint16)
+    for k in range(36):
+        W[k, (k % 9) // 3, (k % 9) % 3, k // 9] = ONE
+    d, w = to_gpu(dO), to_gpu(W)
+    for n, m, ranker in nm_settings() + [(4, 8, oracle.GREEDY), (3, 4, oracle.RANDOM), (4, 16, oracle.GREEDY_ADJUSTED)]:
+        pruned = oracle.prune(dO, n, m, ranker, seed=29)[0]
+        ref, _ = oracle.conv_bwd_data(pruned, W, layer.H, layer.Wd, 1, 1)
+        out = sdgp.sdgp_conv_bwd_data(d, w, layer.H, layer.Wd, 1, 1, n, m, ranker, 29)
+        torch.cuda.synchronize()
+        got = wl.to_f64(to_host(out))
+        assert np.array_equal(got, ref), (n, m, ranker, int(np.count_nonzero(got != ref)))
+        assert np.count_nonzero(ref) > 0
