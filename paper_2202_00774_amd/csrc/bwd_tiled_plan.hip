@@ -61,6 +61,9 @@ int bwd_tiled_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t
     }
     if (B * P * Q >= INT_MAX || B * H * Wd >= INT_MAX || (int64_t)R * S * C_in >= INT_MAX || C_out >= INT_MAX / 2)
         return 1;
+    // the random ranker hashes a 16-channel item with one high word of the flat element index: items start at multiples
+    // of 16 elements, or the tensor stays below 2^32 elements
+    if ((C_out % 16) != 0 && B * P * Q * C_out >= ((int64_t)1 << 32)) return 1;
 
     TiledParams p{};
     p.dO = static_cast<const uint16_t*>(dO);

@@ -397,6 +397,20 @@ __host__ __device__ __forceinline__ void prune_packed(const uint32_t (&w)[M / 2]
 __host__ __device__ __forceinline__ uint32_t sdgp_umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 __host__ __device__ __forceinline__ uint32_t sdgp_umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __host__ __device__ __forceinline__ uint32_t sdgp_rotl(uint32_t x, int s) { return (x << s) | (x >> (32 - s)); }
+// v_perm_b32 for selector bytes 0..7 (byte i of hi:lo) and 12 (zero).
+__host__ __device__ __forceinline__ uint32_t sdgp_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_perm(hi, lo, sel);
+#else
+    const uint64_t both = ((uint64_t)hi << 32) | lo;
+    uint32_t r = 0;
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t c = (sel >> (8 * i)) & 0xFFu;
+        r |= (c < 8 ? (uint32_t)((both >> (8 * c)) & 0xFFu) : 0u) << (8 * i);
+    }
+    return r;
+#endif
+}
 
 template <int M, int RK>
 __host__ __device__ __forceinline__ void prune_compress16_bf16(const uint32_t (&w)[8], int n, uint32_t (&packed)[4],
@@ -513,11 +527,12 @@ __host__ __device__ __forceinline__ void prune_compress16_random(const uint32_t 
     static_assert(M == 4 || M == 8 || M == 16, "group sizes that tile sixteen channels");
     const bool two = n >= 2;
     uint32_t f[4], s[4];  // largest and second largest word of each quad
+    // (the sixteen elements share the high word of their index: e0 is a multiple of 16, or at least of 4 in a tensor of
+    // fewer than 2^32 elements -- the callers see to it)
+    const uint32_t hrow = hash_row(mix, (uint32_t)(e0 >> 32));
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const uint64_t eg = e0 + (uint64_t)((4 * q) / M * M);              // first element of the quad's group
-        const uint32_t hrow = hash_row(mix, (uint32_t)(eg >> 32));
-        const uint32_t e_lo = (uint32_t)eg + (uint32_t)((4 * q) % M);      // the quad's first element
+        const uint32_t e_lo = (uint32_t)e0 + (uint32_t)(4 * q);            // the quad's first element
         const uint32_t c0 = (uint32_t)(15 - (4 * q) % M);
         const uint32_t hq = hash_quad(hrow, e_lo);                         // e_lo is a multiple of 4: one word per quad
         const uint32_t k0 = hash_lane(hq, 0u) | c0;
@@ -548,17 +563,19 @@ __host__ __device__ __forceinline__ void prune_compress16_random(const uint32_t 
     meta = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        // the quad's survivors are among its two largest words; a slot without one keeps a (dropped) position, value +0
-        const bool keep_f = f[q] >= thr[q], keep_s = s[q] >= thr[q];
-        const uint32_t pf = (15u - (f[q] & 15u)) & 3u, ps = (15u - (s[q] & 15u)) & 3u;  // position in the quad
-        const uint32_t d01 = w[2 * q], d23 = w[2 * q + 1];
-        const uint32_t vf = ((pf & 2u) ? d23 : d01) >> (16u * (pf & 1u)) & 0xFFFFu;
-        const uint32_t vs = ((ps & 2u) ? d23 : d01) >> (16u * (ps & 1u)) & 0xFFFFu;
-        const uint32_t xf = keep_f ? vf : 0u, xs = keep_s ? vs : 0u;
+        // the quad's survivors are among its two largest words; a slot without one keeps a (dropped) position, value +0.
+        // Position in the quad from the code (15 - position in the group): its complement's low two bits.
+        const uint32_t pf = ~f[q] & 3u, ps = ~s[q] & 3u;
+        const uint32_t p_lo = sdgp_umin(pf, ps), p_hi = sdgp_umax(pf, ps);
+        // the two values leave the quad's 64 bits by a byte permutation: bytes 2p, 2p + 1 of (d23 : d01)
+        uint32_t sel = (p_lo | (p_hi << 16)) * 0x0202u + 0x01000100u;
+        const bool keep_f = M == 4 ? true : f[q] >= thr[q];     // (a 4-group's threshold is its own first or second word)
+        const bool keep_s = M == 4 ? two : s[q] >= thr[q];
         const bool f_first = pf < ps;
-        const uint32_t p_lo = f_first ? pf : ps, p_hi = f_first ? ps : pf;
-        const uint32_t x_lo = f_first ? xf : xs, x_hi = f_first ? xs : xf;
-        packed[q] = x_lo | (x_hi << 16);
+        const bool keep_lo = f_first ? keep_f : keep_s, keep_hi = f_first ? keep_s : keep_f;
+        sel = keep_lo ? sel : ((sel & 0xFFFF0000u) | 0x00000C0Cu);   // selector 12 yields a zero byte
+        sel = keep_hi ? sel : ((sel & 0x0000FFFFu) | 0x0C0C0000u);
+        packed[q] = sdgp_perm(w[2 * q + 1], w[2 * q], sel);
         meta |= (p_lo | (p_hi << 2)) << (4 * q);
     }
 }
