@@ -561,6 +561,17 @@ __host__ __device__ __forceinline__ void prune_compress16_random(const uint32_t 
         for (int i = 0; i < QG; ++i) thr[g * QG + i] = th;
     }
     meta = 0;
+    if (M == 4 && two) {
+        // 2:4 (n is uniform over the wavefront): a quad's two largest words are its survivors, nothing else to decide
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t pf = ~f[q] & 3u, ps = ~s[q] & 3u;
+            const uint32_t p_lo = sdgp_umin(pf, ps), p_hi = sdgp_umax(pf, ps);
+            packed[q] = sdgp_perm(w[2 * q + 1], w[2 * q], (p_lo | (p_hi << 16)) * 0x0202u + 0x01000100u);
+            meta |= (p_lo | (p_hi << 2)) << (4 * q);
+        }
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         // the quad's survivors are among its two largest words; a slot without one keeps a (dropped) position, value +0.
