@@ -71,12 +71,12 @@ int launch_pw_classes_any(const PwClasses& all, int ncls, int mode, int m, int s
 // gradient row is ranked once per 256 columns; dense: 128 x 128 tiles measured fastest (column tiles of one row tile
 // run side by side on one XCD and find the gradient rows in its L2).
 int pw_shape(int mode, int64_t C_in) {
-    if (C_in <= 64) return (mode != 0) ? 3 : 2;
+    if (C_in <= 64) return 3;   // 128 x 64: 256-row tiles measured the same or slower (fewer workgroups, a longer last round)
     if (mode != 0 && C_in > 128) return 0;
     return 1;
 }
 // Tile shape when the gradient arrives compressed (nothing is ranked in the kernel): the dense kernel's.
-int pw_pre_shape(int64_t C_in) { return C_in <= 64 ? 2 : 1; }
+int pw_pre_shape(int64_t C_in) { return C_in <= 64 ? 3 : 1; }
 
 // Whether a pass that ranks and compresses the gradient first (csrc/compress.hip) pays: the fused kernel would rank
 // every gradient element `times` times, the pass reads it once and writes half of it, and the product that follows
