@@ -255,7 +255,7 @@ def main():
         "layers": rows,
         "note": "ranked_ahead = what sdgp_conv_bwd_data runs on these layers given its workspace (for the Magnitude ranker "
                 "only where the fused kernel would rank four times or more: otherwise both columns are the fused kernel); "
-                "the product kernel alone runs 1.15-1.4x as fast as the dense one (profiles/ranked_ahead_kernel_stats.md)",
+                "the product kernel alone runs 1.15-1.25x as fast as the dense one (profiles/ranked_ahead_kernel_stats.md)",
     }
 
     del data50, shapes
@@ -529,7 +529,7 @@ def roofline_entry(L, ms, setting, sparse, share=None, launches=None):
 
 
 def probe(args, sdgp, wl, torch, np, dev, gpu, call):
-    """A few launches of one kind, each round followed by a plain device copy of COPY_BYTES."""
+    """A few launches of one kind and a plain device copy of COPY_BYTES (the counters' calibration)."""
     src = torch.zeros(COPY_BYTES, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
     if args.probe in ("prune", "channel"):
@@ -557,11 +557,19 @@ def probe(args, sdgp, wl, torch, np, dev, gpu, call):
         dO, W = wl.layer_inputs(L, s[0], s[1], s[2], wl.BF16)
         d, w = gpu(dO), gpu(W)
         out = torch.empty(L.dD_shape, dtype=torch.bfloat16, device=dev)
-        for _ in range(args.reps):
-            call(L, d, w, out, args.n, args.m, args.ranker, seed=i)
-            call(L, d, w, out, args.m, args.m, args.ranker, seed=i)
-            if args.probe == "layer":
+        if args.probe == "layer":
+            # each setting back to back, as the timed table launches them (a launch that follows a different kernel
+            # or the copy finds colder caches and measures up to 20 % longer)
+            for _ in range(args.reps):
+                call(L, d, w, out, args.n, args.m, args.ranker, seed=i)
+            for _ in range(args.reps):
+                call(L, d, w, out, args.m, args.m, args.ranker, seed=i)
+            for _ in range(args.reps):
                 dst.copy_(src)
+        else:
+            for _ in range(args.reps):
+                call(L, d, w, out, args.n, args.m, args.ranker, seed=i)
+                call(L, d, w, out, args.m, args.m, args.ranker, seed=i)
         torch.cuda.synchronize()
         print("layer", i, L.name, "algorithmic bytes", L.bytes_moved(), "copy bytes each way", COPY_BYTES, flush=True)
         del d, w, out

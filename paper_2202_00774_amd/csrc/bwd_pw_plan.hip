@@ -80,7 +80,7 @@ int pw_pre_shape(int64_t C_in) { return C_in <= 64 ? 3 : 1; }
 
 // Whether a pass that ranks and compresses the gradient first (csrc/compress.hip) pays: the fused kernel would rank
 // every gradient element `times` times, the pass reads it once and writes half of it, and the product that follows
-// runs 1.15-1.4 times as fast as the dense one.  Measured on the layers of ResNet-50 at batch 256: from two times on
+// runs 1.15-1.25 times as fast as the dense one.  Measured on the layers of ResNet-50 at batch 256: from two times on
 // with the random ranker (the hash makes ranking dearer), from four on with the magnitude rankers.
 bool pre_pays(int mode, int64_t C_out, int64_t rows_dO, int times, int rk) {
     const int least = rk == kRandom ? 2 : 4;
