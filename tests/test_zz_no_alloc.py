@@ -59,3 +59,15 @@ def test_noalloc_without_scratch_and_refusal():
         sdgp.sdgp_conv_bwd_data_noalloc(d, w, wide.H, wide.Wd, 2, 3, 2, 4, sdgp.GREEDY, 0, out)
     assert e.value.status == -6
     assert torch.all(out == 3.0)
+
+
+def test_noalloc_ranks_ahead_of_the_product_when_the_arrays_fit_the_scratch():
+    """A 1x1 layer onto 2048 channels: the gradient ranked and compressed once needs 73 KB and goes into the scratch
+    array (same kernels as with a workspace, same bits); the same layer at a larger batch needs more than the array
+    holds and runs the fused kernel (same kept values, another summation order)."""
+    small = wl.ConvLayer("pre_1x1_wide", 3, 13, 13, 2048, 128, 1, 1, 1, 0)
+    need = sdgp.conv_bwd_data_workspace(3, 13, 13, 2048, 128, 1, 1, 1, 0, sdgp.BF16, 2, 4)
+    assert 0 < need <= 256 * 1024
+    run_pair(small, 2, 4, sdgp.RANDOM, 3)
+    run_pair(small, 2, 8, sdgp.GREEDY_ADJUSTED, 4)
+    run_pair(small, 2, 4, sdgp.RANDOM, 3)
