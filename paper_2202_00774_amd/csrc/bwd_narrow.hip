@@ -430,9 +430,10 @@ __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
 // with V the filter re-indexed (zeros where r or s falls outside the filter): rows = gradient-grid positions,
 // reduction = 16 window positions x C_out, on v_mfma_f32_16x16x32_bf16 with the result left in registers -- no table
 // of per-tap products in LDS, no per-pixel gather.  A lane ends up with the channels of one input pixel.
-//   * workgroup = 4 wavefronts, tile = 8 x 64 gradient-grid positions (16 x 128 input pixels); wavefront (rq, gp) owns
-//     grid rows 4 rq .. 4 rq + 3 and columns 32 gp .. 32 gp + 31: 4 x 2 accumulators of four registers;
-//   * the reduction runs in chunks of 32 channels: the 11 x 67 gradient pixels the tile's windows reach (64 bytes each,
+//   * workgroup = 4 wavefronts, tile = 16 x 32 gradient-grid positions (32 x 64 input pixels: of the tiles of 512
+//     positions the one with the smallest halo that keeps two 16-column groups per wavefront); wavefront rq owns grid
+//     rows 4 rq .. 4 rq + 3: 4 x 2 accumulators of four registers;
+//   * the reduction runs in chunks of 32 channels: the 19 x 35 gradient pixels the tile's windows reach (64 bytes each,
 //     80-byte pitch: sixteen consecutive pixels read conflict-free, and every fragment address is a per-lane base plus
 //     a constant) and V's chunk (16 window positions x 16 columns, built once per call in the workspace) arrive by
 //     direct-to-LDS copies; slots of pixels outside the gradient are cleared once and skipped by the copies; pruning, when asked
@@ -441,9 +442,10 @@ __global__ void __launch_bounds__(256, 2) bwd_narrow_mm(const NarrowParams p) {
 //     instructions (the output rows whose window holds that gradient row); V's 16 fragments sit in registers.
 constexpr int kFWin = 4;                                  // window positions per dimension
 constexpr int kFKC = 32;                                  // channels per chunk
-constexpr int kFRows = 8, kFCols = 64;                    // tile, in gradient-grid positions
+constexpr int kFRows = 16, kFCols = 32;                   // tile, in gradient-grid positions
 constexpr int kFHaloRows = kFRows + kFWin - 1, kFHaloCols = kFCols + kFWin - 1;
-constexpr int kFPix = kFHaloRows * kFHaloCols;            // 737 gradient pixels
+constexpr int kFPix = kFHaloRows * kFHaloCols;            // 665 gradient pixels
+constexpr uint32_t kFColMagic = 65536u / kFHaloCols + 1u; // x / kFHaloCols == (x * magic) >> 16 for x < 700
 constexpr int kFPitch = 80;                               // bytes per pixel in LDS: 64 of data, 16 of padding
 constexpr int kFAUnits = (kFPix * kFPitch + 1023) / 1024; // 1 KB copy units
 constexpr int kFABytes = kFAUnits * 1024;
@@ -488,7 +490,7 @@ __global__ void __launch_bounds__(kFThreads, 2) bwd_first2(const FirstParams p) 
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int rq = wave >> 1, gp = wave & 1;
+    const int rq = wave, gp = 0;
     const int tile = blockIdx.x;
     const int tj = tile % p.tiles_j, ti = (tile / p.tiles_j) % p.tiles_i, b = tile / (p.tiles_j * p.tiles_i);
     const int i0 = ti * kFRows, j0 = tj * kFCols;
@@ -517,7 +519,7 @@ __global__ void __launch_bounds__(kFThreads, 2) bwd_first2(const FirstParams p) 
         const int slot = u * 64 + lane;                                  // 16-byte slot of the tile
         const int pix = (int)(((uint32_t)slot * 13108u) >> 16);          // slot / 5
         const int part = slot - 5 * pix;                                 // 0..3 data, 4 padding
-        const int hr = (int)(((uint32_t)pix * 979u) >> 16);              // pix / 67
+        const int hr = (int)(((uint32_t)pix * kFColMagic) >> 16);        // pix / kFHaloCols
         const int gi = i0 - 1 + hr, gj = j0 - 1 + (pix - hr * kFHaloCols);
         const bool ok = u < kFAUnits && part < 4 && pix < kFPix && gi >= 0 && gi < p.P && gj >= 0 && gj < p.Q;
         voff[x] = ok ? (uint32_t)((gi * p.Q + gj) * p.C_out + part * 8) * 2u : kNothing;
@@ -540,7 +542,7 @@ __global__ void __launch_bounds__(kFThreads, 2) bwd_first2(const FirstParams p) 
         if constexpr (PRUNE) {
             for (int it = tid; it < kFPix * 2; it += kFThreads) {
                 const int hp = it >> 1, half = it & 1;
-                const int hr = (int)(((uint32_t)hp * 979u) >> 16);
+                const int hr = (int)(((uint32_t)hp * kFColMagic) >> 16);
                 const int gi = i0 - 1 + hr, gj = j0 - 1 + (hp - hr * kFHaloCols);
                 if (gi >= 0 && gi < p.P && gj >= 0 && gj < p.Q) {
                     SDGP_LDSN u32x4n* g0 = (SDGP_LDSN u32x4n*)(smem + hp * kFPitch + half * 32);

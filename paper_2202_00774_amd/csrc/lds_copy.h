@@ -47,44 +47,37 @@ __device__ __forceinline__ void prune16_compressed(const u32x4_t (&v)[2], int n,
 // v[0], v[1]: the two 16-byte halves; e0: flat index of the first element (for the random ranker's hash).
 template <int M, int RK, bool NLE2>
 __device__ __forceinline__ void prune16_dense(u32x4_t (&v)[2], int n, uint32_t mix, uint64_t e0) {
-    if constexpr (NLE2 && RK != kRandom) {
-        // magnitude rankers, n <= 2: rank on packed keys, then spread the two kept values of every quad back to
-        // their positions
+    if constexpr (M == 16 && !NLE2 && RK != kRandom) {
+        // one group, magnitude keys, any n: the packed 16-bit ranker, no unpacking
         const uint32_t w[8] = {v[0][0], v[0][1], v[0][2], v[0][3], v[1][0], v[1][1], v[1][2], v[1][3]};
-        uint32_t packed[4], meta;
-        prune_compress16_bf16<M, RK>(w, n, packed, meta);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const uint32_t i0 = (meta >> (4 * q)) & 3u, i1 = (meta >> (4 * q + 2)) & 3u;
-            const uint64_t x = ((uint64_t)(packed[q] & 0xFFFFu) << (16 * i0)) | ((uint64_t)(packed[q] >> 16) << (16 * i1));
-            v[q >> 1][2 * (q & 1)] = (uint32_t)x;
-            v[q >> 1][2 * (q & 1) + 1] = (uint32_t)(x >> 32);
-        }
-    } else {
-        uint32_t raw[16], out[16];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
-                raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
-            }
-#pragma unroll
-        for (int g = 0; g < 16 / M; ++g) {
-            uint32_t r[M], o[M];
-            bool kk[M];
-#pragma unroll
-            for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
-            const uint64_t eg = e0 + (uint64_t)(g * M);
-            prune_group<kBF16, M, RK, NLE2>(r, n, hash_row(mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
-#pragma unroll
-            for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int x = 0; x < 4; ++x) v[i][x] = out[i * 8 + 2 * x] | (out[i * 8 + 2 * x + 1] << 16);
+        uint32_t o[8];
+        prune_packed<16, RK>(w, n, o);
+        v[0] = u32x4_t{o[0], o[1], o[2], o[3]}, v[1] = u32x4_t{o[4], o[5], o[6], o[7]};
+        return;
     }
+    uint32_t raw[16], out[16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            raw[i * 8 + 2 * x] = v[i][x] & 0xFFFFu;
+            raw[i * 8 + 2 * x + 1] = v[i][x] >> 16;
+        }
+#pragma unroll
+    for (int g = 0; g < 16 / M; ++g) {
+        uint32_t r[M], o[M];
+        bool kk[M];
+#pragma unroll
+        for (int j = 0; j < M; ++j) r[j] = raw[g * M + j];
+        const uint64_t eg = e0 + (uint64_t)(g * M);
+        prune_group<kBF16, M, RK, NLE2>(r, n, hash_row(mix, (uint32_t)(eg >> 32)), (uint32_t)eg, kk, o);
+#pragma unroll
+        for (int j = 0; j < M; ++j) out[g * M + j] = o[j];
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) v[i][x] = out[i * 8 + 2 * x] | (out[i * 8 + 2 * x + 1] << 16);
 }
 
 }  // namespace sdgp
