@@ -60,7 +60,7 @@ struct Plan {
 
 // min_rows: fewest rows a thread should walk (the sums kernel writes one row of partial sums per workgroup, so its
 // threads must amortise it; the pruning kernel has no such cost).
-Plan make_plan(int64_t rows, int64_t C, int dt, int m, bool aligned, int min_rows) {
+Plan make_plan(int64_t rows, int64_t C, int dt, int m, bool aligned, int min_rows, int max_wgs = 2048) {
     Plan p;
     const int pv = (dt == kBF16) ? 8 : 4;
     const int item = m > pv ? m : pv;
@@ -72,9 +72,9 @@ Plan make_plan(int64_t rows, int64_t C, int dt, int m, bool aligned, int min_row
     p.tg = tg;
     p.tr = kBlock / tg;
     p.gx = (int)((p.nslots + tg - 1) / tg);
-    // about 2048 workgroups in all; 64 rows per thread when the tensor is large enough for that many, fewer (down to
-    // min_rows) when it is not
-    const int64_t cap = 2048 / p.gx > 0 ? 2048 / p.gx : 1;
+    // about max_wgs workgroups in all; 64 rows per thread when the tensor is large enough for that many, fewer (down
+    // to min_rows) when it is not
+    const int64_t cap = max_wgs / p.gx > 0 ? max_wgs / p.gx : 1;
     int64_t nb = rows / ((int64_t)p.tr * 64);
     if (nb < cap) nb = rows / ((int64_t)p.tr * min_rows);
     if (nb > cap) nb = cap;
@@ -84,6 +84,11 @@ Plan make_plan(int64_t rows, int64_t C, int dt, int m, bool aligned, int min_row
 }
 
 constexpr int kSumsMinRows = 16, kPruneMinRows = 2;
+
+// The sums kernel keeps 2 x slot fp64 accumulators per thread: its workgroups should all be resident at once (a second,
+// sparse round of workgroups hides no latency), which the registers of the group size bound: four workgroups of four
+// wavefronts per CU up to m = 8, three at 16, two at 32.
+int sums_max_wgs(int m) { return m <= 4 ? 1792 : m == 8 ? 1280 : m == 16 ? 768 : 512; }
 
 // Keep flags of one group by Magnitude; m compiled (M > 0) or at run time (M == 0, rank count).
 template <int DT, int M, bool NLE2>
@@ -124,7 +129,7 @@ __device__ __forceinline__ float abs_as_float(uint32_t raw) {
 // more than 53 bits, and carrying each sum as a pair of floats (error-free additions, six fp32 operations per term)
 // measured a third slower than the fp64 additions.
 template <int DT, int M, bool NLE2>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock, (DT == kBF16 && M == 4) ? 7 : 1)
 channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n, int slot, int64_t nslots, int tg, int tr,
              double* __restrict__ partial) {
     using T = typename Elem<DT>::type;
@@ -147,23 +152,73 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
     if (active) {
         int64_t r = (int64_t)blockIdx.y * tr + ry;
         if constexpr (M > 0) {
-            // the next row's vectors are requested before this row's are ranked
-            u32x4 cur[VECS], nxt[VECS];
-            const T* base = reinterpret_cast<const T*>(dO_) + s * slot;
-            if (r < rows) {
+            // kDepth rows are in flight per thread: a ring of row buffers that the unrolled loop refills in place, so
+            // that a row is waited for with the later requests still outstanding.  Every request inside the loop is
+            // unconditional (an address past the thread's last row is replaced by that row's, and what it returns is
+            // never added), which keeps the count of outstanding requests the same on every path.  The loop takes
+            // whole batches of kDepth rows; the rows left in the ring are added after it.
+            constexpr int kDepth = VECS == 1 ? 3 : 2;
+            u32x4 ring[kDepth][VECS];
+            const char* base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(dO_) + s * slot);
+            const int64_t row_bytes = C * (int64_t)sizeof(T);
+            auto request = [&](const char* at, u32x4 (&dst)[VECS]) {
 #pragma unroll
-                for (int i = 0; i < VECS; ++i) cur[i] = load16<VECS == 1>(reinterpret_cast<const u32x4*>(base + r * C) + i);
-            }
-            for (; r < rows; r += step) {
-                const int64_t rn = r + step;
-                if (rn < rows) {
+                for (int i = 0; i < VECS; ++i) dst[i] = load16<VECS == 1>(reinterpret_cast<const u32x4*>(at) + i);
+            };
+            auto add_row = [&](const u32x4 (&v)[VECS]) {
+                if constexpr (DT == kBF16) {
+                    // bf16: an element widened to fp32 is its half of the dword moved to the top, and that word with
+                    // the position code in its (zero) low bits is the ranking key.  The double of a bf16 has a zero
+                    // low word, so clearing the high word alone turns it into the +0 a dropped element adds.
+                    uint32_t w[SLOT / 2];
 #pragma unroll
-                    for (int i = 0; i < VECS; ++i) nxt[i] = load16<VECS == 1>(reinterpret_cast<const u32x4*>(base + rn * C) + i);
+                    for (int i = 0; i < VECS; ++i) {
+                        w[4 * i] = v[i].x, w[4 * i + 1] = v[i].y;
+                        w[4 * i + 2] = v[i].z, w[4 * i + 3] = v[i].w;
+                    }
+                    auto add_one = [&](int c, uint32_t fbits, uint32_t kbits) {   // |x| into tot, kept |x| (or +0) into kep
+                        tot[c] += (double)__builtin_fabsf(bits_to_float(fbits));
+                        kep[c] += (double)bits_to_float(kbits);
+                    };
+#pragma unroll
+                    for (int g = 0; g < SLOT / GM; ++g) {
+                        if constexpr (GM >= 16) {
+                            uint32_t gw[GM / 2], km[GM / 2];
+#pragma unroll
+                            for (int i = 0; i < GM / 2; ++i) gw[i] = w[g * (GM / 2) + i];
+                            keep_mask_packed<GM>(gw, n, km);
+#pragma unroll
+                            for (int i = 0; i < GM / 2; ++i) {
+                                const uint32_t mag = gw[i] & 0x7FFF7FFFu, kept = mag & km[i];
+                                add_one(g * GM + 2 * i, mag << 16, kept << 16);
+                                add_one(g * GM + 2 * i + 1, mag & 0xFFFF0000u, kept & 0xFFFF0000u);
+                            }
+                        } else {
+                            uint32_t f[GM], key[GM];
+                            bool keep[GM];
+#pragma unroll
+                            for (int j = 0; j < GM; ++j) {
+                                const uint32_t word = w[(g * GM + j) / 2];
+                                f[j] = (j & 1) ? (word & 0xFFFF0000u) : (word << 16);
+                                key[j] = (f[j] & 0x7FFF0000u) | (uint32_t)(GM - 1 - j);   // a lower position wins a tie
+                            }
+                            if constexpr (NLE2) select_top2_distinct<GM>(key, n, keep);
+                            else if constexpr (GM == 8) select_by_sort<GM>(key, n, keep);
+                            else select_by_rank<GM>(key, n, keep);
+#pragma unroll
+                            for (int j = 0; j < GM; ++j) {
+                                const double ad = (double)__builtin_fabsf(bits_to_float(f[j]));
+                                tot[g * GM + j] += ad;
+                                kep[g * GM + j] += __hiloint2double(keep[j] ? __double2hiint(ad) : 0, __double2loint(ad));
+                            }
+                        }
+                    }
+                    return;
                 }
                 uint32_t raw[SLOT];
 #pragma unroll
                 for (int i = 0; i < VECS; ++i) {
-                    const uint32_t w[4] = {cur[i].x, cur[i].y, cur[i].z, cur[i].w};
+                    const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         if constexpr (DT == kBF16) {
@@ -189,8 +244,31 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
                         kep[g * GM + j] += keep[j] ? ad : 0.0;
                     }
                 }
+            };
+            if (r < rows) {
+                // the thread's rows are r, r + step, ...: `at` walks their addresses, `end` is the last one's
+                const int64_t mine = (rows - 1 - r) / step;   // index of the thread's last row
+                const char* at = base + r * row_bytes;
+                const char* const end = at + mine * step * row_bytes;
+                const int64_t stride = step * row_bytes;
+                auto clamped = [&](const char* q) { return q < end ? q : end; };
 #pragma unroll
-                for (int i = 0; i < VECS; ++i) cur[i] = nxt[i];
+                for (int d = 0; d < kDepth; ++d) request(clamped(at + d * stride), ring[d]);
+                int64_t left = mine + 1;   // rows still to add
+                for (; left >= kDepth; left -= kDepth) {
+#pragma unroll
+                    for (int d = 0; d < kDepth; ++d) {
+                        add_row(ring[d]);
+                        __builtin_amdgcn_sched_barrier(0);   // the request stays here, kDepth - 1 rows of work ahead of its wait
+                        request(clamped(at + (d + kDepth) * stride), ring[d]);   // after the last use: the same registers
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    at += kDepth * stride;
+                }
+#pragma unroll
+                for (int d = 0; d < kDepth - 1; ++d) {
+                    if (d < left) add_row(ring[d]);
+                }
             }
         } else {
             for (; r < rows; r += step) {
@@ -228,8 +306,27 @@ channel_sums(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
         }
     };
     if constexpr (M > 0) {
+        // eight accumulators per pass: every thread parks them in LDS, then each of the 8 * tg sums of the pass is
+        // added by a thread of its own over the tr row lanes, in ascending order
+        __shared__ double park[8][kBlock];
 #pragma unroll
-        for (int j = 0; j < SLOT; ++j) reduce_one(j);
+        for (int pass = 0; pass < 2 * SLOT / 8; ++pass) {
+            if (tr > 1) __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int a = pass * 8 + q;
+                park[q][tid] = a < SLOT ? tot[a % SLOT] : kep[a % SLOT];
+            }
+            if (tr > 1) __syncthreads();
+            for (int o = tid; o < 8 * tg; o += kBlock) {
+                const int q = o / tg, x = o - q * tg;
+                double v = park[q][x];
+                for (int y = 1; y < tr; ++y) v += park[q][y * tg + x];
+                const int a = pass * 8 + q, which = a / SLOT, j = a % SLOT;
+                const int64_t so = (int64_t)blockIdx.x * tg + x;
+                if (so < nslots) partial[((int64_t)which * C + so * slot + j) * nbl + blockIdx.y] = v;
+            }
+        }
     } else {
         for (int j = 0; j < slot; ++j) reduce_one(j);
     }
@@ -450,10 +547,10 @@ void prune_dtype(const Plan& p, const void* dO, int64_t rows, int64_t C, int m, 
 
 // Bytes of partial sums channel_scales_launch writes for these arguments (rows > 0, C > 0, C % m == 0).
 size_t channel_scales_workspace(int64_t rows, int64_t C, int dt, int m) {
-    const Plan p = make_plan(rows, C, dt, m, true, kSumsMinRows);
+    const Plan p = make_plan(rows, C, dt, m, true, kSumsMinRows, sums_max_wgs(m));
     // the unaligned plan never has more partial rows than this bound: nb depends on tr = 256 / tg, and the
     // scalar plan's slots are no wider than the vector plan's, so take the larger of the two
-    const Plan q = make_plan(rows, C, dt, m, false, kSumsMinRows);
+    const Plan q = make_plan(rows, C, dt, m, false, kSumsMinRows, sums_max_wgs(m));
     const int nb = p.nb > q.nb ? p.nb : q.nb;
     return (size_t)nb * 2u * (size_t)C * sizeof(double);
 }
@@ -461,7 +558,7 @@ size_t channel_scales_workspace(int64_t rows, int64_t C, int dt, int m) {
 // Validated arguments in.  scale [C] floats, sums [2*C] doubles or NULL, partial = the workspace.
 int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, float* scale, double* sums,
                           void* partial, hipStream_t stream) {
-    const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO), kSumsMinRows);
+    const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO), kSumsMinRows, sums_max_wgs(m));
     double* part = static_cast<double*>(partial);
     if (dt == kBF16) sums_dtype<kBF16>(p, dO, rows, C, m, n, part, stream);
     else sums_dtype<kF32>(p, dO, rows, C, m, n, part, stream);
