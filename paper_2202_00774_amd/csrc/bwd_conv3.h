@@ -128,6 +128,11 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
     static_assert(WPW >= 1 && HPW >= 1 && WPW * NP == W_UNITS && HPW * NP == kC3UnitsPerStep, "copy units divide evenly");
     constexpr int kPer = WPW + HPW;                    // copies a producer wavefront issues per stage
     constexpr int CPR = BN / 8;                        // 16-byte chunks per W row
+    // Swizzle of the W slab: the 16-byte column of row r sits at column ^ (WSW * (r & 3)).  One pass of a transpose read
+    // takes rows r .. r+3 and four columns of each; with 64 banks of 4 bytes a row of 256 bytes or more starts at bank 0,
+    // so the four rows must land in four different quarters of the 256-byte bank window (WSW = 4); a 128-byte row
+    // alternates between the two halves of the window by itself and only needs its halves told apart (WSW = 2).
+    constexpr int WSW = BN >= 128 ? 4 : 2;
     constexpr int RPU = 1024 / L::kWRow;               // W rows per copy unit
 
     extern __shared__ __align__(16) unsigned char smem_generic[];
@@ -215,7 +220,7 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
         for (int i = 0; i < WPW; ++i) {
             const int uu = pw * WPW + i;
             const int row = uu * RPU + lane / CPR;
-            const int lchunk = (lane % CPR) ^ (2 * (row & 3));
+            const int lchunk = (lane % CPR) ^ (WSW * (row & 3));
             int col = n0 + lchunk * 8;
             if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
             w_lane_off[i] = (uint32_t)(row * w_row + col) * 2u;
@@ -361,7 +366,7 @@ __global__ void __launch_bounds__(conv3_threads(MODE)) bwd_conv3(const Conv3Para
         for (int u = 0; u < TN; ++u) {
             const int L16 = lane & 15;
             const int chunk = 8 * wn + 4 * u + 2 * ((lane >> 4) & 1) + ((L16 & 3) >> 1);
-            b_lane[u] = (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (2 * (L16 >> 2))) * 16) + (L16 & 1) * 8;
+            b_lane[u] = (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (WSW * (L16 >> 2))) * 16) + (L16 & 1) * 8;
         }
 
         __syncthreads();  // producers' halo table

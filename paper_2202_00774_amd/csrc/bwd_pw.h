@@ -99,6 +99,11 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     constexpr int KSTEP = SPARSE ? 32 : 16;
     constexpr int NKS = KC / KSTEP;
     constexpr int CPR = BN / 8;                 // 16-byte columns per W row
+    // Swizzle of the W slab: the 16-byte column of row r sits at column ^ (WSW * (r & 3)).  One pass of a transpose read
+    // takes rows r .. r+3 and four columns of each; with 64 banks of 4 bytes a row of 256 bytes or more starts at bank 0,
+    // so the four rows must land in four different quarters of the 256-byte bank window (WSW = 4); a 128-byte row
+    // alternates between the two halves of the window by itself and only needs its halves told apart (WSW = 2).
+    constexpr int WSW = BN >= 128 ? 4 : 2;
     constexpr int RPU = 1024 / L::kWRow > 0 ? 1024 / L::kWRow : 1;  // W rows per copy unit (BN <= 256: at least two)
     constexpr int WU = L::kWUnits;
     constexpr int AU = L::kAUnits;
@@ -156,14 +161,30 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         }
     };
     // W: unit u = rows u*RPU .. of the 32 x BN slab of a chunk, columns swizzled for the transpose reads
-    auto copy_w_unit = [&](int u, int st, uint32_t dst) {
+    auto w_src = [&](int u, int st) {
         const int t = tap_of(st), chunk = st - t * nchunks;
         const int row = u * RPU + lane / CPR;
-        const int lchunk = (lane % CPR) ^ (2 * (row & 3));
+        const int lchunk = (lane % CPR) ^ (WSW * (row & 3));
         int col = n0 + lchunk * 8;
         if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
         const int wtap = GATHER ? p.tap_w[t] : 0;
-        lds_copy16(gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(wtap * p.C_in + col) * 2u), dst);
+        return gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(wtap * p.C_in + col) * 2u);
+    };
+    auto copy_w_unit = [&](int u, int st, uint32_t dst) { lds_copy16(w_src(u, st), dst); };
+    // Dense: the W slab travels through registers (an ordinary 16-byte load per lane, stored to the same LDS position
+    // a direct copy would fill) while the gradient rows take the direct path, so the two halves of a chunk's bytes use
+    // two different ways into LDS.
+    constexpr bool WREG = MODE == 0;
+    constexpr int WPW = WU / NW;   // W units per wavefront and chunk
+    u32x4_t wreg[WPW];
+    auto fetch_w = [&](int st) {
+#pragma unroll
+        for (int j = 0; j < WPW; ++j) wreg[j] = *reinterpret_cast<const u32x4_t*>(w_src(wave + j * NW, st));
+    };
+    auto store_w = [&](int set) {
+#pragma unroll
+        for (int j = 0; j < WPW; ++j)
+            *(SDGP_LDS u32x4_t*)(smem + L::off_w() + set * L::kWSlab + (wave + j * NW) * 1024 + lane * 16) = wreg[j];
     };
     // MODE 3: the positions of 32 rows (8 bytes each, one 4-byte word per lane) of reduction step `st`
     auto copy_meta_unit = [&](int u, int st, uint32_t dst) {
@@ -324,6 +345,11 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         wait_lds_copies<0>();
         __syncthreads();
         prune_chunk(0, 0);
+    } else if constexpr (WREG) {
+        static_assert(SETS == 2, "one chunk ahead");
+        copy_chunk(0, 0, false);
+        fetch_w(0);
+        store_w(0);
     } else {
 #pragma unroll
         for (int i = 0; i < SETS - 1; ++i)
@@ -338,7 +364,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     for (int u = 0; u < TN; ++u) {
         const int L16 = lane & 15;
         const int chunk = 8 * wn + 4 * u + 2 * ((lane >> 4) & 1) + ((L16 & 3) >> 1);
-        b_lane[u] = (uint32_t)(L::off_w() + (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (2 * (L16 >> 2))) * 16) +
+        b_lane[u] = (uint32_t)(L::off_w() + (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (WSW * (L16 >> 2))) * 16) +
                                (L16 & 1) * 8);
     }
     const uint32_t half = (uint32_t)(lane >> 5);
@@ -420,7 +446,10 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
                 for (int i = wave; i < AU; i += NW) copy_a_unit(i, s + 2, a_dst + (uint32_t)i * 1024u);
             }
         } else {
-            if (s + SETS - 1 < nstages) copy_chunk(s + SETS - 1, set_req, true);
+            if (s + SETS - 1 < nstages) {
+                copy_chunk(s + SETS - 1, set_req, !WREG);
+                if constexpr (WREG) fetch_w(s + SETS - 1);
+            }
         }
         load_frags(fr[0], set, 0);
         if constexpr (PRUNES) {
@@ -438,8 +467,13 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         } else {
             // chunk s + 1 has to be there; the requests of the chunks after it (issued in order, the same number by
             // every wavefront) may stay in flight.  Near the end fewer are outstanding: drain.
-            if (s + SETS - 1 < nstages) wait_lds_copies<(SETS - 2) * kCopiesPerChunk>();
-            else wait_lds_copies<0>();
+            if constexpr (WREG) {
+                if (s + 1 < nstages) store_w(set_req);   // (its last readers passed the barrier that ended the previous stage)
+                wait_lds_copies<0>();
+            } else {
+                if (s + SETS - 1 < nstages) wait_lds_copies<(SETS - 2) * kCopiesPerChunk>();
+                else wait_lds_copies<0>();
+            }
             set = set + 1 == SETS ? 0 : set + 1;
             set_req = set_req + 1 == SETS ? 0 : set_req + 1;
         }

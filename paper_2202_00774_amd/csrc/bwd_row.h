@@ -111,6 +111,11 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     constexpr int NKS = KC / KSTEP;
     constexpr int NQ = TS * NKS;                // k-steps per stage
     constexpr int CPR = BN / 8;                 // 16-byte columns per W row
+    // Swizzle of the W slab: the 16-byte column of row r sits at column ^ (WSW * (r & 3)).  One pass of a transpose read
+    // takes rows r .. r+3 and four columns of each; with 64 banks of 4 bytes a row of 256 bytes or more starts at bank 0,
+    // so the four rows must land in four different quarters of the 256-byte bank window (WSW = 4); a 128-byte row
+    // alternates between the two halves of the window by itself and only needs its halves told apart (WSW = 2).
+    constexpr int WSW = BN >= 128 ? 4 : 2;
     constexpr int RPU = 1024 / L::kWRow;        // W rows per copy unit
     constexpr int WU = L::kWUnits;
 
@@ -229,7 +234,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     uint32_t w_voff;  // this lane's byte offset inside a slab's source: the wavefront copies unit (wave % WU) of a slab
     {
         const int row = (wave % WU) * RPU + lane / CPR;
-        const int lchunk = (lane % CPR) ^ (2 * (row & 3));
+        const int lchunk = (lane % CPR) ^ (WSW * (row & 3));
         int col = n0 + lchunk * 8;
         if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
         w_voff = (uint32_t)(row * p.w_row + col) * 2u;
@@ -383,7 +388,7 @@ __global__ void __launch_bounds__(512) bwd_row(const RowParams p) {
     for (int u = 0; u < TN; ++u) {
         const int L16 = lane & 15;
         const int chunk = 8 * wn + 4 * u + 2 * ((lane >> 4) & 1) + ((L16 & 3) >> 1);
-        b_lane[u] = (uint32_t)(L::off_w() + (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (2 * (L16 >> 2))) * 16) +
+        b_lane[u] = (uint32_t)(L::off_w() + (8 * (lane >> 5) + (L16 >> 2)) * L::kWRow + ((chunk ^ (WSW * (L16 >> 2))) * 16) +
                                (L16 & 1) * 8);
     }
     struct Frags {
