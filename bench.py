@@ -218,6 +218,32 @@ def main():
                                         share=dom["count"] * dom["t"]["2:4"] / tot["2:4"], launches=dom["count"])
     result["roofline_dense"] = roofline_entry(dom["layer"], dom["t"]["dense"], "dense", sparse=False)
 
+    # ---- what this GPU sustains with plain kernels (the published peaks are what `frac` divides by; these say how much
+    # of them any kernel can reach here)
+    nbig = 1 << 29
+    pa = torch.empty(nbig, dtype=torch.uint8, device=dev).random_(0, 255)
+    pb = torch.empty(nbig, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(16384, dtype=torch.uint8, device=dev)
+    t_copy = time_call(lambda: sdgp.sdgp_peak_probe(0, pa, pb, nbig), reps=10, warm=2)
+    t_read = time_call(lambda: sdgp.sdgp_peak_probe(1, pa, sink, nbig), reps=10, warm=2)
+    iters = 20000
+    t_dense = time_call(lambda: sdgp.sdgp_peak_probe(2, None, sink, iters=iters), reps=3, warm=1)
+    t_sparse = time_call(lambda: sdgp.sdgp_peak_probe(3, None, sink, iters=iters), reps=3, warm=1)
+    w_dense = sdgp.sdgp_peak_probe(2, None, sink, iters=1) * iters
+    w_sparse = sdgp.sdgp_peak_probe(3, None, sink, iters=1) * iters
+    del pa, pb
+    peaks = {"hbm_copy_GBs": round(2.0 * nbig / (t_copy * 1e-3) / 1e9, 1), "hbm_read_GBs": round(nbig / (t_read * 1e-3) / 1e9, 1),
+             "mfma_bf16_dense_TFLOPs": round(w_dense / (t_dense * 1e-3) / 1e12, 1),
+             "smfmac_bf16_dense_equivalent_TFLOPs": round(w_sparse / (t_sparse * 1e-3) / 1e12, 1),
+             "note": "sdgp_peak_probe: a 512 MB streaming copy (read + write counted) and read, and register-only loops of "
+                     "v_mfma_f32_32x32x16_bf16 / v_smfmac_f32_32x32x32_bf16 (two wavefronts per SIMD, eight independent "
+                     "accumulator tiles); the sparse figure counts 2*32*32*32 operations per instruction"}
+    result["achievable_peaks"] = peaks
+    for key in ("roofline", "roofline_dense"):
+        e = result[key]
+        e["frac_of_measured_peak"] = round(e["achieved"] / (peaks["mfma_bf16_dense_TFLOPs"] if e["bound"] == "mfma"
+                                                            else peaks["hbm_copy_GBs"]), 4)
+
     if args.no_extras:
         print(json.dumps(result))
         return

@@ -303,6 +303,22 @@ int sdgp_conv_bwd_weight(const void* D, const void* dO, float* dW, int64_t B, in
                          int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int dt,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Measurement aid: what the GPU sustains on the two resources the path is bound by (the benchmark reports its
+ * roofline fractions against the published peaks and, beside them, against these).  One launch on `hip_stream`; the
+ * caller times it.
+ *   kind 0  copies `bytes` (rounded down to 16) from a to b with a plain streaming kernel
+ *   kind 1  reads `bytes` of a; b receives one 4-byte word per workgroup (16 KB suffice)
+ *   kind 2  `iters` rounds of eight independent v_mfma_f32_32x32x16_bf16 per wavefront, two wavefronts per SIMD,
+ *           operands in registers; a is ignored, b is not written (it must be a valid device pointer)
+ *   kind 3  the same with v_smfmac_f32_32x32x32_bf16 (the structured-sparse instruction of the fused kernels)
+ * a, b: device pointers, 16-byte aligned for kinds 0 and 1, never overlapping.  *work (HOST pointer) receives the
+ * work of the launch: bytes moved (2 * bytes for the copy) or floating-point operations, dense-equivalent for kind 3
+ * (2 * 32 * 32 * 32 per instruction).  Errors: SDGP_ERR_NULL, SDGP_ERR_SHAPE (kind, alignment, iters outside
+ * 1 .. 2^20), SDGP_ERR_HIP.
+ */
+int sdgp_peak_probe(int kind, const void* a, void* b, size_t bytes, int iters, double* work, void* hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* sdgp_status_string(int status);
 

@@ -9,10 +9,10 @@ call raises.
 """
 from .binding import (BF16, F32, GREEDY, GREEDY_ADJUSTED, RANDOM, SdgpError, conv_bwd_data_workspace,
                       library_path, sdgp_channel_scales, sdgp_conv_bwd_data, sdgp_conv_bwd_data_channel_rescaled,
-                      sdgp_conv_bwd_data_compact, sdgp_conv_bwd_data_grouped, sdgp_conv_bwd_data_noalloc, sdgp_conv_bwd_weight, sdgp_conv_fwd, sdgp_linear_bwd_data, sdgp_linear_bwd_data_channel_rescaled, sdgp_prune,
+                      sdgp_conv_bwd_data_compact, sdgp_conv_bwd_data_grouped, sdgp_conv_bwd_data_noalloc, sdgp_conv_bwd_weight, sdgp_conv_fwd, sdgp_linear_bwd_data, sdgp_linear_bwd_data_channel_rescaled, sdgp_peak_probe, sdgp_prune,
                       sdgp_prune_channel_rescaled, sdgp_scale_filter, status_string, version)
 
 __all__ = ["BF16", "F32", "GREEDY", "GREEDY_ADJUSTED", "RANDOM", "SdgpError", "conv_bwd_data_workspace",
            "library_path", "sdgp_channel_scales", "sdgp_conv_bwd_data", "sdgp_conv_bwd_data_channel_rescaled",
-           "sdgp_conv_bwd_data_compact", "sdgp_conv_bwd_data_grouped", "sdgp_conv_bwd_data_noalloc", "sdgp_conv_bwd_weight", "sdgp_conv_fwd", "sdgp_linear_bwd_data", "sdgp_linear_bwd_data_channel_rescaled", "sdgp_prune",
+           "sdgp_conv_bwd_data_compact", "sdgp_conv_bwd_data_grouped", "sdgp_conv_bwd_data_noalloc", "sdgp_conv_bwd_weight", "sdgp_conv_fwd", "sdgp_linear_bwd_data", "sdgp_linear_bwd_data_channel_rescaled", "sdgp_peak_probe", "sdgp_prune",
            "sdgp_prune_channel_rescaled", "sdgp_scale_filter", "status_string", "version"]

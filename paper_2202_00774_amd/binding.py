@@ -27,7 +27,7 @@ EXPORTS = ("sdgp_prune", "sdgp_linear_bwd_data", "sdgp_conv_bwd_data", "sdgp_con
            "sdgp_conv_bwd_data_compact_workspace", "sdgp_conv_bwd_data_compact",
            "sdgp_conv_bwd_data_grouped_workspace", "sdgp_conv_bwd_data_grouped",
            "sdgp_conv_fwd_workspace", "sdgp_conv_fwd", "sdgp_conv_bwd_weight_workspace", "sdgp_conv_bwd_weight",
-           "sdgp_status_string", "sdgp_version")
+           "sdgp_peak_probe", "sdgp_status_string", "sdgp_version")
 
 
 class SdgpError(RuntimeError):
@@ -94,6 +94,8 @@ def load():
             lib.sdgp_conv_bwd_weight_workspace.argtypes = geom
             lib.sdgp_conv_bwd_weight.restype = i32
             lib.sdgp_conv_bwd_weight.argtypes = [vp, vp, vp] + geom + [vp, sz, vp]
+            lib.sdgp_peak_probe.restype = i32
+            lib.sdgp_peak_probe.argtypes = [i32, vp, vp, sz, i32, ctypes.POINTER(ctypes.c_double), vp]
             lib.sdgp_status_string.restype = ctypes.c_char_p
             lib.sdgp_status_string.argtypes = [i32]
             lib.sdgp_version.restype = i32
@@ -286,6 +288,20 @@ def sdgp_scale_filter(W: torch.Tensor, scale: torch.Tensor, out: torch.Tensor | 
     if rc != 0:
         raise SdgpError(rc, "sdgp_scale_filter")
     return out
+
+
+def sdgp_peak_probe(kind: int, a: torch.Tensor | None, b: torch.Tensor, nbytes: int = 0, iters: int = 1) -> float:
+    """One launch of a measurement kernel (0 copy a -> b, 1 read a, 2 dense / 3 structured-sparse matrix instructions);
+    returns the bytes or floating-point operations of the launch.  The caller times it."""
+    _dev(b, "b")
+    if a is not None:
+        _dev(a, "a")
+    work = ctypes.c_double(0.0)
+    rc = load().sdgp_peak_probe(int(kind), _ptr(a) if a is not None else None, _ptr(b), int(nbytes), int(iters),
+                                ctypes.byref(work), _stream(b))
+    if rc != 0:
+        raise SdgpError(rc, "sdgp_peak_probe")
+    return work.value
 
 
 def sdgp_conv_bwd_data_channel_rescaled(dO: torch.Tensor, W: torch.Tensor, H: int, Wd: int, stride: int, pad: int,

@@ -48,6 +48,7 @@ int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int d
 int scale_rows_launch(const void* W, const float* scale, void* out, int64_t C_out, int64_t inner, int dt, hipStream_t stream);
 int kprime_launch(const void* vals, const uint8_t* idx, const void* W, void* dD, int64_t B, int64_t H, int64_t Wd, int64_t C_in,
                   int64_t C_out, int R, int S, int stride, int pad, int n, int m, hipStream_t stream);
+int peak_probe_launch(int kind, const void* a, void* b, size_t bytes, int iters, double* work, hipStream_t stream);
 int mirror_transpose_filter_launch(const void* W, void* V, int64_t C_out, int64_t C_in, int R, int S, int dt, hipStream_t stream);
 int fwd_narrow_launch(const void* D, const void* W, void* O, int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                       int R, int S, int stride, int pad, int dt, hipStream_t stream);
@@ -491,6 +492,18 @@ int sdgp_conv_bwd_weight(const void* D, const void* dO, float* dW, int64_t B, in
         return SDGP_ERR_WORKSPACE;
     return sdgp::wgrad_launch(D, dO, dW, B, H, Wd, C_in, C_out, R, S, stride, pad, dt, (need > 0 && aligned) ? workspace : nullptr,
                               static_cast<hipStream_t>(hip_stream));
+}
+
+int sdgp_peak_probe(int kind, const void* a, void* b, size_t bytes, int iters, double* work, void* hip_stream) {
+    if (!work || !b) return SDGP_ERR_NULL;
+    if (kind < 0 || kind > 3) return SDGP_ERR_SHAPE;
+    if (kind <= 1) {
+        if (!a) return SDGP_ERR_NULL;
+        if (((uintptr_t)a | (uintptr_t)b) & 15u) return SDGP_ERR_SHAPE;
+    } else if (iters < 1 || iters > (1 << 20)) {
+        return SDGP_ERR_SHAPE;
+    }
+    return sdgp::peak_probe_launch(kind, a, b, bytes, iters, work, static_cast<hipStream_t>(hip_stream));
 }
 
 const char* sdgp_status_string(int status) {

@@ -247,3 +247,16 @@ def test_grouped_argument_errors(lib):
     assert call(4, ws=P, ws_bytes=need(4), dO=None) == E_NULL
     assert call(4, rk=7, ws=P, ws_bytes=need(4)) == E_RANKER
     assert call(4, dt=5) == E_DTYPE and call(4, n=5) == E_NM
+
+
+def test_peak_probe_argument_errors(lib):
+    lib.sdgp_peak_probe.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int,
+                                    ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    work = ctypes.c_double(0.0)
+    w = ctypes.byref(work)
+    assert lib.sdgp_peak_probe(0, P, P, 1024, 1, None, None) == E_NULL
+    assert lib.sdgp_peak_probe(0, None, P, 1024, 1, w, None) == E_NULL
+    assert lib.sdgp_peak_probe(2, None, None, 0, 1, w, None) == E_NULL
+    assert lib.sdgp_peak_probe(4, P, P, 1024, 1, w, None) == E_SHAPE and lib.sdgp_peak_probe(-1, P, P, 1024, 1, w, None) == E_SHAPE
+    assert lib.sdgp_peak_probe(1, ctypes.c_void_p(24), P, 1024, 1, w, None) == E_SHAPE       # not 16-byte aligned
+    assert lib.sdgp_peak_probe(3, None, P, 0, 0, w, None) == E_SHAPE and lib.sdgp_peak_probe(2, None, P, 0, (1 << 20) + 1, w, None) == E_SHAPE
