@@ -226,7 +226,7 @@ def main():
     sink = torch.zeros(16384, dtype=torch.uint8, device=dev)
     t_copy = time_call(lambda: sdgp.sdgp_peak_probe(0, pa, pb, nbig), reps=10, warm=2)
     t_read = time_call(lambda: sdgp.sdgp_peak_probe(1, pa, sink, nbig), reps=10, warm=2)
-    iters = 20000
+    iters = 2000
     t_dense = time_call(lambda: sdgp.sdgp_peak_probe(2, None, sink, iters=iters), reps=3, warm=1)
     t_sparse = time_call(lambda: sdgp.sdgp_peak_probe(3, None, sink, iters=iters), reps=3, warm=1)
     w_dense = sdgp.sdgp_peak_probe(2, None, sink, iters=1) * iters
