@@ -218,6 +218,10 @@ def main():
                                         share=dom["count"] * dom["t"]["2:4"] / tot["2:4"], launches=dom["count"])
     result["roofline_dense"] = roofline_entry(dom["layer"], dom["t"]["dense"], "dense", sparse=False)
 
+    if args.no_extras:
+        print(json.dumps(result))
+        return
+
     # ---- what this GPU sustains with plain kernels (the published peaks are what `frac` divides by; these say how much
     # of them any kernel can reach here)
     nbig = 1 << 29
@@ -226,7 +230,7 @@ def main():
     sink = torch.zeros(16384, dtype=torch.uint8, device=dev)
     t_copy = time_call(lambda: sdgp.sdgp_peak_probe(0, pa, pb, nbig), reps=10, warm=2)
     t_read = time_call(lambda: sdgp.sdgp_peak_probe(1, pa, sink, nbig), reps=10, warm=2)
-    iters = 2000
+    iters = 20000
     t_dense = time_call(lambda: sdgp.sdgp_peak_probe(2, None, sink, iters=iters), reps=3, warm=1)
     t_sparse = time_call(lambda: sdgp.sdgp_peak_probe(3, None, sink, iters=iters), reps=3, warm=1)
     w_dense = sdgp.sdgp_peak_probe(2, None, sink, iters=1) * iters
@@ -243,10 +247,6 @@ def main():
         e = result[key]
         e["frac_of_measured_peak"] = round(e["achieved"] / (peaks["mfma_bf16_dense_TFLOPs"] if e["bound"] == "mfma"
                                                             else peaks["hbm_copy_GBs"]), 4)
-
-    if args.no_extras:
-        print(json.dumps(result))
-        return
 
     result["resnet50_whole"] = {
         "layers": len(r50), "distinct_shapes": len(shapes), "gflop_dense": round(total_flops / 1e9, 1),
