@@ -224,6 +224,13 @@ prune_items(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, v
 // i of each 1 KB part) and the vectors change lanes through LDS on the way in and on the way out; slot c of a
 // wavefront's region holds vector c ^ ((c >> 4) & (V - 1)), V vectors per group, which keeps both the row-wise and
 // the group-wise accesses free of bank conflicts.
+// A wavefront's LDS writes before this point are visible to its own lanes' reads after it (the regions below belong to
+// one wavefront each, so no workgroup barrier is needed: the LDS serves a wavefront's instructions in order).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 template <int M, int RK, bool NLE2>
 __global__ void __launch_bounds__(kBlock)
 prune_items_wide(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t mix, void* __restrict__ pruned_) {
@@ -248,7 +255,7 @@ prune_items_wide(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t m
         const int c = k * 64 + lane;
         region[c ^ ((c >> 4) & (V - 1))] = in[k];
     }
-    __syncthreads();
+    wave_lds_sync();
     uint32_t w[M / 2];
 #pragma unroll
     for (int p = 0; p < V; ++p) {
@@ -269,13 +276,13 @@ prune_items_wide(const void* __restrict__ dO_, int64_t nitems, int n, uint32_t m
 #pragma unroll
         for (int i = 0; i < M / 2; ++i) o[i] = out[2 * i] | (out[2 * i + 1] << 16);
     }
-    __syncthreads();   // every lane has read its group
+    wave_lds_sync();   // every lane has read its group
 #pragma unroll
     for (int p = 0; p < V; ++p) {
         const int c = V * lane + p;
         region[c ^ ((c >> 4) & (V - 1))] = u32x4{o[4 * p], o[4 * p + 1], o[4 * p + 2], o[4 * p + 3]};
     }
-    __syncthreads();
+    wave_lds_sync();
     u32x4* dst = reinterpret_cast<u32x4*>(pruned_);
 #pragma unroll
     for (int k = 0; k < V; ++k) {

@@ -28,7 +28,6 @@ def test_read_and_matrix_probes_report_their_work():
     assert sdgp.sdgp_peak_probe(2, None, sink, iters=3) == waves * 3 * 8 * 2.0 * 32 * 32 * 16
     assert sdgp.sdgp_peak_probe(3, None, sink, iters=3) == waves * 3 * 8 * 2.0 * 32 * 32 * 32
     torch.cuda.synchronize()
-    assert torch.all(sink[:4] == 0) or True   # (the matrix probes write nothing; the read probe wrote its words)
 
 
 def test_matrix_probe_rate_is_below_the_published_peak():
