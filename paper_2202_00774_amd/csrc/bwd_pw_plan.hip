@@ -70,9 +70,9 @@ int launch_pw_classes_any(const PwClasses& all, int ncls, int mode, int m, int s
 // and stores overlap the other's arithmetic.  Pruning: all of C_in (up to 256 columns) in one workgroup, so every
 // gradient row is ranked once per 256 columns; dense: 128 x 128 tiles measured fastest (column tiles of one row tile
 // run side by side on one XCD and find the gradient rows in its L2).
-int pw_shape(int mode, int64_t C_in) {
+int pw_shape(int mode, int64_t C_in, int64_t C_out) {
     if (C_in <= 64) return 3;   // 128 x 64: 256-row tiles measured the same or slower (fewer workgroups, a longer last round)
-    if (mode != 0 && C_in > 128) return 0;
+    if (mode != 0 && C_in > 128 && C_out > 64) return 0;   // (64 channels to rank: ranking them per 128 columns costs less than the third workgroup per CU gains)
     return 1;
 }
 // Tile shape when the gradient arrives compressed (nothing is ranked in the kernel): the dense kernel's.
@@ -112,7 +112,7 @@ int pw_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R
     p.stride = stride, p.P = (int)P, p.Q = (int)Q, p.H = (int)H, p.Wd = (int)Wd;
     p.rows_dO = rows, p.gather = 0, p.ntaps = 1, p.w_taps = 1;
 
-    int shape = pw_shape(mode, C_in);
+    int shape = pw_shape(mode, C_in, C_out);
     const int fused_tiles_n = (int)((C_in + kPwShapes[shape].bn - 1) / kPwShapes[shape].bn);
     out.pre = pre_pays(mode, C_out, rows, fused_tiles_n, rk);
     if (out.pre) shape = pw_pre_shape(C_in);
@@ -144,7 +144,7 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
     if (pw_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, plan) != 0) return 1;
     if (plan.pre && (workspace == nullptr || workspace_bytes < plan.bytes || !is_aligned16(workspace))) {
         // no room for the compressed gradient: the fused kernel
-        const int shape = pw_shape(plan.mode, C_in);
+        const int shape = pw_shape(plan.mode, C_in, C_out);
         const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
         const int64_t blocks = ((plan.p.rows + rows_per - 1) / rows_per) * ((C_in + bn - 1) / bn);
         if (blocks < 64 || blocks >= INT_MAX) return 1;
@@ -203,7 +203,7 @@ int gather_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, i
 
     // every tap of every class ranks the rows it reads: R * S times per gradient element and column tile
     out.pre = want_pre && pre_pays(mode, C_out, base.rows_dO, R * S, kRandom);
-    const int shape = out.pre ? pw_pre_shape(C_in) : pw_shape(mode, C_in);
+    const int shape = out.pre ? pw_pre_shape(C_in) : pw_shape(mode, C_in, C_out);
     const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
     base.ntiles_n = (int)((C_in + bn - 1) / bn);
 
