@@ -416,6 +416,8 @@ def main():
     prune = {name: rate(time_call(prune_call(2, 4, rk), reps=20, warm=3), 4.0) for name, rk in rankers}
     for n_, m_ in ((2, 8), (2, 16), (4, 16), (8, 16), (2, 32), (4, 32), (8, 32), (16, 32)):
         prune["greedy_%d:%d" % (n_, m_)] = rate(time_call(prune_call(n_, m_, sdgp.GREEDY), reps=10, warm=2), 4.0)
+    for n_, m_ in ((4, 16), (4, 32), (16, 32)):
+        prune["random_%d:%d" % (n_, m_)] = rate(time_call(prune_call(n_, m_, sdgp.RANDOM), reps=10, warm=2), 4.0)
     vals = torch.empty(nelem // 2, dtype=torch.bfloat16, device=dev)
     idx = torch.empty(nelem // 2, dtype=torch.uint8, device=dev)
     # compact output (values + uint8 positions, no dense-shaped copy): 2 + 3 n/m bytes per element

@@ -25,7 +25,7 @@ __device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
 // Pairwise rank count: rank[j] = number of elements that beat j, where a lower
 // position wins ties.  keep[j] = rank[j] < n.  Exact for any keys and any n.
 template <int M>
-__device__ __forceinline__ void select_by_rank(const uint32_t (&key)[M], int n, bool (&keep)[M]) {
+__host__ __device__ __forceinline__ void select_by_rank(const uint32_t (&key)[M], int n, bool (&keep)[M]) {
     int rank[M];
 #pragma unroll
     for (int j = 0; j < M; ++j) rank[j] = j;  // every lower position beats j unless j's key is strictly larger
@@ -70,6 +70,49 @@ __device__ __forceinline__ void select_by_sort(const uint32_t (&key)[M], int n, 
     uint32_t thr = s[0];
 #pragma unroll
     for (int i = 1; i < M; ++i) thr = (i == n - 1) ? s[i] : thr;  // n is wavefront-uniform: scalar selects
+#pragma unroll
+    for (int j = 0; j < M; ++j) keep[j] = key[j] >= thr;
+}
+
+// Any n, keys that rarely repeat (hash keys of a group too wide for a position code): the sorting network again.  With
+// s the keys in descending order, the kept set is {key >= s[n-1]} unless the key after the threshold equals it -- only
+// then does position decide between equal keys, and the exact rank count takes over (about one group of 32 in a
+// million for 28-bit hash keys).
+template <int M>
+__host__ __device__ __forceinline__ void select_by_sort_ties(const uint32_t (&key)[M], int n, bool (&keep)[M]) {
+    static_assert((M & (M - 1)) == 0 && M >= 2, "power of two");
+    uint32_t s[M];
+#pragma unroll
+    for (int j = 0; j < M; ++j) s[j] = key[j];
+#pragma unroll
+    for (int k = 2; k <= M; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+            for (int i = 0; i < M; ++i) {
+                const int l = i ^ j;
+                if (l > i) {
+                    const uint32_t a = s[i], b = s[l];
+                    const uint32_t hi = a > b ? a : b, lo = a > b ? b : a;
+                    const bool desc = (i & k) == 0;  // descending runs first: s[0] ends up the largest
+                    s[i] = desc ? hi : lo;
+                    s[l] = desc ? lo : hi;
+                }
+            }
+        }
+    }
+    uint32_t thr = s[0], next = 0;
+    bool has_next = false;
+#pragma unroll
+    for (int i = 1; i < M; ++i) {   // n is wavefront-uniform: scalar selects
+        thr = (i == n - 1) ? s[i] : thr;
+        next = (i == n) ? s[i] : next;
+        has_next = has_next || i == n;
+    }
+    if (has_next && next == thr) {
+        select_by_rank<M>(key, n, keep);
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < M; ++j) keep[j] = key[j] >= thr;
 }
@@ -164,6 +207,8 @@ __device__ __forceinline__ void prune_group(const uint32_t (&raw)[M], int n, uin
     } else if constexpr (NLE2 && M >= 16) {
         // (for eight keys the 28 comparisons of the rank count measured faster than the multiset and its fallback)
         select_top2_ties<M>(key, n, keep);
+    } else if constexpr (RK == kRandom && M == 32) {
+        select_by_sort_ties<M>(key, n, keep);
     } else {
         select_by_rank<M>(key, n, keep);
     }

@@ -5,6 +5,7 @@
 //   * prune_compress16_random against a rank count by (H(seed, e), -position) with H written out from its definition
 //     (28-bit keys: the kernel's word "key | position code" must order exactly like the pair).
 //   * keep_mask_packed (Magnitude on 16 or 32 channels, any n, packed 16-bit arithmetic) against the same rank count.
+//   * select_by_sort_ties (the random ranker's selection in groups of 32) against the rank count, ties included.
 // Prints one line per configuration and returns the number of mismatches.  Test infrastructure, not product code.
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -206,8 +207,41 @@ static int run_packed(int iters, unsigned seed) {
     printf("M=%d packed keep mask: %d mismatches\n", M, bad);
     return bad;
 }
+// select_by_sort_ties (any n on keys that may repeat) against the rank count, on keys drawn from alphabets small enough
+// that the threshold key is shared often and from the full 28-bit range where it almost never is
+template <int M>
+static int run_sort_ties(int iters, unsigned seed) {
+    int bad = 0;
+    srand(seed);
+    for (int it = 0; it < iters; ++it) {
+        uint32_t key[M];
+        const int kind = it % 4;
+        for (int i = 0; i < M; ++i) {
+            const uint32_t r = ((uint32_t)rand() << 16) ^ (uint32_t)rand();
+            key[i] = kind == 0 ? (r & 0xFFFFFFF0u) : kind == 1 ? ((r % 5) << 4) : kind == 2 ? ((r % 40) << 4) : (i % 3 == 0 ? 0x100u : (r & 0xFFFFFFF0u));
+        }
+        for (int n = 1; n <= M; n += (n < 5 ? 1 : 3)) {
+            bool got[M], want[M];
+            select_by_sort_ties<M>(key, n, got);
+            int kept = 0;
+            for (int j = 0; j < M; ++j) {
+                int rank = 0;
+                for (int i = 0; i < M; ++i)
+                    if (key[i] > key[j] || (key[i] == key[j] && i < j)) ++rank;
+                want[j] = rank < n;
+                kept += got[j] ? 1 : 0;
+            }
+            bool ok = kept == n;
+            for (int j = 0; j < M; ++j) ok = ok && got[j] == want[j];
+            if (!ok && bad++ < 5) printf("MISMATCH sort with ties M=%d n=%d kind=%d\n", M, n, kind);
+        }
+    }
+    printf("M=%d sort with ties: %d mismatches\n", M, bad);
+    return bad;
+}
 int main() {
     int bad = 0;
+    bad += run_sort_ties<32>(40000, 9); bad += run_sort_ties<8>(40000, 10);
     bad += run_mag<4, kGreedy>(100000, 1); bad += run_mag<8, kGreedy>(100000, 2); bad += run_mag<16, kGreedy>(100000, 3);
     bad += run_mag<4, kAdjusted>(100000, 4); bad += run_mag<8, kAdjusted>(100000, 5); bad += run_mag<16, kAdjusted>(100000, 6);
     bad += run_rand<4>(200000, 1); bad += run_rand<8>(200000, 2); bad += run_rand<16>(200000, 3);
