@@ -248,3 +248,18 @@ def test_resnet9_layer_at_full_size():
     idx = torch.from_numpy(pixels).cuda()
     sample = wl.to_f64(to_host(out.view(-1, layer.C_in)[idx]))
     assert rel_error(sample, ref, absum) <= 1e-2
+
+
+def test_bench_tensor_at_full_size():
+    """The tensor bench.py times the sweep on ([3211264, 64] bf16, 411 MB, 2:4): sums, factors and the pruned tensor."""
+    rows, C = 256 * 112 * 112, 64
+    dO = wl.laplace_with_zeros((rows, C), 1e-3, 0.3, seed=9000, dtype=oracle.BF16)
+    ref_pruned, ref_scale, ref_total, ref_kept = oracle.prune_channel_rescaled(dO, 2, 4)
+    d = to_gpu(dO)
+    scale, sums = sdgp.sdgp_channel_scales(d, 2, 4, sums=True)
+    sums = sums.cpu().numpy()
+    assert np.all(np.abs(sums[0] - ref_total) <= 1e-12 * ref_total)
+    assert np.all(np.abs(sums[1] - ref_kept) <= 1e-12 * ref_kept)
+    assert ulp_distance_f32(scale.cpu().numpy(), ref_scale).max() <= 1
+    got = sdgp.sdgp_prune_channel_rescaled(d, 2, 4, scale=torch.from_numpy(ref_scale).cuda())
+    assert torch.equal(got.view(torch.int16).cpu(), torch.from_numpy(ref_pruned.view(np.int16)).view(got.shape))
