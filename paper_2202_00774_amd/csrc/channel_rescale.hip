@@ -479,6 +479,54 @@ prune_scaled(const void* __restrict__ dO_, int64_t rows, int64_t C, int m, int n
     }
 }
 
+// bf16 groups of 4 or 8: the same pruned tensor from the prune pass's shape -- a thread takes four 16-byte vectors a
+// workgroup apart, all of them requested before the first is ranked, and reads the eight factors of a vector's
+// channels from the (cached) factor array.  vpr = vectors per row; step = kBlock % vpr.
+template <int M, bool NLE2>
+__global__ void __launch_bounds__(kBlock)
+prune_scaled_flat(const u32x4* __restrict__ src, uint32_t nvec, uint32_t vpr, uint32_t step, int n,
+                  const float* __restrict__ scale, u32x4* __restrict__ dst) {
+    constexpr int K = 4;
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const uint32_t v0 = blockIdx.x * (uint32_t)(kBlock * K) + threadIdx.x;
+    u32x4 in[K];
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+        const uint32_t i = v0 + (uint32_t)u * kBlock;
+        if (i < nvec) in[u] = __builtin_nontemporal_load(src + i);
+    }
+    uint32_t col = v0 % vpr;   // this vector's place in its row; the next one is `step` further, modulo vpr
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+        const uint32_t i = v0 + (uint32_t)u * kBlock;
+        if (i >= nvec) break;
+        const f32x4* f = reinterpret_cast<const f32x4*>(scale + (size_t)col * 8);
+        const f32x4 f0 = f[0], f1 = f[1];
+        const float sc[8] = {f0[0], f0[1], f0[2], f0[3], f1[0], f1[1], f1[2], f1[3]};
+        const uint32_t w[4] = {in[u].x, in[u].y, in[u].z, in[u].w};
+        uint32_t raw[8], out[8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) raw[2 * k] = w[k] & 0xFFFFu, raw[2 * k + 1] = w[k] >> 16;
+#pragma unroll
+        for (int g = 0; g < 8 / M; ++g) {
+            uint32_t gr[M];
+            bool keep[M];
+#pragma unroll
+            for (int j = 0; j < M; ++j) gr[j] = raw[g * M + j];
+            magnitude_keep<kBF16, M, NLE2>(gr, M, n, keep);
+#pragma unroll
+            for (int j = 0; j < M; ++j) {
+                const float y = __fmul_rn(bf16_to_float(gr[j]), sc[g * M + j]);
+                out[g * M + j] = keep[j] ? float_to_bf16(y) : 0u;
+            }
+        }
+        const u32x4 pk = {out[0] | (out[1] << 16), out[2] | (out[3] << 16), out[4] | (out[5] << 16), out[6] | (out[7] << 16)};
+        __builtin_nontemporal_store(pk, dst + i);
+        col += step;
+        col = col >= vpr ? col - vpr : col;
+    }
+}
+
 // ------------------------------------------------------------ filter rows * s
 
 // W [C_out, inner] -> W' [C_out, inner], row k multiplied by scale[k] in fp32 and rounded to the storage type.
@@ -570,6 +618,19 @@ int channel_scales_launch(const void* dO, int64_t rows, int64_t C, int dt, int n
 int prune_channel_rescaled_launch(const void* dO, int64_t rows, int64_t C, int dt, int n, int m, const float* scale,
                                   void* pruned, hipStream_t stream) {
     const Plan p = make_plan(rows, C, dt, m, is_aligned16(dO) && is_aligned16(pruned), kPruneMinRows);
+    const int64_t nvec = rows * (C / 8);
+    if (dt == kBF16 && p.vec && (m == 4 || m == 8) && nvec < ((int64_t)1 << 31) && is_aligned16(scale)) {
+        const uint32_t vpr = (uint32_t)(C / 8);
+        const dim3 grid((unsigned)((nvec + kBlock * 4 - 1) / (kBlock * 4))), block(kBlock);
+        const u32x4* src = static_cast<const u32x4*>(dO);
+        u32x4* dst = static_cast<u32x4*>(pruned);
+#define SDGP_FLAT(M_, NLE2_) \
+    hipLaunchKernelGGL((prune_scaled_flat<M_, NLE2_>), grid, block, 0, stream, src, (uint32_t)nvec, vpr, (uint32_t)kBlock % vpr, n, scale, dst)
+        if (m == 4) { if (n <= 2) SDGP_FLAT(4, true); else SDGP_FLAT(4, false); }
+        else { if (n <= 2) SDGP_FLAT(8, true); else SDGP_FLAT(8, false); }
+#undef SDGP_FLAT
+        return launch_status();
+    }
     if (dt == kBF16) prune_dtype<kBF16>(p, dO, rows, C, m, n, scale, pruned, stream);
     else prune_dtype<kF32>(p, dO, rows, C, m, n, scale, pruned, stream);
     return launch_status();
