@@ -171,6 +171,33 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         return gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(wtap * p.C_in + col) * 2u);
     };
     auto copy_w_unit = [&](int u, int st, uint32_t dst) { lds_copy16(w_src(u, st), dst); };
+    // The units a wavefront copies are wave, wave + NW, ...: without a row table their addresses are a per-lane base
+    // (computed once) plus a wave-uniform step per reduction step, so a copy costs one 64-bit addition.  The W units of
+    // one wavefront are NW * RPU rows apart, a multiple of four, so they share the lane's swizzled column.
+    constexpr int APW = AU / NW;   // gradient units per wavefront and chunk
+    const unsigned char* a_base[APW];
+    const unsigned char* w_base = nullptr;
+    const size_t w_unit_step = (size_t)(NW * RPU) * wrowB, w_chunk_step = (size_t)KC * wrowB;
+    static_assert((NW * RPU) % 4 == 0, "the units of a wavefront share the swizzle");
+    if constexpr (!GATHER) {
+#pragma unroll
+        for (int j = 0; j < APW; ++j) {
+            long long row = m0 + (wave + j * NW) * 16 + (lane >> 2);
+            if (row > last_row) row = last_row;
+            a_base[j] = gdO + ((size_t)row * rowB + c16_a);
+        }
+        w_base = w_src(wave, 0);
+    }
+    // unit wave + j * NW of reduction step `st` into the buffer that starts at `dst`
+    auto copy_a_j = [&](int j, int st, uint32_t dst) {
+        const int u = wave + j * NW;
+        if constexpr (!GATHER) lds_copy16(a_base[j] + (size_t)st * 64u, dst + (uint32_t)u * 1024u);
+        else copy_a_unit(u, st, dst + (uint32_t)u * 1024u);
+    };
+    auto w_src_j = [&](int j, int st) {
+        if constexpr (!GATHER) return w_base + ((size_t)j * w_unit_step + (size_t)st * w_chunk_step);
+        else return w_src(wave + j * NW, st);
+    };
     // Dense: the W slab travels through registers (an ordinary 16-byte load per lane, stored to the same LDS position
     // a direct copy would fill) while the gradient rows take the direct path, so the two halves of a chunk's bytes use
     // two different ways into LDS.
@@ -179,7 +206,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     u32x4_t wreg[WPW];
     auto fetch_w = [&](int st) {
 #pragma unroll
-        for (int j = 0; j < WPW; ++j) wreg[j] = *reinterpret_cast<const u32x4_t*>(w_src(wave + j * NW, st));
+        for (int j = 0; j < WPW; ++j) wreg[j] = *reinterpret_cast<const u32x4_t*>(w_src_j(j, st));
     };
     auto store_w = [&](int set) {
 #pragma unroll
@@ -209,14 +236,20 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     // everything chunk `chunk` needs, into buffer set `set` (pruning: the gradient goes to raw slot `set`)
     auto copy_chunk = [&](int chunk, int set, bool with_w) {
         const uint32_t a_dst = smem_base + (PRUNES ? L::off_raw() + set * L::kRawBytes : L::off_a() + set * L::kABytes);
-        for (int i = wave; i < AU; i += NW) copy_a_unit(i, chunk, a_dst + (uint32_t)i * 1024u);
+#pragma unroll
+        for (int j = 0; j < APW; ++j) copy_a_j(j, chunk, a_dst);
         if constexpr (PRE)
             for (int i = wave; i < ROWS / 32; i += NW) copy_meta_unit(i, chunk, smem_base + L::off_meta() + set * L::kMetaBytes + (uint32_t)i * 256u);
-        if (with_w)
-            for (int i = wave; i < WU; i += NW) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
+        if (with_w) {
+#pragma unroll
+            for (int j = 0; j < WPW; ++j)
+                lds_copy16(w_src_j(j, chunk), smem_base + L::off_w() + set * L::kWSlab + (uint32_t)(wave + j * NW) * 1024u);
+        }
     };
     auto copy_w_chunk = [&](int chunk, int set) {
-        for (int i = wave; i < WU; i += NW) copy_w_unit(i, chunk, smem_base + L::off_w() + set * L::kWSlab + (uint32_t)i * 1024u);
+#pragma unroll
+        for (int j = 0; j < WPW; ++j)
+            lds_copy16(w_src_j(j, chunk), smem_base + L::off_w() + set * L::kWSlab + (uint32_t)(wave + j * NW) * 1024u);
     };
 
     // rank / prune / compress raw slot `set` (chunk `chunk`) into gradient buffer `set`: ROWS * 2 items of 16 channels
@@ -443,7 +476,8 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
             if (s + 1 < nstages) copy_w_chunk(s + 1, set ^ 1);
             if (s + 2 < nstages) {
                 const uint32_t a_dst = smem_base + L::off_raw() + set * L::kRawBytes;
-                for (int i = wave; i < AU; i += NW) copy_a_unit(i, s + 2, a_dst + (uint32_t)i * 1024u);
+#pragma unroll
+                for (int j = 0; j < APW; ++j) copy_a_j(j, s + 2, a_dst);
             }
         } else {
             if (s + SETS - 1 < nstages) {
