@@ -233,13 +233,33 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
             lds_copy4(a, dst);
         }
     };
+    // (the same for the position words: unit wave + j * NW covers 32 rows, a step is one chunk's array of all rows)
+    constexpr int MPW = (ROWS / 32 + NW - 1) / NW;
+    const unsigned char* m_base[MPW];
+    const size_t m_chunk_step = (size_t)p.rows_dO * 8u;
+    if constexpr (PRE && !GATHER) {
+#pragma unroll
+        for (int j = 0; j < MPW; ++j) {
+            long long row = m0 + (wave + j * NW) * 32 + (lane >> 1);
+            if (row > last_row) row = last_row;
+            m_base[j] = p.meta + ((size_t)row * 8u + (uint32_t)(lane & 1) * 4u);
+        }
+    }
     // everything chunk `chunk` needs, into buffer set `set` (pruning: the gradient goes to raw slot `set`)
     auto copy_chunk = [&](int chunk, int set, bool with_w) {
         const uint32_t a_dst = smem_base + (PRUNES ? L::off_raw() + set * L::kRawBytes : L::off_a() + set * L::kABytes);
 #pragma unroll
         for (int j = 0; j < APW; ++j) copy_a_j(j, chunk, a_dst);
-        if constexpr (PRE)
-            for (int i = wave; i < ROWS / 32; i += NW) copy_meta_unit(i, chunk, smem_base + L::off_meta() + set * L::kMetaBytes + (uint32_t)i * 256u);
+        if constexpr (PRE) {
+            static_assert((ROWS / 32) % NW == 0, "every wavefront copies the same number of position units");
+#pragma unroll
+            for (int j = 0; j < MPW; ++j) {
+                const int i = wave + j * NW;
+                const uint32_t dst = smem_base + L::off_meta() + set * L::kMetaBytes + (uint32_t)i * 256u;
+                if constexpr (!GATHER) lds_copy4(m_base[j] + (size_t)chunk * m_chunk_step, dst);
+                else copy_meta_unit(i, chunk, dst);
+            }
+        }
         if (with_w) {
 #pragma unroll
             for (int j = 0; j < WPW; ++j)
