@@ -175,6 +175,10 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     // (computed once) plus a wave-uniform step per reduction step, so a copy costs one 64-bit addition.  The W units of
     // one wavefront are NW * RPU rows apart, a multiple of four, so they share the lane's swizzled column.
     constexpr int APW = AU / NW;   // gradient units per wavefront and chunk
+    constexpr int MPW = (ROWS / 32 + NW - 1) / NW;   // units of position words (32 rows each)
+    // With a row table: the gradient pixel each of this lane's rows reads for tap t, or -1 where the tap falls outside
+    // the gradient (filled once the table is built) -- a copy then needs no table read.
+    int a_src[APW][4], m_src[PRE ? MPW : 1][4];
     const unsigned char* a_base[APW];
     const unsigned char* w_base = nullptr;
     const size_t w_unit_step = (size_t)(NW * RPU) * wrowB, w_chunk_step = (size_t)KC * wrowB;
@@ -191,8 +195,15 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     // unit wave + j * NW of reduction step `st` into the buffer that starts at `dst`
     auto copy_a_j = [&](int j, int st, uint32_t dst) {
         const int u = wave + j * NW;
-        if constexpr (!GATHER) lds_copy16(a_base[j] + (size_t)st * 64u, dst + (uint32_t)u * 1024u);
-        else copy_a_unit(u, st, dst + (uint32_t)u * 1024u);
+        if constexpr (!GATHER) {
+            lds_copy16(a_base[j] + (size_t)st * 64u, dst + (uint32_t)u * 1024u);
+        } else {
+            const int t = tap_of(st), chunk = st - t * nchunks;
+            const int src = t == 0 ? a_src[j][0] : t == 1 ? a_src[j][1] : t == 2 ? a_src[j][2] : a_src[j][3];
+            const unsigned char* a = src >= 0 ? gdO + ((size_t)src * rowB + (size_t)chunk * 64u + c16_a)
+                                              : reinterpret_cast<const unsigned char*>(kPwZeros) + c16_a;
+            lds_copy16(a, dst + (uint32_t)u * 1024u);
+        }
     };
     auto w_src_j = [&](int j, int st) {
         if constexpr (!GATHER) return w_base + ((size_t)j * w_unit_step + (size_t)st * w_chunk_step);
@@ -234,7 +245,6 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         }
     };
     // (the same for the position words: unit wave + j * NW covers 32 rows, a step is one chunk's array of all rows)
-    constexpr int MPW = (ROWS / 32 + NW - 1) / NW;
     const unsigned char* m_base[MPW];
     const size_t m_chunk_step = (size_t)p.rows_dO * 8u;
     if constexpr (PRE && !GATHER) {
@@ -256,8 +266,16 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
             for (int j = 0; j < MPW; ++j) {
                 const int i = wave + j * NW;
                 const uint32_t dst = smem_base + L::off_meta() + set * L::kMetaBytes + (uint32_t)i * 256u;
-                if constexpr (!GATHER) lds_copy4(m_base[j] + (size_t)chunk * m_chunk_step, dst);
-                else copy_meta_unit(i, chunk, dst);
+                if constexpr (!GATHER) {
+                    lds_copy4(m_base[j] + (size_t)chunk * m_chunk_step, dst);
+                } else {
+                    const int t = tap_of(chunk), ch = chunk - t * nchunks;   // (`chunk` is the reduction step here)
+                    const int src = t == 0 ? m_src[j][0] : t == 1 ? m_src[j][1] : t == 2 ? m_src[j][2] : m_src[j][3];
+                    const uint32_t word = (uint32_t)(lane & 1) * 4u;
+                    const unsigned char* a = src >= 0 ? p.meta + (((size_t)ch * (size_t)p.rows_dO + (size_t)src) * 8u + word)
+                                                      : reinterpret_cast<const unsigned char*>(kPwZeros) + word;
+                    lds_copy4(a, dst);
+                }
             }
         }
         if (with_w) {
@@ -388,6 +406,24 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
             rowtab[3 * m] = base, rowtab[3 * m + 1] = ij, rowtab[3 * m + 2] = opix;
         }
         __syncthreads();
+        auto tap_source = [&](int rl, int t) {
+            const int base = rowtab[3 * rl], ij = rowtab[3 * rl + 1];
+            const int i = (ij & 0xFFFF) + p.tap_dp[t], j = (ij >> 16) + p.tap_dq[t];
+            const bool ok = t < p.ntaps && base >= 0 && i >= 0 && i < p.P && j >= 0 && j < p.Q;
+            long long src = (long long)base + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
+            src = src < 0 ? 0 : (src > last_pix ? last_pix : src);  // (a valid tap is inside anyway)
+            return ok ? (int)src : -1;
+        };
+#pragma unroll
+        for (int j = 0; j < APW; ++j)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) a_src[j][t] = tap_source((wave + j * NW) * 16 + (lane >> 2), t);
+        if constexpr (PRE) {
+#pragma unroll
+            for (int j = 0; j < MPW; ++j)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) m_src[j][t] = tap_source((wave + j * NW) * 32 + (lane >> 1), t);
+        }
     }
     constexpr int SETS = L::kSets;
     static_assert(AU % NW == 0 && WU % NW == 0, "every wavefront issues the same number of copies per chunk");
