@@ -141,25 +141,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     // (lane >> 2) holds the swizzled source column.  Rows past the tensor re-read the last row (never stored).
     const uint32_t c16_a = PRUNES ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
                                   : (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
-    // `st` is the reduction step: tap st / nchunks, chunk st % nchunks
-    auto copy_a_unit = [&](int u, int st, uint32_t dst) {
-        if constexpr (!GATHER) {
-            long long row = m0 + u * 16 + (lane >> 2);
-            if (row > last_row) row = last_row;
-            lds_copy16(gdO + ((size_t)row * rowB + (size_t)st * 64u + c16_a), dst);
-        } else {
-            const int t = tap_of(st), chunk = st - t * nchunks;
-            const int rl = u * 16 + (lane >> 2);
-            const int base = rowtab[3 * rl], ij = rowtab[3 * rl + 1];
-            const int i = (ij & 0xFFFF) + p.tap_dp[t], j = (ij >> 16) + p.tap_dq[t];
-            const bool ok = base >= 0 && i >= 0 && i < p.P && j >= 0 && j < p.Q;
-            long long src = (long long)base + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
-            src = src < 0 ? 0 : (src > last_pix ? last_pix : src);  // (a valid tap is inside anyway)
-            const unsigned char* a = ok ? gdO + ((size_t)src * rowB + (size_t)chunk * 64u + c16_a)
-                                        : reinterpret_cast<const unsigned char*>(kPwZeros) + c16_a;
-            lds_copy16(a, dst);
-        }
-    };
+    // `st` below is the reduction step: tap st / nchunks, chunk st % nchunks
     // W: unit u = rows u*RPU .. of the 32 x BN slab of a chunk, columns swizzled for the transpose reads
     auto w_src = [&](int u, int st) {
         const int t = tap_of(st), chunk = st - t * nchunks;
@@ -170,7 +152,6 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         const int wtap = GATHER ? p.tap_w[t] : 0;
         return gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(wtap * p.C_in + col) * 2u);
     };
-    auto copy_w_unit = [&](int u, int st, uint32_t dst) { lds_copy16(w_src(u, st), dst); };
     // The units a wavefront copies are wave, wave + NW, ...: without a row table their addresses are a per-lane base
     // (computed once) plus a wave-uniform step per reduction step, so a copy costs one 64-bit addition.  The W units of
     // one wavefront are NW * RPU rows apart, a multiple of four, so they share the lane's swizzled column.
@@ -224,26 +205,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         for (int j = 0; j < WPW; ++j)
             *(SDGP_LDS u32x4_t*)(smem + L::off_w() + set * L::kWSlab + (wave + j * NW) * 1024 + lane * 16) = wreg[j];
     };
-    // MODE 3: the positions of 32 rows (8 bytes each, one 4-byte word per lane) of reduction step `st`
-    auto copy_meta_unit = [&](int u, int st, uint32_t dst) {
-        const int rl = u * 32 + (lane >> 1);
-        const uint32_t word = (uint32_t)(lane & 1) * 4u;
-        if constexpr (!GATHER) {
-            long long row = m0 + rl;
-            if (row > last_row) row = last_row;
-            lds_copy4(p.meta + (((size_t)st * (size_t)p.rows_dO + (size_t)row) * 8u + word), dst);
-        } else {
-            const int t = tap_of(st), chunk = st - t * nchunks;
-            const int base = rowtab[3 * rl], ij = rowtab[3 * rl + 1];
-            const int i = (ij & 0xFFFF) + p.tap_dp[t], j = (ij >> 16) + p.tap_dq[t];
-            const bool ok = base >= 0 && i >= 0 && i < p.P && j >= 0 && j < p.Q;
-            long long src = (long long)base + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
-            src = src < 0 ? 0 : (src > last_pix ? last_pix : src);
-            const unsigned char* a = ok ? p.meta + (((size_t)chunk * (size_t)p.rows_dO + (size_t)src) * 8u + word)
-                                        : reinterpret_cast<const unsigned char*>(kPwZeros) + word;
-            lds_copy4(a, dst);
-        }
-    };
+    // MODE 3: the positions of 32 rows per unit (8 bytes each, one 4-byte word per lane)
     // (the same for the position words: unit wave + j * NW covers 32 rows, a step is one chunk's array of all rows)
     const unsigned char* m_base[MPW];
     const size_t m_chunk_step = (size_t)p.rows_dO * 8u;
