@@ -142,16 +142,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
     const uint32_t c16_a = PRUNES ? (uint32_t)(((lane & 3) ^ ((lane >> 4) & 1)) * 16)
                                   : (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
     // `st` below is the reduction step: tap st / nchunks, chunk st % nchunks
-    // W: unit u = rows u*RPU .. of the 32 x BN slab of a chunk, columns swizzled for the transpose reads
-    auto w_src = [&](int u, int st) {
-        const int t = tap_of(st), chunk = st - t * nchunks;
-        const int row = u * RPU + lane / CPR;
-        const int lchunk = (lane % CPR) ^ (WSW * (row & 3));
-        int col = n0 + lchunk * 8;
-        if (col > p.C_in - 8) col = p.C_in - 8;  // columns past C_in feed accumulators that are never stored
-        const int wtap = GATHER ? p.tap_w[t] : 0;
-        return gWb + ((size_t)(chunk * KC + row) * wrowB + (size_t)(wtap * p.C_in + col) * 2u);
-    };
+    // W: unit u = rows u*RPU .. of the KC x BN slab of a chunk, columns swizzled for the transpose reads.
     // The units a wavefront copies are wave, wave + NW, ...: without a row table their addresses are a per-lane base
     // (computed once) plus a wave-uniform step per reduction step, so a copy costs one 64-bit addition.  The W units of
     // one wavefront are NW * RPU rows apart, a multiple of four, so they share the lane's swizzled column.
@@ -171,7 +162,14 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
             if (row > last_row) row = last_row;
             a_base[j] = gdO + ((size_t)row * rowB + c16_a);
         }
-        w_base = w_src(wave, 0);
+    }
+    {
+        // (tap 0 of chunk 0; a gathered class adds its tap's column block per step)
+        const int row = wave * RPU + lane / CPR;
+        const int lchunk = (lane % CPR) ^ (WSW * (row & 3));
+        int col = n0 + lchunk * 8;
+        if (col > p.C_in - 8) col = p.C_in - 8;
+        w_base = gWb + ((size_t)row * wrowB + (size_t)col * 2u);
     }
     // unit wave + j * NW of reduction step `st` into the buffer that starts at `dst`
     auto copy_a_j = [&](int j, int st, uint32_t dst) {
@@ -187,8 +185,12 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
         }
     };
     auto w_src_j = [&](int j, int st) {
-        if constexpr (!GATHER) return w_base + ((size_t)j * w_unit_step + (size_t)st * w_chunk_step);
-        else return w_src(wave + j * NW, st);
+        if constexpr (!GATHER) {
+            return w_base + ((size_t)j * w_unit_step + (size_t)st * w_chunk_step);
+        } else {
+            const int t = tap_of(st), chunk = st - t * nchunks;
+            return w_base + ((size_t)j * w_unit_step + (size_t)chunk * w_chunk_step + (size_t)(p.tap_w[t] * p.C_in) * 2u);
+        }
     };
     // Dense: the W slab travels through registers (an ordinary 16-byte load per lane, stored to the same LDS position
     // a direct copy would fill) while the gradient rows take the direct path, so the two halves of a chunk's bytes use
