@@ -284,6 +284,26 @@ def main():
                 "the product kernel alone runs 1.15-1.25x as fast as the dense one (profiles/ranked_ahead_kernel_stats.md)",
     }
 
+    # ---- the 1x1 stride-1 layers are plain GEMMs dD[rows, C_in] = dO[rows, C_out] . W[C_out, C_in]: PyTorch's library GEMM
+    # (hipBLASLt) on the same tensors beside this library's dense and fused kernels
+    rows = []
+    seen = set()
+    for L, dO, W, out in data50:
+        key = (L.H, L.C_in, L.C_out)
+        if L.R != 1 or L.S != 1 or L.stride != 1 or key in seen:
+            continue
+        seen.add(key)
+        a2, w2, o2 = dO.view(-1, L.C_out), W.view(L.C_out, L.C_in), out.view(-1, L.C_in)
+        t_lib = time_call(lambda: torch.matmul(a2, w2, out=o2), reps=5, warm=2)
+        t_dense = time_call(lambda: call(L, dO, W, out, 4, 4, sdgp.GREEDY), reps=5, warm=1)
+        t_fused = time_call(lambda: call(L, dO, W, out, 2, 4, sdgp.RANDOM), reps=5, warm=1)
+        rows.append({"layer": L.name, "rows": L.B * L.H * L.Wd, "C_out": L.C_out, "C_in": L.C_in,
+                     "library_gemm_us": round(t_lib * 1e3, 1), "dense_us": round(t_dense * 1e3, 1),
+                     "2:4_random_us": round(t_fused * 1e3, 1), "dense_vs_library": round(t_lib / t_dense, 2)})
+    result["pointwise_vs_library_gemm"] = {
+        "layers": rows,
+        "note": "library_gemm = torch.matmul(dO[rows, C_out], W[C_out, C_in]) in bf16 on the same tensors (no pruning); "
+                "dense_vs_library > 1: this library's dense kernel is the faster one"}
     del data50, shapes
 
     # ------------------------------------------------------------------ ResNet-9 sweep, batch 512, the three rankers

@@ -146,7 +146,14 @@ int sdgp_conv_bwd_data(const void* dO, const void* W, void* dD, int64_t B, int64
  *     more than 256 input channels, strided filters up to 2*stride taps wide -- ask
  *     for room for the gradient ranked and compressed once (Sec. III-B: kept values
  *     and positions; 9/16 of the gradient's bytes), written by a pass of its own
- *     ahead of the product. */
+ *     ahead of the product.
+ *   - Small bf16 1x1 stride-1 layers (at most 2^24 elements in the gradient and in the
+ *     filter) whose C_out is a multiple of 8 but not of 32 -- a classifier's 1000
+ *     outputs -- ask for room for copies of the gradient and the filter with C_out
+ *     rounded up to 32 (zeros in the new channels), on which the matrix-core kernel
+ *     runs; without the workspace a slower kernel takes the layer.  The result does
+ *     not depend on which one ran (the random ranker indexes rows of C_out elements
+ *     either way). */
 size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out,
                                     int R, int S, int stride, int pad, int dt, int n, int m);
 

@@ -43,6 +43,7 @@ struct PwParams {
     int n;
     uint32_t mix;
     int ntiles_n, nblocks;
+    int idx_pitch;   // channels per gradient row in the random ranker's flat element index (C_out, or what it was before padding)
     // MODE 3: dO points at the compressed values ([rows_dO][C_out / 2] bf16) and meta at the positions
     // ([C_out / 64][rows_dO] x 8 bytes: four 16-bit words of 2-bit positions per row and 64 channels)
     const unsigned char* meta;
@@ -296,7 +297,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
                     long long grow = m0 + row;
                     if constexpr (GATHER) grow = (long long)rowtab[3 * row] + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
                     grow = grow < 0 ? 0 : (grow > last_pix ? last_pix : grow);
-                    e0 = (uint64_t)grow * (uint64_t)p.C_out + (uint64_t)(ch * KC + part * IC);
+                    e0 = (uint64_t)grow * (uint64_t)p.idx_pitch + (uint64_t)(ch * KC + part * IC);
                 }
 #pragma unroll
                 for (int g = 0; g < IC / M; ++g) {
@@ -332,7 +333,7 @@ __device__ __forceinline__ void bwd_pw_body(const PwParams& p) {
                     long long grow = m0 + row;
                     if constexpr (GATHER) grow = (long long)rowtab[3 * row] + (long long)p.tap_dp[t] * p.Q + p.tap_dq[t];
                     grow = grow < 0 ? 0 : (grow > last_pix ? last_pix : grow);  // (rows of zeros: any index will do)
-                    e0 = (uint64_t)grow * (uint64_t)p.C_out + (uint64_t)(ch * KC + part * 16);
+                    e0 = (uint64_t)grow * (uint64_t)p.idx_pitch + (uint64_t)(ch * KC + part * 16);
                 }
                 uint32_t packed[4], meta;
                 prune16_compressed<M, RK>(v, p.n, p.mix, e0, packed, meta);

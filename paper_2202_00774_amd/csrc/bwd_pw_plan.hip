@@ -96,7 +96,7 @@ struct PwPlan {
 
 // 0 and the plan, or 1 when the pointwise kernel does not take the problem.
 int pw_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n, int m,
-            int rk, PwPlan& out) {
+            int rk, PwPlan& out, int force_shape = -1) {
     const int mode = pw_mode(n, m);
     if (mode < 0) return 1;
     if (R != 1 || S != 1 || stride < 1 || stride > 255 || pad != 0 || (C_out % kPwKC) != 0 || (C_in % 8) != 0) return 1;
@@ -107,23 +107,65 @@ int pw_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R
     if (rows < 1 || C_out < kPwKC || C_in < 8 || C_out >= (1 << 24) || C_in >= (1 << 24)) return 1;
 
     PwParams p{};
-    p.rows = rows, p.C_out = (int)C_out, p.C_in = (int)C_in;
+    p.rows = rows, p.C_out = (int)C_out, p.C_in = (int)C_in, p.idx_pitch = (int)C_out;
     p.n = n;
     p.stride = stride, p.P = (int)P, p.Q = (int)Q, p.H = (int)H, p.Wd = (int)Wd;
     p.rows_dO = rows, p.gather = 0, p.ntaps = 1, p.w_taps = 1;
 
-    int shape = pw_shape(mode, C_in, C_out);
+    int shape = force_shape >= 0 ? force_shape : pw_shape(mode, C_in, C_out);
     const int fused_tiles_n = (int)((C_in + kPwShapes[shape].bn - 1) / kPwShapes[shape].bn);
-    out.pre = pre_pays(mode, C_out, rows, fused_tiles_n, rk);
+    out.pre = force_shape < 0 && pre_pays(mode, C_out, rows, fused_tiles_n, rk);
     if (out.pre) shape = pw_pre_shape(C_in);
     const int bn = kPwShapes[shape].bn, rows_per = kPwShapes[shape].rows;
     const int64_t blocks = ((rows + rows_per - 1) / rows_per) * ((C_in + bn - 1) / bn);
-    if (blocks < 64 || blocks >= INT_MAX) return 1;  // too small to be worth a matrix-core launch of this shape
+    // too small to be worth a matrix-core launch of this shape (a forced shape: the caller has decided)
+    if ((blocks < 64 && force_shape < 0) || blocks < 1 || blocks >= INT_MAX) return 1;
     p.ntiles_n = (int)((C_in + bn - 1) / bn);
     p.nblocks = (int)blocks;
     out.p = p, out.mode = mode, out.shape = shape;
     out.bytes = out.pre ? compress_bytes(rows, C_out) : 0;
     return 0;
+}
+
+// ---- small 1x1 / linear problems whose C_out is a multiple of 8 but not of the chunk (a classifier's 1000 outputs):
+// the gradient rows and the filter are copied into the workspace with C_out rounded up to the chunk, zeros in the new
+// channels, and the kernel runs on the copies.  Zero channels change nothing: a group of zeros keeps zeros, a zero
+// filter row adds nothing, and the random ranker's element index keeps the original row pitch.
+typedef uint32_t pad_u32x4 __attribute__((ext_vector_type(4)));
+
+// dst [rows][vout] <- src [rows][vin] 16-byte vectors, zero where the column is new
+__global__ void __launch_bounds__(256) pad_columns(const pad_u32x4* __restrict__ src, pad_u32x4* __restrict__ dst, int64_t total,
+                                                   int vin, int vout) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int64_t r = i / vout;
+    const int c = (int)(i - r * vout);
+    dst[i] = c < vin ? src[r * vin + c] : pad_u32x4{0u, 0u, 0u, 0u};
+}
+// dst [nout] <- src [nin] 16-byte vectors, zeros after them
+__global__ void __launch_bounds__(256) pad_tail(const pad_u32x4* __restrict__ src, pad_u32x4* __restrict__ dst, int64_t nin,
+                                                int64_t nout) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= nout) return;
+    dst[i] = i < nin ? src[i] : pad_u32x4{0u, 0u, 0u, 0u};
+}
+
+struct PadPlan {
+    int64_t rows, Kp;
+    size_t off_w, bytes;
+};
+// Whether the padded path takes the problem (and its workspace): plain 1x1 stride 1, at most 16 M elements in either copy.
+bool pad_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n, int m,
+              PadPlan& out) {
+    if (R != 1 || S != 1 || stride != 1 || pad != 0) return false;
+    if (C_out < kPwKC || (C_out % kPwKC) == 0 || (C_out % 8) != 0 || (C_in % 8) != 0 || C_in < 8) return false;
+    if (pw_mode(n, m) < 0 || (n != m && (C_out % m) != 0)) return false;
+    const int64_t rows = B * H * Wd, Kp = (C_out + kPwKC - 1) / kPwKC * kPwKC;
+    if (rows < 1 || rows * Kp > ((int64_t)1 << 24) || Kp * C_in > ((int64_t)1 << 24)) return false;
+    out.rows = rows, out.Kp = Kp;
+    out.off_w = ((size_t)rows * (size_t)Kp * 2u + 255u) & ~(size_t)255u;
+    out.bytes = out.off_w + (size_t)Kp * (size_t)C_in * 2u;
+    return true;
 }
 
 }  // namespace
@@ -140,6 +182,28 @@ int bwd_pw_launch(const void* dO, const void* W, void* dD, int64_t B, int64_t H,
                   int R, int S, int stride, int pad, int n, int m, int rk, uint64_t seed, void* workspace, size_t workspace_bytes,
                   hipStream_t stream) {
     if (!is_aligned16(dO) || !is_aligned16(W) || !is_aligned16(dD)) return 1;
+    PadPlan padded{};
+    if (pad_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, padded)) {
+        if (workspace == nullptr || workspace_bytes < padded.bytes || !is_aligned16(workspace)) return 1;  // another kernel takes it
+        PwPlan plan{};
+        const int shape = 3;   // 128 x 64 tiles, the most workgroups: these problems are small
+        if (pw_plan(1, 1, padded.rows, C_in, padded.Kp, 1, 1, 1, 0, n, m, rk, plan, shape) != 0) return 1;
+        PwParams& p = plan.p;
+        p.idx_pitch = (int)C_out;
+        pad_u32x4* dOp = static_cast<pad_u32x4*>(workspace);
+        pad_u32x4* Wp = reinterpret_cast<pad_u32x4*>(static_cast<unsigned char*>(workspace) + padded.off_w);
+        const int64_t n_dO = padded.rows * (padded.Kp / 8), n_w_in = C_out * (C_in / 8), n_w_out = padded.Kp * (C_in / 8);
+        hipLaunchKernelGGL(pad_columns, dim3((unsigned)((n_dO + 255) / 256)), dim3(256), 0, stream, static_cast<const pad_u32x4*>(dO), dOp,
+                           n_dO, (int)(C_out / 8), (int)(padded.Kp / 8));
+        hipLaunchKernelGGL(pad_tail, dim3((unsigned)((n_w_out + 255) / 256)), dim3(256), 0, stream, static_cast<const pad_u32x4*>(W), Wp,
+                           n_w_in, n_w_out);
+        if (launch_status() != SDGP_OK) return SDGP_ERR_HIP;
+        p.dO = reinterpret_cast<const uint16_t*>(dOp);
+        p.W = reinterpret_cast<const uint16_t*>(Wp);
+        p.dD = static_cast<uint16_t*>(dD);
+        p.mix = seed_mix(seed);
+        return launch_pw_any(p, plan.mode, m, shape, rk, stream);
+    }
     PwPlan plan{};
     if (pw_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, rk, plan) != 0) return 1;
     if (plan.pre && (workspace == nullptr || workspace_bytes < plan.bytes || !is_aligned16(workspace))) {
@@ -196,7 +260,7 @@ int gather_plan(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, i
         return 1;
 
     PwParams base{};
-    base.C_out = (int)C_out, base.C_in = (int)C_in;
+    base.C_out = (int)C_out, base.C_in = (int)C_in, base.idx_pitch = (int)C_out;
     base.n = n;
     base.stride = stride, base.P = (int)P, base.Q = (int)Q, base.H = (int)H, base.Wd = (int)Wd;
     base.rows_dO = B * P * Q, base.gather = 1, base.w_taps = R * S;
@@ -281,6 +345,8 @@ int bwd_gather_launch(const void* dO, const void* W, void* dD, int64_t B, int64_
 
 size_t bwd_pw_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_in, int64_t C_out, int R, int S, int stride, int pad, int n,
                         int m) {
+    PadPlan padded{};
+    if (pad_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, padded)) return padded.bytes;
     PwPlan one{};
     // (the ranker that takes the pass soonest: the size is enough for any)
     if (pw_plan(B, H, Wd, C_in, C_out, R, S, stride, pad, n, m, kRandom, one) == 0) return one.bytes;

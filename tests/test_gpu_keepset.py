@@ -136,6 +136,16 @@ def test_linear_identity_equals_the_oracle():
     check_exact(layer, False, nm_settings(), npix=rows)
 
 
+def test_padded_reduction_identity_equals_the_oracle():
+    """C_out = 40 and 1000 are multiples of 8 but not of the kernel's 32-channel chunk: small 1x1 problems are padded
+    into the workspace (zero channels, zero filter rows) and the random ranker keeps indexing rows of C_out elements."""
+    for rows, C in ((9001, 40), (300, 1000)):
+        layer = wl.ConvLayer("padded_n%d" % C, rows, 1, 1, C, C, 1, 1, 1, 0)
+        assert sdgp.conv_bwd_data_workspace(rows, 1, 1, C, C, 1, 1, 1, 0, sdgp.BF16, 2, 4) >= 2 * rows * (-(-C // 32) * 32)
+        check_exact(layer, False, [(2, 4, r) for r in RANKERS] + [(2, 8, oracle.RANDOM), (4, 4, oracle.GREEDY), (3, 8, oracle.GREEDY)],
+                    npix=rows)
+
+
 # The gradient ranked and compressed by a pass of its own, then multiplied without ranking (1x1 layers with several
 # column tiles; the strided cases above take the same route): kept values and positions go through global memory.
 RANKED_AHEAD = [
