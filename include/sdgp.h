@@ -169,7 +169,8 @@ size_t sdgp_conv_bwd_data_workspace(int64_t B, int64_t H, int64_t Wd, int64_t C_
  *     ImageNet network with more than 384 output channels) returns SDGP_ERR_WORKSPACE and launches nothing;
  *     SDGP_ERR_HIP when the runtime cannot report the array's address.  Where the workspace of sdgp_conv_bwd_data
  *     only holds the gradient ranked ahead of the product, a problem whose arrays do not fit the scratch runs the
- *     fused kernel instead (same kept values, same result up to summation order).
+ *     fused kernel instead (same kept values, same result up to summation order); likewise a small 1x1 layer whose
+ *     padded copies do not fit runs the kernel that needs none.
  *   - All calls on one GPU share that GPU's array, and it keeps the last call's contents (every call rewrites the
  *     part it reads, nothing has to start at zero).  Calls that overlap in time on one GPU -- different streams,
  *     or different host threads -- race on it: order them on one stream.

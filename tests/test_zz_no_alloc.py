@@ -71,3 +71,15 @@ def test_noalloc_ranks_ahead_of_the_product_when_the_arrays_fit_the_scratch():
     run_pair(small, 2, 4, sdgp.RANDOM, 3)
     run_pair(small, 2, 8, sdgp.GREEDY_ADJUSTED, 4)
     run_pair(small, 2, 4, sdgp.RANDOM, 3)
+
+
+def test_noalloc_pads_a_ragged_reduction_into_the_scratch():
+    """A small 1x1 layer with 40 output channels (a multiple of 8, not of the kernel's 32-channel chunk): the padded
+    copies of gradient and filter (49 KB here) go into the scratch array; a second, smaller call follows."""
+    big = wl.ConvLayer("padded_n40", 3, 11, 11, 96, 40, 1, 1, 1, 0)
+    small = wl.ConvLayer("padded_n40_small", 1, 5, 7, 64, 40, 1, 1, 1, 0)
+    need = sdgp.conv_bwd_data_workspace(3, 11, 11, 96, 40, 1, 1, 1, 0, sdgp.BF16, 2, 4)
+    assert 0 < need <= 256 * 1024
+    for layer in (big, small):
+        run_pair(layer, 2, 4, sdgp.RANDOM, 8)
+    run_pair(small, 4, 4, sdgp.GREEDY, 0)
