@@ -196,7 +196,8 @@ def main():
         "config": {"workload": "full ResNet-50 backward-data pass: 53 convolutions + fc, batch %d, 224x224, NHWC bf16, 2:4, "
                                "random ranker seeded per layer (54 sdgp_conv_bwd_data calls per step: one fused kernel each, except that layers "
                                "whose gradient the fused kernel would rank several times over rank and compress it in a pass of their "
-                               "own first)" % args.batch,
+                               "own first, and the classifier layer copies gradient and filter into the workspace with its 1000 "
+                               "channels padded to 1024)" % args.batch,
                    "n": 2, "m": 4, "batch": args.batch, "ranker": "random"},
         "paper_context": PAPER_CONTEXT,
     }
